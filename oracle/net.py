@@ -1,0 +1,138 @@
+"""The convnet's minibatch gradient, composed from the oracle's layer functions.
+
+A network is a list of layer tuples:
+    ("conv", cout, k, stride, pad)  ("relu",)  ("maxpool", k, stride)
+    ("fc", out)  ("dropout", p[, scale])  ("softmax_ce",)
+The flat parameter vector holds, for each conv/fc layer in order, the weights
+(conv [cout,cin,k,k]; fc [out,in] with in = c*H*W + h*W + w) followed by the bias.
+Section 2 of the paper defines the unit of work: the gradient of the objective
+over one minibatch.
+"""
+import numpy as np
+
+from . import ops
+
+
+class OracleNet:
+    def __init__(self, layers, in_shape):
+        self.layers = [tuple(l) for l in layers]
+        self.in_shape = tuple(in_shape)
+        assert self.layers and self.layers[-1][0] == "softmax_ce"
+        shape = self.in_shape  # (C,H,W) or (F,)
+        self.shapes = []       # output shape of each layer
+        self.param_slices = {}  # layer index -> (w_off, w_shape, b_off, b_len)
+        off = 0
+        for li, l in enumerate(self.layers):
+            kind = l[0]
+            if kind == "conv":
+                _, cout, k, s, p = l
+                c, h, w = shape
+                ho, wo = (h + 2 * p - k) // s + 1, (w + 2 * p - k) // s + 1
+                assert ho > 0 and wo > 0
+                wshape = (cout, c, k, k)
+                self.param_slices[li] = (off, wshape, off + int(np.prod(wshape)), cout)
+                off += int(np.prod(wshape)) + cout
+                shape = (cout, ho, wo)
+            elif kind == "maxpool":
+                _, k, s = l
+                c, h, w = shape
+                ho, wo = (h - k) // s + 1, (w - k) // s + 1
+                assert ho > 0 and wo > 0
+                shape = (c, ho, wo)
+            elif kind == "fc":
+                nin = int(np.prod(shape))
+                wshape = (l[1], nin)
+                self.param_slices[li] = (off, wshape, off + l[1] * nin, l[1])
+                off += l[1] * nin + l[1]
+                shape = (l[1],)
+            elif kind in ("relu", "dropout", "softmax_ce"):
+                pass
+            else:
+                raise ValueError(kind)
+            self.shapes.append(shape)
+        self.param_count = off
+        self.num_classes = int(np.prod(shape))
+
+    def split(self, flat, li):
+        w_off, w_shape, b_off, b_len = self.param_slices[li]
+        n = int(np.prod(w_shape))
+        return flat[w_off:w_off + n].reshape(w_shape), flat[b_off:b_off + b_len]
+
+    def fwd_bwd(self, params, images, labels, dropout_seed=0, step=0, worker=0, want_grads=True,
+                masks=None):
+        """Returns (loss, grads, trace).  ``trace[li]`` holds what layer li produced
+        ("out", and "argmax" / "mask" where they exist); ``trace["dx"][li]`` the
+        gradient w.r.t. that layer's input.  ``masks`` overrides the generated
+        dropout masks (dict layer index -> uint8 array), for tests."""
+        params = np.ascontiguousarray(params, dtype=np.float64)
+        assert params.shape == (self.param_count,)
+        x = np.ascontiguousarray(images, dtype=np.float64)
+        N = x.shape[0]
+        assert x.shape[1:] == self.in_shape
+        trace = {}
+        inputs = []
+        for li, l in enumerate(self.layers):
+            kind = l[0]
+            inputs.append(x)
+            t = {}
+            if kind == "conv":
+                w, b = self.split(params, li)
+                x = ops.conv_fwd(x, w, b, l[3], l[4])
+            elif kind == "relu":
+                x = ops.relu_fwd(x)
+            elif kind == "maxpool":
+                x, t["argmax"] = ops.maxpool_fwd(x, l[1], l[2])
+            elif kind == "fc":
+                w, b = self.split(params, li)
+                x = ops.fc_fwd(x.reshape(N, -1), w, b)
+            elif kind == "dropout":
+                p = l[1]
+                scale = l[2] if len(l) > 2 else 1.0
+                if masks is not None and li in masks:
+                    m = np.ascontiguousarray(masks[li], dtype=np.uint8).reshape(-1)
+                else:
+                    m = ops.dropout_mask(x.size, dropout_seed, step, worker, li, p)
+                t["mask"] = m.reshape(x.shape)
+                x = ops.dropout_apply(x, m, scale)
+            elif kind == "softmax_ce":
+                loss, dz = ops.softmax_ce(x.reshape(N, -1), labels, want_grad=want_grads)
+                t["dz"] = dz
+            t["out"] = x
+            trace[li] = t
+        if not want_grads:
+            return loss, None, trace
+
+        grads = np.zeros((self.param_count,))
+        d = dz
+        trace["dx"] = {}
+        for li in range(len(self.layers) - 1, -1, -1):
+            l = self.layers[li]
+            kind = l[0]
+            xin = inputs[li]
+            if kind == "softmax_ce":
+                pass
+            elif kind == "dropout":
+                scale = l[2] if len(l) > 2 else 1.0
+                d = ops.dropout_apply(d, trace[li]["mask"].reshape(-1), scale).reshape(xin.shape)
+            elif kind == "relu":
+                d = ops.relu_bwd(xin, d.reshape(xin.shape))
+            elif kind == "maxpool":
+                d = ops.maxpool_bwd(d.reshape(trace[li]["out"].shape), trace[li]["argmax"], xin.shape[2:],
+                                    l[1], l[2])
+            elif kind == "fc":
+                w, b = self.split(params, li)
+                w_off, w_shape, b_off, b_len = self.param_slices[li]
+                dx, dw, db = ops.fc_bwd(xin.reshape(N, -1), w, d.reshape(N, -1), need_dx=li > 0)
+                grads[w_off:w_off + dw.size] = dw.reshape(-1)
+                grads[b_off:b_off + b_len] = db
+                d = dx.reshape(xin.shape) if dx is not None else None
+            elif kind == "conv":
+                w, b = self.split(params, li)
+                w_off, w_shape, b_off, b_len = self.param_slices[li]
+                dy = d.reshape(trace[li]["out"].shape)
+                dw, db = ops.conv_bwd_weight(xin, dy, l[2], l[3], l[4])
+                grads[w_off:w_off + dw.size] = dw.reshape(-1)
+                grads[b_off:b_off + b_len] = db
+                d = ops.conv_bwd_data(dy, w, xin.shape[2:], l[3], l[4]) if li > 0 else None
+            trace["dx"][li] = d
+        return loss, grads, trace

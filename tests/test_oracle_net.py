@@ -1,0 +1,154 @@
+"""Pins for the composed network gradient and the A-SGD replay.  No GPU."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import ops, asgd
+from paper_1312_6186_amd import workloads as wl
+
+NET_A = dict(in_shape=(2, 9, 9), classes=5,
+             layers=[("conv", 3, 3, 2, 1), ("relu",), ("conv", 4, 3, 1, 1), ("relu",), ("maxpool", 3, 2),
+                     ("fc", 6), ("relu",), ("dropout", 0.5), ("fc", 5), ("softmax_ce",)])
+NET_B = dict(in_shape=(1, 12, 12), classes=4,   # the Tiny configuration's shape, shrunk
+             layers=[("conv", 3, 5, 1, 2), ("relu",), ("maxpool", 2, 2), ("fc", 4), ("softmax_ce",)])
+
+
+def _setup(cfg, batch, seed):
+    net = oracle.OracleNet(cfg["layers"], cfg["in_shape"])
+    assert net.param_count == wl.param_count(cfg["layers"], cfg["in_shape"])
+    params = wl.make_params(cfg["layers"], cfg["in_shape"], seed).astype(np.float64)
+    rng = np.random.default_rng(seed + 1)
+    params += 0.05 * rng.standard_normal(params.size)       # non-zero biases
+    images, labels = wl.make_batch(cfg["in_shape"], batch, cfg["classes"], seed + 2)
+    return net, params, images.astype(np.float64), labels
+
+
+def test_param_counts_of_the_paper_sized_configs():
+    assert oracle.OracleNet(wl.TINY["layers"], wl.TINY["in_shape"]).param_count == 15898
+    assert oracle.OracleNet(wl.SMALL["layers"], wl.SMALL["in_shape"]).param_count == 116906
+    net = oracle.OracleNet(wl.ALEXNET["layers"], wl.ALEXNET["in_shape"])
+    assert net.param_count == 62378344
+    assert net.shapes[2] == (96, 27, 27) and net.shapes[12] == (256, 6, 6)   # FC fan-in 9216
+
+
+@pytest.mark.parametrize("cfg", [NET_A, NET_B])
+def test_gradient_by_central_finite_differences(cfg):
+    net, params, images, labels = _setup(cfg, 3, 5)
+    loss, grads, _ = net.fwd_bwd(params, images, labels, dropout_seed=9, step=2, worker=1)
+    h = 1e-5
+    fd = np.empty_like(params)
+    for i in range(params.size):
+        pp, pm = params.copy(), params.copy()
+        pp[i] += h; pm[i] -= h
+        lp, _, _ = net.fwd_bwd(pp, images, labels, 9, 2, 1, want_grads=False)
+        lm, _, _ = net.fwd_bwd(pm, images, labels, 9, 2, 1, want_grads=False)
+        fd[i] = (lp - lm) / (2 * h)
+    # a ReLU or pooling kink inside [-h, h] would show as an O(1) relative error on that entry
+    err = np.abs(fd - grads)
+    assert np.median(err) < 1e-9
+    assert (err < 1e-6 * (1 + np.abs(grads))).mean() > 0.995
+    assert np.linalg.norm(fd - grads) / np.linalg.norm(grads) < 1e-5
+
+
+def _torch_fwd_bwd(cfg, params, images, labels, masks):
+    p = torch.tensor(params, requires_grad=True)
+    x = torch.tensor(images)
+    off = 0
+    for li, l in enumerate(cfg["layers"]):
+        if l[0] == "conv":
+            cin = x.shape[1]; n = l[1] * cin * l[2] * l[2]
+            w = p[off:off + n].reshape(l[1], cin, l[2], l[2]); b = p[off + n:off + n + l[1]]; off += n + l[1]
+            x = torch.nn.functional.conv2d(x, w, b, stride=l[3], padding=l[4])
+        elif l[0] == "relu":
+            x = torch.relu(x)
+        elif l[0] == "maxpool":
+            x = torch.nn.functional.max_pool2d(x, l[1], l[2])
+        elif l[0] == "fc":
+            x = x.reshape(x.shape[0], -1); n = l[1] * x.shape[1]
+            w = p[off:off + n].reshape(l[1], x.shape[1]); b = p[off + n:off + n + l[1]]; off += n + l[1]
+            x = x @ w.T + b
+        elif l[0] == "dropout":
+            x = x * torch.tensor(masks[li].astype(np.float64))
+        elif l[0] == "softmax_ce":
+            loss = torch.nn.functional.cross_entropy(x, torch.tensor(labels.astype(np.int64)))
+    loss.backward()
+    return float(loss.detach()), p.grad.numpy()
+
+
+@pytest.mark.parametrize("cfg,batch", [(NET_A, 4), (NET_B, 4),
+                                       (dict(wl.SMALL, classes=10), 6)])
+def test_whole_net_matches_torch_autograd_in_float64(cfg, batch):
+    net, params, images, labels = _setup(cfg, batch, 21)
+    loss, grads, trace = net.fwd_bwd(params, images, labels, dropout_seed=3002, step=4, worker=0)
+    masks = {li: t["mask"] for li, t in trace.items() if isinstance(li, int) and "mask" in t}
+    tl, tg = _torch_fwd_bwd(cfg, params, images, labels, masks)
+    assert abs(loss - tl) < 1e-12 * max(1, abs(tl))
+    assert np.linalg.norm(grads - tg) / np.linalg.norm(tg) < 1e-12
+
+
+def test_dropout_is_unscaled_and_keyed_by_descriptor_index():
+    net, params, images, labels = _setup(NET_A, 4, 3)
+    _, _, trace = net.fwd_bwd(params, images, labels, dropout_seed=5, step=6, worker=7)
+    li = 7
+    np.testing.assert_array_equal(trace[li]["mask"].reshape(-1), ops.dropout_mask(4 * 6, 5, 6, 7, li, 0.5))
+    np.testing.assert_array_equal(trace[li]["out"], trace[li - 1]["out"] * trace[li]["mask"])
+
+
+# ------------------------------------------------------------------ A-SGD
+def _batch_fn(cfg, batch, seed):
+    def fn(a):
+        return wl.make_batch(cfg["in_shape"], batch, cfg["classes"], seed + a)
+    return fn
+
+
+def test_schedule_matches_bigint_reimplementation():
+    from test_oracle_layers import _mix, MASK64
+    T, seed = 64, 4005
+    worker, rv = ops.schedule(T, seed, 4, 3)
+    for a in range(T):
+        s = min(a, (_mix((_mix(seed) + a) & MASK64) >> 32) % 4)
+        assert worker[a] == a % 4 and rv[a] == a - s
+    assert ((np.arange(T) - rv) <= np.minimum(np.arange(T), 3)).all() and (rv >= 0).all()
+    assert set(np.arange(T)[4:] - rv[4:]) == {0, 1, 2, 3}      # every staleness value occurs
+    # causally realisable: the version a worker reads exists after its previous push was applied
+    assert (rv[4:] >= np.arange(T)[4:] - 3).all()
+
+
+def test_zero_staleness_single_worker_is_plain_sgd():
+    net, params, _, _ = _setup(NET_B, 4, 11)
+    T = 5
+    bf = _batch_fn(NET_B, 4, 100)
+    w1, v1, l1 = asgd.sgd_loop(net, params, bf, T, 0.05, 0.9, 1e-3)
+    w2, v2, l2, log = asgd.replay(net, params, np.zeros(T, np.int32), np.arange(T, dtype=np.int32), bf,
+                                  0.05, 0.9, 1e-3)
+    assert w1.tobytes() == w2.tobytes() and v1.tobytes() == v2.tobytes() and l1 == l2
+    np.testing.assert_array_equal(log, np.stack([np.arange(T), np.zeros(T), np.arange(T)], 1))
+
+
+def test_stale_reads_change_the_trajectory_and_replay_is_reproducible():
+    net, params, _, _ = _setup(NET_B, 4, 11)
+    T = 8
+    bf = _batch_fn(NET_B, 4, 100)
+    worker, rv = ops.schedule(T, 4005, 4, 3)
+    assert (rv != np.arange(T)).any()
+    wa, va, la, loga = asgd.replay(net, params, worker, rv, bf, 0.05, 0.9, 0.0)
+    wb, vb, lb, logb = asgd.replay(net, params, worker, rv, bf, 0.05, 0.9, 0.0)
+    assert wa.tobytes() == wb.tobytes() and la == lb and (loga == logb).all()
+    w0, _, _, _ = asgd.replay(net, params, worker, np.arange(T, dtype=np.int32), bf, 0.05, 0.9, 0.0)
+    assert np.linalg.norm(wa - w0) > 1e-6 * np.linalg.norm(w0)
+    # a stale gradient is the gradient at the old version: check update 1 by hand
+    if rv[1] == 0:
+        _, g, _ = net.fwd_bwd(params, *bf(1), 0, 1, int(worker[1]))
+        w, v = params.copy(), np.zeros_like(params)
+        _, g0, _ = net.fwd_bwd(params, *bf(0), 0, 0, int(worker[0]))
+        ops.apply_update(w, v, g0, 0.05, 0.9, 0.0)
+        ops.apply_update(w, v, g, 0.05, 0.9, 0.0)
+        w2, _, _, _ = asgd.replay(net, params, worker[:2], rv[:2], bf, 0.05, 0.9, 0.0)
+        assert w.tobytes() == w2.tobytes()
+
+
+def test_worker_copy_rounding():
+    p = np.array([1.0 + 2.0**-8, 1.0 + 2.0**-30, -3.5])
+    np.testing.assert_array_equal(asgd.worker_copy(p, "bf16"), [1.0, 1.0, -3.5])
+    np.testing.assert_array_equal(asgd.worker_copy(p, "f32"), [1.0 + 2.0**-8, 1.0, -3.5])

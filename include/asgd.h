@@ -1,0 +1,214 @@
+/*
+ * asgd.h — C ABI of the MI355X (gfx950) hot path of GPU A-SGD (arXiv 1312.6186).
+ *
+ * The paper's protocol (Section 2.3, "Our contribution: GPU A-SGD"): each model
+ * replica computes minibatch gradients on a GPU, pushes gradients to a central
+ * parameter server and fetches updated parameters from it.  The three calls of
+ * that protocol are
+ *     asgd_snapshot      (a replica fetches the server's parameters)
+ *     asgd_fwd_bwd       (one replica's minibatch gradient, Section 2)
+ *     asgd_apply_update  (the server applies a pushed gradient)
+ * plus the calls that describe the network and the on-one-GPU A-SGD replay.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory owned by the caller unless stated;
+ *     "host" pointers are ordinary process memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return without synchronising the host.
+ *   - Every call returns 0 on success or a negative asgd_status_t; the text of
+ *     the last error of the calling thread is at asgd_last_error().  Nothing
+ *     aborts or throws across this boundary.
+ *   - Canonical layouts: images [B,C,H,W]; the flat parameter vector holds, for
+ *     every conv / fc layer in descriptor order, the weights then the bias;
+ *     conv weights [cout][cin][k][k], fc weights [out][in] with
+ *     in = c*H*W + h*W + w.  Gradients and momentum use the same order.
+ */
+#ifndef ASGD_H
+#define ASGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ASGD_OK = 0,
+    ASGD_EINVAL = -1,  /* null pointer, bad enum, bad scalar argument        */
+    ASGD_ESHAPE = -2,  /* layer list or sizes that do not form a valid net   */
+    ASGD_ENOMEM = -3,  /* host or device allocation failed                   */
+    ASGD_EHIP = -4,    /* a HIP runtime call failed (no device, launch error) */
+    ASGD_EALIGN = -5   /* a buffer is not aligned as the call requires       */
+} asgd_status_t;
+
+typedef enum { ASGD_F32 = 0, ASGD_BF16 = 1 } asgd_dtype_t;
+
+typedef enum {
+    ASGD_LAYER_CONV = 1,       /* out, k, stride, pad                          */
+    ASGD_LAYER_RELU = 2,       /* must follow a CONV or an FC                  */
+    ASGD_LAYER_MAXPOOL = 3,    /* k, stride (unpadded, floor rule)             */
+    ASGD_LAYER_FC = 4,         /* out                                          */
+    ASGD_LAYER_DROPOUT = 5,    /* p, scale; must follow FC or FC+RELU          */
+    ASGD_LAYER_SOFTMAX_CE = 6  /* last layer; follows an FC                    */
+} asgd_layer_kind_t;
+
+/* One entry of the network description.  Unused fields are ignored.
+ * Dropout (Section 1 cites Hinton et al. 2012): a unit is dropped with
+ * probability p; kept units are multiplied by `scale` (0 is read as 1, the
+ * cited unscaled form). */
+typedef struct {
+    int32_t kind;   /* asgd_layer_kind_t */
+    int32_t out;    /* CONV: output channels; FC: output features */
+    int32_t k;      /* CONV / MAXPOOL: square window size */
+    int32_t stride; /* CONV / MAXPOOL */
+    int32_t pad;    /* CONV: zero padding on each side */
+    float p;        /* DROPOUT: drop probability, 0 <= p < 1 */
+    float scale;    /* DROPOUT: factor on kept units */
+} asgd_layer_desc_t;
+
+/* Where one parameterised layer lives in the flat parameter vector. */
+typedef struct {
+    int32_t layer;       /* index into the descriptor list */
+    int32_t kind;        /* ASGD_LAYER_CONV or ASGD_LAYER_FC */
+    uint64_t w_offset;   /* elements from the start of the flat vector */
+    uint64_t w_count;
+    uint64_t b_offset;
+    uint64_t b_count;
+    int32_t w_shape[4];  /* conv: cout,cin,k,k; fc: out,in,1,1 */
+} asgd_tensor_info_t;
+
+typedef struct asgd_net asgd_net_t;
+
+/* Build the execution plan of a network (the Krizhevsky-style convnet of
+ * Section 3: conv, ReLU, max-pool, fully connected, dropout, softmax
+ * cross-entropy) for a fixed batch size and compute type.
+ *   layers, n_layers : host array; copied.
+ *   batch, in_c/h/w  : minibatch size and image shape.
+ *   compute_dtype    : ASGD_F32 (fp32 MFMA) or ASGD_BF16 (bf16 MFMA, fp32
+ *                      accumulation); it is also the type of the worker's
+ *                      parameter copy and of the images given to asgd_fwd_bwd.
+ *   out              : receives the plan; release with asgd_net_destroy.
+ * Touches no GPU: shapes, parameter layout and workspace size can be queried
+ * on a machine without one.  Device workspace (activations, pooling indices,
+ * split-K partial sums; owned by the plan) is allocated by the first
+ * asgd_fwd_bwd or by asgd_net_prepare.
+ * Errors: ASGD_EINVAL (null, bad dtype), ASGD_ESHAPE (invalid sequence, a
+ * window larger than its input, an FC fan-in that is not a multiple of 8,
+ * sizes beyond 2^31 elements), ASGD_ENOMEM. */
+int asgd_net_create(const asgd_layer_desc_t *layers, int n_layers, int batch, int in_c, int in_h,
+                    int in_w, int compute_dtype, asgd_net_t **out);
+
+/* Allocate the plan's device workspace on the current device now (optional). */
+int asgd_net_prepare(asgd_net_t *net);
+
+/* Free the plan and its workspace.  The caller must have synchronised every
+ * stream the plan was used on. */
+int asgd_net_destroy(asgd_net_t *net);
+
+/* Number of elements of the flat parameter vector (0 if net is NULL). */
+size_t asgd_param_count(const asgd_net_t *net);
+
+/* Fill `info[0..cap)` with the parameterised layers in flat-vector order.
+ * Returns the number of such layers (which may exceed cap), or a negative
+ * status. */
+int asgd_param_layout(const asgd_net_t *net, asgd_tensor_info_t *info, int cap);
+
+/* Output shape of descriptor layer `layer` as (c,h,w); FC-side layers report
+ * (features,1,1). */
+int asgd_layer_shape(const asgd_net_t *net, int layer, int32_t chw[3]);
+
+/* Bytes of device workspace the plan owns once prepared. */
+size_t asgd_workspace_bytes(const asgd_net_t *net);
+
+/* One replica's minibatch gradient (Section 2: the gradient of the objective
+ * over a minibatch): forward, softmax cross-entropy averaged over the batch,
+ * backward.
+ *   params  : device, the worker's copy of the flat parameter vector in the
+ *             plan's compute dtype (fp32, or bf16 as written by asgd_snapshot),
+ *             16-byte aligned; read only.
+ *   images  : device, [B,C,H,W] in the compute dtype; read only.
+ *   labels  : device, int32 [B], each in [0, classes); out-of-range labels are
+ *             not detected and give an undefined loss.
+ *   dropout_seed, step, worker : key of the stateless dropout mask generator
+ *             (SplitMix64 finaliser over seed, step, worker, layer index and
+ *             element index), so that a run can be replayed exactly.
+ *   loss    : device, 1 float; overwritten.
+ *   grads   : device, fp32 [param_count], 16-byte aligned; overwritten (not
+ *             accumulated into).
+ * Everything is enqueued on `stream`; no host synchronisation.  A plan must
+ * not be used on two streams at once (its workspace is shared).
+ * Errors: ASGD_EINVAL, ASGD_EALIGN, ASGD_ENOMEM, ASGD_EHIP. */
+int asgd_fwd_bwd(asgd_net_t *net, const void *params, const void *images, const int32_t *labels,
+                 uint64_t dropout_seed, uint64_t step, uint32_t worker, float *loss, float *grads,
+                 void *stream);
+
+/* The parameter server's update for one pushed gradient (Section 3.1: the
+ * single-GPU settings, i.e. momentum SGD with weight decay), one pass over the
+ * buffers:   t = g + wd*w;  v = mu*v - lr*t;  w = w + v.
+ *   params, momentum : device fp32 [n], updated in place.
+ *   grads            : device fp32 [n], read only.
+ * Errors: ASGD_EINVAL (null with n > 0), ASGD_EHIP. */
+int asgd_apply_update(float *params, float *momentum, const float *grads, size_t n, float lr,
+                      float mu, float wd, void *stream);
+
+/* A replica's fetch (Section 2.3): copy the server's fp32 parameters into the
+ * worker's buffer, as fp32 (dst_dtype ASGD_F32) or rounded to bf16, ties to
+ * even (ASGD_BF16; NaN stays a quiet NaN).
+ *   params : device fp32 [n];  worker_copy : device, n elements of dst_dtype.
+ * Errors: ASGD_EINVAL, ASGD_EHIP. */
+int asgd_snapshot(const float *params, void *worker_copy, size_t n, int dst_dtype, void *stream);
+
+/* Test hook: what the last asgd_fwd_bwd on this plan left behind, converted to
+ * canonical layout into a caller-owned device buffer.
+ *   what = ASGD_DEBUG_OUTPUT : fp32 [B,C,H,W] (or [B,F]) output of `layer`,
+ *          which must be the last layer of a fused group (the RELU after a
+ *          CONV, a MAXPOOL, the RELU/DROPOUT ending an FC group, the last FC).
+ *   what = ASGD_DEBUG_ARGMAX : uint8 [B,C,Ho,Wo], window position ky*k+kx of
+ *          the first maximum (row-major scan) of MAXPOOL `layer`.
+ *   what = ASGD_DEBUG_MASK   : uint8 [B,F], 1 = kept, of DROPOUT `layer`.
+ * `cap_bytes` is the size of dst; too small gives ASGD_EINVAL. */
+typedef enum { ASGD_DEBUG_OUTPUT = 0, ASGD_DEBUG_ARGMAX = 1, ASGD_DEBUG_MASK = 2 } asgd_debug_what_t;
+int asgd_debug_get(asgd_net_t *net, int what, int layer, void *dst, size_t cap_bytes, void *stream);
+
+/* Staleness schedule of the A-SGD replay (Section 3.3 attributes artefacts of
+ * the learning curves to stale updates).  Update a (0-based) is pushed by
+ * worker a mod n_workers and was computed on parameter version
+ * read_version[a] = a - min(a, h(seed, a) mod (max_stale + 1)).  Host arrays of
+ * length T.  Requires 0 <= max_stale < n_workers so that every read is
+ * causally possible.  Errors: ASGD_EINVAL. */
+int asgd_schedule_generate(int32_t *worker, int32_t *read_version, int T, uint64_t seed,
+                           int n_workers, int max_stale);
+
+/* A-SGD on one GPU (Sections 2.2-2.3): n_workers replicas as concurrent HIP
+ * streams, one server stream applying pushed gradients to the shared fp32
+ * parameters in schedule order.  Update a: its worker snapshots the parameters
+ * when exactly read_version[a] updates have been applied, computes the
+ * gradient of minibatch a on that copy, and the server applies it as update a.
+ *   nets          : host array of n_workers plans (same network), one each.
+ *   params, momentum : device fp32 [param_count], shared, updated in place.
+ *   worker_copy, worker_grads : host arrays of n_workers device buffers
+ *                   (param_count elements of the compute dtype / of fp32).
+ *   images, labels : device, T minibatches back to back ([T][B,C,H,W], [T][B]).
+ *   worker, read_version : host, length T (asgd_schedule_generate).
+ *   losses        : device fp32 [T], loss of each pushed gradient.
+ *   log           : device int32 [T][3] = (update, worker, version counter read
+ *                   on the device when the snapshot was taken).
+ *   stream        : the caller's stream; the replay starts after the work
+ *                   already on it and the stream waits for the replay's end.
+ * Errors: ASGD_EINVAL (a read_version outside [a - max over schedule, a], a
+ * worker index out of range, a worker whose next read precedes its previous
+ * push), ASGD_EHIP. */
+int asgd_replay_run(asgd_net_t *const *nets, int n_workers, float *params, float *momentum,
+                    void *const *worker_copy, float *const *worker_grads, const void *images,
+                    const int32_t *labels, const int32_t *worker, const int32_t *read_version, int T,
+                    float lr, float mu, float wd, uint64_t dropout_seed, float *losses, int32_t *log,
+                    void *stream);
+
+/* Text of the last error on the calling thread ("" if none). */
+const char *asgd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASGD_H */

@@ -1,0 +1,653 @@
+// Host side of the C ABI declared in include/asgd.h: network planning, workspace
+// management and the order in which the kernels of one minibatch gradient are
+// enqueued.  No arithmetic of the method happens on the host.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/asgd.h"
+#include "asgd_internal.h"
+
+using namespace asgd;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+int hip_fail(hipError_t e, const char *what) { return fail(ASGD_EHIP, "%s: %s", what, hipGetErrorString(e)); }
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+enum StageKind { ST_CONV = 1, ST_POOL = 2, ST_FC = 3 };
+
+struct Stage {
+    int kind = 0;
+    int first_layer = 0, last_layer = 0;
+    // spatial stages: channel-last tensors [B][H][W][Cp]
+    int inC = 0, inCp = 0, inH = 0, inW = 0;
+    int outC = 0, outCp = 0, outH = 0, outW = 0;
+    // fc stages: [B][ld]
+    int in_f = 0, out_f = 0, out_ld = 0;
+    bool in_is_spatial = false;  // an fc fed by a conv / pool stage (flatten boundary)
+    bool last = false;           // produces the fp32 logits
+    int k = 0, stride = 1, pad = 0;
+    int relu = 0, drop = 0, drop_layer = -1;
+    float drop_p = 0.f, drop_scale = 1.f;
+    uint32_t drop_thr = 0;
+    size_t w_off = 0, w_cnt = 0, b_off = 0, b_cnt = 0;
+    // workspace
+    void *out = nullptr, *dout = nullptr;
+    uint8_t *argmax = nullptr;
+    void *wf = nullptr, *wd = nullptr;
+    void *flat_in = nullptr, *dflat_in = nullptr;
+    GemmPlan p_fwd, p_dgrad, p_wgrad;
+    size_t out_elems() const { return kind == ST_FC ? (size_t)out_ld : (size_t)outH * outW * outCp; }
+};
+
+}  // namespace
+
+struct asgd_net {
+    std::vector<asgd_layer_desc_t> layers;
+    std::vector<int> layer_stage;         // descriptor index -> stage index (-1 for softmax)
+    std::vector<int32_t> layer_shape;     // 3 per layer
+    std::vector<Stage> stages;
+    std::vector<asgd_tensor_info_t> tensors;
+    int batch = 0, in_c = 0, in_cp = 0, in_h = 0, in_w = 0, dtype = 0, classes = 0;
+    size_t param_count = 0;
+    size_t ws_bytes = 0;
+    // device workspace
+    void *arena = nullptr;
+    int device = -1;
+    void *act0 = nullptr;      // staged input
+    float *scratch = nullptr;  // split-K partials and column-sum partials
+    float *row_loss = nullptr;
+    int *version_counter = nullptr;  // device-side count of applied updates (A-SGD replay)
+    size_t scratch_floats = 0;
+    // key of the last forward pass (for the dropout mask export)
+    uint64_t last_seed = 0, last_step = 0;
+    uint32_t last_worker = 0;
+    bool ran = false;
+};
+
+namespace {
+
+struct Carver {
+    size_t off = 0;
+    size_t take(size_t bytes)
+    {
+        const size_t o = off;
+        off += (bytes + 255) / 256 * 256;
+        return o;
+    }
+};
+
+// Lays the workspace out; with base == nullptr only the total size is computed.
+size_t carve(asgd_net &n, char *base)
+{
+    Carver c;
+    const size_t es = dtype_size(n.dtype);
+    const size_t B = (size_t)n.batch;
+    auto at = [&](size_t bytes) -> void * {
+        const size_t o = c.take(bytes);
+        return base ? base + o : nullptr;
+    };
+    n.act0 = at(B * n.in_h * n.in_w * n.in_cp * es);
+    for (size_t i = 0; i < n.stages.size(); ++i) {
+        Stage &s = n.stages[i];
+        const size_t oe = B * s.out_elems();
+        s.out = at(oe * (s.last ? 4 : es));
+        s.dout = at(oe * es);
+        if (s.kind == ST_POOL) s.argmax = static_cast<uint8_t *>(at(oe));
+        if (s.kind == ST_CONV) {
+            s.wf = at((size_t)s.outCp * s.k * s.k * s.inCp * es);
+            s.wd = i > 0 ? at((size_t)s.inCp * s.k * s.k * s.outCp * es) : nullptr;
+        }
+        if (s.kind == ST_FC && s.in_is_spatial) {
+            s.flat_in = at(B * s.in_f * es);
+            s.dflat_in = at(B * s.in_f * es);
+        }
+    }
+    n.row_loss = static_cast<float *>(at(B * 4));
+    n.version_counter = static_cast<int *>(at(256));
+    n.scratch = static_cast<float *>(at(n.scratch_floats * 4));
+    return c.off;
+}
+
+int plan_net(asgd_net &n)
+{
+    const int L = (int)n.layers.size();
+    n.layer_stage.assign(L, -1);
+    n.layer_shape.assign(3 * L, 0);
+    n.in_cp = round_up(n.in_c, 8);
+    int C = n.in_c, H = n.in_h, W = n.in_w;
+    long F = 0;  // > 0 once on the fc side
+    size_t off = 0;
+    int i = 0;
+    while (i < L) {
+        const asgd_layer_desc_t &l = n.layers[i];
+        Stage s;
+        s.first_layer = i;
+        if (l.kind == ASGD_LAYER_CONV) {
+            if (F > 0) return fail(ASGD_ESHAPE, "layer %d: CONV after FC", i);
+            if (l.out <= 0 || l.k <= 0 || l.stride <= 0 || l.pad < 0) return fail(ASGD_ESHAPE, "layer %d: bad CONV parameters", i);
+            if (H + 2 * l.pad < l.k || W + 2 * l.pad < l.k) return fail(ASGD_ESHAPE, "layer %d: filter larger than padded input", i);
+            s.kind = ST_CONV;
+            s.inC = C; s.inCp = round_up(C, 8); s.inH = H; s.inW = W;
+            s.k = l.k; s.stride = l.stride; s.pad = l.pad;
+            s.outC = l.out; s.outCp = round_up(l.out, 8);
+            s.outH = (H + 2 * l.pad - l.k) / l.stride + 1;
+            s.outW = (W + 2 * l.pad - l.k) / l.stride + 1;
+            s.w_off = off; s.w_cnt = (size_t)l.out * C * l.k * l.k; s.b_off = off + s.w_cnt; s.b_cnt = l.out;
+            off += s.w_cnt + s.b_cnt;
+            C = l.out; H = s.outH; W = s.outW;
+            n.layer_shape[3 * i] = C; n.layer_shape[3 * i + 1] = H; n.layer_shape[3 * i + 2] = W;
+            if (i + 1 < L && n.layers[i + 1].kind == ASGD_LAYER_RELU) {
+                s.relu = 1; ++i;
+                n.layer_shape[3 * i] = C; n.layer_shape[3 * i + 1] = H; n.layer_shape[3 * i + 2] = W;
+            }
+        } else if (l.kind == ASGD_LAYER_MAXPOOL) {
+            if (F > 0) return fail(ASGD_ESHAPE, "layer %d: MAXPOOL after FC", i);
+            if (l.k <= 0 || l.k > 15 || l.stride <= 0 || H < l.k || W < l.k) return fail(ASGD_ESHAPE, "layer %d: bad MAXPOOL window", i);
+            s.kind = ST_POOL;
+            s.inC = s.outC = C; s.inCp = s.outCp = round_up(C, 8); s.inH = H; s.inW = W;
+            s.k = l.k; s.stride = l.stride;
+            s.outH = (H - l.k) / l.stride + 1; s.outW = (W - l.k) / l.stride + 1;
+            H = s.outH; W = s.outW;
+            n.layer_shape[3 * i] = C; n.layer_shape[3 * i + 1] = H; n.layer_shape[3 * i + 2] = W;
+        } else if (l.kind == ASGD_LAYER_FC) {
+            if (l.out <= 0) return fail(ASGD_ESHAPE, "layer %d: bad FC size", i);
+            s.kind = ST_FC;
+            s.in_is_spatial = F == 0;
+            const long fin = F > 0 ? F : (long)C * H * W;
+            if (fin % 8 != 0) return fail(ASGD_ESHAPE, "layer %d: FC fan-in %ld is not a multiple of 8", i, fin);
+            if (fin > 0x7fffffffL / 4) return fail(ASGD_ESHAPE, "layer %d: FC fan-in too large", i);
+            if (s.in_is_spatial) { s.inC = C; s.inCp = round_up(C, 8); s.inH = H; s.inW = W; }
+            s.in_f = (int)fin; s.out_f = l.out; s.out_ld = round_up(l.out, 8);
+            s.w_off = off; s.w_cnt = (size_t)l.out * fin; s.b_off = off + s.w_cnt; s.b_cnt = l.out;
+            if (s.w_off % 8 != 0) return fail(ASGD_ESHAPE, "layer %d: FC weights start at element %zu, not a multiple of 8", i, s.w_off);
+            off += s.w_cnt + s.b_cnt;
+            F = l.out;
+            n.layer_shape[3 * i] = (int)F; n.layer_shape[3 * i + 1] = 1; n.layer_shape[3 * i + 2] = 1;
+            if (i + 1 < L && n.layers[i + 1].kind == ASGD_LAYER_RELU) {
+                s.relu = 1; ++i;
+                n.layer_shape[3 * i] = (int)F; n.layer_shape[3 * i + 1] = 1; n.layer_shape[3 * i + 2] = 1;
+                if (i + 1 < L && n.layers[i + 1].kind == ASGD_LAYER_DROPOUT) {
+                    ++i;
+                    const asgd_layer_desc_t &d = n.layers[i];
+                    if (!(d.p >= 0.f && d.p < 1.f)) return fail(ASGD_ESHAPE, "layer %d: dropout p must be in [0,1)", i);
+                    if (d.scale < 0.f) return fail(ASGD_ESHAPE, "layer %d: dropout scale must be positive", i);
+                    s.drop = 1; s.drop_layer = i; s.drop_p = d.p; s.drop_scale = d.scale == 0.f ? 1.f : d.scale;
+                    s.drop_thr = (uint32_t)std::floor((double)d.p * 4294967296.0);
+                    n.layer_shape[3 * i] = (int)F; n.layer_shape[3 * i + 1] = 1; n.layer_shape[3 * i + 2] = 1;
+                }
+            }
+        } else if (l.kind == ASGD_LAYER_SOFTMAX_CE) {
+            if (i != L - 1) return fail(ASGD_ESHAPE, "layer %d: SOFTMAX_CE must be last", i);
+            if (n.stages.empty() || n.stages.back().kind != ST_FC || n.stages.back().relu)
+                return fail(ASGD_ESHAPE, "layer %d: SOFTMAX_CE must directly follow an FC", i);
+            n.stages.back().last = true;
+            n.classes = (int)F;
+            n.layer_shape[3 * i] = (int)F; n.layer_shape[3 * i + 1] = 1; n.layer_shape[3 * i + 2] = 1;
+            ++i;
+            break;
+        } else if (l.kind == ASGD_LAYER_RELU) {
+            return fail(ASGD_ESHAPE, "layer %d: RELU must directly follow a CONV or an FC", i);
+        } else if (l.kind == ASGD_LAYER_DROPOUT) {
+            return fail(ASGD_ESHAPE, "layer %d: DROPOUT must directly follow FC + RELU", i);
+        } else {
+            return fail(ASGD_EINVAL, "layer %d: unknown kind %d", i, l.kind);
+        }
+        s.last_layer = i;
+        for (int j = s.first_layer; j <= s.last_layer; ++j) n.layer_stage[j] = (int)n.stages.size();
+        if ((s.kind == ST_CONV || s.kind == ST_FC)) {
+            asgd_tensor_info_t t;
+            memset(&t, 0, sizeof t);
+            t.layer = s.first_layer; t.kind = s.kind == ST_CONV ? ASGD_LAYER_CONV : ASGD_LAYER_FC;
+            t.w_offset = s.w_off; t.w_count = s.w_cnt; t.b_offset = s.b_off; t.b_count = s.b_cnt;
+            if (s.kind == ST_CONV) { t.w_shape[0] = s.outC; t.w_shape[1] = s.inC; t.w_shape[2] = s.k; t.w_shape[3] = s.k; }
+            else { t.w_shape[0] = s.out_f; t.w_shape[1] = s.in_f; t.w_shape[2] = 1; t.w_shape[3] = 1; }
+            n.tensors.push_back(t);
+        }
+        n.stages.push_back(s);
+        ++i;
+    }
+    if (n.classes == 0 || n.stages.empty() || !n.stages.back().last) return fail(ASGD_ESHAPE, "the layer list must end with FC, SOFTMAX_CE");
+    n.param_count = off;
+
+    // sizes, GEMM plans, scratch
+    const long B = n.batch;
+    size_t scratch = 0;
+    for (size_t si = 0; si < n.stages.size(); ++si) {
+        Stage &s = n.stages[si];
+        if (s.kind == ST_CONV) {
+            const long M = B * s.outH * s.outW, Min = B * s.inH * s.inW;
+            const long K = (long)s.k * s.k * s.inCp;
+            if (M > 0x7fffffffL / 2 || Min > 0x7fffffffL / 2 || M * s.outCp > (1L << 40)) return fail(ASGD_ESHAPE, "layer %d: tensor too large", s.first_layer);
+            s.p_fwd = plan_gemm(M, s.outCp, K, n.dtype, 1);
+            s.p_dgrad = plan_gemm(Min, s.inCp, (long)s.k * s.k * s.outCp, n.dtype, 1);
+            s.p_wgrad = plan_gemm(s.outCp, K, M, n.dtype, 64);
+            scratch = std::max(scratch, s.p_wgrad.ws_floats);
+            scratch = std::max(scratch, colsum_ws_floats(M, s.outC));
+        } else if (s.kind == ST_FC) {
+            s.p_fwd = plan_gemm(B, s.out_ld, s.in_f, n.dtype, 32);
+            s.p_dgrad = plan_gemm(B, s.in_f, s.out_f, n.dtype, 32);
+            s.p_wgrad = plan_gemm(s.out_f, s.in_f, B, n.dtype, 1);
+            scratch = std::max(scratch, std::max(s.p_fwd.ws_floats, s.p_dgrad.ws_floats));
+            scratch = std::max(scratch, colsum_ws_floats(B, s.out_f));
+        }
+    }
+    n.scratch_floats = scratch + 64;
+    n.ws_bytes = carve(n, nullptr);
+    return ASGD_OK;
+}
+
+int ensure_prepared(asgd_net *n)
+{
+    if (n->arena) return ASGD_OK;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    e = hipMalloc(&n->arena, n->ws_bytes);
+    if (e != hipSuccess) { n->arena = nullptr; (void)hipGetLastError(); return fail(ASGD_ENOMEM, "hipMalloc of %zu workspace bytes: %s", n->ws_bytes, hipGetErrorString(e)); }
+    e = hipMemset(n->arena, 0, n->ws_bytes);
+    if (e != hipSuccess) { (void)hipFree(n->arena); n->arena = nullptr; return hip_fail(e, "hipMemset"); }
+    n->device = dev;
+    carve(*n, static_cast<char *>(n->arena));
+    return ASGD_OK;
+}
+
+#define CHECK_LAUNCH(expr, what)                                                             \
+    do {                                                                                     \
+        if ((expr) != 0) {                                                                   \
+            const hipError_t e_ = hipGetLastError();                                         \
+            return fail(ASGD_EHIP, "%s: %s", what, e_ == hipSuccess ? "bad launch arguments" : hipGetErrorString(e_)); \
+        }                                                                                    \
+    } while (0)
+
+const char *param_ptr(const asgd_net *n, const void *params, size_t off) { return static_cast<const char *>(params) + off * dtype_size(n->dtype); }
+
+int forward(asgd_net *n, const void *params, const void *images, const int32_t *labels, uint64_t seed, uint64_t step, uint32_t worker,
+            float *loss, hipStream_t st)
+{
+    const int B = n->batch, dt = n->dtype;
+    CHECK_LAUNCH(launch_stage_input(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, n->in_cp, st), "stage_input");
+    const void *cur = n->act0;
+    for (size_t si = 0; si < n->stages.size(); ++si) {
+        Stage &s = n->stages[si];
+        if (s.kind == ST_CONV) {
+            CHECK_LAUNCH(launch_pack_conv(dt, param_ptr(n, params, s.w_off), s.wf, s.wd, s.outC, s.inC, s.k, s.k, s.outCp, s.inCp, st), "pack_conv");
+            Gather g;
+            g.x = cur; g.N = B; g.H = s.inH; g.W = s.inW; g.C = s.inCp; g.Ho = s.outH; g.Wo = s.outW;
+            g.kh = g.kw = s.k; g.sm = s.stride; g.ds = 1; g.pad = s.pad;
+            Epilogue ep;
+            ep.out = s.out; ep.ld = s.outCp; ep.bias = param_ptr(n, params, s.b_off); ep.bias_n = s.outC; ep.relu = s.relu;
+            CHECK_LAUNCH(gemm_gather_plain(dt, g, s.wf, (long)s.k * s.k * s.inCp, s.outCp, ep, s.p_fwd, n->scratch, st), "conv forward");
+        } else if (s.kind == ST_POOL) {
+            CHECK_LAUNCH(launch_pool_fwd(dt, cur, s.out, s.argmax, B, s.inH, s.inW, s.inCp, s.k, s.stride, st), "pool forward");
+        } else {
+            const void *x = cur;
+            long ldx = si > 0 && n->stages[si - 1].kind == ST_FC ? n->stages[si - 1].out_ld : s.in_f;
+            if (s.in_is_spatial) {
+                CHECK_LAUNCH(launch_flatten(dt, cur, s.flat_in, B, s.inH, s.inW, s.inC, s.inCp, st), "flatten");
+                x = s.flat_in;
+                ldx = s.in_f;
+            }
+            Epilogue ep;
+            ep.out = s.out; ep.ld = s.out_ld; ep.out_f32 = s.last ? 1 : 0;
+            ep.bias = param_ptr(n, params, s.b_off); ep.bias_n = s.out_f; ep.relu = s.relu;
+            if (s.drop) {
+                ep.drop = 1; ep.drop_key = dropout_key(seed, step, worker, (uint32_t)s.drop_layer);
+                ep.drop_thr = s.drop_thr; ep.drop_F = s.out_f; ep.drop_scale = s.drop_scale;
+            }
+            CHECK_LAUNCH(gemm_plain_plain(dt, x, ldx, B, param_ptr(n, params, s.w_off), s.in_f, s.out_ld, s.out_f, s.in_f, ep, s.p_fwd, n->scratch, st),
+                         "fc forward");
+        }
+        cur = s.out;
+    }
+    Stage &last = n->stages.back();
+    CHECK_LAUNCH(launch_softmax_ce(dt, static_cast<const float *>(last.out), last.out_ld, labels, B, n->classes, last.dout, loss, n->row_loss, st),
+                 "softmax cross-entropy");
+    return ASGD_OK;
+}
+
+int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
+{
+    const int B = n->batch, dt = n->dtype;
+    for (int si = (int)n->stages.size() - 1; si >= 0; --si) {
+        Stage &s = n->stages[si];
+        Stage *prev = si > 0 ? &n->stages[si - 1] : nullptr;
+        const void *xin = prev ? prev->out : n->act0;
+        if (s.kind == ST_FC) {
+            const void *x = s.in_is_spatial ? s.flat_in : xin;
+            const long ldx = s.in_is_spatial ? s.in_f : prev->out_ld;
+            Epilogue ew;
+            ew.out = grads + s.w_off; ew.ld = s.in_f; ew.out_f32 = 1;
+            CHECK_LAUNCH(gemm_trans_trans(dt, s.dout, s.out_ld, s.out_f, x, ldx, s.in_f, B, ew, s.p_wgrad, n->scratch, st), "fc weight gradient");
+            CHECK_LAUNCH(launch_colsum(dt, s.dout, s.out_ld, B, s.out_f, grads + s.b_off, n->scratch, st), "fc bias gradient");
+            if (prev) {
+                Epilogue ed;
+                if (s.in_is_spatial) {
+                    ed.out = s.dflat_in; ed.ld = s.in_f;
+                } else {
+                    ed.out = prev->dout; ed.ld = prev->out_ld;
+                    if (prev->relu) { ed.mask_src = prev->out; ed.mask_ld = prev->out_ld; ed.mask_scale = prev->drop ? prev->drop_scale : 1.f; }
+                }
+                CHECK_LAUNCH(gemm_plain_trans(dt, s.dout, s.out_ld, B, param_ptr(n, params, s.w_off), s.in_f, s.in_f, s.out_f, ed, s.p_dgrad,
+                                              n->scratch, st),
+                             "fc data gradient");
+                if (s.in_is_spatial)
+                    CHECK_LAUNCH(launch_unflatten(dt, s.dflat_in, prev->out, prev->kind == ST_CONV && prev->relu, prev->dout, B, s.inH, s.inW, s.inC,
+                                                  s.inCp, st),
+                                 "unflatten");
+            }
+        } else if (s.kind == ST_POOL) {
+            // prev exists: a pool cannot be first... unless the net starts with a pool, which feeds no parameters
+            if (prev)
+                CHECK_LAUNCH(launch_pool_bwd(dt, s.dout, s.argmax, prev->out, prev->kind == ST_CONV && prev->relu, prev->dout, B, s.inH, s.inW, s.inCp,
+                                             s.k, s.stride, st),
+                             "pool backward");
+        } else {
+            const long M = (long)B * s.outH * s.outW;
+            Gather g;
+            g.x = xin; g.N = B; g.H = s.inH; g.W = s.inW; g.C = s.inCp; g.Ho = s.outH; g.Wo = s.outW;
+            g.kh = g.kw = s.k; g.sm = s.stride; g.ds = 1; g.pad = s.pad;
+            Epilogue ew;
+            ew.out = grads + s.w_off; ew.mode = 1; ew.out_f32 = 1;
+            ew.cw_cout = s.outC; ew.cw_cin = s.inC; ew.cw_cinp = s.inCp; ew.cw_kh = s.k; ew.cw_kw = s.k;
+            CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch, st), "conv filter gradient");
+            CHECK_LAUNCH(launch_colsum(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, n->scratch, st), "conv bias gradient");
+            if (prev) {
+                Gather d;
+                d.x = s.dout; d.N = B; d.H = s.outH; d.W = s.outW; d.C = s.outCp; d.Ho = s.inH; d.Wo = s.inW;
+                d.kh = d.kw = s.k; d.sm = 1; d.ds = s.stride; d.pad = s.k - 1 - s.pad;
+                Epilogue ed;
+                ed.out = prev->dout; ed.ld = s.inCp;
+                if (prev->kind == ST_CONV && prev->relu) { ed.mask_src = prev->out; ed.mask_ld = s.inCp; ed.mask_scale = 1.f; }
+                CHECK_LAUNCH(gemm_gather_plain(dt, d, s.wd, (long)s.k * s.k * s.outCp, s.inCp, ed, s.p_dgrad, n->scratch, st), "conv data gradient");
+            }
+        }
+    }
+    return ASGD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *asgd_last_error(void) { return g_err.c_str(); }
+
+int asgd_net_create(const asgd_layer_desc_t *layers, int n_layers, int batch, int in_c, int in_h, int in_w, int compute_dtype, asgd_net_t **out)
+{
+    if (!layers || !out) return fail(ASGD_EINVAL, "asgd_net_create: null argument");
+    *out = nullptr;
+    if (n_layers <= 0 || n_layers > 4096) return fail(ASGD_EINVAL, "asgd_net_create: bad layer count %d", n_layers);
+    if (batch <= 0 || in_c <= 0 || in_h <= 0 || in_w <= 0) return fail(ASGD_ESHAPE, "asgd_net_create: batch and image sizes must be positive");
+    if ((long)batch * in_c * in_h * in_w > 0x7fffffffL) return fail(ASGD_ESHAPE, "asgd_net_create: input larger than 2^31 elements");
+    if (compute_dtype != ASGD_F32 && compute_dtype != ASGD_BF16) return fail(ASGD_EINVAL, "asgd_net_create: unknown dtype %d", compute_dtype);
+    asgd_net *n = new (std::nothrow) asgd_net;
+    if (!n) return fail(ASGD_ENOMEM, "asgd_net_create: out of host memory");
+    try {
+        n->layers.assign(layers, layers + n_layers);
+        n->batch = batch; n->in_c = in_c; n->in_h = in_h; n->in_w = in_w; n->dtype = compute_dtype;
+        const int rc = plan_net(*n);
+        if (rc != ASGD_OK) { delete n; return rc; }
+    } catch (const std::bad_alloc &) {
+        delete n;
+        return fail(ASGD_ENOMEM, "asgd_net_create: out of host memory");
+    }
+    *out = n;
+    return ASGD_OK;
+}
+
+int asgd_net_prepare(asgd_net_t *net)
+{
+    if (!net) return fail(ASGD_EINVAL, "asgd_net_prepare: null plan");
+    return ensure_prepared(net);
+}
+
+int asgd_net_destroy(asgd_net_t *net)
+{
+    if (!net) return ASGD_OK;
+    int rc = ASGD_OK;
+    if (net->arena) {
+        const hipError_t e = hipFree(net->arena);
+        if (e != hipSuccess) rc = hip_fail(e, "hipFree");
+    }
+    delete net;
+    return rc;
+}
+
+size_t asgd_param_count(const asgd_net_t *net) { return net ? net->param_count : 0; }
+
+int asgd_param_layout(const asgd_net_t *net, asgd_tensor_info_t *info, int cap)
+{
+    if (!net || (cap > 0 && !info)) return fail(ASGD_EINVAL, "asgd_param_layout: null argument");
+    const int cnt = (int)net->tensors.size();
+    for (int i = 0; i < cnt && i < cap; ++i) info[i] = net->tensors[i];
+    return cnt;
+}
+
+int asgd_layer_shape(const asgd_net_t *net, int layer, int32_t chw[3])
+{
+    if (!net || !chw) return fail(ASGD_EINVAL, "asgd_layer_shape: null argument");
+    if (layer < 0 || layer >= (int)net->layers.size()) return fail(ASGD_EINVAL, "asgd_layer_shape: layer %d out of range", layer);
+    for (int j = 0; j < 3; ++j) chw[j] = net->layer_shape[3 * layer + j];
+    return ASGD_OK;
+}
+
+size_t asgd_workspace_bytes(const asgd_net_t *net) { return net ? net->ws_bytes : 0; }
+
+int asgd_fwd_bwd(asgd_net_t *net, const void *params, const void *images, const int32_t *labels, uint64_t dropout_seed, uint64_t step,
+                 uint32_t worker, float *loss, float *grads, void *stream)
+{
+    if (!net || !params || !images || !labels || !loss || !grads) return fail(ASGD_EINVAL, "asgd_fwd_bwd: null argument");
+    if (((uintptr_t)params | (uintptr_t)grads | (uintptr_t)images) & 15) return fail(ASGD_EALIGN, "asgd_fwd_bwd: params, images and grads must be 16-byte aligned");
+    if (((uintptr_t)labels | (uintptr_t)loss) & 3) return fail(ASGD_EALIGN, "asgd_fwd_bwd: labels and loss must be 4-byte aligned");
+    int rc = ensure_prepared(net);
+    if (rc != ASGD_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = forward(net, params, images, labels, dropout_seed, step, worker, loss, st);
+    if (rc != ASGD_OK) return rc;
+    net->last_seed = dropout_seed; net->last_step = step; net->last_worker = worker; net->ran = true;
+    return backward(net, params, grads, st);
+}
+
+int asgd_apply_update(float *params, float *momentum, const float *grads, size_t n, float lr, float mu, float wd, void *stream)
+{
+    if (n == 0) return ASGD_OK;
+    if (!params || !momentum || !grads) return fail(ASGD_EINVAL, "asgd_apply_update: null argument");
+    if (((uintptr_t)params | (uintptr_t)momentum | (uintptr_t)grads) & 3) return fail(ASGD_EALIGN, "asgd_apply_update: buffers must be 4-byte aligned");
+    if (launch_update(params, momentum, grads, n, lr, mu, wd, nullptr, static_cast<hipStream_t>(stream)) != 0)
+        return hip_fail(hipGetLastError(), "update kernel");
+    return ASGD_OK;
+}
+
+int asgd_snapshot(const float *params, void *worker_copy, size_t n, int dst_dtype, void *stream)
+{
+    if (dst_dtype != ASGD_F32 && dst_dtype != ASGD_BF16) return fail(ASGD_EINVAL, "asgd_snapshot: unknown dtype %d", dst_dtype);
+    if (n == 0) return ASGD_OK;
+    if (!params || !worker_copy) return fail(ASGD_EINVAL, "asgd_snapshot: null argument");
+    if (((uintptr_t)params & 3) || ((uintptr_t)worker_copy & (dst_dtype == ASGD_BF16 ? 1 : 3))) return fail(ASGD_EALIGN, "asgd_snapshot: misaligned buffer");
+    if (launch_snapshot(params, worker_copy, n, dst_dtype, nullptr, nullptr, 0, 0, static_cast<hipStream_t>(stream)) != 0)
+        return hip_fail(hipGetLastError(), "snapshot kernel");
+    return ASGD_OK;
+}
+
+int asgd_debug_get(asgd_net_t *net, int what, int layer, void *dst, size_t cap_bytes, void *stream)
+{
+    if (!net || !dst) return fail(ASGD_EINVAL, "asgd_debug_get: null argument");
+    if (!net->ran || !net->arena) return fail(ASGD_EINVAL, "asgd_debug_get: no forward pass has run on this plan");
+    if (layer < 0 || layer >= (int)net->layers.size() || net->layer_stage[layer] < 0) return fail(ASGD_EINVAL, "asgd_debug_get: layer %d has no output to export", layer);
+    Stage &s = net->stages[net->layer_stage[layer]];
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int B = net->batch;
+    if (what == ASGD_DEBUG_OUTPUT) {
+        if (layer != s.last_layer) return fail(ASGD_EINVAL, "asgd_debug_get: layer %d is fused into the group ending at layer %d", layer, s.last_layer);
+        if (s.kind == ST_FC) {
+            if (cap_bytes < (size_t)B * s.out_f * 4) return fail(ASGD_EINVAL, "asgd_debug_get: destination too small");
+            CHECK_LAUNCH(launch_export_rows(net->dtype, s.last ? 1 : 0, s.out, s.out_ld, static_cast<float *>(dst), B, s.out_f, st), "export");
+        } else {
+            if (cap_bytes < (size_t)B * s.outC * s.outH * s.outW * 4) return fail(ASGD_EINVAL, "asgd_debug_get: destination too small");
+            CHECK_LAUNCH(launch_export_nhwc(net->dtype, s.out, static_cast<float *>(dst), B, s.outH, s.outW, s.outC, s.outCp, st), "export");
+        }
+        return ASGD_OK;
+    }
+    if (what == ASGD_DEBUG_ARGMAX) {
+        if (s.kind != ST_POOL) return fail(ASGD_EINVAL, "asgd_debug_get: layer %d is not a MAXPOOL", layer);
+        if (cap_bytes < (size_t)B * s.outC * s.outH * s.outW) return fail(ASGD_EINVAL, "asgd_debug_get: destination too small");
+        CHECK_LAUNCH(launch_export_argmax(s.argmax, static_cast<uint8_t *>(dst), B, s.outH, s.outW, s.outC, s.outCp, st), "export");
+        return ASGD_OK;
+    }
+    if (what == ASGD_DEBUG_MASK) {
+        if (s.kind != ST_FC || !s.drop || layer != s.drop_layer) return fail(ASGD_EINVAL, "asgd_debug_get: layer %d is not a DROPOUT", layer);
+        if (cap_bytes < (size_t)B * s.out_f) return fail(ASGD_EINVAL, "asgd_debug_get: destination too small");
+        CHECK_LAUNCH(launch_dropout_mask(static_cast<uint8_t *>(dst), (size_t)B * s.out_f,
+                                         dropout_key(net->last_seed, net->last_step, net->last_worker, (uint32_t)s.drop_layer), s.drop_thr, st),
+                     "export");
+        return ASGD_OK;
+    }
+    return fail(ASGD_EINVAL, "asgd_debug_get: unknown selector %d", what);
+}
+
+int asgd_schedule_generate(int32_t *worker, int32_t *read_version, int T, uint64_t seed, int n_workers, int max_stale)
+{
+    if (T < 0 || (T > 0 && (!worker || !read_version))) return fail(ASGD_EINVAL, "asgd_schedule_generate: null argument");
+    if (n_workers <= 0 || max_stale < 0 || max_stale >= n_workers)
+        return fail(ASGD_EINVAL, "asgd_schedule_generate: need 0 <= max_stale < n_workers");
+    auto mix = [](uint64_t z) {
+        z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+        z ^= z >> 27; z *= 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        return z;
+    };
+    const uint64_t k = mix(seed);
+    for (int a = 0; a < T; ++a) {
+        const uint32_t h = (uint32_t)(mix(k + (uint64_t)a) >> 32);
+        int st = (int)(h % (uint32_t)(max_stale + 1));
+        if (st > a) st = a;
+        worker[a] = a % n_workers;
+        read_version[a] = a - st;
+    }
+    return ASGD_OK;
+}
+
+int asgd_replay_run(asgd_net_t *const *nets, int n_workers, float *params, float *momentum, void *const *worker_copy,
+                    float *const *worker_grads, const void *images, const int32_t *labels, const int32_t *worker,
+                    const int32_t *read_version, int T, float lr, float mu, float wd, uint64_t dropout_seed, float *losses, int32_t *log,
+                    void *stream)
+{
+    if (!nets || !params || !momentum || !worker_copy || !worker_grads || !images || !labels || !worker || !read_version || !losses || !log)
+        return fail(ASGD_EINVAL, "asgd_replay_run: null argument");
+    if (n_workers <= 0 || n_workers > 64 || T < 0) return fail(ASGD_EINVAL, "asgd_replay_run: bad worker count or length");
+    if (T == 0) return ASGD_OK;
+    for (int w = 0; w < n_workers; ++w) {
+        if (!nets[w] || !worker_copy[w] || !worker_grads[w]) return fail(ASGD_EINVAL, "asgd_replay_run: null entry for worker %d", w);
+        if (nets[w]->param_count != nets[0]->param_count || nets[w]->batch != nets[0]->batch || nets[w]->dtype != nets[0]->dtype)
+            return fail(ASGD_EINVAL, "asgd_replay_run: worker %d has a different network", w);
+        for (int u = 0; u < w; ++u)
+            if (nets[u] == nets[w]) return fail(ASGD_EINVAL, "asgd_replay_run: workers %d and %d share a plan", u, w);
+    }
+    // the schedule must be causally possible
+    std::vector<int> last_push(n_workers, -1);
+    for (int a = 0; a < T; ++a) {
+        if (worker[a] < 0 || worker[a] >= n_workers) return fail(ASGD_EINVAL, "asgd_replay_run: update %d names worker %d", a, worker[a]);
+        if (read_version[a] < 0 || read_version[a] > a) return fail(ASGD_EINVAL, "asgd_replay_run: update %d reads version %d", a, read_version[a]);
+        if (read_version[a] <= last_push[worker[a]])
+            return fail(ASGD_EINVAL, "asgd_replay_run: update %d reads version %d before its worker's previous push %d was applied", a,
+                        read_version[a], last_push[worker[a]]);
+        last_push[worker[a]] = a;
+    }
+    for (int w = 0; w < n_workers; ++w) {
+        const int rc = ensure_prepared(nets[w]);
+        if (rc != ASGD_OK) return rc;
+    }
+    const asgd_net *n0 = nets[0];
+    const size_t P = n0->param_count;
+    const size_t img_bytes = (size_t)n0->batch * n0->in_c * n0->in_h * n0->in_w * dtype_size(n0->dtype);
+    int *counter = nets[0]->version_counter;
+    hipStream_t caller = static_cast<hipStream_t>(stream);
+
+    std::vector<hipStream_t> ws(n_workers, nullptr);
+    hipStream_t server = nullptr;
+    std::vector<hipEvent_t> ev;  // everything created here, destroyed at the end
+    int rc = ASGD_OK;
+    auto new_event = [&](hipEvent_t *e) -> bool {
+        if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return false;
+        ev.push_back(*e);
+        return true;
+    };
+#define RP(expr)                                                                    \
+    do {                                                                            \
+        const hipError_t e_ = (expr);                                               \
+        if (e_ != hipSuccess && rc == ASGD_OK) rc = hip_fail(e_, #expr);            \
+    } while (0)
+
+    for (int w = 0; w < n_workers && rc == ASGD_OK; ++w) RP(hipStreamCreateWithFlags(&ws[w], hipStreamNonBlocking));
+    if (rc == ASGD_OK) RP(hipStreamCreateWithFlags(&server, hipStreamNonBlocking));
+    std::vector<hipEvent_t> ev_upd(T, nullptr), ev_snap(T, nullptr), ev_grad(T, nullptr);
+    hipEvent_t ev_start = nullptr, ev_reset = nullptr;
+    if (rc == ASGD_OK) {
+        bool ok = new_event(&ev_start) && new_event(&ev_reset);
+        for (int a = 0; a < T && ok; ++a) ok = new_event(&ev_upd[a]) && new_event(&ev_snap[a]) && new_event(&ev_grad[a]);
+        if (!ok) rc = fail(ASGD_EHIP, "asgd_replay_run: hipEventCreate failed");
+    }
+    if (rc == ASGD_OK) {
+        RP(hipEventRecord(ev_start, caller));
+        RP(hipStreamWaitEvent(server, ev_start, 0));
+        if (launch_fill_zero(counter, 4, server) != 0 && rc == ASGD_OK) rc = hip_fail(hipGetLastError(), "fill kernel");
+        RP(hipEventRecord(ev_reset, server));
+    }
+    // Iteration v enqueues every snapshot that must see exactly v applied updates
+    // (and the gradient computed on it), then update v, which waits for them.
+    for (int v = 0; v < T && rc == ASGD_OK; ++v) {
+        for (int a = v; a < T && rc == ASGD_OK; ++a) {
+            if (read_version[a] != v) continue;
+            const int w = worker[a];
+            RP(hipStreamWaitEvent(ws[w], v > 0 ? ev_upd[v - 1] : ev_reset, 0));
+            if (launch_snapshot(params, worker_copy[w], P, n0->dtype, counter, log + 3 * (size_t)a, a, w, ws[w]) != 0 && rc == ASGD_OK)
+                rc = hip_fail(hipGetLastError(), "snapshot kernel");
+            RP(hipEventRecord(ev_snap[a], ws[w]));
+            if (rc == ASGD_OK)
+                rc = asgd_fwd_bwd(nets[w], worker_copy[w], static_cast<const char *>(images) + (size_t)a * img_bytes,
+                                  labels + (size_t)a * n0->batch, dropout_seed, (uint64_t)a, (uint32_t)w, losses + a, worker_grads[w], ws[w]);
+            RP(hipEventRecord(ev_grad[a], ws[w]));
+        }
+        for (int a = v; a < T && rc == ASGD_OK; ++a)
+            if (read_version[a] == v) RP(hipStreamWaitEvent(server, ev_snap[a], 0));
+        RP(hipStreamWaitEvent(server, ev_grad[v], 0));
+        if (rc == ASGD_OK && launch_update(params, momentum, worker_grads[worker[v]], P, lr, mu, wd, counter, server) != 0)
+            rc = hip_fail(hipGetLastError(), "update kernel");
+        RP(hipEventRecord(ev_upd[v], server));
+    }
+    if (rc == ASGD_OK) RP(hipStreamWaitEvent(caller, ev_upd[T - 1], 0));
+    // Drain the internal streams before their events and the streams themselves go away.
+    for (int w = 0; w < n_workers; ++w)
+        if (ws[w]) { (void)hipStreamSynchronize(ws[w]); }
+    if (server) (void)hipStreamSynchronize(server);
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+    for (int w = 0; w < n_workers; ++w)
+        if (ws[w]) (void)hipStreamDestroy(ws[w]);
+    if (server) (void)hipStreamDestroy(server);
+#undef RP
+    return rc;
+}
+
+}  // extern "C"

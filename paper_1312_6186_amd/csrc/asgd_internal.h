@@ -1,0 +1,113 @@
+// Internal declarations shared by the host orchestration (api.cpp) and the
+// kernel files.  Activations live channel-last, [B][H][W][Cp] with the channel
+// count rounded up to a multiple of 8 (padding channels hold zeros); FC-side
+// activations are [B][ld] row-major.  All kernels target gfx950 only.
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace asgd {
+
+enum DType { kF32 = 0, kBF16 = 1 };
+inline size_t dtype_size(int dt) { return dt == kBF16 ? 2 : 4; }
+
+// n / d for 0 <= n < 2^31 by multiply-high and shift.
+struct FastDiv {
+    uint32_t d, mul, sh;
+};
+FastDiv make_fastdiv(uint32_t d);
+
+// What happens to one accumulator element C[m][n] on its way to memory.
+// The same routine serves the GEMM kernels and the split-K reduction.
+struct Epilogue {
+    void *out = nullptr;   // OutT [M][ld] (mode 0) or fp32 canonical conv filter gradient (mode 1)
+    long ld = 0;
+    int out_f32 = 0;       // 1: out is fp32 whatever the compute type
+    const void *bias = nullptr;  // compute type, [bias_n]; added first to columns n < bias_n
+    int bias_n = 0;
+    int relu = 0;
+    int drop = 0;          // dropout after ReLU: keep iff hash(m*drop_F+n) >= drop_thr
+    uint64_t drop_key = 0;
+    uint32_t drop_thr = 0;
+    int drop_F = 0;
+    float drop_scale = 1.f;
+    const void *mask_src = nullptr;  // compute type, [M][mask_ld]: v = mask_src > 0 ? v*mask_scale : 0
+    long mask_ld = 0;
+    float mask_scale = 1.f;
+    int mode = 0;          // 1: rows are cout, columns are (ky,kx,ci_padded) -> [cout][cin][kh][kw]
+    int cw_cout = 0, cw_cin = 0, cw_cinp = 0, cw_kh = 0, cw_kw = 0;
+};
+
+// Gather description for an implicit-GEMM operand taken from a channel-last
+// tensor x[N][H][W][C].  GEMM rows (direct form) enumerate (n, oy, ox) on a
+// grid Ho x Wo; the K index enumerates (ky, kx, c).  The element is
+// x[n][(oy*sm + ky - pad)/ds][(ox*sm + kx - pad)/ds][c] when both divisions
+// are exact and in range, else 0.  Forward conv: sm = stride, ds = 1.
+// Data gradient: sm = 1, ds = stride, pad = k-1-pad with a flipped filter.
+struct Gather {
+    const void *x = nullptr;
+    int N = 0, H = 0, W = 0, C = 0;
+    int Ho = 0, Wo = 0;
+    int kh = 0, kw = 0, sm = 1, ds = 1, pad = 0;
+};
+
+struct GemmPlan {
+    int splits = 1;          // split-K factor
+    size_t ws_floats = 0;    // fp32 scratch needed when splits > 1
+};
+
+// C[M][N] = A[M][K] * B[N][K]^T; A gathered (direct), B plain K-contiguous.
+GemmPlan plan_gemm(long M, long N, long K, int dtype, int max_splits);
+int gemm_gather_plain(int dtype, const Gather &a, const void *b, long ldb, int N, const Epilogue &ep,
+                      const GemmPlan &plan, float *ws, hipStream_t s);
+// A plain [M][lda], B plain [b_rows][ldb], both K-contiguous; columns n >= b_rows of C are computed as zeros.
+int gemm_plain_plain(int dtype, const void *a, long lda, int M, const void *b, long ldb, int N, int b_rows, int K,
+                     const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s);
+// A plain [M][lda] K-contiguous; B stored [K][ldb] (rows n contiguous).
+int gemm_plain_trans(int dtype, const void *a, long lda, int M, const void *bt, long ldb, int N, int K,
+                     const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s);
+// A stored [K][lda] (rows m contiguous), B stored [K][ldb].
+int gemm_trans_trans(int dtype, const void *at, long lda, int M, const void *bt, long ldb, int N, int K,
+                     const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s);
+// Filter gradient: A stored [K = B*Ho*Wo][lda] (rows = cout), B gathered with the
+// reduction index enumerating (n, oy, ox) and rows enumerating (ky, kx, c).
+int gemm_trans_gather(int dtype, const void *at, long lda, int M, const Gather &b, const Epilogue &ep,
+                      const GemmPlan &plan, float *ws, hipStream_t s);
+
+// ---- streaming kernels (kernels_stream.hip) --------------------------------
+int launch_update(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd,
+                  int *version_counter, hipStream_t s);
+int launch_snapshot(const float *src, void *dst, size_t n, int dst_dtype, const int *version_counter,
+                    int32_t *log_slot, int log_update, int log_worker, hipStream_t s);
+// images [B][C][H][W] (compute type) -> channel-last [B][H][W][Cp], zero padding channels
+int launch_stage_input(int dtype, const void *src, void *dst, int B, int C, int H, int W, int Cp, hipStream_t s);
+// canonical conv filters -> forward pack [coutp][kh][kw][cinp] and flipped data-gradient pack [cinp][kh][kw][coutp]
+int launch_pack_conv(int dtype, const void *w, void *wf, void *wd, int cout, int cin, int kh, int kw, int coutp,
+                     int cinp, hipStream_t s);
+int launch_pool_fwd(int dtype, const void *x, void *y, uint8_t *arg, int B, int H, int W, int Cp, int k, int stride,
+                    hipStream_t s);
+// dx[pixel] = sum of dy over the windows whose recorded maximum is this pixel; times [x > 0] if relu
+int launch_pool_bwd(int dtype, const void *dy, const uint8_t *arg, const void *x, int relu, void *dx, int B, int H,
+                    int W, int Cp, int k, int stride, hipStream_t s);
+// channel-last [B][H][W][Cp] -> [B][C*H*W] in (c,h,w) order, and back (zero padding channels; optional ReLU mask)
+int launch_flatten(int dtype, const void *x, void *flat, int B, int H, int W, int C, int Cp, hipStream_t s);
+int launch_unflatten(int dtype, const void *dflat, const void *x_for_mask, int relu, void *dx, int B, int H, int W,
+                     int C, int Cp, hipStream_t s);
+// db[n] = sum_m dy[m][n], n < N, fp32, fixed summation order
+int launch_colsum(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, hipStream_t s);
+size_t colsum_ws_floats(long M, int N);
+// softmax cross-entropy over fp32 logits [B][ld]: loss (mean) and dz (compute type, [B][ld], zero padding columns)
+int launch_softmax_ce(int dtype, const float *z, long ld, const int32_t *labels, int B, int C, void *dz, float *loss,
+                      float *row_loss, hipStream_t s);
+int launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+// debug exports (canonical layouts)
+int launch_export_nhwc(int dtype, const void *x, float *dst, int B, int H, int W, int C, int Cp, hipStream_t s);
+int launch_export_rows(int dtype, int src_f32, const void *x, long ld, float *dst, int B, int F, hipStream_t s);
+int launch_export_argmax(const uint8_t *arg, uint8_t *dst, int B, int H, int W, int C, int Cp, hipStream_t s);
+int launch_dropout_mask(uint8_t *dst, size_t count, uint64_t key, uint32_t thr, hipStream_t s);
+
+// host-side key of the dropout generator for one (seed, step, worker, layer)
+uint64_t dropout_key(uint64_t seed, uint64_t step, uint32_t worker, uint32_t layer);
+
+}  // namespace asgd

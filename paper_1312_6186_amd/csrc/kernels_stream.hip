@@ -1,0 +1,537 @@
+// Bandwidth-bound kernels of the hot path for gfx950: the fused momentum /
+// weight-decay update, the parameter snapshot, pooling, softmax cross-entropy,
+// bias-gradient column sums and the layout conversions around the channel-last
+// activation format.  Every reduction has a fixed summation order so that a run
+// is reproducible bit for bit.
+#include <hip/hip_runtime.h>
+
+#include "asgd_internal.h"
+
+namespace asgd {
+
+typedef __bf16 bf16_t;
+
+__device__ inline float ldf(const float *p) { return *p; }
+__device__ inline float ldf(const bf16_t *p) { return (float)*p; }
+__device__ inline void stf(float *p, float v) { *p = v; }
+__device__ inline void stf(bf16_t *p, float v) { *p = (bf16_t)v; }
+
+static inline unsigned blocks_for(size_t n, unsigned per_block) { return (unsigned)((n + per_block - 1) / per_block); }
+static inline int launch_ok() { return hipGetLastError() == hipSuccess ? 0 : -1; }
+
+__host__ __device__ inline uint64_t mix64(uint64_t z)
+{
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27; z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+uint64_t dropout_key(uint64_t seed, uint64_t step, uint32_t worker, uint32_t layer)
+{
+    return mix64(mix64(mix64(seed) + step) + (((uint64_t)worker << 32) | (uint64_t)layer));
+}
+
+// ---------------------------------------------------------------- update
+// t = g + wd*w; v = mu*v - lr*t; w = w + v.  20 bytes of traffic per parameter.
+// The compiler may contract a product and the following sum into one fused
+// multiply-add, which differs from the unfused form by at most one rounding.
+__global__ __launch_bounds__(256) void update_kernel(float *__restrict__ w, float *__restrict__ v, const float *__restrict__ g, size_t n4,
+                                                     size_t n, float lr, float mu, float wd, int *version_counter)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    float4 *w4 = reinterpret_cast<float4 *>(w);
+    float4 *v4 = reinterpret_cast<float4 *>(v);
+    const float4 *g4 = reinterpret_cast<const float4 *>(g);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        float4 ww = w4[i], vv = v4[i];
+        const float4 gg = g4[i];
+        vv.x = mu * vv.x - lr * (gg.x + wd * ww.x); ww.x += vv.x;
+        vv.y = mu * vv.y - lr * (gg.y + wd * ww.y); ww.y += vv.y;
+        vv.z = mu * vv.z - lr * (gg.z + wd * ww.z); ww.z += vv.z;
+        vv.w = mu * vv.w - lr * (gg.w + wd * ww.w); ww.w += vv.w;
+        w4[i] = ww; v4[i] = vv;
+    }
+    if (blockIdx.x == 0) {
+        const size_t i = n4 * 4 + threadIdx.x;
+        if (i < n) {
+            const float vv = mu * v[i] - lr * (g[i] + wd * w[i]);
+            v[i] = vv; w[i] += vv;
+        }
+        if (threadIdx.x == 0 && version_counter) *version_counter += 1;
+    }
+}
+
+__global__ __launch_bounds__(256) void update_scalar_kernel(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd,
+                                                            int *version_counter)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const float vv = mu * v[i] - lr * (g[i] + wd * w[i]);
+        v[i] = vv; w[i] += vv;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0 && version_counter) *version_counter += 1;
+}
+
+int launch_update(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd, int *version_counter, hipStream_t s)
+{
+    const bool aligned = (((uintptr_t)w | (uintptr_t)v | (uintptr_t)g) & 15) == 0;
+    if (aligned) {
+        const size_t n4 = n / 4;
+        unsigned blocks = blocks_for(n4 ? n4 : 1, 256);
+        if (blocks > 8192) blocks = 8192;
+        hipLaunchKernelGGL(update_kernel, dim3(blocks), dim3(256), 0, s, w, v, g, n4, n, lr, mu, wd, version_counter);
+    } else {
+        unsigned blocks = blocks_for(n ? n : 1, 256);
+        if (blocks > 8192) blocks = 8192;
+        hipLaunchKernelGGL(update_scalar_kernel, dim3(blocks), dim3(256), 0, s, w, v, g, n, lr, mu, wd, version_counter);
+    }
+    return launch_ok();
+}
+
+// ---------------------------------------------------------------- snapshot
+__device__ inline uint32_t f32_to_bf16_bits(uint32_t u)  // round to nearest even; NaN -> quiet NaN
+{
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (u >> 16) | 0x0040u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+__global__ __launch_bounds__(256) void snapshot_kernel(const float *__restrict__ src, void *__restrict__ dst, size_t n, int to_bf16, int vec,
+                                                       const int *version_counter, int32_t *log_slot, int log_update, int log_worker)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t t0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t0 == 0 && log_slot) {
+        log_slot[0] = log_update;
+        log_slot[1] = log_worker;
+        log_slot[2] = version_counter ? *version_counter : -1;
+    }
+    if (!to_bf16) {
+        float *d = static_cast<float *>(dst);
+        const size_t n4 = vec ? n / 4 : 0;
+        for (size_t i = t0; i < n4; i += stride) reinterpret_cast<float4 *>(d)[i] = reinterpret_cast<const float4 *>(src)[i];
+        for (size_t i = n4 * 4 + t0; i < n; i += stride) d[i] = src[i];
+    } else {
+        uint16_t *d = static_cast<uint16_t *>(dst);
+        const size_t n8 = vec ? n / 8 : 0;
+        for (size_t i = t0; i < n8; i += stride) {
+            const uint4 a = reinterpret_cast<const uint4 *>(src)[2 * i], b = reinterpret_cast<const uint4 *>(src)[2 * i + 1];
+            uint4 o;
+            o.x = f32_to_bf16_bits(a.x) | (f32_to_bf16_bits(a.y) << 16);
+            o.y = f32_to_bf16_bits(a.z) | (f32_to_bf16_bits(a.w) << 16);
+            o.z = f32_to_bf16_bits(b.x) | (f32_to_bf16_bits(b.y) << 16);
+            o.w = f32_to_bf16_bits(b.z) | (f32_to_bf16_bits(b.w) << 16);
+            reinterpret_cast<uint4 *>(d)[i] = o;
+        }
+        for (size_t i = n8 * 8 + t0; i < n; i += stride) d[i] = (uint16_t)f32_to_bf16_bits(__float_as_uint(src[i]));
+    }
+}
+
+int launch_snapshot(const float *src, void *dst, size_t n, int dst_dtype, const int *version_counter, int32_t *log_slot, int log_update,
+                    int log_worker, hipStream_t s)
+{
+    const int vec = (((uintptr_t)src | (uintptr_t)dst) & 15) == 0;
+    const size_t per = dst_dtype == kBF16 ? 8 : 4;
+    unsigned blocks = blocks_for(n / per + 1, 256);
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(snapshot_kernel, dim3(blocks), dim3(256), 0, s, src, dst, n, dst_dtype == kBF16 ? 1 : 0, vec, version_counter, log_slot,
+                       log_update, log_worker);
+    return launch_ok();
+}
+
+// ---------------------------------------------------------------- fill
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *p, size_t words)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += stride) p[i] = 0u;
+}
+int launch_fill_zero(void *p, size_t bytes, hipStream_t s)
+{
+    if (bytes == 0) return 0;
+    if ((bytes & 3) || ((uintptr_t)p & 3)) return -1;
+    unsigned blocks = blocks_for(bytes / 4, 256);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, s, static_cast<uint32_t *>(p), bytes / 4);
+    return launch_ok();
+}
+
+// ---------------------------------------------------------------- input staging and filter packing
+template <typename T> __global__ __launch_bounds__(256) void stage_input_kernel(const T *__restrict__ src, T *__restrict__ dst, int B, int C, int H,
+                                                                              int W, int Cp)
+{
+    const long pix = (long)blockIdx.x * 256 + threadIdx.x;  // (n, h, w)
+    const long HW = (long)H * W;
+    if (pix >= (long)B * HW) return;
+    const long n = pix / HW, hw = pix - n * HW;
+    T *d = dst + pix * Cp;
+    for (int c = 0; c < Cp; ++c) d[c] = c < C ? src[(n * C + c) * HW + hw] : (T)0.f;
+}
+int launch_stage_input(int dtype, const void *src, void *dst, int B, int C, int H, int W, int Cp, hipStream_t s)
+{
+    const unsigned blocks = blocks_for((size_t)B * H * W, 256);
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(stage_input_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(src), static_cast<bf16_t *>(dst), B, C, H, W, Cp);
+    else
+        hipLaunchKernelGGL(stage_input_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(src), static_cast<float *>(dst), B, C, H, W, Cp);
+    return launch_ok();
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void pack_conv_kernel(const T *__restrict__ w, T *__restrict__ wf, T *__restrict__ wd, int cout, int cin, int kh,
+                                                      int kw, int coutp, int cinp)
+{
+    const long nf = (long)coutp * kh * kw * cinp;
+    const long nd = wd ? (long)cinp * kh * kw * coutp : 0;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i < nf) {  // wf[co][ky][kx][ci]
+        const int ci = (int)(i % cinp); long t = i / cinp;
+        const int kx = (int)(t % kw); t /= kw;
+        const int ky = (int)(t % kh);
+        const int co = (int)(t / kh);
+        wf[i] = (co < cout && ci < cin) ? w[(((long)co * cin + ci) * kh + ky) * kw + kx] : (T)0.f;
+    } else if (i < nf + nd) {  // wd[ci][ky'][kx'][co] = w[co][ci][kh-1-ky'][kw-1-kx']
+        const long j = i - nf;
+        const int co = (int)(j % coutp); long t = j / coutp;
+        const int kx = (int)(t % kw); t /= kw;
+        const int ky = (int)(t % kh);
+        const int ci = (int)(t / kh);
+        wd[j] = (co < cout && ci < cin) ? w[(((long)co * cin + ci) * kh + (kh - 1 - ky)) * kw + (kw - 1 - kx)] : (T)0.f;
+    }
+}
+int launch_pack_conv(int dtype, const void *w, void *wf, void *wd, int cout, int cin, int kh, int kw, int coutp, int cinp, hipStream_t s)
+{
+    const size_t total = (size_t)coutp * kh * kw * cinp * (wd ? 2 : 1);
+    const unsigned blocks = blocks_for(total, 256);
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(pack_conv_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(w), static_cast<bf16_t *>(wf),
+                           static_cast<bf16_t *>(wd), cout, cin, kh, kw, coutp, cinp);
+    else
+        hipLaunchKernelGGL(pack_conv_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(w), static_cast<float *>(wf),
+                           static_cast<float *>(wd), cout, cin, kh, kw, coutp, cinp);
+    return launch_ok();
+}
+
+// ---------------------------------------------------------------- max pooling
+// One thread owns VEC consecutive channels (16 bytes) of one output pixel.
+template <typename T> struct Vec16 {
+    static constexpr int N = 16 / sizeof(T);
+    union { uint4 u; T e[16 / sizeof(T)]; };
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void pool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, uint8_t *__restrict__ arg, int B, int H, int W,
+                                                     int Cp, int k, int stride, int Ho, int Wo)
+{
+    constexpr int V = Vec16<T>::N;
+    const int cv = Cp / V;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long)B * Ho * Wo * cv) return;
+    const int c0 = (int)(i % cv) * V; long t = i / cv;
+    const int px = (int)(t % Wo); t /= Wo;
+    const int py = (int)(t % Ho);
+    const int n = (int)(t / Ho);
+    float best[V];
+    uint8_t a[V];
+    for (int ky = 0; ky < k; ++ky)
+        for (int kx = 0; kx < k; ++kx) {
+            Vec16<T> v;
+            v.u = *reinterpret_cast<const uint4 *>(x + (((long)n * H + py * stride + ky) * W + px * stride + kx) * Cp + c0);
+            const int pos = ky * k + kx;
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const float f = ldf(&v.e[e]);
+                if (pos == 0 || f > best[e]) { best[e] = f; a[e] = (uint8_t)pos; }
+            }
+        }
+    Vec16<T> o;
+#pragma unroll
+    for (int e = 0; e < V; ++e) stf(&o.e[e], best[e]);
+    const long off = (((long)n * Ho + py) * Wo + px) * Cp + c0;
+    *reinterpret_cast<uint4 *>(y + off) = o.u;
+    uint64_t packed = 0;
+#pragma unroll
+    for (int e = 0; e < V; ++e) packed |= (uint64_t)a[e] << (8 * e);
+    if (V == 8) *reinterpret_cast<uint64_t *>(arg + off) = packed;
+    else *reinterpret_cast<uint32_t *>(arg + off) = (uint32_t)packed;
+}
+
+int launch_pool_fwd(int dtype, const void *x, void *y, uint8_t *arg, int B, int H, int W, int Cp, int k, int stride, hipStream_t s)
+{
+    const int Ho = (H - k) / stride + 1, Wo = (W - k) / stride + 1;
+    const int V = dtype == kBF16 ? 8 : 4;
+    const unsigned blocks = blocks_for((size_t)B * Ho * Wo * (Cp / V), 256);
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(pool_fwd_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(x), static_cast<bf16_t *>(y), arg, B, H, W,
+                           Cp, k, stride, Ho, Wo);
+    else
+        hipLaunchKernelGGL(pool_fwd_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(x), static_cast<float *>(y), arg, B, H, W, Cp, k,
+                           stride, Ho, Wo);
+    return launch_ok();
+}
+
+// Gather form: an input pixel sums, in (py, px) order, the gradients of the
+// windows whose recorded maximum it is; then the ReLU mask of the layer below.
+template <typename T>
+__global__ __launch_bounds__(256) void pool_bwd_kernel(const T *__restrict__ dy, const uint8_t *__restrict__ arg, const T *__restrict__ x, int relu,
+                                                     T *__restrict__ dx, int B, int H, int W, int Cp, int k, int stride, int Ho, int Wo)
+{
+    constexpr int V = Vec16<T>::N;
+    const int cv = Cp / V;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long)B * H * W * cv) return;
+    const int c0 = (int)(i % cv) * V; long t = i / cv;
+    const int ix = (int)(t % W); t /= W;
+    const int iy = (int)(t % H);
+    const int n = (int)(t / H);
+    float acc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] = 0.f;
+    int py0 = iy - k + 1; py0 = py0 <= 0 ? 0 : (py0 + stride - 1) / stride;
+    int px0 = ix - k + 1; px0 = px0 <= 0 ? 0 : (px0 + stride - 1) / stride;
+    const int py1 = min(iy / stride, Ho - 1), px1 = min(ix / stride, Wo - 1);
+    for (int py = py0; py <= py1; ++py)
+        for (int px = px0; px <= px1; ++px) {
+            const int pos = (iy - py * stride) * k + (ix - px * stride);
+            const long off = (((long)n * Ho + py) * Wo + px) * Cp + c0;
+            Vec16<T> g;
+            g.u = *reinterpret_cast<const uint4 *>(dy + off);
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+                if (arg[off + e] == pos) acc[e] += ldf(&g.e[e]);
+        }
+    const long off = (((long)n * H + iy) * W + ix) * Cp + c0;
+    Vec16<T> o;
+    if (relu) {
+        Vec16<T> xv;
+        xv.u = *reinterpret_cast<const uint4 *>(x + off);
+#pragma unroll
+        for (int e = 0; e < V; ++e) stf(&o.e[e], ldf(&xv.e[e]) > 0.f ? acc[e] : 0.f);
+    } else {
+#pragma unroll
+        for (int e = 0; e < V; ++e) stf(&o.e[e], acc[e]);
+    }
+    *reinterpret_cast<uint4 *>(dx + off) = o.u;
+}
+
+int launch_pool_bwd(int dtype, const void *dy, const uint8_t *arg, const void *x, int relu, void *dx, int B, int H, int W, int Cp, int k, int stride,
+                    hipStream_t s)
+{
+    const int Ho = (H - k) / stride + 1, Wo = (W - k) / stride + 1;
+    const int V = dtype == kBF16 ? 8 : 4;
+    const unsigned blocks = blocks_for((size_t)B * H * W * (Cp / V), 256);
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(pool_bwd_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(dy), arg, static_cast<const bf16_t *>(x), relu,
+                           static_cast<bf16_t *>(dx), B, H, W, Cp, k, stride, Ho, Wo);
+    else
+        hipLaunchKernelGGL(pool_bwd_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(dy), arg, static_cast<const float *>(x), relu,
+                           static_cast<float *>(dx), B, H, W, Cp, k, stride, Ho, Wo);
+    return launch_ok();
+}
+
+// ---------------------------------------------------------------- flatten / unflatten
+template <typename T>
+__global__ __launch_bounds__(256) void flatten_kernel(const T *__restrict__ x, T *__restrict__ flat, int B, int H, int W, int C, int Cp)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;  // (b, c, h, w)
+    if (i >= (long)B * C * H * W) return;
+    const int w = (int)(i % W); long t = i / W;
+    const int h = (int)(t % H); t /= H;
+    const int c = (int)(t % C);
+    const int b = (int)(t / C);
+    flat[i] = x[(((long)b * H + h) * W + w) * Cp + c];
+}
+int launch_flatten(int dtype, const void *x, void *flat, int B, int H, int W, int C, int Cp, hipStream_t s)
+{
+    const unsigned blocks = blocks_for((size_t)B * C * H * W, 256);
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(flatten_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(x), static_cast<bf16_t *>(flat), B, H, W, C, Cp);
+    else
+        hipLaunchKernelGGL(flatten_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(x), static_cast<float *>(flat), B, H, W, C, Cp);
+    return launch_ok();
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void unflatten_kernel(const T *__restrict__ dflat, const T *__restrict__ x, int relu, T *__restrict__ dx, int B, int H,
+                                                      int W, int C, int Cp)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;  // (b, h, w, cp)
+    if (i >= (long)B * H * W * Cp) return;
+    const int c = (int)(i % Cp); long t = i / Cp;
+    const int w = (int)(t % W); t /= W;
+    const int h = (int)(t % H);
+    const int b = (int)(t / H);
+    float v = 0.f;
+    if (c < C) {
+        v = ldf(&dflat[(((long)b * C + c) * H + h) * W + w]);
+        if (relu && !(ldf(&x[i]) > 0.f)) v = 0.f;
+    }
+    stf(&dx[i], v);
+}
+int launch_unflatten(int dtype, const void *dflat, const void *x, int relu, void *dx, int B, int H, int W, int C, int Cp, hipStream_t s)
+{
+    const unsigned blocks = blocks_for((size_t)B * H * W * Cp, 256);
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(unflatten_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(dflat), static_cast<const bf16_t *>(x), relu,
+                           static_cast<bf16_t *>(dx), B, H, W, C, Cp);
+    else
+        hipLaunchKernelGGL(unflatten_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(dflat), static_cast<const float *>(x), relu,
+                           static_cast<float *>(dx), B, H, W, C, Cp);
+    return launch_ok();
+}
+
+// ---------------------------------------------------------------- bias gradient (column sums)
+constexpr int CS_ROWS = 2048;  // rows per first-stage block
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_stage1(const T *__restrict__ dy, long ld, long M, int N, float *__restrict__ ws)
+{
+    __shared__ float part[4][64];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int n = blockIdx.x * 64 + tx;
+    const long m0 = (long)blockIdx.y * CS_ROWS, m1 = min(M, m0 + CS_ROWS);
+    float acc = 0.f;
+    if (n < N)
+        for (long m = m0 + ty; m < m1; m += 4) acc += ldf(&dy[m * ld + n]);
+    part[ty][tx] = acc;
+    __syncthreads();
+    if (ty == 0 && n < N) ws[(long)blockIdx.y * N + n] = ((part[0][tx] + part[1][tx]) + part[2][tx]) + part[3][tx];
+}
+__global__ __launch_bounds__(256) void colsum_stage2(const float *__restrict__ ws, int nblk, int N, float *__restrict__ db)
+{
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    float acc = 0.f;
+    for (int b = 0; b < nblk; ++b) acc += ws[(long)b * N + n];
+    db[n] = acc;
+}
+size_t colsum_ws_floats(long M, int N) { return (size_t)((M + CS_ROWS - 1) / CS_ROWS) * (size_t)N; }
+int launch_colsum(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, hipStream_t s)
+{
+    const int nblk = (int)((M + CS_ROWS - 1) / CS_ROWS);
+    const dim3 grid((N + 63) / 64, nblk);
+    if (dtype == kBF16) hipLaunchKernelGGL(colsum_stage1<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(dy), ld, M, N, ws);
+    else hipLaunchKernelGGL(colsum_stage1<float>, grid, dim3(256), 0, s, static_cast<const float *>(dy), ld, M, N, ws);
+    hipLaunchKernelGGL(colsum_stage2, dim3((N + 255) / 256), dim3(256), 0, s, ws, nblk, N, db);
+    return launch_ok();
+}
+
+// ---------------------------------------------------------------- softmax cross-entropy
+// One wavefront per row: lse = max + log(sum exp(z - max)); the row's loss is
+// lse - z[label]; dz = (exp(z - lse) - [c == label]) / B.
+__device__ inline float wave_max(float v)
+{
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ inline float wave_sum(float v)
+{
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_ce_kernel(const float *__restrict__ z, long ld, const int32_t *__restrict__ labels, int B, int C,
+                                                       T *__restrict__ dz, float *__restrict__ row_loss)
+{
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= B) return;
+    const float *zr = z + (long)row * ld;
+    float m = -INFINITY;
+    for (int c = lane; c < C; c += 64) m = fmaxf(m, zr[c]);
+    m = wave_max(m);
+    float sum = 0.f;
+    for (int c = lane; c < C; c += 64) sum += expf(zr[c] - m);
+    sum = wave_sum(sum);
+    const float lse = m + logf(sum);
+    const int label = labels[row];
+    if (lane == 0) row_loss[row] = lse - zr[label];
+    const float inv_b = 1.f / (float)B;
+    T *dr = dz + (long)row * ld;
+    for (int c = lane; c < (int)ld; c += 64) {
+        float g = 0.f;
+        if (c < C) g = (expf(zr[c] - lse) - (c == label ? 1.f : 0.f)) * inv_b;
+        stf(&dr[c], g);
+    }
+}
+__global__ __launch_bounds__(256) void loss_reduce_kernel(const float *__restrict__ row_loss, int B, float *__restrict__ loss)
+{
+    __shared__ float part[256];
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < B; i += 256) acc += row_loss[i];
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) loss[0] = part[0] / (float)B;
+}
+int launch_softmax_ce(int dtype, const float *z, long ld, const int32_t *labels, int B, int C, void *dz, float *loss, float *row_loss, hipStream_t s)
+{
+    const unsigned blocks = (unsigned)((B + 3) / 4);
+    if (dtype == kBF16) hipLaunchKernelGGL(softmax_ce_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, z, ld, labels, B, C, static_cast<bf16_t *>(dz), row_loss);
+    else hipLaunchKernelGGL(softmax_ce_kernel<float>, dim3(blocks), dim3(256), 0, s, z, ld, labels, B, C, static_cast<float *>(dz), row_loss);
+    hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(256), 0, s, row_loss, B, loss);
+    return launch_ok();
+}
+
+// ---------------------------------------------------------------- debug exports
+template <typename T>
+__global__ __launch_bounds__(256) void export_nhwc_kernel(const T *__restrict__ x, float *__restrict__ dst, int B, int H, int W, int C, int Cp)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;  // (b, c, h, w)
+    if (i >= (long)B * C * H * W) return;
+    const int w = (int)(i % W); long t = i / W;
+    const int h = (int)(t % H); t /= H;
+    const int c = (int)(t % C);
+    const int b = (int)(t / C);
+    dst[i] = ldf(&x[(((long)b * H + h) * W + w) * Cp + c]);
+}
+int launch_export_nhwc(int dtype, const void *x, float *dst, int B, int H, int W, int C, int Cp, hipStream_t s)
+{
+    const unsigned blocks = blocks_for((size_t)B * C * H * W, 256);
+    if (dtype == kBF16) hipLaunchKernelGGL(export_nhwc_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(x), dst, B, H, W, C, Cp);
+    else hipLaunchKernelGGL(export_nhwc_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(x), dst, B, H, W, C, Cp);
+    return launch_ok();
+}
+template <typename T> __global__ __launch_bounds__(256) void export_rows_kernel(const T *__restrict__ x, long ld, float *__restrict__ dst, int B, int F)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long)B * F) return;
+    const long b = i / F, f = i - b * F;
+    dst[i] = ldf(&x[b * ld + f]);
+}
+int launch_export_rows(int dtype, int src_f32, const void *x, long ld, float *dst, int B, int F, hipStream_t s)
+{
+    const unsigned blocks = blocks_for((size_t)B * F, 256);
+    if (dtype == kBF16 && !src_f32) hipLaunchKernelGGL(export_rows_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(x), ld, dst, B, F);
+    else hipLaunchKernelGGL(export_rows_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(x), ld, dst, B, F);
+    return launch_ok();
+}
+__global__ __launch_bounds__(256) void export_argmax_kernel(const uint8_t *__restrict__ arg, uint8_t *__restrict__ dst, int B, int H, int W, int C, int Cp)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;  // (b, c, h, w)
+    if (i >= (long)B * C * H * W) return;
+    const int w = (int)(i % W); long t = i / W;
+    const int h = (int)(t % H); t /= H;
+    const int c = (int)(t % C);
+    const int b = (int)(t / C);
+    dst[i] = arg[(((long)b * H + h) * W + w) * Cp + c];
+}
+int launch_export_argmax(const uint8_t *arg, uint8_t *dst, int B, int H, int W, int C, int Cp, hipStream_t s)
+{
+    hipLaunchKernelGGL(export_argmax_kernel, dim3(blocks_for((size_t)B * C * H * W, 256)), dim3(256), 0, s, arg, dst, B, H, W, C, Cp);
+    return launch_ok();
+}
+__global__ __launch_bounds__(256) void dropout_mask_kernel(uint8_t *dst, size_t count, uint64_t key, uint32_t thr)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    const uint32_t u = (uint32_t)(mix64(key + 0x9E3779B97F4A7C15ull * (uint64_t)(i + 1)) >> 32);
+    dst[i] = u >= thr ? 1 : 0;
+}
+int launch_dropout_mask(uint8_t *dst, size_t count, uint64_t key, uint32_t thr, hipStream_t s)
+{
+    hipLaunchKernelGGL(dropout_mask_kernel, dim3(blocks_for(count, 256)), dim3(256), 0, s, dst, count, key, thr);
+    return launch_ok();
+}
+
+}  // namespace asgd

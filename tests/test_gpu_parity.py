@@ -1,0 +1,211 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle.  GPU only."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import ops as oops, asgd as oasgd
+from paper_1312_6186_amd import binding as B
+from paper_1312_6186_amd import workloads as wl
+from gpu_harness import GpuNet, TOL, rel_l2, oracle_inputs, compare_grads
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+RAGGED = dict(name="ragged", in_shape=(3, 37, 29), classes=10,
+              layers=[("conv", 12, 5, 2, 1), ("relu",), ("conv", 20, 3, 2, 1), ("relu",), ("conv", 12, 3, 1, 0), ("relu",),
+                      ("maxpool", 3, 2), ("fc", 24), ("relu",), ("dropout", 0.3, 1.5), ("fc", 16), ("relu",), ("fc", 10),
+                      ("softmax_ce",)])
+
+
+# ---------------------------------------------------------------- update / snapshot
+@pytest.mark.parametrize("n,offset", [(1, 0), (1023, 0), (4099, 0), (15898, 0), (100003, 1), (1 << 20, 4)])
+def test_apply_update_matches_oracle(n, offset):
+    rng = np.random.default_rng(n)
+    w0, v0, g = (rng.standard_normal(n + offset).astype(np.float32) for _ in range(3))
+    w, v, gd = (torch.from_numpy(a).to(DEV) for a in (w0, v0, g))
+    lr, mu, wd = 0.01, 0.9, 5e-4
+    for _ in range(3):
+        B.asgd_apply_update(w[offset:], v[offset:], gd[offset:], lr, mu, wd)
+    torch.cuda.synchronize()
+    wr, vr = w0[offset:].astype(np.float64), v0[offset:].astype(np.float64)
+    for _ in range(3):
+        oops.apply_update(wr, vr, g[offset:], np.float32(lr), np.float32(mu), np.float32(wd))
+    assert rel_l2(w.cpu().numpy()[offset:], wr) < 1e-6 and rel_l2(v.cpu().numpy()[offset:], vr) < 1e-6
+    np.testing.assert_array_equal(w.cpu().numpy()[:offset], w0[:offset])      # nothing before the view is touched
+    np.testing.assert_array_equal(gd.cpu().numpy(), g)
+
+
+@pytest.mark.parametrize("n,offset", [(1, 0), (7, 0), (4099, 0), (100003, 3), (1 << 20, 0)])
+def test_snapshot_is_bit_exact(n, offset):
+    rng = np.random.default_rng(n)
+    a = (rng.standard_normal(n + offset) * 10.0 ** rng.integers(-20, 20, n + offset)).astype(np.float32)
+    a[:: 97] = np.float32(1.0) + np.float32(2.0 ** -8)         # exact ties
+    if n > 16:
+        a[offset + 1], a[offset + 2], a[offset + 3], a[offset + 4] = np.inf, -0.0, 1e-45, -1e-40
+    src = torch.from_numpy(a).to(DEV)
+    dst = torch.zeros(n + offset + 8, dtype=torch.bfloat16, device=DEV)
+    B.asgd_snapshot(src[offset:], dst[offset:offset + n], B.BF16)
+    torch.cuda.synchronize()
+    got = dst.view(torch.int16).cpu().numpy().view(np.uint16)
+    np.testing.assert_array_equal(got[offset:offset + n], oops.snapshot_bf16(a[offset:]))
+    assert (got[offset + n:] == 0).all() and (got[:offset] == 0).all()
+    dst32 = torch.zeros(n + offset, dtype=torch.float32, device=DEV)
+    B.asgd_snapshot(src[offset:], dst32[offset:], B.F32)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(dst32.cpu().numpy()[offset:].view(np.uint32), a[offset:].view(np.uint32))
+
+
+# ---------------------------------------------------------------- whole-network gradient
+def _net_case(cfg, batch, dtype, seed=0, step=0, worker=0, bias_noise=0.05):
+    layers, in_shape = cfg["layers"], cfg["in_shape"]
+    params = wl.make_params(layers, in_shape, cfg.get("seeds", {}).get("init", 2000))
+    if bias_noise:
+        params = (params + bias_noise * np.random.default_rng(5).standard_normal(params.size).astype(np.float32)
+                  * (params == 0)).astype(np.float32)             # non-zero biases
+    images, labels = wl.make_batch(in_shape, batch, cfg["classes"], cfg.get("seeds", {}).get("data", 1000))
+    g = GpuNet(layers, in_shape, batch, dtype)
+    onet = oracle.OracleNet(layers, in_shape)
+    p64, i64 = oracle_inputs(params, images, dtype)
+    ref_loss, ref_grads, trace = onet.fwd_bwd(p64, i64, labels, seed, step, worker)
+    loss, grads = g.fwd_bwd(params, images, labels, seed, step, worker)
+    return g, onet, (loss, grads), (ref_loss, ref_grads, trace), (params, images, labels)
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("cfg,batch", [(wl.TINY, 8), (RAGGED, 5), (RAGGED, 131), (wl.SMALL, 128)],
+                         ids=["tiny", "ragged5", "ragged131", "small"])
+def test_minibatch_gradient_matches_oracle(cfg, batch, dtype):
+    g, onet, (loss, grads), (ref_loss, ref_grads, trace), _ = _net_case(cfg, batch, dtype, seed=3002, step=4, worker=1)
+    try:
+        tol = TOL[dtype]
+        assert abs(loss - ref_loss) <= tol * abs(ref_loss), (loss, ref_loss)
+        compare_grads(onet, grads, ref_grads, tol, cfg["name"])
+        # layer outputs, masks and pooling positions
+        for li, l in enumerate(cfg["layers"]):
+            nxt = cfg["layers"][li + 1][0] if li + 1 < len(cfg["layers"]) else None
+            group_end = (l[0] == "maxpool" or (l[0] == "relu" and nxt != "dropout") or l[0] == "dropout"
+                         or (l[0] in ("conv", "fc") and nxt != "relu"))
+            if group_end and l[0] != "softmax_ce":
+                out = g.debug(B.DEBUG_OUTPUT, li)
+                assert rel_l2(out, trace[li]["out"]) < tol, ("output of layer", li)
+            if l[0] == "dropout":
+                np.testing.assert_array_equal(g.debug(B.DEBUG_MASK, li).reshape(trace[li]["mask"].shape), trace[li]["mask"])
+            if l[0] == "maxpool":
+                # bit-exact on identical input bytes: the oracle pools the HIP path's own input
+                x = g.debug(B.DEBUG_OUTPUT, li - 1).astype(np.float64)
+                p_ref, idx_ref = oops.maxpool_fwd(x, l[1], l[2])
+                np.testing.assert_array_equal(g.debug(B.DEBUG_ARGMAX, li), idx_ref)
+                np.testing.assert_array_equal(g.debug(B.DEBUG_OUTPUT, li).astype(np.float64), p_ref)
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+def test_fwd_bwd_is_reproducible_bit_for_bit(dtype):
+    cfg = wl.SMALL
+    params = wl.make_params(cfg["layers"], cfg["in_shape"], 1)
+    images, labels = wl.make_batch(cfg["in_shape"], 64, 10, 2)
+    g = GpuNet(cfg["layers"], cfg["in_shape"], 64, dtype)
+    try:
+        l1, g1 = g.fwd_bwd(params, images, labels, 7, 1, 0)
+        g.grads.fill_(float("nan"))
+        l2, g2 = g.fwd_bwd(params, images, labels, 7, 1, 0)
+        assert l1 == l2 and g1.tobytes() == g2.tobytes()          # also: grads are overwritten, not accumulated
+        l3, g3 = g.fwd_bwd(params, images, labels, 7, 2, 0)       # another step -> another dropout mask
+        assert g3.tobytes() != g1.tobytes()
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+def test_alexnet_layers_small_batch(dtype):
+    """Every layer shape of the AlexNet-style net, at a batch the oracle finishes in seconds."""
+    g, onet, (loss, grads), (ref_loss, ref_grads, trace), _ = _net_case(wl.ALEXNET, 4, dtype, seed=3003, step=0, worker=0,
+                                                                       bias_noise=0.0)
+    try:
+        tol = TOL[dtype]
+        assert abs(loss - ref_loss) <= tol * abs(ref_loss), (loss, ref_loss)
+        errs = compare_grads(onet, grads, ref_grads, tol, "alexnet")
+        print(errs)
+    finally:
+        g.close()
+
+
+# ---------------------------------------------------------------- training steps (Small config, 20 steps)
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+def test_small_cnn_twenty_sgd_steps(dtype):
+    cfg = wl.SMALL
+    layers, in_shape, batch, T = cfg["layers"], cfg["in_shape"], cfg["batch"], 20
+    lr, mu, wd = cfg["lr"], cfg["mu"], cfg["wd"]
+    params0 = wl.make_params(layers, in_shape, cfg["seeds"]["init"])
+    onet = oracle.OracleNet(layers, in_shape)
+
+    def batch_fn(a):
+        images, labels = wl.make_batch(in_shape, batch, cfg["classes"], cfg["seeds"]["data"] + a)
+        return (wl.round_to_bf16(images) if dtype == B.BF16 else images), labels
+
+    wdt = "bf16" if dtype == B.BF16 else "f32"
+    w_ref, v_ref, losses_ref = oasgd.sgd_loop(onet, params0, batch_fn, T, np.float32(lr), np.float32(mu), np.float32(wd),
+                                               dropout_seed=cfg["seeds"]["dropout"], worker_dtype=wdt)
+    g = GpuNet(layers, in_shape, batch, dtype)
+    try:
+        w = torch.from_numpy(params0).to(DEV)
+        v = torch.zeros_like(w)
+        losses = []
+        for a in range(T):                                        # free-running: the HIP path's own trajectory
+            images, labels = batch_fn(a)
+            loss, _ = g.fwd_bwd(w, images, labels, cfg["seeds"]["dropout"], a, 0)
+            B.asgd_apply_update(w, v, g.grads, lr, mu, wd)
+            losses.append(loss)
+        torch.cuda.synchronize()
+        tol = TOL[dtype]
+        assert rel_l2(losses, losses_ref) < tol
+        assert rel_l2(w.cpu().numpy(), w_ref) < tol
+        assert rel_l2(v.cpu().numpy(), v_ref) < (tol if dtype == B.F32 else 5 * tol)  # momentum sums 20 rounded gradients
+    finally:
+        g.close()
+
+
+# ---------------------------------------------------------------- A-SGD replay
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+def test_asgd_replay_matches_oracle_and_logs_the_schedule(dtype):
+    cfg = wl.TINY
+    layers, in_shape, batch = cfg["layers"], cfg["in_shape"], 8
+    W, T, lr, mu, wd = 4, 24, 0.01, 0.9, 5e-4
+    worker, rv = B.asgd_schedule_generate(T, 4005, W, 3)
+    w_o, rv_o = oops.schedule(T, 4005, W, 3)
+    np.testing.assert_array_equal(worker, w_o); np.testing.assert_array_equal(rv, rv_o)
+    params0 = wl.make_params(layers, in_shape, 2001)
+    batches = [wl.make_batch(in_shape, batch, 10, 1005 + a) for a in range(T)]
+    if dtype == B.BF16:
+        batches = [(wl.round_to_bf16(i), l) for i, l in batches]
+    onet = oracle.OracleNet(layers, in_shape)
+    w_ref, v_ref, losses_ref, log_ref = oasgd.replay(onet, params0, worker, rv, lambda a: batches[a], np.float32(lr),
+                                                     np.float32(mu), np.float32(wd), dropout_seed=9,
+                                                     worker_dtype="bf16" if dtype == B.BF16 else "f32")
+    tdt = torch.bfloat16 if dtype == B.BF16 else torch.float32
+    nets = [B.asgd_net_create(layers, batch, in_shape, dtype) for _ in range(W)]
+    P = B.asgd_param_count(nets[0])
+    try:
+        results = []
+        for rep in range(2):
+            params = torch.from_numpy(params0).to(DEV); mom = torch.zeros_like(params)
+            copies = [torch.empty(P, dtype=tdt, device=DEV) for _ in range(W)]
+            grads = [torch.empty(P, dtype=torch.float32, device=DEV) for _ in range(W)]
+            images = torch.from_numpy(np.stack([b[0] for b in batches])).to(DEV).to(tdt).contiguous()
+            labels = torch.from_numpy(np.stack([b[1] for b in batches]).astype(np.int32)).to(DEV)
+            losses = torch.zeros(T, dtype=torch.float32, device=DEV)
+            log = torch.full((T, 3), -7, dtype=torch.int32, device=DEV)
+            B.asgd_replay_run(nets, params, mom, copies, grads, images, labels, worker, rv, lr, mu, wd, 9, losses, log)
+            torch.cuda.synchronize()
+            results.append((params.cpu().numpy(), mom.cpu().numpy(), losses.cpu().numpy(), log.cpu().numpy()))
+        p, m, ls, lg = results[0]
+        np.testing.assert_array_equal(lg, log_ref)               # (update, worker, version read) as prescribed
+        tol = TOL[dtype]
+        assert rel_l2(ls, losses_ref) < tol and rel_l2(p, w_ref) < tol and rel_l2(m, v_ref) < tol
+        for a, b in zip(results[0], results[1]):                  # replay is reproducible bit for bit
+            assert a.tobytes() == b.tobytes()
+    finally:
+        for n in nets:
+            B.asgd_net_destroy(n)

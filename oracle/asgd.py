@@ -22,21 +22,21 @@ def worker_copy(params, worker_dtype):
     raise ValueError(worker_dtype)
 
 
-def sgd_loop(net, params0, batch_fn, T, lr, mu, wd, dropout_seed=0, worker_dtype="f64"):
+def sgd_loop(net, params0, batch_fn, T, lr, mu, wd, dropout_seed=0, worker_dtype="f64", act_dtype="f64"):
     """Plain single-worker momentum SGD: T steps, step a uses batch_fn(a)."""
     w = np.array(params0, dtype=np.float64)
     v = np.zeros_like(w)
     losses = []
     for a in range(T):
         images, labels = batch_fn(a)
-        loss, g, _ = net.fwd_bwd(worker_copy(w, worker_dtype), images, labels, dropout_seed, a, 0)
+        loss, g, _ = net.fwd_bwd(worker_copy(w, worker_dtype), images, labels, dropout_seed, a, 0, act_dtype=act_dtype)
         ops.apply_update(w, v, g, lr, mu, wd)
         losses.append(loss)
     return w, v, losses
 
 
 def replay(net, params0, worker, read_version, batch_fn, lr, mu, wd, dropout_seed=0,
-           worker_dtype="f64"):
+           worker_dtype="f64", act_dtype="f64"):
     """A-SGD with the given schedule.  Returns final params, momentum, the loss of
     every pushed gradient and the log of (update, worker, version read)."""
     T = len(worker)
@@ -49,7 +49,7 @@ def replay(net, params0, worker, read_version, batch_fn, lr, mu, wd, dropout_see
         assert 0 <= r <= a
         images, labels = batch_fn(a)
         loss, g, _ = net.fwd_bwd(worker_copy(versions[r], worker_dtype), images, labels, dropout_seed, a,
-                                 int(worker[a]))
+                                 int(worker[a]), act_dtype=act_dtype)
         ops.apply_update(w, v, g, lr, mu, wd)
         versions[a + 1] = w.copy()
         oldest_needed = min([int(read_version[b]) for b in range(a + 1, T)] + [a + 1])

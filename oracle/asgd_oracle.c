@@ -356,6 +356,23 @@ void oracle_snapshot_bf16(const float *params, uint16_t *copy, size_t count)
     }
 }
 
+/* Rounding of a stored activation to bf16 (round to nearest even of the fp32
+ * value), for networks whose activations are kept in bf16 between layers: the
+ * integer decisions that follow (pooling position, ReLU mask) are then taken on
+ * the same values as in the implementation under test. */
+void oracle_round_bf16(double *a, size_t count)
+{
+    for (size_t i = 0; i < count; ++i) {
+        const float f = (float)a[i];
+        uint16_t b;
+        oracle_snapshot_bf16(&f, &b, 1);
+        const uint32_t u = (uint32_t)b << 16;
+        float r;
+        memcpy(&r, &u, 4);
+        a[i] = (double)r;
+    }
+}
+
 /* ---------------------------------------------------------------------------
  * Staleness schedule for the A-SGD replay (Section 3.3 attributes artefacts
  * of the learning curves to stale updates).  Update a (0-based) is pushed by

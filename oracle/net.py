@@ -59,11 +59,15 @@ class OracleNet:
         return flat[w_off:w_off + n].reshape(w_shape), flat[b_off:b_off + b_len]
 
     def fwd_bwd(self, params, images, labels, dropout_seed=0, step=0, worker=0, want_grads=True,
-                masks=None):
+                masks=None, act_dtype="f64"):
         """Returns (loss, grads, trace).  ``trace[li]`` holds what layer li produced
         ("out", and "argmax" / "mask" where they exist); ``trace["dx"][li]`` the
         gradient w.r.t. that layer's input.  ``masks`` overrides the generated
-        dropout masks (dict layer index -> uint8 array), for tests."""
+        dropout masks (dict layer index -> uint8 array), for tests.
+        ``act_dtype="bf16"`` models a network that stores its activations in bf16:
+        every stored activation (the output of a conv or fc layer after its ReLU /
+        dropout, except the final logits) is rounded to bf16, so that pooling
+        positions and ReLU masks are decided on the stored values."""
         params = np.ascontiguousarray(params, dtype=np.float64)
         assert params.shape == (self.param_count,)
         x = np.ascontiguousarray(images, dtype=np.float64)
@@ -97,6 +101,12 @@ class OracleNet:
             elif kind == "softmax_ce":
                 loss, dz = ops.softmax_ce(x.reshape(N, -1), labels, want_grad=want_grads)
                 t["dz"] = dz
+            if act_dtype == "bf16" and kind != "softmax_ce":
+                nxt = self.layers[li + 1][0]
+                stored = ((kind in ("conv", "fc") and nxt not in ("relu", "softmax_ce"))
+                          or (kind == "relu" and nxt != "dropout") or kind == "dropout")
+                if stored:
+                    x = ops.round_bf16(x)
             t["out"] = x
             trace[li] = t
         if not want_grads:
@@ -115,7 +125,9 @@ class OracleNet:
                 scale = l[2] if len(l) > 2 else 1.0
                 d = ops.dropout_apply(d, trace[li]["mask"].reshape(-1), scale).reshape(xin.shape)
             elif kind == "relu":
-                d = ops.relu_bwd(xin, d.reshape(xin.shape))
+                # the mask is taken on the stored ReLU output, which is positive exactly where the input was
+                # (a positive input may only round to zero in bf16 when it is below the smallest bf16 subnormal)
+                d = ops.relu_bwd(trace[li]["out"] if act_dtype == "bf16" else xin, d.reshape(xin.shape))
             elif kind == "maxpool":
                 d = ops.maxpool_bwd(d.reshape(trace[li]["out"].shape), trace[li]["argmax"], xin.shape[2:],
                                     l[1], l[2])

@@ -203,6 +203,13 @@ def bf16_to_f64(bits):
     return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
+def round_bf16(a):
+    """Round a float64 array to bf16-representable values (via fp32, ties to even), in a copy."""
+    out = np.array(a, dtype=np.float64, order="C")
+    _load().oracle_round_bf16(_d(out), ctypes.c_size_t(out.size))
+    return out
+
+
 def schedule(T, seed, n_workers=4, max_stale=3):
     worker = np.empty((T,), dtype=np.int32)
     read_version = np.empty((T,), dtype=np.int32)

@@ -11,6 +11,9 @@ from gpu_harness import GpuNet, TOL, rel_l2, oracle_inputs, compare_grads
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+# bf16 networks store their activations in bf16: the oracle rounds at the same points so that pooling
+# positions and ReLU masks are decided in the same precision on both sides
+ACT = {B.F32: "f64", B.BF16: "bf16"}
 
 RAGGED = dict(name="ragged", in_shape=(3, 37, 29), classes=10,
               layers=[("conv", 12, 5, 2, 1), ("relu",), ("conv", 20, 3, 2, 1), ("relu",), ("conv", 12, 3, 1, 0), ("relu",),
@@ -67,7 +70,7 @@ def _net_case(cfg, batch, dtype, seed=0, step=0, worker=0, bias_noise=0.05):
     g = GpuNet(layers, in_shape, batch, dtype)
     onet = oracle.OracleNet(layers, in_shape)
     p64, i64 = oracle_inputs(params, images, dtype)
-    ref_loss, ref_grads, trace = onet.fwd_bwd(p64, i64, labels, seed, step, worker)
+    ref_loss, ref_grads, trace = onet.fwd_bwd(p64, i64, labels, seed, step, worker, act_dtype=ACT[dtype])
     loss, grads = g.fwd_bwd(params, images, labels, seed, step, worker)
     return g, onet, (loss, grads), (ref_loss, ref_grads, trace), (params, images, labels)
 
@@ -147,7 +150,7 @@ def test_small_cnn_twenty_sgd_steps(dtype):
 
     wdt = "bf16" if dtype == B.BF16 else "f32"
     w_ref, v_ref, losses_ref = oasgd.sgd_loop(onet, params0, batch_fn, T, np.float32(lr), np.float32(mu), np.float32(wd),
-                                               dropout_seed=cfg["seeds"]["dropout"], worker_dtype=wdt)
+                                               dropout_seed=cfg["seeds"]["dropout"], worker_dtype=wdt, act_dtype=ACT[dtype])
     g = GpuNet(layers, in_shape, batch, dtype)
     try:
         w = torch.from_numpy(params0).to(DEV)
@@ -183,7 +186,7 @@ def test_asgd_replay_matches_oracle_and_logs_the_schedule(dtype):
     onet = oracle.OracleNet(layers, in_shape)
     w_ref, v_ref, losses_ref, log_ref = oasgd.replay(onet, params0, worker, rv, lambda a: batches[a], np.float32(lr),
                                                      np.float32(mu), np.float32(wd), dropout_seed=9,
-                                                     worker_dtype="bf16" if dtype == B.BF16 else "f32")
+                                                     worker_dtype="bf16" if dtype == B.BF16 else "f32", act_dtype=ACT[dtype])
     tdt = torch.bfloat16 if dtype == B.BF16 else torch.float32
     nets = [B.asgd_net_create(layers, batch, in_shape, dtype) for _ in range(W)]
     P = B.asgd_param_count(nets[0])

@@ -152,3 +152,19 @@ def test_worker_copy_rounding():
     p = np.array([1.0 + 2.0**-8, 1.0 + 2.0**-30, -3.5])
     np.testing.assert_array_equal(asgd.worker_copy(p, "bf16"), [1.0, 1.0, -3.5])
     np.testing.assert_array_equal(asgd.worker_copy(p, "f32"), [1.0 + 2.0**-8, 1.0, -3.5])
+
+
+def test_bf16_activation_storage_mode():
+    # rounding helper: ties to even, exact on representable values (pinned against torch's cast)
+    a = np.concatenate([np.random.default_rng(3).standard_normal(2000) * 7, [1.0 + 2.0**-8, 1.0 + 3 * 2.0**-8, 0.0, -2.5]])
+    ref = torch.tensor(a, dtype=torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(ops.round_bf16(a), ref)
+    net, params, images, labels = _setup(NET_A, 4, 3)
+    l0, g0, t0 = net.fwd_bwd(params, images, labels, 5, 6, 7)
+    l1, g1, t1 = net.fwd_bwd(params, images, labels, 5, 6, 7, act_dtype="bf16")
+    # stored activations are bf16-representable and within half a bf16 ulp of the unrounded forward pass up to there
+    for li in (1, 3, 4, 7):
+        np.testing.assert_array_equal(t1[li]["out"], ops.round_bf16(t1[li]["out"]))
+    assert np.abs(t1[1]["out"] - t0[1]["out"]).max() <= 2.0**-9 * np.abs(t0[1]["out"]).max()
+    assert 0 < np.linalg.norm(g1 - g0) / np.linalg.norm(g0) < 0.05
+    assert abs(l1 - l0) < 0.01 * abs(l0)

@@ -7,7 +7,7 @@ leg do.  It shares no code with the HIP library.
 """
 from .ops import (  # noqa: F401
     build, num_threads, conv_fwd, conv_bwd_data, conv_bwd_weight, relu_fwd, relu_bwd,
-    maxpool_fwd, maxpool_bwd, fc_fwd, fc_bwd, dropout_threshold, dropout_mask,
+    maxpool_fwd, maxpool_bwd, maxpool_gather, fc_fwd, fc_bwd, dropout_threshold, dropout_mask,
     dropout_apply, softmax_ce, apply_update, snapshot_bf16, bf16_to_f64, schedule, round_bf16,
 )
 from .net import OracleNet  # noqa: F401

@@ -193,6 +193,22 @@ void oracle_maxpool_fwd(const double *r, double *p, uint8_t *idx,
     }
 }
 
+/* Pooling with the positions given instead of searched: p = r at position idx of
+ * each window.  Used when a near-tie between two window elements may legitimately
+ * be decided either way (values equal up to rounding) and the rest of the
+ * computation is to be followed for one particular valid choice. */
+void oracle_maxpool_gather(const double *r, const uint8_t *idx, double *p,
+                           int N, int C, int H, int W, int k, int s)
+{
+    const int Ho = out_extent(H, k, s, 0), Wo = out_extent(W, k, s, 0);
+    for (int nc = 0; nc < N * C; ++nc)
+        for (int py = 0; py < Ho; ++py)
+            for (int px = 0; px < Wo; ++px) {
+                const int a = idx[((size_t)nc * Ho + py) * Wo + px];
+                p[((size_t)nc * Ho + py) * Wo + px] = r[(size_t)nc * H * W + (py * s + a / k) * W + px * s + a % k];
+            }
+}
+
 /* Each pooled gradient goes to the recorded position of its window
  * (windows may overlap, so positions accumulate):  dr[argmax] += dp. */
 void oracle_maxpool_bwd(const double *dp, const uint8_t *idx, double *dr,

@@ -59,7 +59,7 @@ class OracleNet:
         return flat[w_off:w_off + n].reshape(w_shape), flat[b_off:b_off + b_len]
 
     def fwd_bwd(self, params, images, labels, dropout_seed=0, step=0, worker=0, want_grads=True,
-                masks=None, act_dtype="f64"):
+                masks=None, act_dtype="f64", decisions=None):
         """Returns (loss, grads, trace).  ``trace[li]`` holds what layer li produced
         ("out", and "argmax" / "mask" where they exist); ``trace["dx"][li]`` the
         gradient w.r.t. that layer's input.  ``masks`` overrides the generated
@@ -67,7 +67,14 @@ class OracleNet:
         ``act_dtype="bf16"`` models a network that stores its activations in bf16:
         every stored activation (the output of a conv or fc layer after its ReLU /
         dropout, except the final logits) is rounded to bf16, so that pooling
-        positions and ReLU masks are decided on the stored values."""
+        positions and ReLU masks are decided on the stored values.
+        ``decisions`` = {"relu": {li: bool array}, "argmax": {li: uint8 array}} fixes
+        the ReLU masks / pooling positions of those layers instead of deriving them:
+        a unit whose input is zero up to rounding, or a window with two maxima equal
+        up to rounding, can validly go either way, and the caller (having checked
+        that validity) asks for the gradient of one particular choice."""
+        dec_relu = (decisions or {}).get("relu", {})
+        dec_arg = (decisions or {}).get("argmax", {})
         params = np.ascontiguousarray(params, dtype=np.float64)
         assert params.shape == (self.param_count,)
         x = np.ascontiguousarray(images, dtype=np.float64)
@@ -83,9 +90,18 @@ class OracleNet:
                 w, b = self.split(params, li)
                 x = ops.conv_fwd(x, w, b, l[3], l[4])
             elif kind == "relu":
-                x = ops.relu_fwd(x)
+                t["pre"] = x
+                if li in dec_relu:
+                    t["relu_mask"] = np.asarray(dec_relu[li], dtype=bool).reshape(x.shape)
+                    x = np.where(t["relu_mask"], x, 0.0)
+                else:
+                    x = ops.relu_fwd(x)
             elif kind == "maxpool":
-                x, t["argmax"] = ops.maxpool_fwd(x, l[1], l[2])
+                if li in dec_arg:
+                    t["argmax"] = np.ascontiguousarray(dec_arg[li], dtype=np.uint8)
+                    x = ops.maxpool_gather(x, t["argmax"], l[1], l[2])
+                else:
+                    x, t["argmax"] = ops.maxpool_fwd(x, l[1], l[2])
             elif kind == "fc":
                 w, b = self.split(params, li)
                 x = ops.fc_fwd(x.reshape(N, -1), w, b)
@@ -127,7 +143,10 @@ class OracleNet:
             elif kind == "relu":
                 # the mask is taken on the stored ReLU output, which is positive exactly where the input was
                 # (a positive input may only round to zero in bf16 when it is below the smallest bf16 subnormal)
-                d = ops.relu_bwd(trace[li]["out"] if act_dtype == "bf16" else xin, d.reshape(xin.shape))
+                if li in dec_relu:
+                    d = np.where(trace[li]["relu_mask"], d.reshape(xin.shape), 0.0)
+                else:
+                    d = ops.relu_bwd(trace[li]["out"] if act_dtype == "bf16" else xin, d.reshape(xin.shape))
             elif kind == "maxpool":
                 d = ops.maxpool_bwd(d.reshape(trace[li]["out"].shape), trace[li]["argmax"], xin.shape[2:],
                                     l[1], l[2])

@@ -114,6 +114,17 @@ def maxpool_fwd(r, k, stride):
     return p, idx
 
 
+def maxpool_gather(r, idx, k, stride):
+    """Values of r at the given window positions (see oracle_maxpool_gather)."""
+    r = _f64(r)
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    N, C, H, W = r.shape
+    assert idx.shape == (N, C, _extent(H, k, stride, 0), _extent(W, k, stride, 0)) and idx.max() < k * k
+    p = np.empty(idx.shape)
+    _load().oracle_maxpool_gather(_d(r), idx.ctypes.data_as(_U8), _d(p), N, C, H, W, k, stride)
+    return p
+
+
 def maxpool_bwd(dp, idx, in_hw, k, stride):
     dp = _f64(dp)
     idx = np.ascontiguousarray(idx, dtype=np.uint8)

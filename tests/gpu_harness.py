@@ -75,3 +75,45 @@ def compare_grads(onet, gpu_grads, ref_grads, tol, label=""):
     bad = [(n, e) for n, e in errs if not e < tol]
     assert not bad, "relative L2 above %g: %s" % (tol, bad)
     return errs
+
+
+def gpu_decisions(g, layers, trace, dtype):
+    """ReLU masks and pooling positions the HIP path took, checked for validity against the oracle's values.
+
+    The two sides sum in different orders, so a pre-activation that is zero up to rounding, or two window
+    elements equal up to rounding, can be decided differently; either decision is correct.  Every decision
+    that differs from the oracle's is required to be such a near-tie; the caller then follows the gradient
+    of the HIP path's (valid) choice.  Returns (decisions, number of differing decisions)."""
+    relu_atol = 1e-4                                   # of the layer's rms pre-activation
+    pool_rtol = 2.0 ** -7 * 1.01 if dtype == B.BF16 else 1e-5   # one bf16 ulp / a few fp32 ulps
+    dec = {"relu": {}, "argmax": {}}
+    flips = 0
+    for li, l in enumerate(layers):
+        if l[0] == "relu":
+            pre = trace[li]["pre"]
+            o_mask = pre > 0
+            if layers[li + 1][0] == "dropout":
+                kept = trace[li + 1]["mask"].reshape(pre.shape) == 1
+                g_mask = np.where(kept, g.debug(B.DEBUG_OUTPUT, li + 1).reshape(pre.shape) > 0, o_mask)
+            else:
+                g_mask = g.debug(B.DEBUG_OUTPUT, li).reshape(pre.shape) > 0
+            diff = g_mask != o_mask
+            if diff.any():
+                rms = np.sqrt(np.mean(pre ** 2))
+                assert np.abs(pre[diff]).max() <= relu_atol * rms, ("ReLU decision differs away from zero", li)
+                flips += int(diff.sum())
+            dec["relu"][li] = g_mask
+        elif l[0] == "maxpool":
+            k, s = l[1], l[2]
+            o_arg = trace[li]["argmax"]
+            g_arg = g.debug(B.DEBUG_ARGMAX, li)
+            assert g_arg.max() < k * k
+            diff = g_arg != o_arg
+            if diff.any():
+                at_gpu = oops.maxpool_gather(trace[li - 1]["out"], g_arg, k, s)
+                p = trace[li]["out"]
+                assert (np.abs(at_gpu - p)[diff] <= pool_rtol * np.abs(p)[diff] + 1e-30).all(), \
+                    ("pooling position differs although the window has a clear maximum", li)
+                flips += int(diff.sum())
+            dec["argmax"][li] = g_arg
+    return dec, flips

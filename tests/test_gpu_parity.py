@@ -7,7 +7,7 @@ import oracle
 from oracle import ops as oops, asgd as oasgd
 from paper_1312_6186_amd import binding as B
 from paper_1312_6186_amd import workloads as wl
-from gpu_harness import GpuNet, TOL, rel_l2, oracle_inputs, compare_grads
+from gpu_harness import GpuNet, TOL, rel_l2, oracle_inputs, compare_grads, gpu_decisions
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -72,6 +72,10 @@ def _net_case(cfg, batch, dtype, seed=0, step=0, worker=0, bias_noise=0.05):
     p64, i64 = oracle_inputs(params, images, dtype)
     ref_loss, ref_grads, trace = onet.fwd_bwd(p64, i64, labels, seed, step, worker, act_dtype=ACT[dtype])
     loss, grads = g.fwd_bwd(params, images, labels, seed, step, worker)
+    dec, flips = gpu_decisions(g, layers, trace, dtype)
+    print("%s batch %d dtype %d: %d ReLU/pooling decisions differ (all near-ties)" % (cfg["name"], batch, dtype, flips))
+    if flips:   # follow the gradient of the HIP path's equally valid decisions
+        ref_loss, ref_grads, trace = onet.fwd_bwd(p64, i64, labels, seed, step, worker, act_dtype=ACT[dtype], decisions=dec)
     return g, onet, (loss, grads), (ref_loss, ref_grads, trace), (params, images, labels)
 
 
@@ -94,12 +98,35 @@ def test_minibatch_gradient_matches_oracle(cfg, batch, dtype):
                 assert rel_l2(out, trace[li]["out"]) < tol, ("output of layer", li)
             if l[0] == "dropout":
                 np.testing.assert_array_equal(g.debug(B.DEBUG_MASK, li).reshape(trace[li]["mask"].shape), trace[li]["mask"])
-            if l[0] == "maxpool":
-                # bit-exact on identical input bytes: the oracle pools the HIP path's own input
-                x = g.debug(B.DEBUG_OUTPUT, li - 1).astype(np.float64)
-                p_ref, idx_ref = oops.maxpool_fwd(x, l[1], l[2])
-                np.testing.assert_array_equal(g.debug(B.DEBUG_ARGMAX, li), idx_ref)
-                np.testing.assert_array_equal(g.debug(B.DEBUG_OUTPUT, li).astype(np.float64), p_ref)
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("k,stride", [(2, 2), (3, 2), (3, 1)])
+def test_pooling_positions_are_bit_exact(k, stride, dtype):
+    """A 1x1 convolution with identity weights and zero bias passes the image through exactly in any
+    precision, so the pooling kernel and the oracle see identical values: positions (first maximum in
+    row-major order, many exact ties) and pooled values must agree bit for bit."""
+    C, H, W, batch = 8, 13, 11, 9
+    layers = [("conv", C, 1, 1, 0), ("relu",), ("maxpool", k, stride), ("fc", 10), ("softmax_ce",)]
+    onet = oracle.OracleNet(layers, (C, H, W))
+    rng = np.random.default_rng(k * 10 + stride)
+    params = np.zeros(onet.param_count, dtype=np.float32)
+    params[:C * C] = np.eye(C, dtype=np.float32).reshape(-1)
+    fc_off = onet.param_slices[3][0]
+    params[fc_off:] = wl.round_to_bf16(0.1 * rng.standard_normal(params.size - fc_off).astype(np.float32))
+    images = (rng.integers(-3, 4, size=(batch, C, H, W)) * 0.25).astype(np.float32)    # few distinct values: ties everywhere
+    labels = rng.integers(0, 10, batch).astype(np.int32)
+    g = GpuNet(layers, (C, H, W), batch, dtype)
+    try:
+        g.fwd_bwd(params, images, labels)
+        _, _, trace = onet.fwd_bwd(params.astype(np.float64), images.astype(np.float64), labels, act_dtype=ACT[dtype])
+        np.testing.assert_array_equal(g.debug(B.DEBUG_OUTPUT, 1).astype(np.float64), trace[1]["out"])
+        idx = g.debug(B.DEBUG_ARGMAX, 2)
+        np.testing.assert_array_equal(idx, trace[2]["argmax"])
+        np.testing.assert_array_equal(g.debug(B.DEBUG_OUTPUT, 2).astype(np.float64), trace[2]["out"])
+        assert (trace[1]["out"] == 0).mean() > 0.3 and len(np.unique(idx)) == k * k
     finally:
         g.close()
 

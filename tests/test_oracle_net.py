@@ -168,3 +168,25 @@ def test_bf16_activation_storage_mode():
     assert np.abs(t1[1]["out"] - t0[1]["out"]).max() <= 2.0**-9 * np.abs(t0[1]["out"]).max()
     assert 0 < np.linalg.norm(g1 - g0) / np.linalg.norm(g0) < 0.05
     assert abs(l1 - l0) < 0.01 * abs(l0)
+
+
+def test_fixed_decisions_reproduce_and_alter_the_gradient():
+    net, params, images, labels = _setup(NET_A, 4, 3)
+    l0, g0, t0 = net.fwd_bwd(params, images, labels, 5, 6, 7)
+    # feeding the oracle's own decisions back changes nothing
+    dec = {"relu": {1: t0[1]["out"] > 0, 3: t0[3]["out"] > 0, 6: t0[5]["out"] > 0}, "argmax": {4: t0[4]["argmax"]}}
+    l1, g1, t1 = net.fwd_bwd(params, images, labels, 5, 6, 7, decisions=dec)
+    assert l0 == l1 and g0.tobytes() == g1.tobytes()
+    # pooling at given positions is a gather of the window element
+    r = t0[3]["out"]
+    idx = (t0[4]["argmax"] + 1) % 9
+    p = ops.maxpool_gather(r, idx, 3, 2)
+    n, c, py, px = 1, 2, 1, 0
+    a = idx[n, c, py, px]
+    assert p[n, c, py, px] == r[n, c, py * 2 + a // 3, px * 2 + a % 3]
+    # another choice gives another gradient, routed to the chosen positions
+    _, g2, t2 = net.fwd_bwd(params, images, labels, 5, 6, 7, decisions={"argmax": {4: idx}})
+    assert np.linalg.norm(g2 - g0) > 1e-3 * np.linalg.norm(g0)
+    dr = t2["dx"][4]
+    dp = t2["dx"][5].reshape(t2[4]["out"].shape)
+    assert dr[n, c, py * 2 + a // 3, px * 2 + a % 3] != 0 or dp[n, c, py, px] == 0

@@ -1,0 +1,172 @@
+"""Benchmark of the GPU A-SGD hot path on one MI355X.
+
+A step is one worker's whole cycle on one minibatch of synthetic data resident
+in HBM: snapshot (fetch the server's fp32 parameters into the worker's copy),
+fwd+bwd (the minibatch gradient) and the server's momentum / weight-decay
+update.  Prints ONE JSON line: images/sec, the roofline fraction of the
+dominant kernel class (timed with HIP events on the stream the kernels run on),
+the per-class table, and the CPU oracle timed on a bounded sample.
+
+    python bench.py [--steps K] [--warmup W] [--workload alexnet_bf16_bs128]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+WORKLOADS = {
+    # name: (batch, compute dtype)
+    "alexnet_bf16_bs128": (128, "bf16"),   # the headline: AlexNet-style single column, bf16 MFMA, fp32 master weights
+    "alexnet_f32_bs128": (128, "f32"),
+    "alexnet_bf16_bs256": (256, "bf16"),
+}
+PEAK = {"hbm": 8000.0, "mfma_bf16": 2500.0, "mfma_f32": 157.3}   # GB/s, TFLOP/s (MI355X, dense)
+MFMA_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad", "fc_fwd", "fc_dgrad", "fc_wgrad")
+
+
+def cpu_baseline(layers, in_shape, classes, sample_batch, hp):
+    """The oracle as it stands, on the host cores: one fwd+bwd+update on `sample_batch` images of the same net."""
+    import numpy as np
+    import oracle
+    from oracle import ops as oops
+    from paper_1312_6186_amd import workloads as wl
+    net = oracle.OracleNet(layers, in_shape)
+    params = wl.make_params(layers, in_shape, 2003).astype(np.float64)
+    mom = np.zeros_like(params)
+    images, labels = wl.make_batch(in_shape, sample_batch, classes, 1003)
+    t0 = time.perf_counter()
+    _, grads, _ = net.fwd_bwd(params, images, labels, 3003, 0, 0)
+    oops.apply_update(params, mom, grads, hp[0], hp[1], hp[2])
+    dt = time.perf_counter() - t0
+    return {"value": sample_batch / dt, "unit": "images/sec", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "one fwd+bwd+update of the same AlexNet-style net on %d images (%.1f s)" % (sample_batch, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="alexnet_bf16_bs128", choices=sorted(WORKLOADS))
+    ap.add_argument("--cpu-sample", type=int, default=8, help="images in the oracle's timed sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1312_6186_amd import binding as B
+    from paper_1312_6186_amd import workloads as wl
+
+    batch, dtname = WORKLOADS[args.workload]
+    dtype = B.BF16 if dtname == "bf16" else B.F32
+    tdt = torch.bfloat16 if dtname == "bf16" else torch.float32
+    cfg = wl.ALEXNET
+    layers, in_shape, classes = cfg["layers"], cfg["in_shape"], cfg["classes"]
+    lr, mu, wd = cfg["lr"], cfg["mu"], cfg["wd"]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    net = B.asgd_net_create(layers, batch, in_shape, dtype)
+    P = B.asgd_param_count(net)
+    master = torch.from_numpy(wl.make_params(layers, in_shape, cfg["seeds"]["init"])).to(dev)
+    momentum = torch.zeros_like(master)
+    copy = torch.empty(P, dtype=tdt, device=dev)
+    grads = torch.empty(P, dtype=torch.float32, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    images_np, labels_np = wl.make_batch(in_shape, batch, classes, cfg["seeds"]["data"])
+    images = torch.from_numpy(images_np).to(dev).to(tdt).contiguous()
+    labels = torch.from_numpy(labels_np).to(dev)
+    B.asgd_net_prepare(net)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        B.asgd_snapshot(master, copy, dtype, stream)
+        B.asgd_fwd_bwd(net, copy, images, labels, cfg["seeds"]["dropout"], i, 0, loss, grads, stream)
+        B.asgd_apply_update(master, momentum, grads, lr, mu, wd, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    final_loss = float(loss.item())
+
+    # the same steps again with a pair of HIP events around every operation, on the stream the kernels run on
+    B.asgd_profile_begin(net)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    tp0 = time.perf_counter()
+    for i in range(args.steps):
+        e = ev[i]
+        e[0].record(stream)
+        B.asgd_snapshot(master, copy, dtype, stream)
+        e[1].record(stream)
+        B.asgd_fwd_bwd(net, copy, images, labels, cfg["seeds"]["dropout"], args.warmup + args.steps + i, 0, loss, grads, stream)
+        e[2].record(stream)
+        B.asgd_apply_update(master, momentum, grads, lr, mu, wd, stream)
+        e[3].record(stream)
+    torch.cuda.synchronize()
+    profiled_ms = 1e3 * (time.perf_counter() - tp0) / args.steps
+    prof = B.asgd_profile_end(net)
+    K = args.steps
+    es = 2 if dtname == "bf16" else 4
+    classes_out = {}
+    for name, p in prof.items():
+        if p["launches"] == 0:
+            continue
+        ms = p["ms"] / K
+        if name in MFMA_CLASSES:
+            ach = p["flops"] / K / (ms * 1e-3) / 1e12
+            peak = PEAK["mfma_" + dtname]
+            classes_out[name] = {"bound": "mfma", "ms_per_step": ms, "launches_per_step": p["launches"] / K,
+                                 "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
+                                 "hbm_GBps_on_algorithmic_bytes": p["bytes"] / K / (ms * 1e-3) / 1e9}
+        else:
+            ach = p["bytes"] / K / (ms * 1e-3) / 1e9
+            classes_out[name] = {"bound": "hbm", "ms_per_step": ms, "launches_per_step": p["launches"] / K,
+                                 "achieved": ach, "peak": PEAK["hbm"], "unit": "GB/s", "frac": ach / PEAK["hbm"]}
+    snap_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / K
+    upd_ms = sum(e[2].elapsed_time(e[3]) for e in ev) / K
+    for name, ms, nbytes in (("snapshot", snap_ms, P * (4 + es)), ("update", upd_ms, P * 20)):
+        ach = nbytes / (ms * 1e-3) / 1e9
+        classes_out[name] = {"bound": "hbm", "ms_per_step": ms, "launches_per_step": 1, "achieved": ach, "peak": PEAK["hbm"],
+                             "unit": "GB/s", "frac": ach / PEAK["hbm"]}
+    dominant = max(classes_out, key=lambda k: classes_out[k]["ms_per_step"])
+    d = classes_out[dominant]
+    roofline = {"kernel": dominant, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"], "unit": d["unit"],
+                "frac": d["frac"], "traffic": None, "ms_per_launch": d["ms_per_step"] / d["launches_per_step"]}
+    mfma_ms = sum(c["ms_per_step"] for n, c in classes_out.items() if n in MFMA_CLASSES)
+    mfma_flops = sum(prof[n]["flops"] for n in MFMA_CLASSES) / K
+    B.asgd_net_destroy(net)
+
+    out = {
+        "metric": "images/sec fwd+bwd+update, AlexNet-style bs128; % MFMA peak (conv/FC)",
+        "value": batch * args.steps / elapsed, "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if dtname == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "net": "AlexNet-style single column (62378344 parameters)", "batch": batch,
+                   "step": "snapshot + fwd_bwd + apply_update", "lr": lr, "mu": mu, "wd": wd},
+        "loss": final_loss,
+        "roofline": roofline,
+        "mfma_all_gemms": {"achieved": mfma_flops / (mfma_ms * 1e-3) / 1e12, "peak": PEAK["mfma_" + dtname], "unit": "TFLOP/s",
+                           "frac": mfma_flops / (mfma_ms * 1e-3) / 1e12 / PEAK["mfma_" + dtname], "ms_per_step": mfma_ms},
+        "profiled_ms_per_step": profiled_ms,
+        "kernel_classes": classes_out,
+    }
+    if args.cpu_sample > 0:
+        out["cpu_baseline"] = cpu_baseline(layers, in_shape, classes, args.cpu_sample, (lr, mu, wd))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -171,6 +171,32 @@ int asgd_snapshot(const float *params, void *worker_copy, size_t n, int dst_dtyp
 typedef enum { ASGD_DEBUG_OUTPUT = 0, ASGD_DEBUG_ARGMAX = 1, ASGD_DEBUG_MASK = 2 } asgd_debug_what_t;
 int asgd_debug_get(asgd_net_t *net, int what, int layer, void *dst, size_t cap_bytes, void *stream);
 
+/* Per-kernel-class timing of asgd_fwd_bwd, for roofline reports.  Between
+ * asgd_profile_begin and asgd_profile_end every operation enqueued by
+ * asgd_fwd_bwd on this plan is bracketed by a pair of HIP events on the stream it
+ * runs on (an operation is one layer's GEMM including its split-K reduction, or
+ * one streaming kernel).  asgd_profile_end synchronises those events (host
+ * blocks) and fills out[0..ASGD_K_COUNT) with, per class: the number of
+ * operations, their summed duration, and the algorithmic work they stand for
+ * (2 * multiply-adds of the layer definition; bytes of the tensors an operation
+ * must read and write once, at their true, unpadded sizes).
+ * Errors: ASGD_EINVAL (null, end without begin), ASGD_EHIP. */
+typedef enum {
+    ASGD_K_CONV_FWD = 0, ASGD_K_CONV_DGRAD = 1, ASGD_K_CONV_WGRAD = 2,
+    ASGD_K_FC_FWD = 3, ASGD_K_FC_DGRAD = 4, ASGD_K_FC_WGRAD = 5,
+    ASGD_K_POOL_FWD = 6, ASGD_K_POOL_BWD = 7, ASGD_K_BIAS_GRAD = 8,
+    ASGD_K_SOFTMAX_CE = 9, ASGD_K_LAYOUT = 10, ASGD_K_COUNT = 11
+} asgd_kernel_class_t;
+typedef struct {
+    int32_t kclass;
+    int32_t launches;
+    double ms;
+    double flops;
+    double bytes;
+} asgd_profile_entry_t;
+int asgd_profile_begin(asgd_net_t *net);
+int asgd_profile_end(asgd_net_t *net, asgd_profile_entry_t *out);
+
 /* Staleness schedule of the A-SGD replay (Section 3.3 attributes artefacts of
  * the learning curves to stale updates).  Update a (0-based) is pushed by
  * worker a mod n_workers and was computed on parameter version

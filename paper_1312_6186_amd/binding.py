@@ -18,7 +18,10 @@ OK, EINVAL, ESHAPE, ENOMEM, EHIP, EALIGN = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["asgd_net_create", "asgd_net_prepare", "asgd_net_destroy", "asgd_param_count", "asgd_param_layout",
            "asgd_layer_shape", "asgd_workspace_bytes", "asgd_fwd_bwd", "asgd_apply_update", "asgd_snapshot",
-           "asgd_debug_get", "asgd_schedule_generate", "asgd_replay_run", "asgd_last_error"]
+           "asgd_debug_get", "asgd_profile_begin", "asgd_profile_end", "asgd_schedule_generate", "asgd_replay_run",
+           "asgd_last_error"]
+KERNEL_CLASSES = ["conv_fwd", "conv_dgrad", "conv_wgrad", "fc_fwd", "fc_dgrad", "fc_wgrad", "pool_fwd", "pool_bwd",
+                  "bias_grad", "softmax_ce", "layout"]
 
 
 class LayerDesc(ctypes.Structure):
@@ -30,6 +33,11 @@ class TensorInfo(ctypes.Structure):
     _fields_ = [("layer", ctypes.c_int32), ("kind", ctypes.c_int32), ("w_offset", ctypes.c_uint64),
                 ("w_count", ctypes.c_uint64), ("b_offset", ctypes.c_uint64), ("b_count", ctypes.c_uint64),
                 ("w_shape", ctypes.c_int32 * 4)]
+
+
+class ProfileEntry(ctypes.Structure):
+    _fields_ = [("kclass", ctypes.c_int32), ("launches", ctypes.c_int32), ("ms", ctypes.c_double),
+                ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
 
 
 class AsgdError(RuntimeError):
@@ -63,6 +71,8 @@ def lib():
         L.asgd_apply_update.argtypes = [vp, vp, vp, ctypes.c_size_t, ctypes.c_float, ctypes.c_float, ctypes.c_float, vp]
         L.asgd_snapshot.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
         L.asgd_debug_get.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp]
+        L.asgd_profile_begin.argtypes = [vp]
+        L.asgd_profile_end.argtypes = [vp, ctypes.POINTER(ProfileEntry)]
         L.asgd_schedule_generate.argtypes = [i32p, i32p, ctypes.c_int, ctypes.c_uint64, ctypes.c_int, ctypes.c_int]
         L.asgd_replay_run.argtypes = [ctypes.POINTER(vp), ctypes.c_int, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp,
                                       i32p, i32p, ctypes.c_int, ctypes.c_float, ctypes.c_float, ctypes.c_float,
@@ -169,6 +179,17 @@ def asgd_snapshot(params, worker_copy, dst_dtype, stream=None, n=None):
 
 def asgd_debug_get(net, what, layer, dst, stream=None):
     _check(lib().asgd_debug_get(net, what, layer, _ptr(dst), dst.numel() * dst.element_size(), _stream(stream)))
+
+
+def asgd_profile_begin(net):
+    _check(lib().asgd_profile_begin(net))
+
+
+def asgd_profile_end(net):
+    """{class name: dict(launches, ms, flops, bytes)} for the calls since asgd_profile_begin."""
+    arr = (ProfileEntry * len(KERNEL_CLASSES))()
+    _check(lib().asgd_profile_end(net, arr))
+    return {KERNEL_CLASSES[e.kclass]: dict(launches=e.launches, ms=e.ms, flops=e.flops, bytes=e.bytes) for e in arr}
 
 
 def asgd_schedule_generate(T, seed, n_workers, max_stale):

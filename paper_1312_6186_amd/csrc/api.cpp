@@ -85,6 +85,11 @@ struct asgd_net {
     uint64_t last_seed = 0, last_step = 0;
     uint32_t last_worker = 0;
     bool ran = false;
+    // per-class event timing (asgd_profile_begin / asgd_profile_end)
+    bool prof_on = false;
+    std::vector<hipEvent_t> prof_ev;    // start, stop pairs
+    std::vector<int> prof_cls;
+    double prof_flops[ASGD_K_COUNT] = {0}, prof_bytes[ASGD_K_COUNT] = {0};
 };
 
 namespace {
@@ -282,18 +287,44 @@ int ensure_prepared(asgd_net *n)
         }                                                                                    \
     } while (0)
 
+// Brackets one operation with a pair of events when profiling is on.
+struct ProfScope {
+    asgd_net *n; hipStream_t st; hipEvent_t stop = nullptr;
+    ProfScope(asgd_net *net, hipStream_t s, int cls, double flops, double bytes) : n(net), st(s)
+    {
+        if (!n->prof_on) return;
+        hipEvent_t a = nullptr, b = nullptr;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { if (a) (void)hipEventDestroy(a); return; }
+        (void)hipEventRecord(a, st);
+        n->prof_ev.push_back(a); n->prof_ev.push_back(b); n->prof_cls.push_back(cls);
+        n->prof_flops[cls] += flops; n->prof_bytes[cls] += bytes;
+        stop = b;
+    }
+    ~ProfScope() { if (stop) (void)hipEventRecord(stop, st); }
+};
+
 const char *param_ptr(const asgd_net *n, const void *params, size_t off) { return static_cast<const char *>(params) + off * dtype_size(n->dtype); }
 
 int forward(asgd_net *n, const void *params, const void *images, const int32_t *labels, uint64_t seed, uint64_t step, uint32_t worker,
             float *loss, hipStream_t st)
 {
     const int B = n->batch, dt = n->dtype;
-    CHECK_LAUNCH(launch_stage_input(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, n->in_cp, st), "stage_input");
+    const double es = (double)dtype_size(dt), Bd = (double)B;
+    {
+        ProfScope ps(n, st, ASGD_K_LAYOUT, 0, 2 * Bd * n->in_c * n->in_h * n->in_w * es);
+        CHECK_LAUNCH(launch_stage_input(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, n->in_cp, st), "stage_input");
+    }
     const void *cur = n->act0;
     for (size_t si = 0; si < n->stages.size(); ++si) {
         Stage &s = n->stages[si];
         if (s.kind == ST_CONV) {
-            CHECK_LAUNCH(launch_pack_conv(dt, param_ptr(n, params, s.w_off), s.wf, s.wd, s.outC, s.inC, s.k, s.k, s.outCp, s.inCp, st), "pack_conv");
+            {
+                ProfScope ps(n, st, ASGD_K_LAYOUT, 0, (double)s.w_cnt * es * (s.wd ? 3 : 2));
+                CHECK_LAUNCH(launch_pack_conv(dt, param_ptr(n, params, s.w_off), s.wf, s.wd, s.outC, s.inC, s.k, s.k, s.outCp, s.inCp, st), "pack_conv");
+            }
+            const double Mo = Bd * s.outH * s.outW;
+            ProfScope ps(n, st, ASGD_K_CONV_FWD, 2 * Mo * s.outC * s.inC * s.k * s.k,
+                         (Bd * s.inH * s.inW * s.inC + (double)s.w_cnt + Mo * s.outC) * es);
             Gather g;
             g.x = cur; g.N = B; g.H = s.inH; g.W = s.inW; g.C = s.inCp; g.Ho = s.outH; g.Wo = s.outW;
             g.kh = g.kw = s.k; g.sm = s.stride; g.ds = 1; g.pad = s.pad;
@@ -301,11 +332,13 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
             ep.out = s.out; ep.ld = s.outCp; ep.bias = param_ptr(n, params, s.b_off); ep.bias_n = s.outC; ep.relu = s.relu;
             CHECK_LAUNCH(gemm_gather_plain(dt, g, s.wf, (long)s.k * s.k * s.inCp, s.outCp, ep, s.p_fwd, n->scratch, st), "conv forward");
         } else if (s.kind == ST_POOL) {
+            ProfScope ps(n, st, ASGD_K_POOL_FWD, 0, Bd * s.outC * ((double)s.inH * s.inW * es + (double)s.outH * s.outW * (es + 1)));
             CHECK_LAUNCH(launch_pool_fwd(dt, cur, s.out, s.argmax, B, s.inH, s.inW, s.inCp, s.k, s.stride, st), "pool forward");
         } else {
             const void *x = cur;
             long ldx = si > 0 && n->stages[si - 1].kind == ST_FC ? n->stages[si - 1].out_ld : s.in_f;
             if (s.in_is_spatial) {
+                ProfScope ps(n, st, ASGD_K_LAYOUT, 0, 2 * Bd * s.in_f * es);
                 CHECK_LAUNCH(launch_flatten(dt, cur, s.flat_in, B, s.inH, s.inW, s.inC, s.inCp, st), "flatten");
                 x = s.flat_in;
                 ldx = s.in_f;
@@ -317,12 +350,14 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
                 ep.drop = 1; ep.drop_key = dropout_key(seed, step, worker, (uint32_t)s.drop_layer);
                 ep.drop_thr = s.drop_thr; ep.drop_F = s.out_f; ep.drop_scale = s.drop_scale;
             }
+            ProfScope ps(n, st, ASGD_K_FC_FWD, 2 * Bd * s.in_f * s.out_f, (Bd * s.in_f + (double)s.w_cnt) * es + Bd * s.out_f * (s.last ? 4 : es));
             CHECK_LAUNCH(gemm_plain_plain(dt, x, ldx, B, param_ptr(n, params, s.w_off), s.in_f, s.out_ld, s.out_f, s.in_f, ep, s.p_fwd, n->scratch, st),
                          "fc forward");
         }
         cur = s.out;
     }
     Stage &last = n->stages.back();
+    ProfScope ps(n, st, ASGD_K_SOFTMAX_CE, 0, Bd * n->classes * (4 + es));
     CHECK_LAUNCH(launch_softmax_ce(dt, static_cast<const float *>(last.out), last.out_ld, labels, B, n->classes, last.dout, loss, n->row_loss, st),
                  "softmax cross-entropy");
     return ASGD_OK;
@@ -331,6 +366,7 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
 int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
 {
     const int B = n->batch, dt = n->dtype;
+    const double es = (double)dtype_size(dt), Bd = (double)B;
     for (int si = (int)n->stages.size() - 1; si >= 0; --si) {
         Stage &s = n->stages[si];
         Stage *prev = si > 0 ? &n->stages[si - 1] : nullptr;
@@ -340,8 +376,14 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
             const long ldx = s.in_is_spatial ? s.in_f : prev->out_ld;
             Epilogue ew;
             ew.out = grads + s.w_off; ew.ld = s.in_f; ew.out_f32 = 1;
-            CHECK_LAUNCH(gemm_trans_trans(dt, s.dout, s.out_ld, s.out_f, x, ldx, s.in_f, B, ew, s.p_wgrad, n->scratch, st), "fc weight gradient");
-            CHECK_LAUNCH(launch_colsum(dt, s.dout, s.out_ld, B, s.out_f, grads + s.b_off, n->scratch, st), "fc bias gradient");
+            {
+                ProfScope ps(n, st, ASGD_K_FC_WGRAD, 2 * Bd * s.in_f * s.out_f, Bd * (s.in_f + s.out_f) * es + (double)s.w_cnt * 4);
+                CHECK_LAUNCH(gemm_trans_trans(dt, s.dout, s.out_ld, s.out_f, x, ldx, s.in_f, B, ew, s.p_wgrad, n->scratch, st), "fc weight gradient");
+            }
+            {
+                ProfScope ps(n, st, ASGD_K_BIAS_GRAD, 0, Bd * s.out_f * es + s.out_f * 4.0);
+                CHECK_LAUNCH(launch_colsum(dt, s.dout, s.out_ld, B, s.out_f, grads + s.b_off, n->scratch, st), "fc bias gradient");
+            }
             if (prev) {
                 Epilogue ed;
                 if (s.in_is_spatial) {
@@ -350,9 +392,13 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
                     ed.out = prev->dout; ed.ld = prev->out_ld;
                     if (prev->relu) { ed.mask_src = prev->out; ed.mask_ld = prev->out_ld; ed.mask_scale = prev->drop ? prev->drop_scale : 1.f; }
                 }
-                CHECK_LAUNCH(gemm_plain_trans(dt, s.dout, s.out_ld, B, param_ptr(n, params, s.w_off), s.in_f, s.in_f, s.out_f, ed, s.p_dgrad,
-                                              n->scratch, st),
-                             "fc data gradient");
+                {
+                    ProfScope ps(n, st, ASGD_K_FC_DGRAD, 2 * Bd * s.in_f * s.out_f, (Bd * s.out_f + (double)s.w_cnt + Bd * s.in_f * (ed.mask_src ? 2 : 1)) * es);
+                    CHECK_LAUNCH(gemm_plain_trans(dt, s.dout, s.out_ld, B, param_ptr(n, params, s.w_off), s.in_f, s.in_f, s.out_f, ed, s.p_dgrad,
+                                                  n->scratch, st),
+                                 "fc data gradient");
+                }
+                ProfScope ps(n, st, ASGD_K_LAYOUT, 0, s.in_is_spatial ? 3 * Bd * s.in_f * es : 0);
                 if (s.in_is_spatial)
                     CHECK_LAUNCH(launch_unflatten(dt, s.dflat_in, prev->out, prev->kind == ST_CONV && prev->relu, prev->dout, B, s.inH, s.inW, s.inC,
                                                   s.inCp, st),
@@ -360,6 +406,8 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
             }
         } else if (s.kind == ST_POOL) {
             // prev exists: a pool cannot be first... unless the net starts with a pool, which feeds no parameters
+            ProfScope ps(n, st, ASGD_K_POOL_BWD, 0,
+                         Bd * s.outC * ((double)s.outH * s.outW * (es + 1) + (double)s.inH * s.inW * es * (prev && prev->relu ? 2 : 1)));
             if (prev)
                 CHECK_LAUNCH(launch_pool_bwd(dt, s.dout, s.argmax, prev->out, prev->kind == ST_CONV && prev->relu, prev->dout, B, s.inH, s.inW, s.inCp,
                                              s.k, s.stride, st),
@@ -372,8 +420,15 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
             Epilogue ew;
             ew.out = grads + s.w_off; ew.mode = 1; ew.out_f32 = 1;
             ew.cw_cout = s.outC; ew.cw_cin = s.inC; ew.cw_cinp = s.inCp; ew.cw_kh = s.k; ew.cw_kw = s.k;
-            CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch, st), "conv filter gradient");
-            CHECK_LAUNCH(launch_colsum(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, n->scratch, st), "conv bias gradient");
+            const double Mo = (double)M, conv_flops = 2 * Mo * s.outC * s.inC * s.k * s.k;
+            {
+                ProfScope ps(n, st, ASGD_K_CONV_WGRAD, conv_flops, (Mo * s.outC + Bd * s.inH * s.inW * s.inC) * es + (double)s.w_cnt * 4);
+                CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch, st), "conv filter gradient");
+            }
+            {
+                ProfScope ps(n, st, ASGD_K_BIAS_GRAD, 0, Mo * s.outC * es + s.outC * 4.0);
+                CHECK_LAUNCH(launch_colsum(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, n->scratch, st), "conv bias gradient");
+            }
             if (prev) {
                 Gather d;
                 d.x = s.dout; d.N = B; d.H = s.outH; d.W = s.outW; d.C = s.outCp; d.Ho = s.inH; d.Wo = s.inW;
@@ -381,6 +436,8 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
                 Epilogue ed;
                 ed.out = prev->dout; ed.ld = s.inCp;
                 if (prev->kind == ST_CONV && prev->relu) { ed.mask_src = prev->out; ed.mask_ld = s.inCp; ed.mask_scale = 1.f; }
+                ProfScope ps(n, st, ASGD_K_CONV_DGRAD, conv_flops,
+                             (Mo * s.outC + (double)s.w_cnt + Bd * s.inH * s.inW * s.inC * (ed.mask_src ? 2 : 1)) * es);
                 CHECK_LAUNCH(gemm_gather_plain(dt, d, s.wd, (long)s.k * s.k * s.outCp, s.inCp, ed, s.p_dgrad, n->scratch, st), "conv data gradient");
             }
         }
@@ -427,6 +484,7 @@ int asgd_net_destroy(asgd_net_t *net)
 {
     if (!net) return ASGD_OK;
     int rc = ASGD_OK;
+    for (hipEvent_t e : net->prof_ev) (void)hipEventDestroy(e);
     if (net->arena) {
         const hipError_t e = hipFree(net->arena);
         if (e != hipSuccess) rc = hip_fail(e, "hipFree");
@@ -525,6 +583,37 @@ int asgd_debug_get(asgd_net_t *net, int what, int layer, void *dst, size_t cap_b
         return ASGD_OK;
     }
     return fail(ASGD_EINVAL, "asgd_debug_get: unknown selector %d", what);
+}
+
+int asgd_profile_begin(asgd_net_t *net)
+{
+    if (!net) return fail(ASGD_EINVAL, "asgd_profile_begin: null plan");
+    for (hipEvent_t e : net->prof_ev) (void)hipEventDestroy(e);
+    net->prof_ev.clear(); net->prof_cls.clear();
+    for (int c = 0; c < ASGD_K_COUNT; ++c) net->prof_flops[c] = net->prof_bytes[c] = 0;
+    net->prof_on = true;
+    return ASGD_OK;
+}
+
+int asgd_profile_end(asgd_net_t *net, asgd_profile_entry_t *out)
+{
+    if (!net || !out) return fail(ASGD_EINVAL, "asgd_profile_end: null argument");
+    if (!net->prof_on) return fail(ASGD_EINVAL, "asgd_profile_end: profiling was not begun on this plan");
+    net->prof_on = false;
+    for (int c = 0; c < ASGD_K_COUNT; ++c) { out[c].kclass = c; out[c].launches = 0; out[c].ms = 0; out[c].flops = net->prof_flops[c]; out[c].bytes = net->prof_bytes[c]; }
+    int rc = ASGD_OK;
+    for (size_t i = 0; i < net->prof_cls.size(); ++i) {
+        hipEvent_t a = net->prof_ev[2 * i], b = net->prof_ev[2 * i + 1];
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+        if (e != hipSuccess) { if (rc == ASGD_OK) rc = hip_fail(e, "profile event"); continue; }
+        out[net->prof_cls[i]].launches += 1;
+        out[net->prof_cls[i]].ms += ms;
+    }
+    for (hipEvent_t e : net->prof_ev) (void)hipEventDestroy(e);
+    net->prof_ev.clear(); net->prof_cls.clear();
+    return rc;
 }
 
 int asgd_schedule_generate(int32_t *worker, int32_t *read_version, int T, uint64_t seed, int n_workers, int max_stale)

@@ -79,6 +79,7 @@ struct asgd_net {
     void *act0 = nullptr;      // staged input
     float *scratch = nullptr;  // split-K partials and column-sum partials
     float *row_loss = nullptr;
+    void *zero_page = nullptr;       // 256 zero bytes, never written
     int *version_counter = nullptr;  // device-side count of applied updates (A-SGD replay)
     size_t scratch_floats = 0;
     // key of the last forward pass (for the dropout mask export)
@@ -114,12 +115,15 @@ size_t carve(asgd_net &n, char *base)
         const size_t o = c.take(bytes);
         return base ? base + o : nullptr;
     };
-    n.act0 = at(B * n.in_h * n.in_w * n.in_cp * es);
+    // every activation / gradient tensor is followed by 256 zero bytes (the arena is cleared once and the
+    // tail is never written): the gathers read out-of-image pieces from there
+    n.act0 = at(B * n.in_h * n.in_w * n.in_cp * es + 256);
+    n.zero_page = at(256);
     for (size_t i = 0; i < n.stages.size(); ++i) {
         Stage &s = n.stages[i];
         const size_t oe = B * s.out_elems();
-        s.out = at(oe * (s.last ? 4 : es));
-        s.dout = at(oe * es);
+        s.out = at(oe * (s.last ? 4 : es) + 256);
+        s.dout = at(oe * es + 256);
         if (s.kind == ST_POOL) s.argmax = static_cast<uint8_t *>(at(oe));
         if (s.kind == ST_CONV) {
             s.wf = at((size_t)s.outCp * s.k * s.k * s.inCp * es);
@@ -152,7 +156,7 @@ int plan_net(asgd_net &n)
         s.first_layer = i;
         if (l.kind == ASGD_LAYER_CONV) {
             if (F > 0) return fail(ASGD_ESHAPE, "layer %d: CONV after FC", i);
-            if (l.out <= 0 || l.k <= 0 || l.stride <= 0 || l.pad < 0) return fail(ASGD_ESHAPE, "layer %d: bad CONV parameters", i);
+            if (l.out <= 0 || l.k <= 0 || l.k > 15 || l.stride <= 0 || l.pad < 0) return fail(ASGD_ESHAPE, "layer %d: bad CONV parameters (filter size 1..15)", i);
             if (H + 2 * l.pad < l.k || W + 2 * l.pad < l.k) return fail(ASGD_ESHAPE, "layer %d: filter larger than padded input", i);
             s.kind = ST_CONV;
             s.inC = C; s.inCp = round_up(C, 8); s.inH = H; s.inW = W;
@@ -245,18 +249,18 @@ int plan_net(asgd_net &n)
         if (s.kind == ST_CONV) {
             const long M = B * s.outH * s.outW, Min = B * s.inH * s.inW;
             const long K = (long)s.k * s.k * s.inCp;
-            if (M > 0x7fffffffL / 2 || Min > 0x7fffffffL / 2 || M * s.outCp > (1L << 40)) return fail(ASGD_ESHAPE, "layer %d: tensor too large", s.first_layer);
+            if (M > 0x7fffffffL / 2 || Min > 0x7fffffffL / 2 || M * s.outCp * 4 > 0x7fffffffL || Min * s.inCp * 4 > 0x7fffffffL) return fail(ASGD_ESHAPE, "layer %d: tensor too large", s.first_layer);
             s.p_fwd = plan_gemm(M, s.outCp, K, n.dtype, 1);
             s.p_dgrad = plan_gemm(Min, s.inCp, (long)s.k * s.k * s.outCp, n.dtype, 1);
             s.p_wgrad = plan_gemm(s.outCp, K, M, n.dtype, 64);
             scratch = std::max(scratch, s.p_wgrad.ws_floats);
-            scratch = std::max(scratch, colsum_ws_floats(M, s.outC));
+            scratch = std::max(scratch, colsum_ws_floats(n.dtype, M, s.outCp));
         } else if (s.kind == ST_FC) {
             s.p_fwd = plan_gemm(B, s.out_ld, s.in_f, n.dtype, 32);
             s.p_dgrad = plan_gemm(B, s.in_f, s.out_f, n.dtype, 32);
             s.p_wgrad = plan_gemm(s.out_f, s.in_f, B, n.dtype, 1);
             scratch = std::max(scratch, std::max(s.p_fwd.ws_floats, s.p_dgrad.ws_floats));
-            scratch = std::max(scratch, colsum_ws_floats(B, s.out_f));
+            scratch = std::max(scratch, colsum_ws_floats(n.dtype, B, s.out_ld));
         }
     }
     n.scratch_floats = scratch + 64;
@@ -328,9 +332,10 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
             Gather g;
             g.x = cur; g.N = B; g.H = s.inH; g.W = s.inW; g.C = s.inCp; g.Ho = s.outH; g.Wo = s.outW;
             g.kh = g.kw = s.k; g.sm = s.stride; g.ds = 1; g.pad = s.pad;
+            g.zero_off = (size_t)B * s.inH * s.inW * s.inCp * dtype_size(dt);
             Epilogue ep;
             ep.out = s.out; ep.ld = s.outCp; ep.bias = param_ptr(n, params, s.b_off); ep.bias_n = s.outC; ep.relu = s.relu;
-            CHECK_LAUNCH(gemm_gather_plain(dt, g, s.wf, (long)s.k * s.k * s.inCp, s.outCp, ep, s.p_fwd, n->scratch, st), "conv forward");
+            CHECK_LAUNCH(gemm_gather_plain(dt, g, s.wf, (long)s.k * s.k * s.inCp, s.outCp, ep, s.p_fwd, n->scratch, n->zero_page, st), "conv forward");
         } else if (s.kind == ST_POOL) {
             ProfScope ps(n, st, ASGD_K_POOL_FWD, 0, Bd * s.outC * ((double)s.inH * s.inW * es + (double)s.outH * s.outW * (es + 1)));
             CHECK_LAUNCH(launch_pool_fwd(dt, cur, s.out, s.argmax, B, s.inH, s.inW, s.inCp, s.k, s.stride, st), "pool forward");
@@ -351,7 +356,7 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
                 ep.drop_thr = s.drop_thr; ep.drop_F = s.out_f; ep.drop_scale = s.drop_scale;
             }
             ProfScope ps(n, st, ASGD_K_FC_FWD, 2 * Bd * s.in_f * s.out_f, (Bd * s.in_f + (double)s.w_cnt) * es + Bd * s.out_f * (s.last ? 4 : es));
-            CHECK_LAUNCH(gemm_plain_plain(dt, x, ldx, B, param_ptr(n, params, s.w_off), s.in_f, s.out_ld, s.out_f, s.in_f, ep, s.p_fwd, n->scratch, st),
+            CHECK_LAUNCH(gemm_plain_plain(dt, x, ldx, B, param_ptr(n, params, s.w_off), s.in_f, s.out_ld, s.out_f, s.in_f, ep, s.p_fwd, n->scratch, n->zero_page, st),
                          "fc forward");
         }
         cur = s.out;
@@ -378,7 +383,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
             ew.out = grads + s.w_off; ew.ld = s.in_f; ew.out_f32 = 1;
             {
                 ProfScope ps(n, st, ASGD_K_FC_WGRAD, 2 * Bd * s.in_f * s.out_f, Bd * (s.in_f + s.out_f) * es + (double)s.w_cnt * 4);
-                CHECK_LAUNCH(gemm_trans_trans(dt, s.dout, s.out_ld, s.out_f, x, ldx, s.in_f, B, ew, s.p_wgrad, n->scratch, st), "fc weight gradient");
+                CHECK_LAUNCH(gemm_trans_trans(dt, s.dout, s.out_ld, s.out_f, x, ldx, s.in_f, B, ew, s.p_wgrad, n->scratch, n->zero_page, st), "fc weight gradient");
             }
             {
                 ProfScope ps(n, st, ASGD_K_BIAS_GRAD, 0, Bd * s.out_f * es + s.out_f * 4.0);
@@ -395,7 +400,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
                 {
                     ProfScope ps(n, st, ASGD_K_FC_DGRAD, 2 * Bd * s.in_f * s.out_f, (Bd * s.out_f + (double)s.w_cnt + Bd * s.in_f * (ed.mask_src ? 2 : 1)) * es);
                     CHECK_LAUNCH(gemm_plain_trans(dt, s.dout, s.out_ld, B, param_ptr(n, params, s.w_off), s.in_f, s.in_f, s.out_f, ed, s.p_dgrad,
-                                                  n->scratch, st),
+                                                  n->scratch, n->zero_page, st),
                                  "fc data gradient");
                 }
                 ProfScope ps(n, st, ASGD_K_LAYOUT, 0, s.in_is_spatial ? 3 * Bd * s.in_f * es : 0);
@@ -417,13 +422,14 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
             Gather g;
             g.x = xin; g.N = B; g.H = s.inH; g.W = s.inW; g.C = s.inCp; g.Ho = s.outH; g.Wo = s.outW;
             g.kh = g.kw = s.k; g.sm = s.stride; g.ds = 1; g.pad = s.pad;
+            g.zero_off = (size_t)B * s.inH * s.inW * s.inCp * dtype_size(dt);
             Epilogue ew;
             ew.out = grads + s.w_off; ew.mode = 1; ew.out_f32 = 1;
             ew.cw_cout = s.outC; ew.cw_cin = s.inC; ew.cw_cinp = s.inCp; ew.cw_kh = s.k; ew.cw_kw = s.k;
             const double Mo = (double)M, conv_flops = 2 * Mo * s.outC * s.inC * s.k * s.k;
             {
                 ProfScope ps(n, st, ASGD_K_CONV_WGRAD, conv_flops, (Mo * s.outC + Bd * s.inH * s.inW * s.inC) * es + (double)s.w_cnt * 4);
-                CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch, st), "conv filter gradient");
+                CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch, n->zero_page, st), "conv filter gradient");
             }
             {
                 ProfScope ps(n, st, ASGD_K_BIAS_GRAD, 0, Mo * s.outC * es + s.outC * 4.0);
@@ -433,12 +439,13 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
                 Gather d;
                 d.x = s.dout; d.N = B; d.H = s.outH; d.W = s.outW; d.C = s.outCp; d.Ho = s.inH; d.Wo = s.inW;
                 d.kh = d.kw = s.k; d.sm = 1; d.ds = s.stride; d.pad = s.k - 1 - s.pad;
+                d.zero_off = (size_t)B * s.outH * s.outW * s.outCp * dtype_size(dt);
                 Epilogue ed;
                 ed.out = prev->dout; ed.ld = s.inCp;
                 if (prev->kind == ST_CONV && prev->relu) { ed.mask_src = prev->out; ed.mask_ld = s.inCp; ed.mask_scale = 1.f; }
                 ProfScope ps(n, st, ASGD_K_CONV_DGRAD, conv_flops,
                              (Mo * s.outC + (double)s.w_cnt + Bd * s.inH * s.inW * s.inC * (ed.mask_src ? 2 : 1)) * es);
-                CHECK_LAUNCH(gemm_gather_plain(dt, d, s.wd, (long)s.k * s.k * s.outCp, s.inCp, ed, s.p_dgrad, n->scratch, st), "conv data gradient");
+                CHECK_LAUNCH(gemm_gather_plain(dt, d, s.wd, (long)s.k * s.k * s.outCp, s.inCp, ed, s.p_dgrad, n->scratch, n->zero_page, st), "conv data gradient");
             }
         }
     }

@@ -3,17 +3,23 @@
 // connected layers.  C[M][N] = sum_k A[m][k] * B[n][k], fp32 accumulation.
 //
 // Geometry (identical in bytes for both element types): a workgroup of 256
-// threads (4 wave64) owns a 128x128 tile of C; one K tile is 128 bytes per row
+// threads (4 wave64, arranged 2x2) owns a BM x BN tile of C (256x128 for the
+// large convolution GEMMs, 128x128 otherwise); one K tile is 128 bytes per row
 // (64 bf16 or 32 fp32).  Both operand tiles sit in LDS with K contiguous, as
-// 128 rows x 8 slots of 16 bytes, the slot index XOR-swizzled with the row so
-// that the 16-byte reads of the MFMA fragments, the direct stores and the
-// transposed stores are all spread over the banks.  Operands whose memory
-// layout has the reduction index strided (filter gradients, FC data gradient)
-// are transposed in registers between the global load and the LDS store.
-// Each wave computes 64x64 as 2x2 MFMA 32x32 blocks; the MFMA is issued with the
-// B-matrix fragment as its first operand so that a lane ends up with four
-// consecutive n for one m and can store them as one vector.
+// rows x 8 slots of 16 bytes, the slot index XOR-swizzled with the row so that
+// the 16-byte reads of the MFMA fragments, the direct stores and the transposed
+// stores are all spread over the banks.  Operands whose memory layout has the
+// reduction index strided (filter gradients, FC data gradient) are transposed
+// in registers between the global load and the LDS store.  Each wave computes
+// (BM/2)x(BN/2) as MFMA 32x32 blocks; the MFMA is issued with the B-matrix
+// fragment as its first operand so that a lane ends up with four consecutive n
+// for one m and can store them as one vector.  Workgroup ids are remapped so
+// that each of the 8 XCDs (which receive ids round-robin) works on a contiguous
+// range of tiles and its L2 sees neighbouring tiles' shared operand rows.
 #include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <type_traits>
 
 #include "asgd_internal.h"
 
@@ -27,7 +33,18 @@ template <typename T> struct Geo;
 template <> struct Geo<bf16_t> { enum { CH = 8, BK = 64, KSTEPS = 4 }; };
 template <> struct Geo<float> { enum { CH = 4, BK = 32, KSTEPS = 2 }; };
 
-constexpr int BM = 128, BN = 128, NT = 256;
+constexpr int NT = 256;
+#define ASGD_INLINE __attribute__((always_inline))
+
+// Compile-time loop: indices reach the body as constants, so register arrays are never addressed dynamically.
+template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 
 FastDiv make_fastdiv(uint32_t d)
 {
@@ -41,37 +58,105 @@ FastDiv make_fastdiv(uint32_t d)
     return f;
 }
 
-__device__ inline uint32_t fdiv(uint32_t n, const FastDiv &f) { return (__umulhi(n, f.mul) + n) >> f.sh; }
-__device__ inline uint4 ld16(const void *p) { return *reinterpret_cast<const uint4 *>(p); }
-__device__ inline uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
-__device__ inline int swz(int row) { return (row ^ (row >> 3)) & 7; }
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) { return (__umulhi(n, f.mul) + n) >> f.sh; }
+__device__ __forceinline__ uint4 ld16(const void *p) { return *reinterpret_cast<const uint4 *>(p); }
+__device__ __forceinline__ uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
+__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
-__device__ inline float to_f32(float v) { return v; }
-__device__ inline float to_f32(bf16_t v) { return (float)v; }
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
 
 // ------------------------------------------------------------------ loaders
 // Direct loaders hand out 16-byte pieces of a row that are contiguous in K.
 template <typename T> struct PlainK {
     static constexpr bool kTrans = false;
-    const T *base; long ld; int rows; int K;
+    const T *base; long ld; int rows; int K; const T *zero;   // zero: 16 readable zero bytes
     struct Row { const T *p; };
     struct KPos { int k; };
-    __device__ Row row(int r) const { return Row{r < rows ? base + (long)r * ld : nullptr}; }
-    __device__ KPos kpos(int k) const { return KPos{k}; }
-    __device__ void advance(KPos &kp, int dk) const { kp.k += dk; }
-    __device__ uint4 load(const Row &r, const KPos &kp) const
+    __device__ __forceinline__ Row row(int r) const { return Row{r < rows ? base + (long)r * ld : nullptr}; }
+    __device__ __forceinline__ KPos kpos(int k) const { return KPos{k}; }
+    __device__ __forceinline__ void advance(KPos &kp, int dk) const { kp.k += dk; }
+    __device__ __forceinline__ uint4 load(const Row &r, const KPos &kp) const
     {
-        return (r.p != nullptr && kp.k < K) ? ld16(r.p + kp.k) : zero16();
+        return ld16((r.p != nullptr && kp.k < K) ? r.p + kp.k : zero);
     }
 };
 
-template <typename T> struct GatherK {
+// Implicit-GEMM gather, unit divisor (forward convolution, stride-1 data gradient).
+// All per-row work is done once: a row keeps the byte offset of its window origin
+// and a bit mask saying which window positions (ky, kx) fall inside the image; a K
+// position keeps the byte offset of (ky, kx, c) relative to a window origin and
+// the bit of its window position.  Fetching a piece is then one mask test, one add
+// and one select (out-of-image pieces read 16 zero bytes that sit right behind the
+// tensor).  WIDE = windows of more than 32 positions (two 16-bit masks, one per axis).
+template <typename T, bool WIDE> struct GatherK {
+    static constexpr bool kTrans = false;
+    const char *x; unsigned zero_off;
+    int H, W, C, Ho, Wo, kh, kw, sm, pad, M;
+    FastDiv dWo, dHoWo, dC, dkw;
+    struct Row { unsigned off, mask; };
+    struct KPos { int ky, kx, c; unsigned delta, bit; };
+    __device__ __forceinline__ Row row(int m) const
+    {
+        if (m >= M) return Row{0u, 0u};
+        const int n = (int)fdiv((uint32_t)m, dHoWo);
+        const int rem = m - n * (Ho * Wo);
+        const int oy = (int)fdiv((uint32_t)rem, dWo);
+        const int ox = rem - oy * Wo;
+        const int y0 = oy * sm - pad, x0 = ox * sm - pad;
+        // ky is inside for max(0,-y0) <= ky < min(kh, H-y0); the same along x
+        const int ylo = max(0, -y0), yhi = max(ylo, min(kh, H - y0));
+        const int xlo = max(0, -x0), xhi = max(xlo, min(kw, W - x0));
+        const unsigned ym = ((1u << yhi) - 1u) & ~((1u << ylo) - 1u), xm = ((1u << xhi) - 1u) & ~((1u << xlo) - 1u);
+        unsigned mask = 0;
+        if (WIDE) {
+            mask = ym | (xm << 16);
+        } else {
+            for (int a = 0; a < kh; ++a)
+                if ((ym >> a) & 1u) mask |= xm << (a * kw);
+        }
+        return Row{(unsigned)(((n * H + y0) * W + x0) * C) * (unsigned)sizeof(T), mask};
+    }
+    __device__ __forceinline__ unsigned bit_of(int ky, int kx) const
+    {
+        if (ky >= kh) return 0u;
+        return WIDE ? ((1u << ky) | (1u << (16 + kx))) : (1u << (ky * kw + kx));
+    }
+    __device__ __forceinline__ KPos kpos(int k) const
+    {
+        const int t = (int)fdiv((uint32_t)k, dC);
+        const int ky = (int)fdiv((uint32_t)t, dkw);
+        const int kx = t - ky * kw, c = k - t * C;
+        return KPos{ky, kx, c, (unsigned)((ky * W + kx) * C + c) * (unsigned)sizeof(T), bit_of(ky, kx)};
+    }
+    __device__ __forceinline__ void advance(KPos &kp, int dk) const
+    {
+        kp.c += dk;
+        kp.delta += (unsigned)dk * (unsigned)sizeof(T);
+        if (kp.c >= C) {
+            do {
+                kp.c -= C;
+                if (++kp.kx == kw) { kp.kx = 0; ++kp.ky; kp.delta += (unsigned)((W - kw) * C) * (unsigned)sizeof(T); }
+            } while (kp.c >= C);
+            kp.bit = bit_of(kp.ky, kp.kx);
+        }
+    }
+    __device__ __forceinline__ uint4 load(const Row &r, const KPos &kp) const
+    {
+        const bool ok = WIDE ? (kp.bit != 0u && (r.mask & kp.bit) == kp.bit) : ((r.mask & kp.bit) != 0u);
+        return ld16(x + (ok ? r.off + kp.delta : zero_off));
+    }
+};
+
+// The same gather with a divisor (data gradient of a strided convolution): positions
+// that are not multiples of the stride contribute nothing.  Rare, kept simple.
+template <typename T> struct GatherKS {
     static constexpr bool kTrans = false;
     const T *x; int H, W, C, Ho, Wo, kh, kw, sm, ds, pad, M;
     FastDiv dWo, dHoWo, dC, dkw;
     struct Row { int pix0, y0, x0; };  // pix0 < 0: row out of range
     struct KPos { int ky, kx, c; };
-    __device__ Row row(int m) const
+    __device__ __forceinline__ Row row(int m) const
     {
         if (m >= M) return Row{-1, 0, 0};
         const int n = (int)fdiv((uint32_t)m, dHoWo);
@@ -80,13 +165,13 @@ template <typename T> struct GatherK {
         const int ox = rem - oy * Wo;
         return Row{n * H * W, oy * sm - pad, ox * sm - pad};
     }
-    __device__ KPos kpos(int k) const
+    __device__ __forceinline__ KPos kpos(int k) const
     {
         const int t = (int)fdiv((uint32_t)k, dC);
         const int ky = (int)fdiv((uint32_t)t, dkw);
         return KPos{ky, t - ky * kw, k - t * C};
     }
-    __device__ void advance(KPos &kp, int dk) const
+    __device__ __forceinline__ void advance(KPos &kp, int dk) const
     {
         kp.c += dk;
         while (kp.c >= C) {
@@ -94,15 +179,13 @@ template <typename T> struct GatherK {
             if (++kp.kx == kw) { kp.kx = 0; ++kp.ky; }
         }
     }
-    __device__ uint4 load(const Row &r, const KPos &kp) const
+    __device__ __forceinline__ uint4 load(const Row &r, const KPos &kp) const
     {
         if (r.pix0 < 0 || kp.ky >= kh) return zero16();
         int y = r.y0 + kp.ky, xx = r.x0 + kp.kx;
         if (y < 0 || xx < 0) return zero16();
-        if (ds > 1) {
-            if ((y % ds) != 0 || (xx % ds) != 0) return zero16();
-            y /= ds; xx /= ds;
-        }
+        if ((y % ds) != 0 || (xx % ds) != 0) return zero16();
+        y /= ds; xx /= ds;
         if (y >= H || xx >= W) return zero16();
         return ld16(x + ((long)(r.pix0 + y * W + xx) * C + kp.c));
     }
@@ -114,31 +197,42 @@ template <typename T> struct GatherK {
 template <typename T> struct PlainT {
     static constexpr bool kTrans = true;
     static constexpr int CH = Geo<T>::CH;
-    const T *base; long ld; int rows; int K;
-    struct Unit { int row0; };
-    __device__ Unit unit(int row0) const { return Unit{row0}; }
-    __device__ void load(const Unit &u, int k, uint4 (&out)[CH]) const
+    const T *base; long ld; int rows; int K; const T *zero;
+    struct Unit { const T *p; };   // nullptr: rows out of range
+    __device__ __forceinline__ Unit unit(int row0) const { return Unit{row0 < rows ? base + row0 : nullptr}; }
+    __device__ __forceinline__ void load(const Unit &u, int k, uint4 (&out)[CH]) const
     {
-#pragma unroll
-        for (int j = 0; j < CH; ++j)
-            out[j] = (u.row0 < rows && k + j < K) ? ld16(base + (long)(k + j) * ld + u.row0) : zero16();
+        static_for<0, CH>([&](auto j) ASGD_INLINE {
+            out[j] = ld16((u.p != nullptr && k + j < K) ? u.p + (long)(k + j) * ld : zero);
+        });
     }
 };
 
+// Filter-gradient gather: rows enumerate (ky, kx, c) (fixed per unit), the reduction
+// index enumerates output pixels (n, oy, ox).  The valid oy / ox ranges of a unit
+// are precomputed; the pixel offset is advanced incrementally along the 8 (or 4)
+// consecutive reduction indices of a unit.
 template <typename T> struct GatherT {
     static constexpr bool kTrans = true;
     static constexpr int CH = Geo<T>::CH;
-    const T *x; int H, W, C, Ho, Wo, kh, kw, sm, pad, M, Krows;
+    const char *x; unsigned zero_off;
+    int H, W, C, Ho, Wo, kh, kw, sm, pad, M, Krows;
     FastDiv dWo, dHoWo, dC, dkw;
-    struct Unit { int ky, kx, c; };  // ky < 0: rows out of range
-    __device__ Unit unit(int row0) const
+    struct Unit { int ylo, yspan, xlo, xspan; unsigned off; };   // yspan < 0: rows out of range
+    __device__ __forceinline__ Unit unit(int row0) const
     {
-        if (row0 >= Krows) return Unit{-1, 0, 0};
+        if (row0 >= Krows) return Unit{0, -1, 0, -1, 0u};
         const int t = (int)fdiv((uint32_t)row0, dC);
         const int ky = (int)fdiv((uint32_t)t, dkw);
-        return Unit{ky, t - ky * kw, row0 - t * C};
+        const int kx = t - ky * kw, c = row0 - t * C;
+        // oy valid iff 0 <= oy*sm + ky - pad < H
+        const int ylo = ky >= pad ? 0 : (pad - ky + sm - 1) / sm;
+        const int yhi = (H - 1 + pad - ky) >= 0 ? min(Ho - 1, (H - 1 + pad - ky) / sm) : -1;
+        const int xlo = kx >= pad ? 0 : (pad - kx + sm - 1) / sm;
+        const int xhi = (W - 1 + pad - kx) >= 0 ? min(Wo - 1, (W - 1 + pad - kx) / sm) : -1;
+        return Unit{ylo, yhi - ylo, xlo, xhi - xlo, (unsigned)(((ky - pad) * W + (kx - pad)) * C + c) * (unsigned)sizeof(T)};
     }
-    __device__ void load(const Unit &u, int m0, uint4 (&out)[CH]) const
+    __device__ __forceinline__ void load(const Unit &u, int m0, uint4 (&out)[CH]) const
     {
         int n = 0, oy = 0, ox = 0;
         if (m0 < M) {
@@ -147,50 +241,59 @@ template <typename T> struct GatherT {
             oy = (int)fdiv((uint32_t)rem, dWo);
             ox = rem - oy * Wo;
         }
-#pragma unroll
-        for (int j = 0; j < CH; ++j) {
-            uint4 v = zero16();
-            if (u.ky >= 0 && m0 + j < M) {
-                const int y = oy * sm + u.ky - pad, xx = ox * sm + u.kx - pad;
-                if (y >= 0 && y < H && xx >= 0 && xx < W) v = ld16(x + ((long)((n * H + y) * W + xx) * C + u.c));
+        const unsigned es = (unsigned)sizeof(T);
+        unsigned poff = u.off + (unsigned)(((n * H + oy * sm) * W + ox * sm) * C) * es;
+        const unsigned step_x = (unsigned)(sm * C) * es;
+        const unsigned step_row = (unsigned)((sm * W - Wo * sm) * C) * es;       // extra on wrapping to the next output row
+        const unsigned step_img = (unsigned)((H - Ho * sm) * W * C) * es;        // extra on wrapping to the next image
+        static_for<0, CH>([&](auto j) ASGD_INLINE {
+            const bool ok = m0 + j < M && (unsigned)(oy - u.ylo) <= (unsigned)u.yspan && (unsigned)(ox - u.xlo) <= (unsigned)u.xspan &&
+                            u.yspan >= 0 && u.xspan >= 0;
+            out[j] = ld16(x + (ok ? poff : zero_off));
+            poff += step_x;
+            if (++ox == Wo) {
+                ox = 0; poff += step_row;
+                if (++oy == Ho) { oy = 0; poff += step_img; }
             }
-            out[j] = v;
-            if (++ox == Wo) { ox = 0; if (++oy == Ho) { oy = 0; ++n; } }
-        }
+        });
     }
 };
 
 // ------------------------------------------------------------------ staging
-template <typename T, class L, bool kTrans = L::kTrans> struct Stage;
+template <typename T, class L, int ROWS, bool kTrans = L::kTrans> struct Stage;
 
-template <typename T, class L> struct Stage<T, L, false> {
-    static constexpr int SLOTS = BM * 8 / NT;
+template <typename T, class L, int ROWS> struct Stage<T, L, ROWS, false> {
+    static constexpr int SLOTS = ROWS * 8 / NT;
     typename L::Row rows[SLOTS];
     typename L::KPos kp;
-    uint4 r[SLOTS];
-    __device__ void init(const L &l, int row0, int k0, int tid, int)
+    uint4 r[2][SLOTS];   // two K tiles in flight
+    unsigned wo[2];      // LDS byte offset of slot 0 / slot 1; slot s sits s/2 * 64 rows further
+    __device__ __forceinline__ void init(const L &l, int row0, int k0, int tid, int)
     {
-#pragma unroll
-        for (int s = 0; s < SLOTS; ++s) rows[s] = l.row(row0 + (tid >> 3) + s * (NT / 8));
+        static_for<0, 2>([&](auto par) ASGD_INLINE {
+            const int row = (tid >> 3) + par * (NT / 8);
+            wo[par] = (unsigned)(row * 8 + ((tid & 7) ^ swz(row))) * 16u;
+        });
+        static_for<0, SLOTS>([&](auto s) ASGD_INLINE { rows[s] = l.row(row0 + (tid >> 3) + s * (NT / 8)); });
         kp = l.kpos(k0 + (tid & 7) * Geo<T>::CH);
     }
-    __device__ void load(const L &l)
+    // fetch the K tile at the cursor into register set RB and advance the cursor
+    template <int RB> __device__ __forceinline__ void load(const L &l)
     {
-#pragma unroll
-        for (int s = 0; s < SLOTS; ++s) r[s] = l.load(rows[s], kp);
+        static_for<0, SLOTS>([&](auto s) ASGD_INLINE { r[RB][s] = l.load(rows[s], kp); });
+        l.advance(kp, Geo<T>::BK);
     }
-    __device__ void next(const L &l) { l.advance(kp, Geo<T>::BK); }
-    __device__ void store(uint4 *sm, int tid) const
+    template <int RB> __device__ __forceinline__ void store(uint4 *sm, int tid) const
     {
-#pragma unroll
-        for (int s = 0; s < SLOTS; ++s) {
-            const int row = (tid >> 3) + s * (NT / 8);
-            sm[row * 8 + ((tid & 7) ^ swz(row))] = r[s];
-        }
+        // rows 64 apart share the swizzle, so the offset of slot s is that of slot s%2 plus a constant
+        char *base = reinterpret_cast<char *>(sm);
+        static_for<0, SLOTS>([&](auto s) ASGD_INLINE {
+            *reinterpret_cast<uint4 *>(base + wo[s % 2] + (s / 2) * (2 * (NT / 8) * 128)) = r[RB][s];
+        });
     }
 };
 
-__device__ inline void transpose_unit(const uint4 (&r)[4], uint4 (&o)[4])  // fp32: 4 k x 4 rows
+__device__ __forceinline__ void transpose_unit(const uint4 (&r)[4], uint4 (&o)[4])  // fp32: 4 k x 4 rows
 {
     o[0] = make_uint4(r[0].x, r[1].x, r[2].x, r[3].x);
     o[1] = make_uint4(r[0].y, r[1].y, r[2].y, r[3].y);
@@ -198,10 +301,10 @@ __device__ inline void transpose_unit(const uint4 (&r)[4], uint4 (&o)[4])  // fp
     o[3] = make_uint4(r[0].w, r[1].w, r[2].w, r[3].w);
 }
 
-__device__ inline uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
-__device__ inline uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
+__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
-__device__ inline void transpose_unit(const uint4 (&r)[8], uint4 (&o)[8])  // bf16: 8 k x 8 rows
+__device__ __forceinline__ void transpose_unit(const uint4 (&r)[8], uint4 (&o)[8])  // bf16: 8 k x 8 rows
 {
     o[0] = make_uint4(pack_lo(r[0].x, r[1].x), pack_lo(r[2].x, r[3].x), pack_lo(r[4].x, r[5].x), pack_lo(r[6].x, r[7].x));
     o[1] = make_uint4(pack_hi(r[0].x, r[1].x), pack_hi(r[2].x, r[3].x), pack_hi(r[4].x, r[5].x), pack_hi(r[6].x, r[7].x));
@@ -213,63 +316,103 @@ __device__ inline void transpose_unit(const uint4 (&r)[8], uint4 (&o)[8])  // bf
     o[7] = make_uint4(pack_hi(r[0].w, r[1].w), pack_hi(r[2].w, r[3].w), pack_hi(r[4].w, r[5].w), pack_hi(r[6].w, r[7].w));
 }
 
-template <typename T, class L> struct Stage<T, L, true> {
+template <typename T, class L, int ROWS> struct Stage<T, L, ROWS, true> {
     static constexpr int CH = Geo<T>::CH;
-    static constexpr int RCH = BM / CH;              // row chunks per tile
+    static constexpr int RCH = ROWS / CH;            // row chunks per tile
     static constexpr int NUNITS = RCH * 8;           // x 8 slots along K
-    typename L::Unit un;
-    int rowchunk, kq, k;
-    bool active;
-    uint4 r[CH];
-    __device__ void init(const L &l, int row0, int k0, int tid, int shift)
+    static constexpr int UPT = (NUNITS + NT - 1) / NT;  // units per thread
+    typename L::Unit un[UPT];
+    int k;
+    int vt;
+    uint4 r[2][UPT][CH];
+    __device__ __forceinline__ void init(const L &l, int row0, int k0, int tid, int shift)
     {
-        const int vt = (tid + shift) & (NT - 1);     // spreads the two operands over different waves
-        active = vt < NUNITS;
-        rowchunk = vt % RCH;
-        kq = vt / RCH;
-        un = l.unit(row0 + rowchunk * CH);
-        k = k0 + kq * CH;
+        vt = (tid + shift) & (NT - 1);               // spreads the two operands over different waves
+        k = k0;
+        static_for<0, UPT>([&](auto u) ASGD_INLINE {
+            const int id = vt + u * NT;
+            un[u] = l.unit(row0 + (id % RCH) * CH);
+        });
     }
-    __device__ void load(const L &l)
+    template <int RB> __device__ __forceinline__ void load(const L &l)
     {
-        if (active) l.load(un, k, r);
+        static_for<0, UPT>([&](auto u) ASGD_INLINE {
+            const int id = vt + u * NT;
+            if (id < NUNITS) l.load(un[u], k + (id / RCH) * CH, r[RB][u]);
+        });
+        k += Geo<T>::BK;
     }
-    __device__ void next(const L &) { k += Geo<T>::BK; }
-    __device__ void store(uint4 *sm, int) const
+    template <int RB> __device__ __forceinline__ void store(uint4 *sm, int) const
     {
-        if (!active) return;
-        uint4 o[CH];
-        transpose_unit(r, o);
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int row = rowchunk * CH + i;
-            sm[row * 8 + (kq ^ swz(row))] = o[i];
-        }
+        static_for<0, UPT>([&](auto u) ASGD_INLINE {
+            const int id = vt + u * NT;
+            if (id < NUNITS) {
+                const int rowchunk = id % RCH, kq = id / RCH;
+                uint4 o[CH];
+                transpose_unit(r[RB][u], o);
+                static_for<0, CH>([&](auto i) ASGD_INLINE {
+                    const int row = rowchunk * CH + i;
+                    sm[row * 8 + (kq ^ swz(row))] = o[i];
+                });
+            }
+        });
     }
 };
 
 // ------------------------------------------------------------------ MFMA step
+// A fragment is the 8 consecutive K elements of one row that a lane feeds to the
+// MFMA.  FragOff holds, per K step, the LDS byte offset of that piece for the
+// lane's row in row block 0 and in row block 1 (blocks 64 rows apart share it), so
+// the inner loop issues its LDS reads with no address arithmetic.
 template <typename T> struct Frag;
+template <typename T> struct FragOff;
+template <> struct FragOff<bf16_t> {
+    unsigned o[Geo<bf16_t>::KSTEPS][2];
+    __device__ __forceinline__ void init(int row0, int lrow, int half)
+    {
+        static_for<0, Geo<bf16_t>::KSTEPS>([&](auto ks) ASGD_INLINE {
+            static_for<0, 2>([&](auto par) ASGD_INLINE {
+                const int row = row0 + par * 32 + lrow;
+                o[ks][par] = (unsigned)(row * 8 + ((ks * 2 + half) ^ swz(row))) * 16u;
+            });
+        });
+    }
+};
+template <> struct FragOff<float> {
+    unsigned o[Geo<float>::KSTEPS][2][2];
+    __device__ __forceinline__ void init(int row0, int lrow, int half)
+    {
+        static_for<0, Geo<float>::KSTEPS>([&](auto ks) ASGD_INLINE {
+            static_for<0, 2>([&](auto par) ASGD_INLINE {
+                const int row = row0 + par * 32 + lrow, q = ks * 4 + half * 2, z = swz(row);
+                o[ks][par][0] = (unsigned)(row * 8 + (q ^ z)) * 16u;
+                o[ks][par][1] = (unsigned)(row * 8 + ((q + 1) ^ z)) * 16u;
+            });
+        });
+    }
+};
 template <> struct Frag<bf16_t> {
     uint4 v;
-    __device__ void read(const uint4 *sm, int row, int ks, int half) { v = sm[row * 8 + ((ks * 2 + half) ^ swz(row))]; }
+    template <int KS, int BLK> __device__ __forceinline__ void read(const char *sm, const FragOff<bf16_t> &fo)
+    {
+        v = *reinterpret_cast<const uint4 *>(sm + fo.o[KS][BLK % 2] + (BLK / 2) * (64 * 128));
+    }
 };
 template <> struct Frag<float> {
     uint4 v[2];
-    __device__ void read(const uint4 *sm, int row, int ks, int half)
+    template <int KS, int BLK> __device__ __forceinline__ void read(const char *sm, const FragOff<float> &fo)
     {
-        const int q = ks * 4 + half * 2, z = swz(row);
-        v[0] = sm[row * 8 + (q ^ z)];
-        v[1] = sm[row * 8 + ((q + 1) ^ z)];
+        v[0] = *reinterpret_cast<const uint4 *>(sm + fo.o[KS][BLK % 2][0] + (BLK / 2) * (64 * 128));
+        v[1] = *reinterpret_cast<const uint4 *>(sm + fo.o[KS][BLK % 2][1] + (BLK / 2) * (64 * 128));
     }
 };
 
-__device__ inline void mma(f32x16 &acc, const Frag<bf16_t> &first, const Frag<bf16_t> &second)
+__device__ __forceinline__ void mma(f32x16 &acc, const Frag<bf16_t> &first, const Frag<bf16_t> &second)
 {
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, first.v), __builtin_bit_cast(bf16x8, second.v),
                                                   acc, 0, 0, 0);
 }
-__device__ inline void mma(f32x16 &acc, const Frag<float> &first, const Frag<float> &second)
+__device__ __forceinline__ void mma(f32x16 &acc, const Frag<float> &first, const Frag<float> &second)
 {
     const uint32_t a[8] = {first.v[0].x, first.v[0].y, first.v[0].z, first.v[0].w, first.v[1].x, first.v[1].y, first.v[1].z, first.v[1].w};
     const uint32_t b[8] = {second.v[0].x, second.v[0].y, second.v[0].z, second.v[0].w, second.v[1].x, second.v[1].y, second.v[1].z, second.v[1].w};
@@ -279,7 +422,7 @@ __device__ inline void mma(f32x16 &acc, const Frag<float> &first, const Frag<flo
 }
 
 // ------------------------------------------------------------------ epilogue
-__device__ inline uint64_t mix64(uint64_t z)
+__device__ __forceinline__ uint64_t mix64(uint64_t z)
 {
     z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
     z ^= z >> 27; z *= 0x94D049BB133111EBull;
@@ -287,13 +430,13 @@ __device__ inline uint64_t mix64(uint64_t z)
     return z;
 }
 
-template <typename T> __device__ inline void store4(T *p, const float (&v)[4]);
-template <> __device__ inline void store4<float>(float *p, const float (&v)[4])
+template <typename T> __device__ __forceinline__ void store4(T *p, const float (&v)[4]);
+template <> __device__ __forceinline__ void store4<float>(float *p, const float (&v)[4])
 {
     if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
     else { p[0] = v[0]; p[1] = v[1]; p[2] = v[2]; p[3] = v[3]; }
 }
-template <> __device__ inline void store4<bf16_t>(bf16_t *p, const float (&v)[4])
+template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t *p, const float (&v)[4])
 {
     union { bf16_t h[4]; uint2 u; } t;
     t.h[0] = (bf16_t)v[0]; t.h[1] = (bf16_t)v[1]; t.h[2] = (bf16_t)v[2]; t.h[3] = (bf16_t)v[3];
@@ -302,7 +445,14 @@ template <> __device__ inline void store4<bf16_t>(bf16_t *p, const float (&v)[4]
 }
 
 // Four consecutive columns n0..n0+3 of row m (n0 a multiple of 4, all in range).
-template <typename T> __device__ inline void epilogue4(const Epilogue &ep, int m, int n0, float (&v)[4])
+template <typename T> struct Vec4;
+template <> struct Vec4<float> { union { float4 u; float e[4]; }; };
+template <> struct Vec4<bf16_t> { union { uint2 u; bf16_t e[4]; }; };
+
+// Four consecutive columns n0..n0+3 of row m (n0 a multiple of 4, all in range).
+// row_out = m * ep.ld and row_mask = m * ep.mask_ld are passed in so that a caller
+// handling several column groups of one row multiplies once.
+template <typename T> __device__ __forceinline__ void epilogue4(const Epilogue &ep, int m, long row_out, long row_mask, int n0, float (&v)[4])
 {
     if (ep.mode == 1) {  // conv filter gradient: (cout, (ky,kx,ci_padded)) -> canonical [cout][cin][kh][kw]
         if (m >= ep.cw_cout) return;
@@ -333,87 +483,112 @@ template <typename T> __device__ inline void epilogue4(const Epilogue &ep, int m
         }
     }
     if (ep.mask_src) {
-        const T *ms = static_cast<const T *>(ep.mask_src) + (long)m * ep.mask_ld + n0;
+        Vec4<T> ms;   // the mask tensor is a workspace tensor: rows and column groups are aligned
+        ms.u = *reinterpret_cast<const decltype(ms.u) *>(static_cast<const T *>(ep.mask_src) + row_mask + n0);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] = to_f32(ms[r]) > 0.f ? v[r] * ep.mask_scale : 0.f;
+        for (int r = 0; r < 4; ++r) v[r] = to_f32(ms.e[r]) > 0.f ? v[r] * ep.mask_scale : 0.f;
     }
-    if (ep.out_f32) store4<float>(static_cast<float *>(ep.out) + (long)m * ep.ld + n0, v);
-    else store4<T>(static_cast<T *>(ep.out) + (long)m * ep.ld + n0, v);
+    if (ep.out_f32) store4<float>(static_cast<float *>(ep.out) + row_out + n0, v);
+    else store4<T>(static_cast<T *>(ep.out) + row_out + n0, v);
 }
 
 // ------------------------------------------------------------------ kernel
-template <typename T, class LA, class LB>
-__global__ __launch_bounds__(NT) void gemm_kernel(LA la, LB lb, Epilogue ep, int M, int N, int nkt, int kt_per_split,
-                                                  int tiles_m, int tiles_n, float *ws)
+// One K tile out of LDS.  The fragments of K step ks+1 are requested before the
+// MFMAs of step ks are issued, so the LDS latency hides behind the matrix pipe.
+template <typename T, int BM, int BN>
+__device__ __forceinline__ void compute_tile(const uint4 *sA, const uint4 *sB, f32x16 (&acc)[BN / 64][BM / 64], const FragOff<T> &foA,
+                                             const FragOff<T> &foB)
+{
+    constexpr int MB = BM / 64, NB = BN / 64, KS = Geo<T>::KSTEPS;
+    const char *pa = reinterpret_cast<const char *>(sA), *pb = reinterpret_cast<const char *>(sB);
+    Frag<T> fa[2][MB], fb[2][NB];
+    static_for<0, MB>([&](auto mb) ASGD_INLINE { fa[0][mb].template read<0, mb>(pa, foA); });
+    static_for<0, NB>([&](auto nb) ASGD_INLINE { fb[0][nb].template read<0, nb>(pb, foB); });
+    static_for<0, KS>([&](auto ks) ASGD_INLINE {
+        constexpr int cur = ks % 2, nxt = (ks + 1) % 2;
+        if constexpr (ks + 1 < KS) {
+            static_for<0, MB>([&](auto mb) ASGD_INLINE { fa[nxt][mb].template read<ks + 1, mb>(pa, foA); });
+            static_for<0, NB>([&](auto nb) ASGD_INLINE { fb[nxt][nb].template read<ks + 1, nb>(pb, foB); });
+        }
+        static_for<0, NB>([&](auto nb) ASGD_INLINE { static_for<0, MB>([&](auto mb) ASGD_INLINE { mma(acc[nb][mb], fb[cur][nb], fa[cur][mb]); }); });
+    });
+}
+
+// Software pipeline: two K tiles are in flight in registers while a third is
+// being multiplied out of LDS; LDS holds two stages so that one barrier per K
+// tile suffices.  At the top of step t, LDS stage t%2 holds tile t, register set
+// (t+1)%2 holds tile t+1 (possibly still arriving) and register set t%2 is free.
+template <typename T, int BM, int BN, class LA, class LB>
+__global__ __launch_bounds__(NT, (BM > 128 ? 1 : 2)) void gemm_kernel(LA la, LB lb, Epilogue ep, int M, int N, int nkt, int kt_per_split,
+                                                                    int tiles_m, int tiles_n, float *ws)
 {
     constexpr int BK = Geo<T>::BK;
-    __shared__ uint4 sA[BM * 8];
-    __shared__ uint4 sB[BN * 8];
+    constexpr int MB = BM / 64, NB = BN / 64;   // MFMA 32x32 blocks per wave in m and n
+    __shared__ uint4 sA[2][BM * 8];
+    __shared__ uint4 sB[2][BN * 8];
     const int tid = threadIdx.x;
-    int bid = blockIdx.x;
+    // XCD-aware remap: ids congruent mod 8 run on one XCD; give that XCD a contiguous range of tiles
+    int bid;
+    {
+        const int nb = gridDim.x, q = nb >> 3, r = nb & 7, x = blockIdx.x & 7;
+        bid = x * q + (x < r ? x : r) + (blockIdx.x >> 3);
+    }
     const int tn = bid % tiles_n; bid /= tiles_n;
     const int tm = bid % tiles_m;
     const int split = bid / tiles_m;
     const int kt0 = split * kt_per_split;
-    const int kt1 = min(nkt, kt0 + kt_per_split);
+    const int nt = min(nkt, kt0 + kt_per_split) - kt0;   // K tiles of this workgroup (>= 1)
 
-    Stage<T, LA> stA;
-    Stage<T, LB> stB;
+    Stage<T, LA, BM> stA;
+    Stage<T, LB, BN> stB;
     stA.init(la, tm * BM, kt0 * BK, tid, 0);
     stB.init(lb, tn * BN, kt0 * BK, tid, NT / 2);
 
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    f32x16 acc[NB][MB];
+    static_for<0, NB>([&](auto i) ASGD_INLINE { static_for<0, MB>([&](auto j) ASGD_INLINE { acc[i][j] = f32x16{}; }); });
 
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave & 1) * 64, wn = (wave >> 1) * 64;
+    const int wm = (wave & 1) * (BM / 2), wn = (wave >> 1) * (BN / 2);
     const int lrow = lane & 31, half = lane >> 5;
+    FragOff<T> foA, foB;
+    foA.init(wm, lrow, half);
+    foB.init(wn, lrow, half);
 
-    if (kt0 < kt1) { stA.load(la); stB.load(lb); }
-    for (int kt = kt0; kt < kt1; ++kt) {
-        stA.store(sA, tid);
-        stB.store(sB, tid);
+    stA.template load<0>(la); stB.template load<0>(lb);
+    if (nt > 1) { stA.template load<1>(la); stB.template load<1>(lb); }
+    stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid);
+    for (int t = 0; t < nt; t += 2) {
+        // step t (even): compute from LDS stage 0; register set 0 is free, set 1 holds tile t+1
         __syncthreads();
-        if (kt + 1 < kt1) {
-            stA.next(la); stB.next(lb);
-            stA.load(la); stB.load(lb);
+        if (t + 2 < nt) { stA.template load<0>(la); stB.template load<0>(lb); }
+        compute_tile<T, BM, BN>(sA[0], sB[0], acc, foA, foB);
+        if (t + 1 < nt) {
+            stA.template store<1>(sA[1], tid); stB.template store<1>(sB[1], tid);
+            // step t+1 (odd): compute from LDS stage 1; register set 1 is free, set 0 holds tile t+2
+            __syncthreads();
+            if (t + 3 < nt) { stA.template load<1>(la); stB.template load<1>(lb); }
+            compute_tile<T, BM, BN>(sA[1], sB[1], acc, foA, foB);
+            if (t + 2 < nt) { stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid); }
         }
-#pragma unroll
-        for (int ks = 0; ks < Geo<T>::KSTEPS; ++ks) {
-            Frag<T> fa[2], fb[2];
-            fa[0].read(sA, wm + lrow, ks, half);
-            fa[1].read(sA, wm + 32 + lrow, ks, half);
-            fb[0].read(sB, wn + lrow, ks, half);
-            fb[1].read(sB, wn + 32 + lrow, ks, half);
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb) mma(acc[nb][mb], fb[nb], fa[mb]);
-        }
-        __syncthreads();
     }
 
     // acc[nb][mb][v]: m = wm + mb*32 + lrow, n = wn + nb*32 + 8*(v/4) + 4*half + v%4
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
+    static_for<0, MB>([&](auto mb) ASGD_INLINE {
         const int m = tm * BM + wm + mb * 32 + lrow;
-        if (m >= M) continue;
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n0 = tn * BN + wn + nb * 32 + 8 * g + 4 * half;
-                if (n0 >= N) continue;
-                float v[4] = {acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]};
-                if (ws) store4<float>(ws + ((long)split * M + m) * N + n0, v);
-                else epilogue4<T>(ep, m, n0, v);
-            }
-    }
+        if (m < M) {
+            const long row_out = (long)m * ep.ld, row_mask = (long)m * ep.mask_ld;
+            static_for<0, NB>([&](auto nb) ASGD_INLINE {
+                static_for<0, 4>([&](auto g) ASGD_INLINE {
+                    const int n0 = tn * BN + wn + nb * 32 + 8 * g + 4 * half;
+                    if (n0 < N) {
+                        float v[4] = {acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]};
+                        if (ws) store4<float>(ws + ((long)split * M + m) * N + n0, v);
+                        else epilogue4<T>(ep, m, row_out, row_mask, n0, v);
+                    }
+                });
+            });
+        }
+    });
 }
 
 template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int splits, Epilogue ep, int M, int N)
@@ -427,13 +602,24 @@ template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_kerne
         const float4 p = *reinterpret_cast<const float4 *>(ws + ((long)s * M + m) * N + n0);
         v[0] += p.x; v[1] += p.y; v[2] += p.z; v[3] += p.w;
     }
-    epilogue4<T>(ep, m, n0, v);
+    epilogue4<T>(ep, m, (long)m * ep.ld, (long)m * ep.mask_ld, n0, v);
 }
 
 // ------------------------------------------------------------------ host side
+// 256-row tiles when they do not add much padding over 128-row tiles.
+static int pick_bm(long M)
+{
+    static const char *force = getenv("ASGD_TILE");
+    if (!force || force[0] != '2') return 128;   // 256-row tiles measured slower so far
+    if (M < 256) return 128;
+    const long p256 = (M + 255) / 256 * 256, p128 = (M + 127) / 128 * 128;
+    return p256 * 100 <= p128 * 112 ? 256 : 128;
+}
+
 GemmPlan plan_gemm(long M, long N, long K, int dtype, int max_splits)
 {
     const int BK = dtype == kBF16 ? (int)Geo<bf16_t>::BK : (int)Geo<float>::BK;
+    const int BM = pick_bm(M), BN = 128;
     const long tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
     const long nkt = (K + BK - 1) / BK;
     long splits = 1;
@@ -453,10 +639,9 @@ GemmPlan plan_gemm(long M, long N, long K, int dtype, int max_splits)
     return p;
 }
 
-template <typename T, class LA, class LB>
-static int run(const LA &la, const LB &lb, int M, int N, int K, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
+template <typename T, int BM, int BN, class LA, class LB>
+static int run_tile(const LA &la, const LB &lb, int M, int N, int K, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
-    if (M <= 0 || N <= 0 || K <= 0 || (N & 3)) return -1;
     constexpr int BK = Geo<T>::BK;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int nkt = (K + BK - 1) / BK;
@@ -466,7 +651,7 @@ static int run(const LA &la, const LB &lb, int M, int N, int K, const Epilogue &
     splits = (nkt + per - 1) / per;
     const long blocks = (long)tiles_m * tiles_n * splits;
     if (blocks > 0x7fffffffL) return -1;
-    hipLaunchKernelGGL((gemm_kernel<T, LA, LB>), dim3((unsigned)blocks), dim3(NT), 0, s, la, lb, ep, M, N, nkt, per, tiles_m,
+    hipLaunchKernelGGL((gemm_kernel<T, BM, BN, LA, LB>), dim3((unsigned)blocks), dim3(NT), 0, s, la, lb, ep, M, N, nkt, per, tiles_m,
                        tiles_n, splits > 1 ? ws : nullptr);
     if (splits > 1) {
         const long groups = (long)M * (N / 4);
@@ -475,9 +660,26 @@ static int run(const LA &la, const LB &lb, int M, int N, int K, const Epilogue &
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-template <typename T> static GatherK<T> make_gather_k(const Gather &g)
+template <typename T, class LA, class LB>
+static int run(const LA &la, const LB &lb, int M, int N, int K, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
-    GatherK<T> l;
+    if (M <= 0 || N <= 0 || K <= 0 || (N & 3)) return -1;
+    if (pick_bm(M) == 256) return run_tile<T, 256, 128>(la, lb, M, N, K, ep, plan, ws, s);
+    return run_tile<T, 128, 128>(la, lb, M, N, K, ep, plan, ws, s);
+}
+
+template <typename T, bool WIDE> static GatherK<T, WIDE> make_gather_k(const Gather &g)
+{
+    GatherK<T, WIDE> l;
+    l.x = static_cast<const char *>(g.x); l.zero_off = (unsigned)g.zero_off;
+    l.H = g.H; l.W = g.W; l.C = g.C; l.Ho = g.Ho; l.Wo = g.Wo; l.kh = g.kh; l.kw = g.kw;
+    l.sm = g.sm; l.pad = g.pad; l.M = g.N * g.Ho * g.Wo;
+    l.dWo = make_fastdiv(g.Wo); l.dHoWo = make_fastdiv(g.Ho * g.Wo); l.dC = make_fastdiv(g.C); l.dkw = make_fastdiv(g.kw);
+    return l;
+}
+template <typename T> static GatherKS<T> make_gather_ks(const Gather &g)
+{
+    GatherKS<T> l;
     l.x = static_cast<const T *>(g.x);
     l.H = g.H; l.W = g.W; l.C = g.C; l.Ho = g.Ho; l.Wo = g.Wo; l.kh = g.kh; l.kw = g.kw;
     l.sm = g.sm; l.ds = g.ds; l.pad = g.pad; l.M = g.N * g.Ho * g.Wo;
@@ -487,63 +689,72 @@ template <typename T> static GatherK<T> make_gather_k(const Gather &g)
 template <typename T> static GatherT<T> make_gather_t(const Gather &g)
 {
     GatherT<T> l;
-    l.x = static_cast<const T *>(g.x);
+    l.x = static_cast<const char *>(g.x); l.zero_off = (unsigned)g.zero_off;
     l.H = g.H; l.W = g.W; l.C = g.C; l.Ho = g.Ho; l.Wo = g.Wo; l.kh = g.kh; l.kw = g.kw;
     l.sm = g.sm; l.pad = g.pad; l.M = g.N * g.Ho * g.Wo; l.Krows = g.kh * g.kw * g.C;
     l.dWo = make_fastdiv(g.Wo); l.dHoWo = make_fastdiv(g.Ho * g.Wo); l.dC = make_fastdiv(g.C); l.dkw = make_fastdiv(g.kw);
     return l;
 }
-template <typename T> static PlainK<T> make_plain_k(const void *p, long ld, int rows, int K)
+template <typename T> static PlainK<T> make_plain_k(const void *p, long ld, int rows, int K, const void *zero)
 {
-    return PlainK<T>{static_cast<const T *>(p), ld, rows, K};
+    return PlainK<T>{static_cast<const T *>(p), ld, rows, K, static_cast<const T *>(zero)};
 }
-template <typename T> static PlainT<T> make_plain_t(const void *p, long ld, int rows, int K)
+template <typename T> static PlainT<T> make_plain_t(const void *p, long ld, int rows, int K, const void *zero)
 {
-    return PlainT<T>{static_cast<const T *>(p), ld, rows, K};
+    return PlainT<T>{static_cast<const T *>(p), ld, rows, K, static_cast<const T *>(zero)};
 }
 
 template <typename T>
-static int gather_plain_t(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
+static int gather_plain_t(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, const void *zero,
+                          hipStream_t s)
 {
     const int K = a.kh * a.kw * a.C;
-    return run<T>(make_gather_k<T>(a), make_plain_k<T>(b, ldb, N, K), a.N * a.Ho * a.Wo, N, K, ep, plan, ws, s);
+    if (a.ds == 1 && a.kh * a.kw <= 32)
+        return run<T>(make_gather_k<T, false>(a), make_plain_k<T>(b, ldb, N, K, zero), a.N * a.Ho * a.Wo, N, K, ep, plan, ws, s);
+    if (a.ds == 1)
+        return run<T>(make_gather_k<T, true>(a), make_plain_k<T>(b, ldb, N, K, zero), a.N * a.Ho * a.Wo, N, K, ep, plan, ws, s);
+    return run<T>(make_gather_ks<T>(a), make_plain_k<T>(b, ldb, N, K, zero), a.N * a.Ho * a.Wo, N, K, ep, plan, ws, s);
 }
 int gemm_gather_plain(int dtype, const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws,
-                      hipStream_t s)
+                      const void *zero, hipStream_t s)
 {
     if (a.ds != 1 && a.sm != 1) return -1;
-    return dtype == kBF16 ? gather_plain_t<bf16_t>(a, b, ldb, N, ep, plan, ws, s) : gather_plain_t<float>(a, b, ldb, N, ep, plan, ws, s);
+    if (a.kh > 15 || a.kw > 15) return -1;
+    return dtype == kBF16 ? gather_plain_t<bf16_t>(a, b, ldb, N, ep, plan, ws, zero, s) : gather_plain_t<float>(a, b, ldb, N, ep, plan, ws, zero, s);
 }
 
 int gemm_plain_plain(int dtype, const void *a, long lda, int M, const void *b, long ldb, int N, int b_rows, int K, const Epilogue &ep,
-                     const GemmPlan &plan, float *ws, hipStream_t s)
+                     const GemmPlan &plan, float *ws, const void *zero, hipStream_t s)
 {
     if (b_rows > N) return -1;
-    if (dtype == kBF16) return run<bf16_t>(make_plain_k<bf16_t>(a, lda, M, K), make_plain_k<bf16_t>(b, ldb, b_rows, K), M, N, K, ep, plan, ws, s);
-    return run<float>(make_plain_k<float>(a, lda, M, K), make_plain_k<float>(b, ldb, b_rows, K), M, N, K, ep, plan, ws, s);
+    if (dtype == kBF16)
+        return run<bf16_t>(make_plain_k<bf16_t>(a, lda, M, K, zero), make_plain_k<bf16_t>(b, ldb, b_rows, K, zero), M, N, K, ep, plan, ws, s);
+    return run<float>(make_plain_k<float>(a, lda, M, K, zero), make_plain_k<float>(b, ldb, b_rows, K, zero), M, N, K, ep, plan, ws, s);
 }
 
 int gemm_plain_trans(int dtype, const void *a, long lda, int M, const void *bt, long ldb, int N, int K, const Epilogue &ep,
-                     const GemmPlan &plan, float *ws, hipStream_t s)
+                     const GemmPlan &plan, float *ws, const void *zero, hipStream_t s)
 {
-    if (dtype == kBF16) return run<bf16_t>(make_plain_k<bf16_t>(a, lda, M, K), make_plain_t<bf16_t>(bt, ldb, N, K), M, N, K, ep, plan, ws, s);
-    return run<float>(make_plain_k<float>(a, lda, M, K), make_plain_t<float>(bt, ldb, N, K), M, N, K, ep, plan, ws, s);
+    if (dtype == kBF16)
+        return run<bf16_t>(make_plain_k<bf16_t>(a, lda, M, K, zero), make_plain_t<bf16_t>(bt, ldb, N, K, zero), M, N, K, ep, plan, ws, s);
+    return run<float>(make_plain_k<float>(a, lda, M, K, zero), make_plain_t<float>(bt, ldb, N, K, zero), M, N, K, ep, plan, ws, s);
 }
 
 int gemm_trans_trans(int dtype, const void *at, long lda, int M, const void *bt, long ldb, int N, int K, const Epilogue &ep,
-                     const GemmPlan &plan, float *ws, hipStream_t s)
+                     const GemmPlan &plan, float *ws, const void *zero, hipStream_t s)
 {
-    if (dtype == kBF16) return run<bf16_t>(make_plain_t<bf16_t>(at, lda, M, K), make_plain_t<bf16_t>(bt, ldb, N, K), M, N, K, ep, plan, ws, s);
-    return run<float>(make_plain_t<float>(at, lda, M, K), make_plain_t<float>(bt, ldb, N, K), M, N, K, ep, plan, ws, s);
+    if (dtype == kBF16)
+        return run<bf16_t>(make_plain_t<bf16_t>(at, lda, M, K, zero), make_plain_t<bf16_t>(bt, ldb, N, K, zero), M, N, K, ep, plan, ws, s);
+    return run<float>(make_plain_t<float>(at, lda, M, K, zero), make_plain_t<float>(bt, ldb, N, K, zero), M, N, K, ep, plan, ws, s);
 }
 
 int gemm_trans_gather(int dtype, const void *at, long lda, int M, const Gather &b, const Epilogue &ep, const GemmPlan &plan, float *ws,
-                      hipStream_t s)
+                      const void *zero, hipStream_t s)
 {
     if (b.ds != 1) return -1;
     const int K = b.N * b.Ho * b.Wo, N = b.kh * b.kw * b.C;
-    if (dtype == kBF16) return run<bf16_t>(make_plain_t<bf16_t>(at, lda, M, K), make_gather_t<bf16_t>(b), M, N, K, ep, plan, ws, s);
-    return run<float>(make_plain_t<float>(at, lda, M, K), make_gather_t<float>(b), M, N, K, ep, plan, ws, s);
+    if (dtype == kBF16) return run<bf16_t>(make_plain_t<bf16_t>(at, lda, M, K, zero), make_gather_t<bf16_t>(b), M, N, K, ep, plan, ws, s);
+    return run<float>(make_plain_t<float>(at, lda, M, K, zero), make_gather_t<float>(b), M, N, K, ep, plan, ws, s);
 }
 
 }  // namespace asgd

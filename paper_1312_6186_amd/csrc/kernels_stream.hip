@@ -159,16 +159,27 @@ int launch_fill_zero(void *p, size_t bytes, hipStream_t s)
 template <typename T> __global__ __launch_bounds__(256) void stage_input_kernel(const T *__restrict__ src, T *__restrict__ dst, int B, int C, int H,
                                                                               int W, int Cp)
 {
-    const long pix = (long)blockIdx.x * 256 + threadIdx.x;  // (n, h, w)
+    // one thread per pixel and 16-byte channel group: reads are contiguous along w for each channel,
+    // the store is one vector
+    constexpr int V = 16 / sizeof(T);
+    const int groups = Cp / V;
     const long HW = (long)H * W;
-    if (pix >= (long)B * HW) return;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long)B * HW * groups) return;
+    const long pix = i % ((long)B * HW);       // pixels fastest: neighbouring threads read neighbouring w
+    const int gidx = (int)(i / ((long)B * HW));
     const long n = pix / HW, hw = pix - n * HW;
-    T *d = dst + pix * Cp;
-    for (int c = 0; c < Cp; ++c) d[c] = c < C ? src[(n * C + c) * HW + hw] : (T)0.f;
+    union { uint4 u; T e[V]; } v;
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        const int c = gidx * V + e;
+        v.e[e] = c < C ? src[(n * C + c) * HW + hw] : (T)0.f;
+    }
+    *reinterpret_cast<uint4 *>(dst + pix * Cp + gidx * V) = v.u;
 }
 int launch_stage_input(int dtype, const void *src, void *dst, int B, int C, int H, int W, int Cp, hipStream_t s)
 {
-    const unsigned blocks = blocks_for((size_t)B * H * W, 256);
+    const unsigned blocks = blocks_for((size_t)B * H * W * (Cp / (dtype == kBF16 ? 8 : 4)), 256);
     if (dtype == kBF16)
         hipLaunchKernelGGL(stage_input_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(src), static_cast<bf16_t *>(dst), B, C, H, W, Cp);
     else
@@ -380,37 +391,92 @@ int launch_unflatten(int dtype, const void *dflat, const void *x, int relu, void
 }
 
 // ---------------------------------------------------------------- bias gradient (column sums)
-constexpr int CS_ROWS = 2048;  // rows per first-stage block
+// Stage 1: a block owns a band of rows and up to 256 column chunks of 16 bytes;
+// thread (c, r) adds rows r, r+RL, ... of chunk c, the RL row lanes are then
+// added in lane order.  Stage 2 adds the bands in order.  No atomics, so the
+// result does not depend on scheduling.
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_stage1(const T *__restrict__ dy, long ld, long M, int N, float *__restrict__ ws)
+__global__ __launch_bounds__(256) void colsum_stage1(const T *__restrict__ dy, long ld, long M, int chunks, int cpb, int rl, long rows_per_block,
+                                                    float *__restrict__ ws)
 {
-    __shared__ float part[4][64];
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const int n = blockIdx.x * 64 + tx;
-    const long m0 = (long)blockIdx.y * CS_ROWS, m1 = min(M, m0 + CS_ROWS);
-    float acc = 0.f;
-    if (n < N)
-        for (long m = m0 + ty; m < m1; m += 4) acc += ldf(&dy[m * ld + n]);
-    part[ty][tx] = acc;
+    constexpr int V = 16 / sizeof(T);
+    __shared__ float part[256 * V];
+    const int c = threadIdx.x % cpb, r = threadIdx.x / cpb;
+    const int gc = blockIdx.x * cpb + c;
+    const long m0 = (long)blockIdx.y * rows_per_block, m1 = min(M, m0 + rows_per_block);
+    float acc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] = 0.f;
+    if (r < rl && gc < chunks) {
+        for (long m = m0 + r; m < m1; m += rl) {
+            union { uint4 u; T e[V]; } v;
+            v.u = *reinterpret_cast<const uint4 *>(dy + m * ld + (long)gc * V);
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[e] += ldf(&v.e[e]);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) part[threadIdx.x * V + e] = acc[e];
     __syncthreads();
-    if (ty == 0 && n < N) ws[(long)blockIdx.y * N + n] = ((part[0][tx] + part[1][tx]) + part[2][tx]) + part[3][tx];
+    if (r == 0 && gc < chunks) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            float t = 0.f;
+            for (int j = 0; j < rl; ++j) t += part[(j * cpb + c) * V + e];
+            ws[(long)blockIdx.y * ld + (long)gc * V + e] = t;
+        }
+    }
 }
-__global__ __launch_bounds__(256) void colsum_stage2(const float *__restrict__ ws, int nblk, int N, float *__restrict__ db)
+__global__ __launch_bounds__(256) void colsum_stage2(const float *__restrict__ ws, int nblk, long ld, int N, float *__restrict__ db)
 {
-    const int n = blockIdx.x * 256 + threadIdx.x;
-    if (n >= N) return;
-    float acc = 0.f;
-    for (int b = 0; b < nblk; ++b) acc += ws[(long)b * N + n];
-    db[n] = acc;
+    // 8 columns per block, 32 lanes per column; a lane adds bands lane, lane+32, ... (four loads in flight),
+    // then the lanes are added in order
+    __shared__ float part[32][8];
+    const int tx = threadIdx.x & 7, ty = threadIdx.x >> 3;
+    const int n = blockIdx.x * 8 + tx;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    if (n < N) {
+        int b = ty;
+        for (; b + 96 < nblk; b += 128) {
+            a0 += ws[(long)b * ld + n]; a1 += ws[(long)(b + 32) * ld + n];
+            a2 += ws[(long)(b + 64) * ld + n]; a3 += ws[(long)(b + 96) * ld + n];
+        }
+        for (; b < nblk; b += 32) a0 += ws[(long)b * ld + n];
+    }
+    part[ty][tx] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    if (ty == 0 && n < N) {
+        float t = 0.f;
+        for (int j = 0; j < 32; ++j) t += part[j][tx];
+        db[n] = t;
+    }
 }
-size_t colsum_ws_floats(long M, int N) { return (size_t)((M + CS_ROWS - 1) / CS_ROWS) * (size_t)N; }
+static void colsum_geometry(int dtype, long ld, long M, int &chunks, int &cpb, int &rl, long &rows_per_block, int &nblk)
+{
+    const int V = dtype == kBF16 ? 8 : 4;
+    chunks = (int)(ld / V);
+    cpb = chunks < 256 ? chunks : 256;
+    rl = 256 / cpb;
+    rows_per_block = (M + 511) / 512;
+    if (rows_per_block < 4L * rl) rows_per_block = 4L * rl;
+    rows_per_block = (rows_per_block + rl - 1) / rl * rl;
+    nblk = (int)((M + rows_per_block - 1) / rows_per_block);
+}
+size_t colsum_ws_floats(int dtype, long M, long ld)
+{
+    int chunks, cpb, rl, nblk; long rpb;
+    colsum_geometry(dtype, ld, M, chunks, cpb, rl, rpb, nblk);
+    return (size_t)nblk * (size_t)ld;
+}
+// dy is [M][ld] with ld a multiple of 8 and columns N..ld-1 zero or ignorable
 int launch_colsum(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, hipStream_t s)
 {
-    const int nblk = (int)((M + CS_ROWS - 1) / CS_ROWS);
-    const dim3 grid((N + 63) / 64, nblk);
-    if (dtype == kBF16) hipLaunchKernelGGL(colsum_stage1<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(dy), ld, M, N, ws);
-    else hipLaunchKernelGGL(colsum_stage1<float>, grid, dim3(256), 0, s, static_cast<const float *>(dy), ld, M, N, ws);
-    hipLaunchKernelGGL(colsum_stage2, dim3((N + 255) / 256), dim3(256), 0, s, ws, nblk, N, db);
+    int chunks, cpb, rl, nblk; long rpb;
+    colsum_geometry(dtype, ld, M, chunks, cpb, rl, rpb, nblk);
+    const dim3 grid((chunks + cpb - 1) / cpb, nblk);
+    if (dtype == kBF16) hipLaunchKernelGGL(colsum_stage1<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(dy), ld, M, chunks, cpb, rl, rpb, ws);
+    else hipLaunchKernelGGL(colsum_stage1<float>, grid, dim3(256), 0, s, static_cast<const float *>(dy), ld, M, chunks, cpb, rl, rpb, ws);
+    hipLaunchKernelGGL(colsum_stage2, dim3((N + 7) / 8), dim3(256), 0, s, ws, nblk, ld, N, db);
     return launch_ok();
 }
 

@@ -33,7 +33,16 @@ template <typename T> struct Geo;
 template <> struct Geo<bf16_t> { enum { CH = 8, BK = 64, KSTEPS = 4 }; };
 template <> struct Geo<float> { enum { CH = 4, BK = 32, KSTEPS = 2 }; };
 
-constexpr int NT = 256;
+// Tile configuration: block tile BM x BN, WAVES_M x WAVES_N wave64s, DEPTH K tiles in flight in registers,
+// MINB workgroups per CU the register budget is sized for.
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int DEPTH_, int MINB_> struct TileCfg {
+    static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, DEPTH = DEPTH_, MINB = MINB_;
+    static constexpr int NT = 64 * WAVES_M_ * WAVES_N_;
+    static constexpr int MB = BM_ / WAVES_M_ / 32, NB = BN_ / WAVES_N_ / 32;   // MFMA 32x32 blocks per wave
+    static_assert((BM_ / WAVES_M_) % 64 == 0 && (BN_ / WAVES_N_) % 64 == 0, "wave tiles are multiples of 64");
+};
+using CfgSmall = TileCfg<128, 128, 2, 2, 2, 2>;   // 256 threads, two workgroups per CU
+using CfgLarge = TileCfg<256, 256, 2, 2, 2, 1>;   // 256 threads, 128x128 per wave (accumulators fill the AGPRs), one workgroup per CU
 #define ASGD_INLINE __attribute__((always_inline))
 
 // Compile-time loop: indices reach the body as constants, so register arrays are never addressed dynamically.
@@ -93,6 +102,7 @@ template <typename T, bool WIDE> struct GatherK {
     static constexpr bool kTrans = false;
     const char *x; unsigned zero_off;
     int H, W, C, Ho, Wo, kh, kw, sm, pad, M;
+    int adv_px, adv_c;   // one K tile = adv_px whole pixels + adv_c channels
     FastDiv dWo, dHoWo, dC, dkw;
     struct Row { unsigned off, mask; };
     struct KPos { int ky, kx, c; unsigned delta, bit; };
@@ -119,8 +129,8 @@ template <typename T, bool WIDE> struct GatherK {
     }
     __device__ __forceinline__ unsigned bit_of(int ky, int kx) const
     {
-        if (ky >= kh) return 0u;
-        return WIDE ? ((1u << ky) | (1u << (16 + kx))) : (1u << (ky * kw + kx));
+        const unsigned b = WIDE ? ((1u << (ky & 15)) | (1u << (16 + kx))) : (1u << ((ky * kw + kx) & 31));
+        return ky < kh ? b : 0u;
     }
     __device__ __forceinline__ KPos kpos(int k) const
     {
@@ -129,17 +139,18 @@ template <typename T, bool WIDE> struct GatherK {
         const int kx = t - ky * kw, c = k - t * C;
         return KPos{ky, kx, c, (unsigned)((ky * W + kx) * C + c) * (unsigned)sizeof(T), bit_of(ky, kx)};
     }
-    __device__ __forceinline__ void advance(KPos &kp, int dk) const
+    // branch-free: no divergent control flow between the loads of a pipeline step
+    __device__ __forceinline__ void advance(KPos &kp, int) const
     {
-        kp.c += dk;
-        kp.delta += (unsigned)dk * (unsigned)sizeof(T);
-        if (kp.c >= C) {
-            do {
-                kp.c -= C;
-                if (++kp.kx == kw) { kp.kx = 0; ++kp.ky; kp.delta += (unsigned)((W - kw) * C) * (unsigned)sizeof(T); }
-            } while (kp.c >= C);
-            kp.bit = bit_of(kp.ky, kp.kx);
-        }
+        kp.c += adv_c;
+        const int wrap = kp.c >= C ? 1 : 0;
+        kp.c -= wrap * C;
+        kp.kx += adv_px + wrap;
+        const int up = (int)fdiv((uint32_t)kp.kx, dkw);
+        kp.kx -= up * kw;
+        kp.ky += up;
+        kp.delta = (unsigned)((kp.ky * W + kp.kx) * C + kp.c) * (unsigned)sizeof(T);
+        kp.bit = bit_of(kp.ky, kp.kx);
     }
     __device__ __forceinline__ uint4 load(const Row &r, const KPos &kp) const
     {
@@ -260,13 +271,13 @@ template <typename T> struct GatherT {
 };
 
 // ------------------------------------------------------------------ staging
-template <typename T, class L, int ROWS, bool kTrans = L::kTrans> struct Stage;
+template <typename T, class L, int ROWS, int NT, int DEPTH, bool kTrans = L::kTrans> struct Stage;
 
-template <typename T, class L, int ROWS> struct Stage<T, L, ROWS, false> {
+template <typename T, class L, int ROWS, int NT, int DEPTH> struct Stage<T, L, ROWS, NT, DEPTH, false> {
     static constexpr int SLOTS = ROWS * 8 / NT;
     typename L::Row rows[SLOTS];
     typename L::KPos kp;
-    uint4 r[2][SLOTS];   // two K tiles in flight
+    uint4 r[DEPTH][SLOTS];   // DEPTH K tiles in flight
     unsigned wo[2];      // LDS byte offset of slot 0 / slot 1; slot s sits s/2 * 64 rows further
     __device__ __forceinline__ void init(const L &l, int row0, int k0, int tid, int)
     {
@@ -316,7 +327,7 @@ __device__ __forceinline__ void transpose_unit(const uint4 (&r)[8], uint4 (&o)[8
     o[7] = make_uint4(pack_hi(r[0].w, r[1].w), pack_hi(r[2].w, r[3].w), pack_hi(r[4].w, r[5].w), pack_hi(r[6].w, r[7].w));
 }
 
-template <typename T, class L, int ROWS> struct Stage<T, L, ROWS, true> {
+template <typename T, class L, int ROWS, int NT, int DEPTH> struct Stage<T, L, ROWS, NT, DEPTH, true> {
     static constexpr int CH = Geo<T>::CH;
     static constexpr int RCH = ROWS / CH;            // row chunks per tile
     static constexpr int NUNITS = RCH * 8;           // x 8 slots along K
@@ -324,7 +335,7 @@ template <typename T, class L, int ROWS> struct Stage<T, L, ROWS, true> {
     typename L::Unit un[UPT];
     int k;
     int vt;
-    uint4 r[2][UPT][CH];
+    uint4 r[DEPTH][UPT][CH];
     __device__ __forceinline__ void init(const L &l, int row0, int k0, int tid, int shift)
     {
         vt = (tid + shift) & (NT - 1);               // spreads the two operands over different waves
@@ -430,29 +441,36 @@ __device__ __forceinline__ uint64_t mix64(uint64_t z)
     return z;
 }
 
-template <typename T> __device__ __forceinline__ void store4(T *p, const float (&v)[4]);
-template <> __device__ __forceinline__ void store4<float>(float *p, const float (&v)[4])
+// Store of 8 consecutive output elements (32 bytes fp32 / 16 bytes bf16), vectorised when aligned.
+template <typename T> __device__ __forceinline__ void store8(T *p, const float (&v)[8]);
+template <> __device__ __forceinline__ void store8<float>(float *p, const float (&v)[8])
 {
-    if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
-    else { p[0] = v[0]; p[1] = v[1]; p[2] = v[2]; p[3] = v[3]; }
+    if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) {
+        reinterpret_cast<float4 *>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
+        reinterpret_cast<float4 *>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) p[r] = v[r];
+    }
 }
-template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t *p, const float (&v)[4])
+template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t *p, const float (&v)[8])
 {
-    union { bf16_t h[4]; uint2 u; } t;
-    t.h[0] = (bf16_t)v[0]; t.h[1] = (bf16_t)v[1]; t.h[2] = (bf16_t)v[2]; t.h[3] = (bf16_t)v[3];
-    if ((reinterpret_cast<uintptr_t>(p) & 7) == 0) *reinterpret_cast<uint2 *>(p) = t.u;
-    else { p[0] = t.h[0]; p[1] = t.h[1]; p[2] = t.h[2]; p[3] = t.h[3]; }
+    union { bf16_t h[8]; uint4 u; } t;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) t.h[r] = (bf16_t)v[r];
+    if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) *reinterpret_cast<uint4 *>(p) = t.u;
+    else {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) p[r] = t.h[r];
+    }
 }
 
-// Four consecutive columns n0..n0+3 of row m (n0 a multiple of 4, all in range).
-template <typename T> struct Vec4;
-template <> struct Vec4<float> { union { float4 u; float e[4]; }; };
-template <> struct Vec4<bf16_t> { union { uint2 u; bf16_t e[4]; }; };
+template <typename T> struct Vec8;
+template <> struct Vec8<float> { union { float4 u[2]; float e[8]; }; };
+template <> struct Vec8<bf16_t> { union { uint4 u[1]; bf16_t e[8]; }; };
 
-// Four consecutive columns n0..n0+3 of row m (n0 a multiple of 4, all in range).
-// row_out = m * ep.ld and row_mask = m * ep.mask_ld are passed in so that a caller
-// handling several column groups of one row multiplies once.
-template <typename T> __device__ __forceinline__ void epilogue4(const Epilogue &ep, int m, long row_out, long row_mask, int n0, float (&v)[4])
+// Eight consecutive columns n0..n0+7 of row m (n0 a multiple of 8, all in range).
+template <typename T> __device__ __forceinline__ void epilogue8(const Epilogue &ep, int m, int n0, float (&v)[8])
 {
     if (ep.mode == 1) {  // conv filter gradient: (cout, (ky,kx,ci_padded)) -> canonical [cout][cin][kh][kw]
         if (m >= ep.cw_cout) return;
@@ -460,46 +478,47 @@ template <typename T> __device__ __forceinline__ void epilogue4(const Epilogue &
         const int ky = t / ep.cw_kw, kx = t - ky * ep.cw_kw;
         float *o = static_cast<float *>(ep.out);
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < 8; ++r)
             if (ci0 + r < ep.cw_cin) o[(((long)m * ep.cw_cin + ci0 + r) * ep.cw_kh + ky) * ep.cw_kw + kx] = v[r];
         return;
     }
     if (ep.bias) {
         const T *b = static_cast<const T *>(ep.bias);
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < 8; ++r)
             if (n0 + r < ep.bias_n) v[r] += to_f32(b[n0 + r]);
     }
     if (ep.relu) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] = v[r] > 0.f ? v[r] : 0.f;
+        for (int r = 0; r < 8; ++r) v[r] = v[r] > 0.f ? v[r] : 0.f;
     }
     if (ep.drop) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < 8; ++r) {
             const uint64_t idx = (uint64_t)m * (uint64_t)ep.drop_F + (uint64_t)(n0 + r);
             const uint32_t u = (uint32_t)(mix64(ep.drop_key + 0x9E3779B97F4A7C15ull * (idx + 1)) >> 32);
             v[r] = (u >= ep.drop_thr) ? v[r] * ep.drop_scale : 0.f;
         }
     }
     if (ep.mask_src) {
-        Vec4<T> ms;   // the mask tensor is a workspace tensor: rows and column groups are aligned
-        ms.u = *reinterpret_cast<const decltype(ms.u) *>(static_cast<const T *>(ep.mask_src) + row_mask + n0);
+        Vec8<T> ms;   // the mask tensor is a workspace tensor: rows and column groups are 16-byte aligned
+        const T *mp = static_cast<const T *>(ep.mask_src) + (long)m * ep.mask_ld + n0;
+        static_for<0, sizeof(ms.u) / 16>([&](auto i) ASGD_INLINE { ms.u[i] = reinterpret_cast<const std::remove_reference_t<decltype(ms.u[0])> *>(mp)[i]; });
 #pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] = to_f32(ms.e[r]) > 0.f ? v[r] * ep.mask_scale : 0.f;
+        for (int r = 0; r < 8; ++r) v[r] = to_f32(ms.e[r]) > 0.f ? v[r] * ep.mask_scale : 0.f;
     }
-    if (ep.out_f32) store4<float>(static_cast<float *>(ep.out) + row_out + n0, v);
-    else store4<T>(static_cast<T *>(ep.out) + row_out + n0, v);
+    if (ep.out_f32) store8<float>(static_cast<float *>(ep.out) + (long)m * ep.ld + n0, v);
+    else store8<T>(static_cast<T *>(ep.out) + (long)m * ep.ld + n0, v);
 }
 
 // ------------------------------------------------------------------ kernel
 // One K tile out of LDS.  The fragments of K step ks+1 are requested before the
 // MFMAs of step ks are issued, so the LDS latency hides behind the matrix pipe.
-template <typename T, int BM, int BN>
-__device__ __forceinline__ void compute_tile(const uint4 *sA, const uint4 *sB, f32x16 (&acc)[BN / 64][BM / 64], const FragOff<T> &foA,
+template <typename T, int MB, int NB>
+__device__ __forceinline__ void compute_tile(const uint4 *sA, const uint4 *sB, f32x16 (&acc)[NB][MB], const FragOff<T> &foA,
                                              const FragOff<T> &foB)
 {
-    constexpr int MB = BM / 64, NB = BN / 64, KS = Geo<T>::KSTEPS;
+    constexpr int KS = Geo<T>::KSTEPS;
     const char *pa = reinterpret_cast<const char *>(sA), *pb = reinterpret_cast<const char *>(sB);
     Frag<T> fa[2][MB], fb[2][NB];
     static_for<0, MB>([&](auto mb) ASGD_INLINE { fa[0][mb].template read<0, mb>(pa, foA); });
@@ -514,18 +533,18 @@ __device__ __forceinline__ void compute_tile(const uint4 *sA, const uint4 *sB, f
     });
 }
 
-// Software pipeline: two K tiles are in flight in registers while a third is
-// being multiplied out of LDS; LDS holds two stages so that one barrier per K
-// tile suffices.  At the top of step t, LDS stage t%2 holds tile t, register set
-// (t+1)%2 holds tile t+1 (possibly still arriving) and register set t%2 is free.
-template <typename T, int BM, int BN, class LA, class LB>
-__global__ __launch_bounds__(NT, (BM > 128 ? 1 : 2)) void gemm_kernel(LA la, LB lb, Epilogue ep, int M, int N, int nkt, int kt_per_split,
-                                                                    int tiles_m, int tiles_n, float *ws)
+// Software pipeline.  LDS holds two stages so that one barrier per K tile
+// suffices; DEPTH K tiles are in flight in registers while another is being
+// multiplied out of LDS.  At the top of step t, LDS stage t%2 holds tile t and
+// the register sets hold tiles t+1 .. t+DEPTH-1 (possibly still arriving).
+template <typename T, class Cfg, class LA, class LB>
+__global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, Epilogue ep, int M, int N, int nkt, int kt_per_split,
+                                                                int tiles_m, int tiles_n, float *ws, int dbg)
 {
-    constexpr int BK = Geo<T>::BK;
-    constexpr int MB = BM / 64, NB = BN / 64;   // MFMA 32x32 blocks per wave in m and n
-    __shared__ uint4 sA[2][BM * 8];
-    __shared__ uint4 sB[2][BN * 8];
+    constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB, DEPTH = Cfg::DEPTH;
+    __shared__ uint4 smem[2 * (BM + BN) * 8];   // two stages of A and B tiles; reused to stage the output
+    uint4 (*sA)[BM * 8] = reinterpret_cast<uint4 (*)[BM * 8]>(smem);
+    uint4 (*sB)[BN * 8] = reinterpret_cast<uint4 (*)[BN * 8]>(smem + 2 * BM * 8);
     const int tid = threadIdx.x;
     // XCD-aware remap: ids congruent mod 8 run on one XCD; give that XCD a contiguous range of tiles
     int bid;
@@ -539,8 +558,8 @@ __global__ __launch_bounds__(NT, (BM > 128 ? 1 : 2)) void gemm_kernel(LA la, LB 
     const int kt0 = split * kt_per_split;
     const int nt = min(nkt, kt0 + kt_per_split) - kt0;   // K tiles of this workgroup (>= 1)
 
-    Stage<T, LA, BM> stA;
-    Stage<T, LB, BN> stB;
+    Stage<T, LA, BM, NT, DEPTH> stA;
+    Stage<T, LB, BN, NT, DEPTH> stB;
     stA.init(la, tm * BM, kt0 * BK, tid, 0);
     stB.init(lb, tn * BN, kt0 * BK, tid, NT / 2);
 
@@ -548,83 +567,108 @@ __global__ __launch_bounds__(NT, (BM > 128 ? 1 : 2)) void gemm_kernel(LA la, LB 
     static_for<0, NB>([&](auto i) ASGD_INLINE { static_for<0, MB>([&](auto j) ASGD_INLINE { acc[i][j] = f32x16{}; }); });
 
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave & 1) * (BM / 2), wn = (wave >> 1) * (BN / 2);
+    const int wm = (wave % Cfg::WAVES_M) * (BM / Cfg::WAVES_M), wn = (wave / Cfg::WAVES_M) * (BN / Cfg::WAVES_N);
     const int lrow = lane & 31, half = lane >> 5;
     FragOff<T> foA, foB;
     foA.init(wm, lrow, half);
     foB.init(wn, lrow, half);
 
+    // register set that receives tile j is j % DEPTH (tile 0 goes through set 0 straight into LDS stage 0)
     stA.template load<0>(la); stB.template load<0>(lb);
-    if (nt > 1) { stA.template load<1>(la); stB.template load<1>(lb); }
+    if constexpr (DEPTH == 2) { stA.template load<1>(la); stB.template load<1>(lb); }
     stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid);
     for (int t = 0; t < nt; t += 2) {
-        // step t (even): compute from LDS stage 0; register set 0 is free, set 1 holds tile t+1
+        // step t (even): multiply out of LDS stage 0, fetch tile t+DEPTH, then move tile t+1 into stage 1
         __syncthreads();
-        if (t + 2 < nt) { stA.template load<0>(la); stB.template load<0>(lb); }
-        compute_tile<T, BM, BN>(sA[0], sB[0], acc, foA, foB);
+        if (!(dbg & 1)) { stA.template load<0>(la); stB.template load<0>(lb); }   // past the last tile this fetches zeros, which nothing consumes
+        if (!(dbg & 4)) compute_tile<T, MB, NB>(sA[0], sB[0], acc, foA, foB);
         if (t + 1 < nt) {
-            stA.template store<1>(sA[1], tid); stB.template store<1>(sB[1], tid);
-            // step t+1 (odd): compute from LDS stage 1; register set 1 is free, set 0 holds tile t+2
+            if (!(dbg & 2)) { stA.template store<DEPTH - 1>(sA[1], tid); stB.template store<DEPTH - 1>(sB[1], tid); }
+            // step t+1 (odd): multiply out of LDS stage 1, fetch tile t+1+DEPTH, then move tile t+2 into stage 0
             __syncthreads();
-            if (t + 3 < nt) { stA.template load<1>(la); stB.template load<1>(lb); }
-            compute_tile<T, BM, BN>(sA[1], sB[1], acc, foA, foB);
-            if (t + 2 < nt) { stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid); }
+            if (!(dbg & 1)) { stA.template load<DEPTH - 1>(la); stB.template load<DEPTH - 1>(lb); }
+            if (!(dbg & 4)) compute_tile<T, MB, NB>(sA[1], sB[1], acc, foA, foB);
+            if (t + 2 < nt && !(dbg & 2)) { stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid); }
         }
     }
 
+    // Output: the accumulators go through LDS, 64 rows of the block tile at a time, so that every lane ends
+    // up with 8 consecutive columns of one row and a wave stores whole row segments (the MFMA layout gives a
+    // lane 4 columns of one row and its neighbours other rows).
     // acc[nb][mb][v]: m = wm + mb*32 + lrow, n = wn + nb*32 + 8*(v/4) + 4*half + v%4
-    static_for<0, MB>([&](auto mb) ASGD_INLINE {
-        const int m = tm * BM + wm + mb * 32 + lrow;
-        if (m < M) {
-            const long row_out = (long)m * ep.ld, row_mask = (long)m * ep.mask_ld;
-            static_for<0, NB>([&](auto nb) ASGD_INLINE {
-                static_for<0, 4>([&](auto g) ASGD_INLINE {
-                    const int n0 = tn * BN + wn + nb * 32 + 8 * g + 4 * half;
-                    if (n0 < N) {
-                        float v[4] = {acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]};
-                        if (ws) store4<float>(ws + ((long)split * M + m) * N + n0, v);
-                        else epilogue4<T>(ep, m, row_out, row_mask, n0, v);
-                    }
+    constexpr int PITCH = BN + 4;                 // floats; 64 * PITCH * 4 bytes fit the tile buffers
+    static_assert(64 * PITCH * 4 <= (int)sizeof(smem), "staging area");
+    float *stg = reinterpret_cast<float *>(smem);
+    constexpr int LPR = BN / 8, RPR = NT / LPR;   // lanes per row, rows per round
+    static_for<0, BM / 64>([&](auto p) ASGD_INLINE {
+        __syncthreads();
+        static_for<0, MB>([&](auto mb) ASGD_INLINE {
+            const int rb = wm + mb * 32 - 64 * p;   // first row of this block within the pass
+            if (rb == 0 || rb == 32) {
+                static_for<0, NB>([&](auto nb) ASGD_INLINE {
+                    static_for<0, 4>([&](auto g) ASGD_INLINE {
+                        *reinterpret_cast<float4 *>(stg + (rb + lrow) * PITCH + wn + nb * 32 + 8 * g + 4 * half) =
+                            make_float4(acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]);
+                    });
                 });
-            });
-        }
+            }
+        });
+        __syncthreads();
+        static_for<0, 64 / RPR>([&](auto r) ASGD_INLINE {
+            const int row = r * RPR + tid / LPR, col = (tid % LPR) * 8;
+            const int m = tm * BM + 64 * p + row, n0 = tn * BN + col;
+            if (m < M && n0 < N) {
+                const float4 lo = *reinterpret_cast<const float4 *>(stg + row * PITCH + col);
+                const float4 hi = *reinterpret_cast<const float4 *>(stg + row * PITCH + col + 4);
+                float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                if (ws) store8<float>(ws + ((long)split * M + m) * N + n0, v);
+                else epilogue8<T>(ep, m, n0, v);
+            }
+        });
     });
 }
 
 template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int splits, Epilogue ep, int M, int N)
 {
     const long g = (long)blockIdx.x * 256 + threadIdx.x;
-    const int n4 = N / 4;
-    if (g >= (long)M * n4) return;
-    const int m = (int)(g / n4), n0 = (int)(g - (long)m * n4) * 4;
-    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    const int n8 = N / 8;
+    if (g >= (long)M * n8) return;
+    const int m = (int)(g / n8), n0 = (int)(g - (long)m * n8) * 8;
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < splits; ++s) {
-        const float4 p = *reinterpret_cast<const float4 *>(ws + ((long)s * M + m) * N + n0);
-        v[0] += p.x; v[1] += p.y; v[2] += p.z; v[3] += p.w;
+        const float4 *p = reinterpret_cast<const float4 *>(ws + ((long)s * M + m) * N + n0);
+        const float4 a = p[0], b = p[1];
+        v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
+        v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
     }
-    epilogue4<T>(ep, m, (long)m * ep.ld, (long)m * ep.mask_ld, n0, v);
+    epilogue8<T>(ep, m, n0, v);
 }
 
 // ------------------------------------------------------------------ host side
-// 256-row tiles when they do not add much padding over 128-row tiles.
-static int pick_bm(long M)
+// The large tile pays off when it fills the chip about as evenly as the small one.
+static bool pick_large(long M, long N)
 {
     static const char *force = getenv("ASGD_TILE");
-    if (!force || force[0] != '2') return 128;   // 256-row tiles measured slower so far
-    if (M < 256) return 128;
-    const long p256 = (M + 255) / 256 * 256, p128 = (M + 127) / 128 * 128;
-    return p256 * 100 <= p128 * 112 ? 256 : 128;
+    if (force && force[0] == '1') return false;
+    if (force && force[0] == '2') return M >= 256 && N >= 256;
+    if (M < 2048 || N < 256) return false;
+    const long tl = ((M + 255) / 256) * ((N + 255) / 256);
+    const double waste = (double)(tl * 256 * 256) / ((double)((M + 127) / 128 * 128) * (double)((N + 127) / 128 * 128));
+    const double rounds = (double)tl / 256.0, eff = rounds / (double)(long)(rounds + 0.999999);
+    return waste <= 1.10 && eff >= 0.80;
 }
 
 GemmPlan plan_gemm(long M, long N, long K, int dtype, int max_splits)
 {
     const int BK = dtype == kBF16 ? (int)Geo<bf16_t>::BK : (int)Geo<float>::BK;
-    const int BM = pick_bm(M), BN = 128;
+    const bool large = pick_large(M, N);
+    const int BM = large ? 256 : 128, BN = large ? 256 : 128;
     const long tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
     const long nkt = (K + BK - 1) / BK;
+    const long target = large ? 256 : 512;
     long splits = 1;
-    if (max_splits > 1 && tiles < 512) {
-        splits = (512 + tiles - 1) / tiles;
+    if (max_splits > 1 && tiles < target) {
+        splits = (target + tiles - 1) / tiles;
         if (splits > nkt / 4) splits = nkt / 4;   // at least four K tiles per split
         if (splits > max_splits) splits = max_splits;
         if (splits < 1) splits = 1;
@@ -639,10 +683,10 @@ GemmPlan plan_gemm(long M, long N, long K, int dtype, int max_splits)
     return p;
 }
 
-template <typename T, int BM, int BN, class LA, class LB>
+template <typename T, class Cfg, class LA, class LB>
 static int run_tile(const LA &la, const LB &lb, int M, int N, int K, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
-    constexpr int BK = Geo<T>::BK;
+    constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int nkt = (K + BK - 1) / BK;
     int splits = plan.splits;
@@ -651,10 +695,10 @@ static int run_tile(const LA &la, const LB &lb, int M, int N, int K, const Epilo
     splits = (nkt + per - 1) / per;
     const long blocks = (long)tiles_m * tiles_n * splits;
     if (blocks > 0x7fffffffL) return -1;
-    hipLaunchKernelGGL((gemm_kernel<T, BM, BN, LA, LB>), dim3((unsigned)blocks), dim3(NT), 0, s, la, lb, ep, M, N, nkt, per, tiles_m,
-                       tiles_n, splits > 1 ? ws : nullptr);
+    hipLaunchKernelGGL((gemm_kernel<T, Cfg, LA, LB>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, la, lb, ep, M, N, nkt, per, tiles_m,
+                       tiles_n, splits > 1 ? ws : nullptr, getenv("ASGD_DBG") ? atoi(getenv("ASGD_DBG")) : 0);
     if (splits > 1) {
-        const long groups = (long)M * (N / 4);
+        const long groups = (long)M * (N / 8);
         hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);
     }
     return hipGetLastError() == hipSuccess ? 0 : -1;
@@ -663,9 +707,9 @@ static int run_tile(const LA &la, const LB &lb, int M, int N, int K, const Epilo
 template <typename T, class LA, class LB>
 static int run(const LA &la, const LB &lb, int M, int N, int K, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
-    if (M <= 0 || N <= 0 || K <= 0 || (N & 3)) return -1;
-    if (pick_bm(M) == 256) return run_tile<T, 256, 128>(la, lb, M, N, K, ep, plan, ws, s);
-    return run_tile<T, 128, 128>(la, lb, M, N, K, ep, plan, ws, s);
+    if (M <= 0 || N <= 0 || K <= 0 || (N & 7)) return -1;
+    if (pick_large(M, N)) return run_tile<T, CfgLarge>(la, lb, M, N, K, ep, plan, ws, s);
+    return run_tile<T, CfgSmall>(la, lb, M, N, K, ep, plan, ws, s);
 }
 
 template <typename T, bool WIDE> static GatherK<T, WIDE> make_gather_k(const Gather &g)
@@ -674,6 +718,7 @@ template <typename T, bool WIDE> static GatherK<T, WIDE> make_gather_k(const Gat
     l.x = static_cast<const char *>(g.x); l.zero_off = (unsigned)g.zero_off;
     l.H = g.H; l.W = g.W; l.C = g.C; l.Ho = g.Ho; l.Wo = g.Wo; l.kh = g.kh; l.kw = g.kw;
     l.sm = g.sm; l.pad = g.pad; l.M = g.N * g.Ho * g.Wo;
+    l.adv_px = (int)Geo<T>::BK / g.C; l.adv_c = (int)Geo<T>::BK % g.C;
     l.dWo = make_fastdiv(g.Wo); l.dHoWo = make_fastdiv(g.Ho * g.Wo); l.dC = make_fastdiv(g.C); l.dkw = make_fastdiv(g.kw);
     return l;
 }

@@ -202,37 +202,40 @@ template <typename T> struct GatherKS {
     }
 };
 
-// Transposing loaders: memory has the GEMM row index contiguous and the
-// reduction index strided.  A unit is CH consecutive rows x CH consecutive
-// reduction indices, fetched as CH 16-byte loads.
+// Row-contiguous loaders: memory has the GEMM row index contiguous and the
+// reduction index strided ([k][rows]).  The tile is copied to LDS in that same
+// orientation, 16 bytes (8 or 4 consecutive rows) at a time; the transposition
+// the MFMA needs happens in the LDS read (ds_read_b64_tr_b16 for 16-bit data).
+// A thread keeps one column of 16-byte pieces (Col) and walks down the K axis
+// (KState per slot).
 template <typename T> struct PlainT {
     static constexpr bool kTrans = true;
-    static constexpr int CH = Geo<T>::CH;
     const T *base; long ld; int rows; int K; const T *zero;
-    struct Unit { const T *p; };   // nullptr: rows out of range
-    __device__ __forceinline__ Unit unit(int row0) const { return Unit{row0 < rows ? base + row0 : nullptr}; }
-    __device__ __forceinline__ void load(const Unit &u, int k, uint4 (&out)[CH]) const
+    struct Col { const T *p; };    // nullptr: rows out of range
+    struct KState { int k; };
+    __device__ __forceinline__ Col col(int row0) const { return Col{row0 < rows ? base + row0 : nullptr}; }
+    __device__ __forceinline__ KState kstate(int k) const { return KState{k}; }
+    __device__ __forceinline__ void advance(KState &ks, int dk) const { ks.k += dk; }
+    __device__ __forceinline__ uint4 load(const Col &c, const KState &ks) const
     {
-        static_for<0, CH>([&](auto j) ASGD_INLINE {
-            out[j] = ld16((u.p != nullptr && k + j < K) ? u.p + (long)(k + j) * ld : zero);
-        });
+        return ld16((c.p != nullptr && ks.k < K) ? c.p + (long)ks.k * ld : zero);
     }
 };
 
-// Filter-gradient gather: rows enumerate (ky, kx, c) (fixed per unit), the reduction
-// index enumerates output pixels (n, oy, ox).  The valid oy / ox ranges of a unit
-// are precomputed; the pixel offset is advanced incrementally along the 8 (or 4)
-// consecutive reduction indices of a unit.
+// Filter-gradient gather: rows enumerate (ky, kx, c) (fixed per column of pieces),
+// the reduction index enumerates output pixels m = (n, oy, ox).  The valid oy / ox
+// ranges of a column are precomputed; a K state carries (n, oy, ox) and is moved
+// down the K axis without branches.
 template <typename T> struct GatherT {
     static constexpr bool kTrans = true;
-    static constexpr int CH = Geo<T>::CH;
     const char *x; unsigned zero_off;
     int H, W, C, Ho, Wo, kh, kw, sm, pad, M, Krows;
-    FastDiv dWo, dHoWo, dC, dkw;
-    struct Unit { int ylo, yspan, xlo, xspan; unsigned off; };   // yspan < 0: rows out of range
-    __device__ __forceinline__ Unit unit(int row0) const
+    FastDiv dWo, dHo, dHoWo, dC, dkw;
+    struct Col { int ylo, xlo; unsigned yspan, xspan, off; };   // out-of-range columns: ylo huge, so no oy qualifies
+    struct KState { int m, n, oy, ox; };
+    __device__ __forceinline__ Col col(int row0) const
     {
-        if (row0 >= Krows) return Unit{0, -1, 0, -1, 0u};
+        if (row0 >= Krows) return Col{1 << 30, 0, 0u, 0u, 0u};
         const int t = (int)fdiv((uint32_t)row0, dC);
         const int ky = (int)fdiv((uint32_t)t, dkw);
         const int kx = t - ky * kw, c = row0 - t * C;
@@ -241,32 +244,33 @@ template <typename T> struct GatherT {
         const int yhi = (H - 1 + pad - ky) >= 0 ? min(Ho - 1, (H - 1 + pad - ky) / sm) : -1;
         const int xlo = kx >= pad ? 0 : (pad - kx + sm - 1) / sm;
         const int xhi = (W - 1 + pad - kx) >= 0 ? min(Wo - 1, (W - 1 + pad - kx) / sm) : -1;
-        return Unit{ylo, yhi - ylo, xlo, xhi - xlo, (unsigned)(((ky - pad) * W + (kx - pad)) * C + c) * (unsigned)sizeof(T)};
+        if (yhi < ylo || xhi < xlo) return Col{1 << 30, 0, 0u, 0u, 0u};
+        return Col{ylo, xlo, (unsigned)(yhi - ylo), (unsigned)(xhi - xlo),
+                   (unsigned)(((ky - pad) * W + (kx - pad)) * C + c) * (unsigned)sizeof(T)};
     }
-    __device__ __forceinline__ void load(const Unit &u, int m0, uint4 (&out)[CH]) const
+    __device__ __forceinline__ KState kstate(int m) const
     {
-        int n = 0, oy = 0, ox = 0;
-        if (m0 < M) {
-            n = (int)fdiv((uint32_t)m0, dHoWo);
-            const int rem = m0 - n * (Ho * Wo);
-            oy = (int)fdiv((uint32_t)rem, dWo);
-            ox = rem - oy * Wo;
-        }
-        const unsigned es = (unsigned)sizeof(T);
-        unsigned poff = u.off + (unsigned)(((n * H + oy * sm) * W + ox * sm) * C) * es;
-        const unsigned step_x = (unsigned)(sm * C) * es;
-        const unsigned step_row = (unsigned)((sm * W - Wo * sm) * C) * es;       // extra on wrapping to the next output row
-        const unsigned step_img = (unsigned)((H - Ho * sm) * W * C) * es;        // extra on wrapping to the next image
-        static_for<0, CH>([&](auto j) ASGD_INLINE {
-            const bool ok = m0 + j < M && (unsigned)(oy - u.ylo) <= (unsigned)u.yspan && (unsigned)(ox - u.xlo) <= (unsigned)u.xspan &&
-                            u.yspan >= 0 && u.xspan >= 0;
-            out[j] = ld16(x + (ok ? poff : zero_off));
-            poff += step_x;
-            if (++ox == Wo) {
-                ox = 0; poff += step_row;
-                if (++oy == Ho) { oy = 0; poff += step_img; }
-            }
-        });
+        const int n = (int)fdiv((uint32_t)m, dHoWo);
+        const int rem = m - n * (Ho * Wo);
+        const int oy = (int)fdiv((uint32_t)rem, dWo);
+        return KState{m, n, oy, rem - oy * Wo};
+    }
+    __device__ __forceinline__ void advance(KState &ks, int dk) const
+    {
+        ks.m += dk;
+        ks.ox += dk;
+        const int q = (int)fdiv((uint32_t)ks.ox, dWo);
+        ks.ox -= q * Wo;
+        ks.oy += q;
+        const int q2 = (int)fdiv((uint32_t)ks.oy, dHo);
+        ks.oy -= q2 * Ho;
+        ks.n += q2;
+    }
+    __device__ __forceinline__ uint4 load(const Col &c, const KState &ks) const
+    {
+        const bool ok = ks.m < M && (unsigned)(ks.oy - c.ylo) <= c.yspan && (unsigned)(ks.ox - c.xlo) <= c.xspan;
+        const unsigned off = c.off + (unsigned)(((ks.n * H + ks.oy * sm) * W + ks.ox * sm) * C) * (unsigned)sizeof(T);
+        return ld16(x + (ok ? off : zero_off));
     }
 };
 
@@ -304,68 +308,41 @@ template <typename T, class L, int ROWS, int NT, int DEPTH> struct Stage<T, L, R
     }
 };
 
-__device__ __forceinline__ void transpose_unit(const uint4 (&r)[4], uint4 (&o)[4])  // fp32: 4 k x 4 rows
-{
-    o[0] = make_uint4(r[0].x, r[1].x, r[2].x, r[3].x);
-    o[1] = make_uint4(r[0].y, r[1].y, r[2].y, r[3].y);
-    o[2] = make_uint4(r[0].z, r[1].z, r[2].z, r[3].z);
-    o[3] = make_uint4(r[0].w, r[1].w, r[2].w, r[3].w);
-}
-
-__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
-__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
-
-__device__ __forceinline__ void transpose_unit(const uint4 (&r)[8], uint4 (&o)[8])  // bf16: 8 k x 8 rows
-{
-    o[0] = make_uint4(pack_lo(r[0].x, r[1].x), pack_lo(r[2].x, r[3].x), pack_lo(r[4].x, r[5].x), pack_lo(r[6].x, r[7].x));
-    o[1] = make_uint4(pack_hi(r[0].x, r[1].x), pack_hi(r[2].x, r[3].x), pack_hi(r[4].x, r[5].x), pack_hi(r[6].x, r[7].x));
-    o[2] = make_uint4(pack_lo(r[0].y, r[1].y), pack_lo(r[2].y, r[3].y), pack_lo(r[4].y, r[5].y), pack_lo(r[6].y, r[7].y));
-    o[3] = make_uint4(pack_hi(r[0].y, r[1].y), pack_hi(r[2].y, r[3].y), pack_hi(r[4].y, r[5].y), pack_hi(r[6].y, r[7].y));
-    o[4] = make_uint4(pack_lo(r[0].z, r[1].z), pack_lo(r[2].z, r[3].z), pack_lo(r[4].z, r[5].z), pack_lo(r[6].z, r[7].z));
-    o[5] = make_uint4(pack_hi(r[0].z, r[1].z), pack_hi(r[2].z, r[3].z), pack_hi(r[4].z, r[5].z), pack_hi(r[6].z, r[7].z));
-    o[6] = make_uint4(pack_lo(r[0].w, r[1].w), pack_lo(r[2].w, r[3].w), pack_lo(r[4].w, r[5].w), pack_lo(r[6].w, r[7].w));
-    o[7] = make_uint4(pack_hi(r[0].w, r[1].w), pack_hi(r[2].w, r[3].w), pack_hi(r[4].w, r[5].w), pack_hi(r[6].w, r[7].w));
-}
+// LDS tile of a row-contiguous operand: BK lines of ROWS elements, each line padded by 32 bytes so that the
+// four K lines a transposing read touches fall into different banks.
+template <typename T, int ROWS> struct TransTile {
+    static constexpr int LINE = ROWS * (int)sizeof(T) + 32;   // bytes
+    static constexpr int BYTES = Geo<T>::BK * LINE;
+};
 
 template <typename T, class L, int ROWS, int NT, int DEPTH> struct Stage<T, L, ROWS, NT, DEPTH, true> {
-    static constexpr int CH = Geo<T>::CH;
-    static constexpr int RCH = ROWS / CH;            // row chunks per tile
-    static constexpr int NUNITS = RCH * 8;           // x 8 slots along K
-    static constexpr int UPT = (NUNITS + NT - 1) / NT;  // units per thread
-    typename L::Unit un[UPT];
-    int k;
-    int vt;
-    uint4 r[DEPTH][UPT][CH];
-    __device__ __forceinline__ void init(const L &l, int row0, int k0, int tid, int shift)
+    static constexpr int CPL = ROWS * (int)sizeof(T) / 16;   // 16-byte pieces per K line
+    static constexpr int LPP = NT / CPL;                     // K lines covered by one pass of the workgroup
+    static constexpr int SLOTS = Geo<T>::BK / LPP;
+    static_assert(NT % CPL == 0 && Geo<T>::BK % LPP == 0, "tile / thread-count mismatch");
+    typename L::Col c;
+    typename L::KState ks[SLOTS];
+    uint4 r[DEPTH][SLOTS];
+    unsigned wo;   // LDS byte offset of slot 0
+    __device__ __forceinline__ void init(const L &l, int row0, int k0, int tid, int)
     {
-        vt = (tid + shift) & (NT - 1);               // spreads the two operands over different waves
-        k = k0;
-        static_for<0, UPT>([&](auto u) ASGD_INLINE {
-            const int id = vt + u * NT;
-            un[u] = l.unit(row0 + (id % RCH) * CH);
-        });
+        const int cc = tid % CPL, line = tid / CPL;
+        c = l.col(row0 + cc * (16 / (int)sizeof(T)));
+        static_for<0, SLOTS>([&](auto s) ASGD_INLINE { ks[s] = l.kstate(k0 + line + s * LPP); });
+        wo = (unsigned)(line * TransTile<T, ROWS>::LINE + cc * 16);
     }
     template <int RB> __device__ __forceinline__ void load(const L &l)
     {
-        static_for<0, UPT>([&](auto u) ASGD_INLINE {
-            const int id = vt + u * NT;
-            if (id < NUNITS) l.load(un[u], k + (id / RCH) * CH, r[RB][u]);
+        static_for<0, SLOTS>([&](auto s) ASGD_INLINE {
+            r[RB][s] = l.load(c, ks[s]);
+            l.advance(ks[s], Geo<T>::BK);
         });
-        k += Geo<T>::BK;
     }
     template <int RB> __device__ __forceinline__ void store(uint4 *sm, int) const
     {
-        static_for<0, UPT>([&](auto u) ASGD_INLINE {
-            const int id = vt + u * NT;
-            if (id < NUNITS) {
-                const int rowchunk = id % RCH, kq = id / RCH;
-                uint4 o[CH];
-                transpose_unit(r[RB][u], o);
-                static_for<0, CH>([&](auto i) ASGD_INLINE {
-                    const int row = rowchunk * CH + i;
-                    sm[row * 8 + (kq ^ swz(row))] = o[i];
-                });
-            }
+        char *base = reinterpret_cast<char *>(sm);
+        static_for<0, SLOTS>([&](auto s) ASGD_INLINE {
+            *reinterpret_cast<uint4 *>(base + wo + s * (LPP * TransTile<T, ROWS>::LINE)) = r[RB][s];
         });
     }
 };
@@ -376,11 +353,12 @@ template <typename T, class L, int ROWS, int NT, int DEPTH> struct Stage<T, L, R
 // lane's row in row block 0 and in row block 1 (blocks 64 rows apart share it), so
 // the inner loop issues its LDS reads with no address arithmetic.
 template <typename T> struct Frag;
-template <typename T> struct FragOff;
-template <> struct FragOff<bf16_t> {
+template <typename T, bool TRANS, int ROWS> struct FragOff;
+template <int ROWS> struct FragOff<bf16_t, false, ROWS> {
     unsigned o[Geo<bf16_t>::KSTEPS][2];
-    __device__ __forceinline__ void init(int row0, int lrow, int half)
+    __device__ __forceinline__ void init(int row0, int lane)
     {
+        const int lrow = lane & 31, half = lane >> 5;
         static_for<0, Geo<bf16_t>::KSTEPS>([&](auto ks) ASGD_INLINE {
             static_for<0, 2>([&](auto par) ASGD_INLINE {
                 const int row = row0 + par * 32 + lrow;
@@ -389,10 +367,11 @@ template <> struct FragOff<bf16_t> {
         });
     }
 };
-template <> struct FragOff<float> {
+template <int ROWS> struct FragOff<float, false, ROWS> {
     unsigned o[Geo<float>::KSTEPS][2][2];
-    __device__ __forceinline__ void init(int row0, int lrow, int half)
+    __device__ __forceinline__ void init(int row0, int lane)
     {
+        const int lrow = lane & 31, half = lane >> 5;
         static_for<0, Geo<float>::KSTEPS>([&](auto ks) ASGD_INLINE {
             static_for<0, 2>([&](auto par) ASGD_INLINE {
                 const int row = row0 + par * 32 + lrow, q = ks * 4 + half * 2, z = swz(row);
@@ -402,19 +381,58 @@ template <> struct FragOff<float> {
         });
     }
 };
+// Row-contiguous tiles.  16-bit data: ds_read_b64_tr_b16 works on blocks of 16 lanes; when lane j of a block
+// points at K line (j >> 2) and row piece (j & 3) of a 4 x 16 patch, lane i receives row i of the patch for the
+// four K lines in order.  Lane L = 16*b + i of the wave wants row 16*(b & 1) + i and K lines 8*(b >> 1) + 0..7
+// of the K step, i.e. two such reads.  32-bit data needs no hardware help: eight 4-byte reads down the K axis.
+template <int ROWS> struct FragOff<bf16_t, true, ROWS> {
+    unsigned base;
+    __device__ __forceinline__ void init(int row0, int lane)
+    {
+        const int b = lane >> 4, i = lane & 15;
+        base = (unsigned)((8 * (b >> 1) + (i >> 2)) * TransTile<bf16_t, ROWS>::LINE + (row0 + 16 * (b & 1) + 4 * (i & 3)) * 2);
+    }
+};
+template <int ROWS> struct FragOff<float, true, ROWS> {
+    unsigned base;
+    __device__ __forceinline__ void init(int row0, int lane)
+    {
+        base = (unsigned)(8 * (lane >> 5) * TransTile<float, ROWS>::LINE + (row0 + (lane & 31)) * 4);
+    }
+};
+typedef short short4v __attribute__((ext_vector_type(4)));
 template <> struct Frag<bf16_t> {
     uint4 v;
-    template <int KS, int BLK> __device__ __forceinline__ void read(const char *sm, const FragOff<bf16_t> &fo)
+    template <int KS, int BLK, int ROWS> __device__ __forceinline__ void read(const char *sm, const FragOff<bf16_t, false, ROWS> &fo)
     {
         v = *reinterpret_cast<const uint4 *>(sm + fo.o[KS][BLK % 2] + (BLK / 2) * (64 * 128));
+    }
+    template <int KS, int BLK, int ROWS> __device__ __forceinline__ void read(const char *sm, const FragOff<bf16_t, true, ROWS> &fo)
+    {
+        constexpr int LINE = TransTile<bf16_t, ROWS>::LINE;
+        typedef __attribute__((address_space(3))) short4v lds_s4;
+        const char *p = sm + fo.base + KS * 16 * LINE + BLK * 64;
+        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)(p));
+        const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)(p + 4 * LINE));
+        const uint2 a = __builtin_bit_cast(uint2, lo), b = __builtin_bit_cast(uint2, hi);
+        v = make_uint4(a.x, a.y, b.x, b.y);
     }
 };
 template <> struct Frag<float> {
     uint4 v[2];
-    template <int KS, int BLK> __device__ __forceinline__ void read(const char *sm, const FragOff<float> &fo)
+    template <int KS, int BLK, int ROWS> __device__ __forceinline__ void read(const char *sm, const FragOff<float, false, ROWS> &fo)
     {
         v[0] = *reinterpret_cast<const uint4 *>(sm + fo.o[KS][BLK % 2][0] + (BLK / 2) * (64 * 128));
         v[1] = *reinterpret_cast<const uint4 *>(sm + fo.o[KS][BLK % 2][1] + (BLK / 2) * (64 * 128));
+    }
+    template <int KS, int BLK, int ROWS> __device__ __forceinline__ void read(const char *sm, const FragOff<float, true, ROWS> &fo)
+    {
+        constexpr int LINE = TransTile<float, ROWS>::LINE;
+        const char *p = sm + fo.base + KS * 16 * LINE + BLK * 128;
+        uint32_t e[8];
+        static_for<0, 8>([&](auto j) ASGD_INLINE { e[j] = *reinterpret_cast<const uint32_t *>(p + j * LINE); });
+        v[0] = make_uint4(e[0], e[1], e[2], e[3]);
+        v[1] = make_uint4(e[4], e[5], e[6], e[7]);
     }
 };
 
@@ -514,9 +532,8 @@ template <typename T> __device__ __forceinline__ void epilogue8(const Epilogue &
 // ------------------------------------------------------------------ kernel
 // One K tile out of LDS.  The fragments of K step ks+1 are requested before the
 // MFMAs of step ks are issued, so the LDS latency hides behind the matrix pipe.
-template <typename T, int MB, int NB>
-__device__ __forceinline__ void compute_tile(const uint4 *sA, const uint4 *sB, f32x16 (&acc)[NB][MB], const FragOff<T> &foA,
-                                             const FragOff<T> &foB)
+template <typename T, int MB, int NB, class FOA, class FOB>
+__device__ __forceinline__ void compute_tile(const uint4 *sA, const uint4 *sB, f32x16 (&acc)[NB][MB], const FOA &foA, const FOB &foB)
 {
     constexpr int KS = Geo<T>::KSTEPS;
     const char *pa = reinterpret_cast<const char *>(sA), *pb = reinterpret_cast<const char *>(sB);
@@ -542,9 +559,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
                                                                 int tiles_m, int tiles_n, float *ws, int dbg)
 {
     constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB, DEPTH = Cfg::DEPTH;
-    __shared__ uint4 smem[2 * (BM + BN) * 8];   // two stages of A and B tiles; reused to stage the output
-    uint4 (*sA)[BM * 8] = reinterpret_cast<uint4 (*)[BM * 8]>(smem);
-    uint4 (*sB)[BN * 8] = reinterpret_cast<uint4 (*)[BN * 8]>(smem + 2 * BM * 8);
+    constexpr int TA = LA::kTrans ? TransTile<T, BM>::BYTES : BM * 128, TB = LB::kTrans ? TransTile<T, BN>::BYTES : BN * 128;
+    __shared__ uint4 smem[2 * (TA + TB) / 16];   // two stages of A and B tiles; reused to stage the output
+    uint4 (*sA)[TA / 16] = reinterpret_cast<uint4 (*)[TA / 16]>(smem);
+    uint4 (*sB)[TB / 16] = reinterpret_cast<uint4 (*)[TB / 16]>(smem + 2 * TA / 16);
     const int tid = threadIdx.x;
     // XCD-aware remap: ids congruent mod 8 run on one XCD; give that XCD a contiguous range of tiles
     int bid;
@@ -569,9 +587,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = (wave % Cfg::WAVES_M) * (BM / Cfg::WAVES_M), wn = (wave / Cfg::WAVES_M) * (BN / Cfg::WAVES_N);
     const int lrow = lane & 31, half = lane >> 5;
-    FragOff<T> foA, foB;
-    foA.init(wm, lrow, half);
-    foB.init(wn, lrow, half);
+    FragOff<T, LA::kTrans, BM> foA;
+    FragOff<T, LB::kTrans, BN> foB;
+    foA.init(wm, lane);
+    foB.init(wn, lane);
 
     // register set that receives tile j is j % DEPTH (tile 0 goes through set 0 straight into LDS stage 0)
     stA.template load<0>(la); stB.template load<0>(lb);
@@ -737,7 +756,7 @@ template <typename T> static GatherT<T> make_gather_t(const Gather &g)
     l.x = static_cast<const char *>(g.x); l.zero_off = (unsigned)g.zero_off;
     l.H = g.H; l.W = g.W; l.C = g.C; l.Ho = g.Ho; l.Wo = g.Wo; l.kh = g.kh; l.kw = g.kw;
     l.sm = g.sm; l.pad = g.pad; l.M = g.N * g.Ho * g.Wo; l.Krows = g.kh * g.kw * g.C;
-    l.dWo = make_fastdiv(g.Wo); l.dHoWo = make_fastdiv(g.Ho * g.Wo); l.dC = make_fastdiv(g.C); l.dkw = make_fastdiv(g.kw);
+    l.dWo = make_fastdiv(g.Wo); l.dHo = make_fastdiv(g.Ho); l.dHoWo = make_fastdiv(g.Ho * g.Wo); l.dC = make_fastdiv(g.C); l.dkw = make_fastdiv(g.kw);
     return l;
 }
 template <typename T> static PlainK<T> make_plain_k(const void *p, long ld, int rows, int K, const void *zero)

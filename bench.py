@@ -23,6 +23,9 @@ WORKLOADS = {
     "alexnet_bf16_bs128": (128, "bf16"),   # the headline: AlexNet-style single column, bf16 MFMA, fp32 master weights
     "alexnet_f32_bs128": (128, "f32"),
     "alexnet_bf16_bs256": (256, "bf16"),
+    # A-SGD on one GPU: 4 workers as concurrent streams, batch 32 each, snapshots up to 3 updates stale;
+    # a step is one pushed gradient (snapshot + fwd_bwd + server update)
+    "asgd_4x32_bf16": (32, "bf16"),
 }
 PEAK = {"hbm": 8000.0, "mfma_bf16": 2500.0, "mfma_f32": 157.3}   # GB/s, TFLOP/s (MI355X, dense)
 MFMA_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad", "fc_fwd", "fc_dgrad", "fc_wgrad")
@@ -46,6 +49,54 @@ def cpu_baseline(layers, in_shape, classes, sample_batch, hp):
             "sample": "one fwd+bwd+update of the same AlexNet-style net on %d images (%.1f s)" % (sample_batch, dt)}
 
 
+def bench_asgd(args, batch):
+    """Replay of a seeded staleness schedule: `steps` pushed gradients, 4 worker streams + a server stream."""
+    import numpy as np
+    import torch
+    from paper_1312_6186_amd import binding as B
+    from paper_1312_6186_amd import workloads as wl
+    cfg = wl.ALEXNET
+    layers, in_shape, classes = cfg["layers"], cfg["in_shape"], cfg["classes"]
+    lr, mu, wd, W = 1e-3, cfg["mu"], cfg["wd"], 4
+    dev = torch.device("cuda:0")
+    nets = [B.asgd_net_create(layers, batch, in_shape, B.BF16) for _ in range(W)]
+    P = B.asgd_param_count(nets[0])
+    params = torch.from_numpy(wl.make_params(layers, in_shape, cfg["seeds"]["init"])).to(dev)
+    mom = torch.zeros_like(params)
+    copies = [torch.empty(P, dtype=torch.bfloat16, device=dev) for _ in range(W)]
+    grads = [torch.empty(P, dtype=torch.float32, device=dev) for _ in range(W)]
+    nb = max(args.steps, args.warmup, 1)
+    rng = np.random.default_rng(1005)
+    images = torch.from_numpy(rng.standard_normal((nb, batch) + tuple(in_shape), dtype=np.float32)).to(dev).to(torch.bfloat16)
+    labels = torch.from_numpy(rng.integers(0, classes, size=(nb, batch), dtype=np.int32)).to(dev)
+    losses = torch.zeros(nb, dtype=torch.float32, device=dev)
+    log = torch.zeros((nb, 3), dtype=torch.int32, device=dev)
+
+    def run(T):
+        worker, rv = B.asgd_schedule_generate(T, 4005, W, 3)
+        B.asgd_replay_run(nets, params, mom, copies, grads, images, labels, worker, rv, lr, mu, wd, 3003, losses, log)
+        torch.cuda.synchronize()
+        return worker, rv
+
+    if args.warmup > 0:
+        run(args.warmup)
+    t0 = time.perf_counter()
+    worker, rv = run(args.steps)
+    elapsed = time.perf_counter() - t0
+    ok = bool((log[:args.steps].cpu().numpy() == np.stack([np.arange(args.steps), worker, rv], 1)).all())
+    for n in nets:
+        B.asgd_net_destroy(n)
+    print(json.dumps({
+        "metric": "images/sec fwd+bwd+update, AlexNet-style bs128; % MFMA peak (conv/FC)",
+        "value": batch * args.steps / elapsed, "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "net": "AlexNet-style single column (62378344 parameters)", "workers": W,
+                   "batch_per_worker": batch, "max_staleness": 3, "schedule_seed": 4005,
+                   "step": "one pushed gradient: snapshot + fwd_bwd on a worker stream, update on the server stream"},
+        "schedule_log_matches": ok, "roofline": None, "cpu_baseline": None}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -65,6 +116,8 @@ def main():
     from paper_1312_6186_amd import workloads as wl
 
     batch, dtname = WORKLOADS[args.workload]
+    if args.workload.startswith("asgd"):
+        return bench_asgd(args, batch)
     dtype = B.BF16 if dtname == "bf16" else B.F32
     tdt = torch.bfloat16 if dtname == "bf16" else torch.float32
     cfg = wl.ALEXNET

@@ -265,3 +265,101 @@ def test_asgd_replay_matches_oracle_and_logs_the_schedule(dtype):
     finally:
         for n in nets:
             B.asgd_net_destroy(n)
+
+
+# ---------------------------------------------------------------- full size, in the configuration bench.py times
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+def test_alexnet_full_batch_sampled_against_oracle(dtype):
+    """AlexNet-style net at batch 128 (the benchmark's launch configuration).  The oracle cannot run the whole
+    batch in test time, so: (i) the forward pass is per image, so the logits of sampled images are compared with
+    the oracle run on those images alone (with their rows of the dropout masks); (ii) the loss is the mean of the
+    per-image losses, recomputed from the exported logits by the oracle's softmax cross-entropy."""
+    cfg = wl.ALEXNET
+    layers, in_shape, batch = cfg["layers"], cfg["in_shape"], 128
+    params = wl.make_params(layers, in_shape, cfg["seeds"]["init"])
+    images, labels = wl.make_batch(in_shape, batch, cfg["classes"], cfg["seeds"]["data"])
+    g = GpuNet(layers, in_shape, batch, dtype)
+    try:
+        seed, step, worker = cfg["seeds"]["dropout"], 3, 0
+        loss, grads = g.fwd_bwd(params, images, labels, seed, step, worker)
+        assert np.isfinite(grads).all() and np.isfinite(loss)
+        logits = g.debug(B.DEBUG_OUTPUT, len(layers) - 2).reshape(batch, -1).astype(np.float64)
+        ref_loss, _ = oops.softmax_ce(logits, labels, want_grad=False)
+        assert abs(loss - ref_loss) <= 1e-5 * abs(ref_loss)       # loss kernel on the exported logits (fp32 both sides)
+        onet = oracle.OracleNet(layers, in_shape)
+        p64, i64 = oracle_inputs(params, images, dtype)
+        sample = [0, 77, 127]
+        drop_layers = [li for li, l in enumerate(layers) if l[0] == "dropout"]
+        full_masks = {li: oops.dropout_mask(batch * onet.shapes[li][0], seed, step, worker, li, layers[li][1]).reshape(batch, -1)
+                      for li in drop_layers}
+        for n in sample:
+            masks = {li: full_masks[li][n:n + 1] for li in drop_layers}
+            _, _, trace = onet.fwd_bwd(p64, i64[n:n + 1], labels[n:n + 1], want_grads=False, masks=masks, act_dtype=ACT[dtype])
+            ref = trace[len(layers) - 2]["out"].reshape(-1)
+            assert rel_l2(logits[n], ref) < (TOL[dtype] if dtype == B.F32 else 2 * TOL[dtype]), ("logits of image", n)
+        for li in drop_layers:   # masks of the full batch, bit for bit
+            np.testing.assert_array_equal(g.debug(B.DEBUG_MASK, li).reshape(batch, -1), full_masks[li])
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+def test_alexnet_full_batch_gradient_is_the_mean_of_its_chunks(dtype):
+    """A property that holds at any size: the minibatch-mean gradient of 128 images equals the mean of the
+    gradients of its four 32-image chunks (dropout off so the masks do not depend on the position in the batch).
+    The 32-image plan is the A-SGD worker shape; small batches of the same net are checked against the oracle
+    directly in test_alexnet_layers_small_batch."""
+    cfg = wl.ALEXNET
+    layers = [l if l[0] != "dropout" else ("dropout", 0.0) for l in cfg["layers"]]
+    in_shape = cfg["in_shape"]
+    params = wl.make_params(layers, in_shape, cfg["seeds"]["init"])
+    images, labels = wl.make_batch(in_shape, 128, cfg["classes"], cfg["seeds"]["data"] + 1)
+    big, small = GpuNet(layers, in_shape, 128, dtype), GpuNet(layers, in_shape, 32, dtype)
+    try:
+        loss, grads = big.fwd_bwd(params, images, labels)
+        acc, lsum = np.zeros_like(grads, dtype=np.float64), 0.0
+        for c in range(4):
+            l_c, g_c = small.fwd_bwd(params, images[32 * c:32 * c + 32], labels[32 * c:32 * c + 32])
+            acc += g_c; lsum += l_c
+        onet = oracle.OracleNet(layers, in_shape)
+        assert abs(loss - lsum / 4) <= 1e-5 * abs(loss)
+        compare_grads(onet, grads, acc / 4, 1e-4 if dtype == B.F32 else 2e-3, "chunks")
+    finally:
+        big.close(); small.close()
+
+
+def test_asgd_replay_at_worker_shape_logs_and_reproduces():
+    """Four workers on the AlexNet-style net at batch 32 in bf16 (the worker shape of the on-one-GPU A-SGD
+    configuration): the device-side log must equal the prescribed schedule and two replays must agree bit for
+    bit.  (Values are checked against the oracle on the small net in the test above; a 62 M-parameter oracle
+    replay does not fit test time.)"""
+    cfg = wl.ALEXNET
+    layers, in_shape, batch, W, T = cfg["layers"], cfg["in_shape"], 32, 4, 12
+    worker, rv = B.asgd_schedule_generate(T, 4005, W, 3)
+    params0 = wl.make_params(layers, in_shape, cfg["seeds"]["init"])
+    rng = np.random.default_rng(1005)
+    images_np = wl.round_to_bf16(rng.standard_normal((T, batch) + tuple(in_shape), dtype=np.float32))
+    labels_np = rng.integers(0, cfg["classes"], size=(T, batch), dtype=np.int32)
+    nets = [B.asgd_net_create(layers, batch, in_shape, B.BF16) for _ in range(W)]
+    P = B.asgd_param_count(nets[0])
+    try:
+        images = torch.from_numpy(images_np).to(DEV).to(torch.bfloat16).contiguous()
+        labels = torch.from_numpy(labels_np).to(DEV)
+        results = []
+        for rep in range(2):
+            params = torch.from_numpy(params0).to(DEV); mom = torch.zeros_like(params)
+            copies = [torch.empty(P, dtype=torch.bfloat16, device=DEV) for _ in range(W)]
+            grads = [torch.empty(P, dtype=torch.float32, device=DEV) for _ in range(W)]
+            losses = torch.zeros(T, dtype=torch.float32, device=DEV)
+            log = torch.full((T, 3), -7, dtype=torch.int32, device=DEV)
+            B.asgd_replay_run(nets, params, mom, copies, grads, images, labels, worker, rv, 1e-3, 0.9, 5e-4, 3003, losses, log)
+            torch.cuda.synchronize()
+            results.append((params.cpu().numpy(), mom.cpu().numpy(), losses.cpu().numpy(), log.cpu().numpy()))
+        np.testing.assert_array_equal(results[0][3], np.stack([np.arange(T), worker, rv], 1))
+        assert np.isfinite(results[0][2]).all() and (results[0][2] > 0).all()
+        for a, b in zip(results[0], results[1]):
+            assert a.tobytes() == b.tobytes()
+        assert (results[0][0] != params0).mean() > 0.9      # the shared parameters were updated
+    finally:
+        for n in nets:
+            B.asgd_net_destroy(n)

@@ -49,6 +49,8 @@ struct Stage {
     bool in_is_spatial = false;  // an fc fed by a conv / pool stage (flatten boundary)
     bool last = false;           // produces the fp32 logits
     int k = 0, stride = 1, pad = 0;
+    // window-row form (first stage, <= 4 input channels): bordered input [B][rwHp][rwWp][4], K = k * rwKW
+    int rw = 0, rwKW = 0, rwHp = 0, rwWp = 0;
     int relu = 0, drop = 0, drop_layer = -1;
     float drop_p = 0.f, drop_scale = 1.f;
     uint32_t drop_thr = 0;
@@ -117,7 +119,8 @@ size_t carve(asgd_net &n, char *base)
     };
     // every activation / gradient tensor is followed by 256 zero bytes (the arena is cleared once and the
     // tail is never written): the gathers read out-of-image pieces from there
-    n.act0 = at(B * n.in_h * n.in_w * n.in_cp * es + 256);
+    const Stage *s0 = n.stages.empty() ? nullptr : &n.stages[0];
+    n.act0 = at((s0 && s0->rw ? B * s0->rwHp * s0->rwWp * 4 : B * n.in_h * n.in_w * n.in_cp) * es + 256);
     n.zero_page = at(256);
     for (size_t i = 0; i < n.stages.size(); ++i) {
         Stage &s = n.stages[i];
@@ -126,7 +129,7 @@ size_t carve(asgd_net &n, char *base)
         s.dout = at(oe * es + 256);
         if (s.kind == ST_POOL) s.argmax = static_cast<uint8_t *>(at(oe));
         if (s.kind == ST_CONV) {
-            s.wf = at((size_t)s.outCp * s.k * s.k * s.inCp * es);
+            s.wf = at((size_t)s.outCp * s.k * (s.rw ? s.rwKW : s.k * s.inCp) * es);
             s.wd = i > 0 ? at((size_t)s.inCp * s.k * s.k * s.outCp * es) : nullptr;
         }
         if (s.kind == ST_FC && s.in_is_spatial) {
@@ -164,6 +167,15 @@ int plan_net(asgd_net &n)
             s.outC = l.out; s.outCp = round_up(l.out, 8);
             s.outH = (H + 2 * l.pad - l.k) / l.stride + 1;
             s.outW = (W + 2 * l.pad - l.k) / l.stride + 1;
+            // First layer over <= 4 channels: padding them to 8 would make most of the reduction zeros.  Keep 4 per
+            // pixel and merge (kx, c) into one contiguous run instead, if the 16-byte pieces stay aligned.
+            const int es0 = (int)dtype_size(n.dtype);
+            if (n.stages.empty() && C <= 4 && (l.stride * 4 * es0) % 16 == 0) {
+                s.rw = 1;
+                s.rwKW = round_up(l.k * 4, 8);   // the filter-gradient GEMM wants its column count in eights
+                s.rwHp = H + 2 * l.pad;
+                s.rwWp = round_up(std::max(W + 2 * l.pad, (s.outW - 1) * l.stride + s.rwKW / 4), 16 / (4 * es0) > 1 ? 2 : 1);
+            }
             s.w_off = off; s.w_cnt = (size_t)l.out * C * l.k * l.k; s.b_off = off + s.w_cnt; s.b_cnt = l.out;
             off += s.w_cnt + s.b_cnt;
             C = l.out; H = s.outH; W = s.outW;
@@ -248,7 +260,8 @@ int plan_net(asgd_net &n)
         Stage &s = n.stages[si];
         if (s.kind == ST_CONV) {
             const long M = B * s.outH * s.outW, Min = B * s.inH * s.inW;
-            const long K = (long)s.k * s.k * s.inCp;
+            const long K = s.rw ? (long)s.k * s.rwKW : (long)s.k * s.k * s.inCp;
+            if (s.rw && (long)B * s.rwHp * s.rwWp * 16 > 0x7fffffffL) return fail(ASGD_ESHAPE, "layer %d: tensor too large", s.first_layer);
             if (M > 0x7fffffffL / 2 || Min > 0x7fffffffL / 2 || M * s.outCp * 4 > 0x7fffffffL || Min * s.inCp * 4 > 0x7fffffffL) return fail(ASGD_ESHAPE, "layer %d: tensor too large", s.first_layer);
             s.p_fwd = plan_gemm(M, s.outCp, K, n.dtype, 1);
             s.p_dgrad = plan_gemm(Min, s.inCp, (long)s.k * s.k * s.outCp, n.dtype, 1);
@@ -307,6 +320,23 @@ struct ProfScope {
     ~ProfScope() { if (stop) (void)hipEventRecord(stop, st); }
 };
 
+// The input side of a convolution stage as a gather over its (possibly bordered) input tensor x.
+Gather conv_gather(const Stage &s, const void *x, int B, int dt)
+{
+    const size_t es = dtype_size(dt);
+    Gather g;
+    g.x = x; g.N = B; g.Ho = s.outH; g.Wo = s.outW; g.sm = s.stride; g.ds = 1;
+    if (s.rw) {
+        g.H = s.rwHp; g.W = s.rwWp; g.C = s.rwKW; g.kh = s.k; g.kw = 1; g.pad = 0;
+        g.pix = 4 * es; g.rowb = (size_t)s.rwWp * 4 * es;
+        g.zero_off = (size_t)B * s.rwHp * s.rwWp * 4 * es;
+    } else {
+        g.H = s.inH; g.W = s.inW; g.C = s.inCp; g.kh = g.kw = s.k; g.pad = s.pad;
+        g.zero_off = (size_t)B * s.inH * s.inW * s.inCp * es;
+    }
+    return g;
+}
+
 const char *param_ptr(const asgd_net *n, const void *params, size_t off) { return static_cast<const char *>(params) + off * dtype_size(n->dtype); }
 
 int forward(asgd_net *n, const void *params, const void *images, const int32_t *labels, uint64_t seed, uint64_t step, uint32_t worker,
@@ -316,7 +346,9 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
     const double es = (double)dtype_size(dt), Bd = (double)B;
     {
         ProfScope ps(n, st, ASGD_K_LAYOUT, 0, 2 * Bd * n->in_c * n->in_h * n->in_w * es);
-        CHECK_LAUNCH(launch_stage_input(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, n->in_cp, st), "stage_input");
+        const Stage &s0 = n->stages[0];
+        if (s0.rw) CHECK_LAUNCH(launch_stage_input_rw(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, s0.pad, s0.rwWp, st), "stage_input");
+        else CHECK_LAUNCH(launch_stage_input(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, n->in_cp, st), "stage_input");
     }
     const void *cur = n->act0;
     for (size_t si = 0; si < n->stages.size(); ++si) {
@@ -324,18 +356,16 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
         if (s.kind == ST_CONV) {
             {
                 ProfScope ps(n, st, ASGD_K_LAYOUT, 0, (double)s.w_cnt * es * (s.wd ? 3 : 2));
-                CHECK_LAUNCH(launch_pack_conv(dt, param_ptr(n, params, s.w_off), s.wf, s.wd, s.outC, s.inC, s.k, s.k, s.outCp, s.inCp, st), "pack_conv");
+                if (s.rw) CHECK_LAUNCH(launch_pack_conv_rw(dt, param_ptr(n, params, s.w_off), s.wf, s.outC, s.inC, s.k, s.k, s.outCp, s.rwKW, st), "pack_conv");
+                else CHECK_LAUNCH(launch_pack_conv(dt, param_ptr(n, params, s.w_off), s.wf, s.wd, s.outC, s.inC, s.k, s.k, s.outCp, s.inCp, st), "pack_conv");
             }
             const double Mo = Bd * s.outH * s.outW;
             ProfScope ps(n, st, ASGD_K_CONV_FWD, 2 * Mo * s.outC * s.inC * s.k * s.k,
                          (Bd * s.inH * s.inW * s.inC + (double)s.w_cnt + Mo * s.outC) * es);
-            Gather g;
-            g.x = cur; g.N = B; g.H = s.inH; g.W = s.inW; g.C = s.inCp; g.Ho = s.outH; g.Wo = s.outW;
-            g.kh = g.kw = s.k; g.sm = s.stride; g.ds = 1; g.pad = s.pad;
-            g.zero_off = (size_t)B * s.inH * s.inW * s.inCp * dtype_size(dt);
+            const Gather g = conv_gather(s, cur, B, dt);
             Epilogue ep;
             ep.out = s.out; ep.ld = s.outCp; ep.bias = param_ptr(n, params, s.b_off); ep.bias_n = s.outC; ep.relu = s.relu;
-            CHECK_LAUNCH(gemm_gather_plain(dt, g, s.wf, (long)s.k * s.k * s.inCp, s.outCp, ep, s.p_fwd, n->scratch, n->zero_page, st), "conv forward");
+            CHECK_LAUNCH(gemm_gather_plain(dt, g, s.wf, (long)g.kh * g.kw * g.C, s.outCp, ep, s.p_fwd, n->scratch, n->zero_page, st), "conv forward");
         } else if (s.kind == ST_POOL) {
             ProfScope ps(n, st, ASGD_K_POOL_FWD, 0, Bd * s.outC * ((double)s.inH * s.inW * es + (double)s.outH * s.outW * (es + 1)));
             CHECK_LAUNCH(launch_pool_fwd(dt, cur, s.out, s.argmax, B, s.inH, s.inW, s.inCp, s.k, s.stride, st), "pool forward");
@@ -419,13 +449,10 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
                              "pool backward");
         } else {
             const long M = (long)B * s.outH * s.outW;
-            Gather g;
-            g.x = xin; g.N = B; g.H = s.inH; g.W = s.inW; g.C = s.inCp; g.Ho = s.outH; g.Wo = s.outW;
-            g.kh = g.kw = s.k; g.sm = s.stride; g.ds = 1; g.pad = s.pad;
-            g.zero_off = (size_t)B * s.inH * s.inW * s.inCp * dtype_size(dt);
+            const Gather g = conv_gather(s, xin, B, dt);
             Epilogue ew;
-            ew.out = grads + s.w_off; ew.mode = 1; ew.out_f32 = 1;
-            ew.cw_cout = s.outC; ew.cw_cin = s.inC; ew.cw_cinp = s.inCp; ew.cw_kh = s.k; ew.cw_kw = s.k;
+            ew.out = grads + s.w_off; ew.mode = s.rw ? 2 : 1; ew.out_f32 = 1;
+            ew.cw_cout = s.outC; ew.cw_cin = s.inC; ew.cw_cinp = s.rw ? s.rwKW : s.inCp; ew.cw_kh = s.k; ew.cw_kw = s.k;
             const double Mo = (double)M, conv_flops = 2 * Mo * s.outC * s.inC * s.k * s.k;
             {
                 ProfScope ps(n, st, ASGD_K_CONV_WGRAD, conv_flops, (Mo * s.outC + Bd * s.inH * s.inW * s.inC) * es + (double)s.w_cnt * 4);

@@ -36,6 +36,7 @@ struct Epilogue {
     long mask_ld = 0;
     float mask_scale = 1.f;
     int mode = 0;          // 1: rows are cout, columns are (ky,kx,ci_padded) -> [cout][cin][kh][kw]
+                           // 2: columns are (ky, kx*4+ci) over window rows of cw_cinp elements -> the same
     int cw_cout = 0, cw_cin = 0, cw_cinp = 0, cw_kh = 0, cw_kw = 0;
 };
 
@@ -51,6 +52,11 @@ struct Gather {
     int Ho = 0, Wo = 0;
     int kh = 0, kw = 0, sm = 1, ds = 1, pad = 0;
     size_t zero_off = 0;   // byte offset from x of at least 16 readable zero bytes (just behind the tensor)
+    // Byte strides between image rows and between pixels; 0 = dense (W*C and C elements).  Window-row form of a
+    // convolution over few input channels: the tensor is stored with its zero border, 4 channels per pixel, and
+    // described as kw = 1, pad = 0, C = one padded window row (kw*4 elements rounded up to 16 bytes), so that
+    // the K index is (ky, kx*4 + c) and a whole window row is one contiguous run.
+    size_t rowb = 0, pix = 0;
 };
 
 struct GemmPlan {
@@ -84,6 +90,10 @@ int launch_snapshot(const float *src, void *dst, size_t n, int dst_dtype, const 
                     int32_t *log_slot, int log_update, int log_worker, hipStream_t s);
 // images [B][C][H][W] (compute type) -> channel-last [B][H][W][Cp], zero padding channels
 int launch_stage_input(int dtype, const void *src, void *dst, int B, int C, int H, int W, int Cp, hipStream_t s);
+// the same into the interior of a bordered [B][H+2*pad][Wp][4] tensor (C <= 4; the border is not written)
+int launch_stage_input_rw(int dtype, const void *src, void *dst, int B, int C, int H, int W, int pad, int Wp, hipStream_t s);
+// canonical conv filters -> window-row pack [coutp][kh][KW], element (ky, kx*4 + ci), zeros elsewhere
+int launch_pack_conv_rw(int dtype, const void *w, void *wf, int cout, int cin, int kh, int kw, int coutp, int KW, hipStream_t s);
 // canonical conv filters -> forward pack [coutp][kh][kw][cinp] and flipped data-gradient pack [cinp][kh][kw][coutp]
 int launch_pack_conv(int dtype, const void *w, void *wf, void *wd, int cout, int cin, int kh, int kw, int coutp,
                      int cinp, hipStream_t s);

@@ -101,6 +101,7 @@ template <typename T> struct PlainK {
 template <typename T, bool WIDE> struct GatherK {
     static constexpr bool kTrans = false;
     const char *x; unsigned zero_off;
+    unsigned rowb, pix;  // bytes from one image row / one pixel to the next
     int H, W, C, Ho, Wo, kh, kw, sm, pad, M;
     int adv_px, adv_c;   // one K tile = adv_px whole pixels + adv_c channels
     FastDiv dWo, dHoWo, dC, dkw;
@@ -125,7 +126,7 @@ template <typename T, bool WIDE> struct GatherK {
             for (int a = 0; a < kh; ++a)
                 if ((ym >> a) & 1u) mask |= xm << (a * kw);
         }
-        return Row{(unsigned)(((n * H + y0) * W + x0) * C) * (unsigned)sizeof(T), mask};
+        return Row{(unsigned)(n * H + y0) * rowb + (unsigned)x0 * pix, mask};
     }
     __device__ __forceinline__ unsigned bit_of(int ky, int kx) const
     {
@@ -137,7 +138,7 @@ template <typename T, bool WIDE> struct GatherK {
         const int t = (int)fdiv((uint32_t)k, dC);
         const int ky = (int)fdiv((uint32_t)t, dkw);
         const int kx = t - ky * kw, c = k - t * C;
-        return KPos{ky, kx, c, (unsigned)((ky * W + kx) * C + c) * (unsigned)sizeof(T), bit_of(ky, kx)};
+        return KPos{ky, kx, c, (unsigned)ky * rowb + (unsigned)kx * pix + (unsigned)c * (unsigned)sizeof(T), bit_of(ky, kx)};
     }
     // branch-free: no divergent control flow between the loads of a pipeline step
     __device__ __forceinline__ void advance(KPos &kp, int) const
@@ -149,7 +150,7 @@ template <typename T, bool WIDE> struct GatherK {
         const int up = (int)fdiv((uint32_t)kp.kx, dkw);
         kp.kx -= up * kw;
         kp.ky += up;
-        kp.delta = (unsigned)((kp.ky * W + kp.kx) * C + kp.c) * (unsigned)sizeof(T);
+        kp.delta = (unsigned)kp.ky * rowb + (unsigned)kp.kx * pix + (unsigned)kp.c * (unsigned)sizeof(T);
         kp.bit = bit_of(kp.ky, kp.kx);
     }
     __device__ __forceinline__ uint4 load(const Row &r, const KPos &kp) const
@@ -229,6 +230,7 @@ template <typename T> struct PlainT {
 template <typename T> struct GatherT {
     static constexpr bool kTrans = true;
     const char *x; unsigned zero_off;
+    unsigned rowb, pix;  // bytes from one image row / one pixel to the next
     int H, W, C, Ho, Wo, kh, kw, sm, pad, M, Krows;
     FastDiv dWo, dHo, dHoWo, dC, dkw;
     struct Col { int ylo, xlo; unsigned yspan, xspan, off; };   // out-of-range columns: ylo huge, so no oy qualifies
@@ -246,7 +248,7 @@ template <typename T> struct GatherT {
         const int xhi = (W - 1 + pad - kx) >= 0 ? min(Wo - 1, (W - 1 + pad - kx) / sm) : -1;
         if (yhi < ylo || xhi < xlo) return Col{1 << 30, 0, 0u, 0u, 0u};
         return Col{ylo, xlo, (unsigned)(yhi - ylo), (unsigned)(xhi - xlo),
-                   (unsigned)(((ky - pad) * W + (kx - pad)) * C + c) * (unsigned)sizeof(T)};
+                   (unsigned)(ky - pad) * rowb + (unsigned)(kx - pad) * pix + (unsigned)c * (unsigned)sizeof(T)};
     }
     __device__ __forceinline__ KState kstate(int m) const
     {
@@ -269,7 +271,7 @@ template <typename T> struct GatherT {
     __device__ __forceinline__ uint4 load(const Col &c, const KState &ks) const
     {
         const bool ok = ks.m < M && (unsigned)(ks.oy - c.ylo) <= c.yspan && (unsigned)(ks.ox - c.xlo) <= c.xspan;
-        const unsigned off = c.off + (unsigned)(((ks.n * H + ks.oy * sm) * W + ks.ox * sm) * C) * (unsigned)sizeof(T);
+        const unsigned off = c.off + (unsigned)(ks.n * H + ks.oy * sm) * rowb + (unsigned)(ks.ox * sm) * pix;
         return ld16(x + (ok ? off : zero_off));
     }
 };
@@ -500,6 +502,17 @@ template <typename T> __device__ __forceinline__ void epilogue8(const Epilogue &
             if (ci0 + r < ep.cw_cin) o[(((long)m * ep.cw_cin + ci0 + r) * ep.cw_kh + ky) * ep.cw_kw + kx] = v[r];
         return;
     }
+    if (ep.mode == 2) {  // the same for window rows: columns are (ky, j), j = kx*4 + ci over a padded row of cw_cinp elements
+        if (m >= ep.cw_cout) return;
+        const int ky = n0 / ep.cw_cinp, j0 = n0 - ky * ep.cw_cinp;
+        float *o = static_cast<float *>(ep.out);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int kx = (j0 + r) >> 2, ci = (j0 + r) & 3;
+            if (ci < ep.cw_cin && kx < ep.cw_kw) o[(((long)m * ep.cw_cin + ci) * ep.cw_kh + ky) * ep.cw_kw + kx] = v[r];
+        }
+        return;
+    }
     if (ep.bias) {
         const T *b = static_cast<const T *>(ep.bias);
 #pragma unroll
@@ -619,6 +632,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
     static_assert(64 * PITCH * 4 <= (int)sizeof(smem), "staging area");
     float *stg = reinterpret_cast<float *>(smem);
     constexpr int LPR = BN / 8, RPR = NT / LPR;   // lanes per row, rows per round
+    if (dbg & 8) return;
     static_for<0, BM / 64>([&](auto p) ASGD_INLINE {
         __syncthreads();
         static_for<0, MB>([&](auto mb) ASGD_INLINE {
@@ -673,6 +687,14 @@ static bool pick_large(long M, long N)
     return force && force[0] == '2' && M >= 256 && N >= 256;
 }
 
+// ASGD_DBG in the environment switches phases of the GEMM kernel off (bit 0: global loads, 1: LDS stores,
+// 2: MFMAs, 3: the output phase) to time the others; results are then wrong.  For experiments only.
+static int debug_bits()
+{
+    static const int bits = getenv("ASGD_DBG") ? atoi(getenv("ASGD_DBG")) : 0;
+    return bits;
+}
+
 GemmPlan plan_gemm(long M, long N, long K, int dtype, int max_splits)
 {
     const int BK = dtype == kBF16 ? (int)Geo<bf16_t>::BK : (int)Geo<float>::BK;
@@ -680,7 +702,9 @@ GemmPlan plan_gemm(long M, long N, long K, int dtype, int max_splits)
     const int BM = large ? 256 : 128, BN = large ? 256 : 128;
     const long tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
     const long nkt = (K + BK - 1) / BK;
-    const long target = large ? 256 : 512;
+    // A single row of tiles with a moderate K (the FC layers at batch <= 128) is bound by the partial sums it
+    // writes and re-reads: one workgroup per CU with a deeper K range each beats two with half of it.
+    const long target = (large || (M <= BM && nkt <= 256)) ? 256 : 512;
     long splits = 1;
     if (max_splits > 1 && tiles < target) {
         splits = (target + tiles - 1) / tiles;
@@ -711,7 +735,7 @@ static int run_tile(const LA &la, const LB &lb, int M, int N, int K, const Epilo
     const long blocks = (long)tiles_m * tiles_n * splits;
     if (blocks > 0x7fffffffL) return -1;
     hipLaunchKernelGGL((gemm_kernel<T, Cfg, LA, LB>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, la, lb, ep, M, N, nkt, per, tiles_m,
-                       tiles_n, splits > 1 ? ws : nullptr, getenv("ASGD_DBG") ? atoi(getenv("ASGD_DBG")) : 0);
+                       tiles_n, splits > 1 ? ws : nullptr, debug_bits());
     if (splits > 1) {
         const long groups = (long)M * (N / 8);
         hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);
@@ -731,6 +755,7 @@ template <typename T, bool WIDE> static GatherK<T, WIDE> make_gather_k(const Gat
 {
     GatherK<T, WIDE> l;
     l.x = static_cast<const char *>(g.x); l.zero_off = (unsigned)g.zero_off;
+    l.pix = g.pix ? (unsigned)g.pix : (unsigned)(g.C * sizeof(T)); l.rowb = g.rowb ? (unsigned)g.rowb : (unsigned)(g.W * g.C * sizeof(T));
     l.H = g.H; l.W = g.W; l.C = g.C; l.Ho = g.Ho; l.Wo = g.Wo; l.kh = g.kh; l.kw = g.kw;
     l.sm = g.sm; l.pad = g.pad; l.M = g.N * g.Ho * g.Wo;
     l.adv_px = (int)Geo<T>::BK / g.C; l.adv_c = (int)Geo<T>::BK % g.C;
@@ -750,6 +775,7 @@ template <typename T> static GatherT<T> make_gather_t(const Gather &g)
 {
     GatherT<T> l;
     l.x = static_cast<const char *>(g.x); l.zero_off = (unsigned)g.zero_off;
+    l.pix = g.pix ? (unsigned)g.pix : (unsigned)(g.C * sizeof(T)); l.rowb = g.rowb ? (unsigned)g.rowb : (unsigned)(g.W * g.C * sizeof(T));
     l.H = g.H; l.W = g.W; l.C = g.C; l.Ho = g.Ho; l.Wo = g.Wo; l.kh = g.kh; l.kw = g.kw;
     l.sm = g.sm; l.pad = g.pad; l.M = g.N * g.Ho * g.Wo; l.Krows = g.kh * g.kw * g.C;
     l.dWo = make_fastdiv(g.Wo); l.dHo = make_fastdiv(g.Ho); l.dHoWo = make_fastdiv(g.Ho * g.Wo); l.dC = make_fastdiv(g.C); l.dkw = make_fastdiv(g.kw);

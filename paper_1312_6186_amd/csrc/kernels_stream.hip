@@ -199,6 +199,52 @@ int launch_stage_input(int dtype, const void *src, void *dst, int B, int C, int 
     return launch_ok();
 }
 
+template <typename T> __global__ __launch_bounds__(256) void stage_input_rw_kernel(const T *__restrict__ src, T *__restrict__ dst, int B, int C,
+                                                                                 int H, int W, int pad, int Wp)
+{
+    const long HW = (long)H * W;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long)B * HW) return;
+    const long n = i / HW, hw = i - n * HW;
+    const int h = (int)(hw / W), w = (int)(hw - (long)h * W);
+    union { T e[4]; uint2 u2; uint4 u4; } v;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v.e[c] = c < C ? src[(n * C + c) * HW + hw] : (T)0.f;
+    T *o = dst + ((n * (H + 2 * pad) + h + pad) * Wp + w + pad) * 4;
+    if constexpr (sizeof(T) == 2) *reinterpret_cast<uint2 *>(o) = v.u2;
+    else *reinterpret_cast<uint4 *>(o) = v.u4;
+}
+int launch_stage_input_rw(int dtype, const void *src, void *dst, int B, int C, int H, int W, int pad, int Wp, hipStream_t s)
+{
+    if (C > 4) return -1;
+    const unsigned blocks = blocks_for((size_t)B * H * W, 256);
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(stage_input_rw_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(src), static_cast<bf16_t *>(dst), B, C, H, W, pad, Wp);
+    else
+        hipLaunchKernelGGL(stage_input_rw_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(src), static_cast<float *>(dst), B, C, H, W, pad, Wp);
+    return launch_ok();
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void pack_conv_rw_kernel(const T *__restrict__ w, T *__restrict__ wf, int cout, int cin, int kh, int kw, int coutp, int KW)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long)coutp * kh * KW) return;
+    const int j = (int)(i % KW); long t = i / KW;
+    const int ky = (int)(t % kh), co = (int)(t / kh);
+    const int kx = j >> 2, ci = j & 3;
+    wf[i] = (co < cout && ci < cin && kx < kw) ? w[(((long)co * cin + ci) * kh + ky) * kw + kx] : (T)0.f;
+}
+int launch_pack_conv_rw(int dtype, const void *w, void *wf, int cout, int cin, int kh, int kw, int coutp, int KW, hipStream_t s)
+{
+    const unsigned blocks = blocks_for((size_t)coutp * kh * KW, 256);
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(pack_conv_rw_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(w), static_cast<bf16_t *>(wf), cout, cin, kh, kw, coutp, KW);
+    else
+        hipLaunchKernelGGL(pack_conv_rw_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(w), static_cast<float *>(wf), cout, cin, kh, kw, coutp, KW);
+    return launch_ok();
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void pack_conv_kernel(const T *__restrict__ w, T *__restrict__ wf, T *__restrict__ wd, int cout, int cin, int kh,
                                                       int kw, int coutp, int cinp)

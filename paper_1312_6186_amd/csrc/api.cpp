@@ -329,10 +329,10 @@ Gather conv_gather(const Stage &s, const void *x, int B, int dt)
     if (s.rw) {
         g.H = s.rwHp; g.W = s.rwWp; g.C = s.rwKW; g.kh = s.k; g.kw = 1; g.pad = 0;
         g.pix = 4 * es; g.rowb = (size_t)s.rwWp * 4 * es;
-        g.zero_off = (size_t)B * s.rwHp * s.rwWp * 4 * es;
+        g.bytes = (size_t)B * s.rwHp * s.rwWp * 4 * es;
     } else {
         g.H = s.inH; g.W = s.inW; g.C = s.inCp; g.kh = g.kw = s.k; g.pad = s.pad;
-        g.zero_off = (size_t)B * s.inH * s.inW * s.inCp * es;
+        g.bytes = (size_t)B * s.inH * s.inW * s.inCp * es;
     }
     return g;
 }
@@ -365,7 +365,7 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
             const Gather g = conv_gather(s, cur, B, dt);
             Epilogue ep;
             ep.out = s.out; ep.ld = s.outCp; ep.bias = param_ptr(n, params, s.b_off); ep.bias_n = s.outC; ep.relu = s.relu;
-            CHECK_LAUNCH(gemm_gather_plain(dt, g, s.wf, (long)g.kh * g.kw * g.C, s.outCp, ep, s.p_fwd, n->scratch, n->zero_page, st), "conv forward");
+            CHECK_LAUNCH(gemm_gather_plain(dt, g, s.wf, (long)g.kh * g.kw * g.C, s.outCp, ep, s.p_fwd, n->scratch, st), "conv forward");
         } else if (s.kind == ST_POOL) {
             ProfScope ps(n, st, ASGD_K_POOL_FWD, 0, Bd * s.outC * ((double)s.inH * s.inW * es + (double)s.outH * s.outW * (es + 1)));
             CHECK_LAUNCH(launch_pool_fwd(dt, cur, s.out, s.argmax, B, s.inH, s.inW, s.inCp, s.k, s.stride, st), "pool forward");
@@ -386,7 +386,7 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
                 ep.drop_thr = s.drop_thr; ep.drop_F = s.out_f; ep.drop_scale = s.drop_scale;
             }
             ProfScope ps(n, st, ASGD_K_FC_FWD, 2 * Bd * s.in_f * s.out_f, (Bd * s.in_f + (double)s.w_cnt) * es + Bd * s.out_f * (s.last ? 4 : es));
-            CHECK_LAUNCH(gemm_plain_plain(dt, x, ldx, B, param_ptr(n, params, s.w_off), s.in_f, s.out_ld, s.out_f, s.in_f, ep, s.p_fwd, n->scratch, n->zero_page, st),
+            CHECK_LAUNCH(gemm_plain_plain(dt, x, ldx, B, param_ptr(n, params, s.w_off), s.in_f, s.out_ld, s.out_f, s.in_f, ep, s.p_fwd, n->scratch, st),
                          "fc forward");
         }
         cur = s.out;
@@ -413,7 +413,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
             ew.out = grads + s.w_off; ew.ld = s.in_f; ew.out_f32 = 1;
             {
                 ProfScope ps(n, st, ASGD_K_FC_WGRAD, 2 * Bd * s.in_f * s.out_f, Bd * (s.in_f + s.out_f) * es + (double)s.w_cnt * 4);
-                CHECK_LAUNCH(gemm_trans_trans(dt, s.dout, s.out_ld, s.out_f, x, ldx, s.in_f, B, ew, s.p_wgrad, n->scratch, n->zero_page, st), "fc weight gradient");
+                CHECK_LAUNCH(gemm_trans_trans(dt, s.dout, s.out_ld, s.out_f, x, ldx, s.in_f, B, ew, s.p_wgrad, n->scratch, st), "fc weight gradient");
             }
             {
                 ProfScope ps(n, st, ASGD_K_BIAS_GRAD, 0, Bd * s.out_f * es + s.out_f * 4.0);
@@ -430,7 +430,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
                 {
                     ProfScope ps(n, st, ASGD_K_FC_DGRAD, 2 * Bd * s.in_f * s.out_f, (Bd * s.out_f + (double)s.w_cnt + Bd * s.in_f * (ed.mask_src ? 2 : 1)) * es);
                     CHECK_LAUNCH(gemm_plain_trans(dt, s.dout, s.out_ld, B, param_ptr(n, params, s.w_off), s.in_f, s.in_f, s.out_f, ed, s.p_dgrad,
-                                                  n->scratch, n->zero_page, st),
+                                                  n->scratch, st),
                                  "fc data gradient");
                 }
                 ProfScope ps(n, st, ASGD_K_LAYOUT, 0, s.in_is_spatial ? 3 * Bd * s.in_f * es : 0);
@@ -456,7 +456,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
             const double Mo = (double)M, conv_flops = 2 * Mo * s.outC * s.inC * s.k * s.k;
             {
                 ProfScope ps(n, st, ASGD_K_CONV_WGRAD, conv_flops, (Mo * s.outC + Bd * s.inH * s.inW * s.inC) * es + (double)s.w_cnt * 4);
-                CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch, n->zero_page, st), "conv filter gradient");
+                CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch, st), "conv filter gradient");
             }
             {
                 ProfScope ps(n, st, ASGD_K_BIAS_GRAD, 0, Mo * s.outC * es + s.outC * 4.0);
@@ -466,13 +466,13 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
                 Gather d;
                 d.x = s.dout; d.N = B; d.H = s.outH; d.W = s.outW; d.C = s.outCp; d.Ho = s.inH; d.Wo = s.inW;
                 d.kh = d.kw = s.k; d.sm = 1; d.ds = s.stride; d.pad = s.k - 1 - s.pad;
-                d.zero_off = (size_t)B * s.outH * s.outW * s.outCp * dtype_size(dt);
+                d.bytes = (size_t)B * s.outH * s.outW * s.outCp * dtype_size(dt);
                 Epilogue ed;
                 ed.out = prev->dout; ed.ld = s.inCp;
                 if (prev->kind == ST_CONV && prev->relu) { ed.mask_src = prev->out; ed.mask_ld = s.inCp; ed.mask_scale = 1.f; }
                 ProfScope ps(n, st, ASGD_K_CONV_DGRAD, conv_flops,
                              (Mo * s.outC + (double)s.w_cnt + Bd * s.inH * s.inW * s.inC * (ed.mask_src ? 2 : 1)) * es);
-                CHECK_LAUNCH(gemm_gather_plain(dt, d, s.wd, (long)s.k * s.k * s.outCp, s.inCp, ed, s.p_dgrad, n->scratch, n->zero_page, st), "conv data gradient");
+                CHECK_LAUNCH(gemm_gather_plain(dt, d, s.wd, (long)s.k * s.k * s.outCp, s.inCp, ed, s.p_dgrad, n->scratch, st), "conv data gradient");
             }
         }
     }

@@ -51,7 +51,7 @@ struct Gather {
     int N = 0, H = 0, W = 0, C = 0;
     int Ho = 0, Wo = 0;
     int kh = 0, kw = 0, sm = 1, ds = 1, pad = 0;
-    size_t zero_off = 0;   // byte offset from x of at least 16 readable zero bytes (just behind the tensor)
+    size_t bytes = 0;      // size of the tensor in bytes (at most 1 GiB); pieces outside it read as zeros
     // Byte strides between image rows and between pixels; 0 = dense (W*C and C elements).  Window-row form of a
     // convolution over few input channels: the tensor is stored with its zero border, 4 channels per pixel, and
     // described as kw = 1, pad = 0, C = one padded window row (kw*4 elements rounded up to 16 bytes), so that
@@ -64,24 +64,24 @@ struct GemmPlan {
     size_t ws_floats = 0;    // fp32 scratch needed when splits > 1
 };
 
-// `zero` points at 16 readable zero bytes in device memory (out-of-range pieces are fetched from there).
+// Every operand must fit in 1 GiB.
 // C[M][N] = A[M][K] * B[N][K]^T; A gathered (direct), B plain K-contiguous.
 GemmPlan plan_gemm(long M, long N, long K, int dtype, int max_splits);
 int gemm_gather_plain(int dtype, const Gather &a, const void *b, long ldb, int N, const Epilogue &ep,
-                      const GemmPlan &plan, float *ws, const void *zero, hipStream_t s);
+                      const GemmPlan &plan, float *ws, hipStream_t s);
 // A plain [M][lda], B plain [b_rows][ldb], both K-contiguous; columns n >= b_rows of C are computed as zeros.
 int gemm_plain_plain(int dtype, const void *a, long lda, int M, const void *b, long ldb, int N, int b_rows, int K,
-                     const Epilogue &ep, const GemmPlan &plan, float *ws, const void *zero, hipStream_t s);
+                     const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s);
 // A plain [M][lda] K-contiguous; B stored [K][ldb] (rows n contiguous).
 int gemm_plain_trans(int dtype, const void *a, long lda, int M, const void *bt, long ldb, int N, int K,
-                     const Epilogue &ep, const GemmPlan &plan, float *ws, const void *zero, hipStream_t s);
+                     const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s);
 // A stored [K][lda] (rows m contiguous), B stored [K][ldb].
 int gemm_trans_trans(int dtype, const void *at, long lda, int M, const void *bt, long ldb, int N, int K,
-                     const Epilogue &ep, const GemmPlan &plan, float *ws, const void *zero, hipStream_t s);
+                     const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s);
 // Filter gradient: A stored [K = B*Ho*Wo][lda] (rows = cout), B gathered with the
 // reduction index enumerating (n, oy, ox) and rows enumerating (ky, kx, c).
 int gemm_trans_gather(int dtype, const void *at, long lda, int M, const Gather &b, const Epilogue &ep,
-                      const GemmPlan &plan, float *ws, const void *zero, hipStream_t s);
+                      const GemmPlan &plan, float *ws, hipStream_t s);
 
 // ---- streaming kernels (kernels_stream.hip) --------------------------------
 int launch_update(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd,

@@ -41,8 +41,7 @@ template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int DEPTH_, int MINB_> s
     static constexpr int MB = BM_ / WAVES_M_ / 32, NB = BN_ / WAVES_N_ / 32;   // MFMA 32x32 blocks per wave
     static_assert((BM_ / WAVES_M_) % 64 == 0 && (BN_ / WAVES_N_) % 64 == 0, "wave tiles are multiples of 64");
 };
-using CfgSmall = TileCfg<128, 128, 2, 2, 2, 2>;   // 256 threads, two workgroups per CU
-using CfgLarge = TileCfg<256, 256, 2, 2, 2, 1>;   // 256 threads, 128x128 per wave (accumulators fill the AGPRs), one workgroup per CU
+using Cfg128 = TileCfg<128, 128, 2, 2, 2, 2>;   // 256 threads, two workgroups per CU
 #define ASGD_INLINE __attribute__((always_inline))
 
 // Compile-time loop: indices reach the body as constants, so register arrays are never addressed dynamically.
@@ -68,27 +67,53 @@ FastDiv make_fastdiv(uint32_t d)
 }
 
 __device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) { return (__umulhi(n, f.mul) + n) >> f.sh; }
-__device__ __forceinline__ uint4 ld16(const void *p) { return *reinterpret_cast<const uint4 *>(p); }
-__device__ __forceinline__ uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
 
 // ------------------------------------------------------------------ loaders
+// All operand fetches are 16-byte buffer loads: the operand tensor is described to the hardware as a byte range,
+// a lane passes a 32-bit byte offset, and an offset outside the range returns zeros.  A loader therefore never
+// builds a 64-bit address and never branches: pieces that must read as zero (rows or K positions past the end,
+// window positions outside the image) get an offset with the top two bits set.  Offsets of valid pieces stay
+// below 1 GiB (checked on the host), so the sum of a valid and an invalid part is still out of range.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+constexpr unsigned kInv = 0xC0000000u;
+constexpr unsigned kMaxOperandBytes = 0x40000000u;
+
+struct Operand {
+    const void *base; unsigned bytes;
+    __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc() const
+    {
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+    }
+};
+__device__ __forceinline__ uint4 buf_ld16(__amdgpu_buffer_rsrc_t rs, unsigned off)
+{
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+// value of lane S of the caller's quad (4 consecutive lanes)
+template <int S> __device__ __forceinline__ unsigned quad_bcast(unsigned v)
+{
+    return (unsigned)__builtin_amdgcn_mov_dpp((int)v, S * 0x55, 0xF, 0xF, true);
+}
+
 // Direct loaders hand out 16-byte pieces of a row that are contiguous in K.
 template <typename T> struct PlainK {
     static constexpr bool kTrans = false;
-    const T *base; long ld; int rows; int K; const T *zero;   // zero: 16 readable zero bytes
-    struct Row { const T *p; };
-    struct KPos { int k; };
-    __device__ __forceinline__ Row row(int r) const { return Row{r < rows ? base + (long)r * ld : nullptr}; }
-    __device__ __forceinline__ KPos kpos(int k) const { return KPos{k}; }
-    __device__ __forceinline__ void advance(KPos &kp, int dk) const { kp.k += dk; }
-    __device__ __forceinline__ uint4 load(const Row &r, const KPos &kp) const
+    Operand op; unsigned ldb; int rows, K;   // ldb: bytes from one row to the next
+    struct Row { unsigned off; };
+    struct KPos { int k; unsigned koff; };
+    __device__ __forceinline__ Row row(int r) const { return Row{r < rows ? (unsigned)r * ldb : kInv}; }
+    __device__ __forceinline__ KPos kpos(int k) const { return KPos{k, k < K ? (unsigned)k * (unsigned)sizeof(T) : kInv}; }
+    __device__ __forceinline__ void advance(KPos &kp, int dk) const
     {
-        return ld16((r.p != nullptr && kp.k < K) ? r.p + kp.k : zero);
+        kp.k += dk;
+        kp.koff = kp.k < K ? (unsigned)kp.k * (unsigned)sizeof(T) : kInv;
     }
+    __device__ __forceinline__ unsigned voff(const Row &r, const KPos &kp) const { return r.off + kp.koff; }
 };
 
 // Implicit-GEMM gather, unit divisor (forward convolution, stride-1 data gradient).
@@ -96,11 +121,10 @@ template <typename T> struct PlainK {
 // and a bit mask saying which window positions (ky, kx) fall inside the image; a K
 // position keeps the byte offset of (ky, kx, c) relative to a window origin and
 // the bit of its window position.  Fetching a piece is then one mask test, one add
-// and one select (out-of-image pieces read 16 zero bytes that sit right behind the
-// tensor).  WIDE = windows of more than 32 positions (two 16-bit masks, one per axis).
+// and one select.  WIDE = windows of more than 32 positions (two 16-bit masks, one per axis).
 template <typename T, bool WIDE> struct GatherK {
     static constexpr bool kTrans = false;
-    const char *x; unsigned zero_off;
+    Operand op;
     unsigned rowb, pix;  // bytes from one image row / one pixel to the next
     int H, W, C, Ho, Wo, kh, kw, sm, pad, M;
     int adv_px, adv_c;   // one K tile = adv_px whole pixels + adv_c channels
@@ -153,10 +177,10 @@ template <typename T, bool WIDE> struct GatherK {
         kp.delta = (unsigned)kp.ky * rowb + (unsigned)kp.kx * pix + (unsigned)kp.c * (unsigned)sizeof(T);
         kp.bit = bit_of(kp.ky, kp.kx);
     }
-    __device__ __forceinline__ uint4 load(const Row &r, const KPos &kp) const
+    __device__ __forceinline__ unsigned voff(const Row &r, const KPos &kp) const
     {
         const bool ok = WIDE ? (kp.bit != 0u && (r.mask & kp.bit) == kp.bit) : ((r.mask & kp.bit) != 0u);
-        return ld16(x + (ok ? r.off + kp.delta : zero_off));
+        return ok ? r.off + kp.delta : kInv;
     }
 };
 
@@ -164,7 +188,7 @@ template <typename T, bool WIDE> struct GatherK {
 // that are not multiples of the stride contribute nothing.  Rare, kept simple.
 template <typename T> struct GatherKS {
     static constexpr bool kTrans = false;
-    const T *x; int H, W, C, Ho, Wo, kh, kw, sm, ds, pad, M;
+    Operand op; int H, W, C, Ho, Wo, kh, kw, sm, ds, pad, M;
     FastDiv dWo, dHoWo, dC, dkw;
     struct Row { int pix0, y0, x0; };  // pix0 < 0: row out of range
     struct KPos { int ky, kx, c; };
@@ -191,15 +215,15 @@ template <typename T> struct GatherKS {
             if (++kp.kx == kw) { kp.kx = 0; ++kp.ky; }
         }
     }
-    __device__ __forceinline__ uint4 load(const Row &r, const KPos &kp) const
+    __device__ __forceinline__ unsigned voff(const Row &r, const KPos &kp) const
     {
-        if (r.pix0 < 0 || kp.ky >= kh) return zero16();
+        if (r.pix0 < 0 || kp.ky >= kh) return kInv;
         int y = r.y0 + kp.ky, xx = r.x0 + kp.kx;
-        if (y < 0 || xx < 0) return zero16();
-        if ((y % ds) != 0 || (xx % ds) != 0) return zero16();
+        if (y < 0 || xx < 0) return kInv;
+        if ((y % ds) != 0 || (xx % ds) != 0) return kInv;
         y /= ds; xx /= ds;
-        if (y >= H || xx >= W) return zero16();
-        return ld16(x + ((long)(r.pix0 + y * W + xx) * C + kp.c));
+        if (y >= H || xx >= W) return kInv;
+        return (unsigned)((r.pix0 + y * W + xx) * C + kp.c) * (unsigned)sizeof(T);
     }
 };
 
@@ -207,48 +231,45 @@ template <typename T> struct GatherKS {
 // reduction index strided ([k][rows]).  The tile is copied to LDS in that same
 // orientation, 16 bytes (8 or 4 consecutive rows) at a time; the transposition
 // the MFMA needs happens in the LDS read (ds_read_b64_tr_b16 for 16-bit data).
-// A thread keeps one column of 16-byte pieces (Col) and walks down the K axis
-// (KState per slot).
+// A thread keeps one column of 16-byte pieces (Col) and walks down the K axis.
 template <typename T> struct PlainT {
-    static constexpr bool kTrans = true;
-    const T *base; long ld; int rows; int K; const T *zero;
-    struct Col { const T *p; };    // nullptr: rows out of range
-    struct KState { int k; };
-    __device__ __forceinline__ Col col(int row0) const { return Col{row0 < rows ? base + row0 : nullptr}; }
-    __device__ __forceinline__ KState kstate(int k) const { return KState{k}; }
-    __device__ __forceinline__ void advance(KState &ks, int dk) const { ks.k += dk; }
-    __device__ __forceinline__ uint4 load(const Col &c, const KState &ks) const
+    static constexpr bool kTrans = true, kShared = false;
+    Operand op; unsigned ldb; int rows, K;
+    struct Col { unsigned off; };
+    struct KState { int k; unsigned koff; };
+    __device__ __forceinline__ Col col(int row0) const { return Col{row0 < rows ? (unsigned)row0 * (unsigned)sizeof(T) : kInv}; }
+    __device__ __forceinline__ KState kstate(int k) const { return KState{k, k < K ? (unsigned)k * ldb : kInv}; }
+    __device__ __forceinline__ void advance(KState &ks, int dk) const
     {
-        return ld16((c.p != nullptr && ks.k < K) ? c.p + (long)ks.k * ld : zero);
+        ks.k += dk;
+        ks.koff = ks.k < K ? ks.koff + (unsigned)dk * ldb : kInv;   // once past K it stays past K
     }
+    __device__ __forceinline__ unsigned voff(const Col &c, const KState &ks) const { return c.off + ks.koff; }
 };
 
-// Filter-gradient gather: rows enumerate (ky, kx, c) (fixed per column of pieces),
-// the reduction index enumerates output pixels m = (n, oy, ox).  The valid oy / ox
-// ranges of a column are precomputed; a K state carries (n, oy, ox) and is moved
-// down the K axis without branches.
+// Filter-gradient gather: rows enumerate (ky, kx, c) (fixed per column of pieces), the reduction index
+// enumerates output pixels m = (n, oy, ox).  What depends on the pixel alone (the byte offset of its window
+// origin and the mask of window positions that fall inside the image) is computed once per pixel and K tile:
+// the four lanes of a quad copy the same column for four different pixels, each works out one pixel and the
+// quad exchanges the results with DPP moves.  A column keeps its offset inside the window and the mask bits of
+// its (ky, kx); a piece is fetched iff the pixel's mask has both bits.
 template <typename T> struct GatherT {
-    static constexpr bool kTrans = true;
-    const char *x; unsigned zero_off;
+    static constexpr bool kTrans = true, kShared = true;
+    Operand op;
     unsigned rowb, pix;  // bytes from one image row / one pixel to the next
     int H, W, C, Ho, Wo, kh, kw, sm, pad, M, Krows;
     FastDiv dWo, dHo, dHoWo, dC, dkw;
-    struct Col { int ylo, xlo; unsigned yspan, xspan, off; };   // out-of-range columns: ylo huge, so no oy qualifies
+    struct Col { unsigned off, bits; };   // out-of-range columns: bits no pixel mask can have
     struct KState { int m, n, oy, ox; };
+    struct Pixel { unsigned base, mask; };
     __device__ __forceinline__ Col col(int row0) const
     {
-        if (row0 >= Krows) return Col{1 << 30, 0, 0u, 0u, 0u};
+        if (row0 >= Krows) return Col{0u, 0xFFFFFFFFu};
         const int t = (int)fdiv((uint32_t)row0, dC);
         const int ky = (int)fdiv((uint32_t)t, dkw);
         const int kx = t - ky * kw, c = row0 - t * C;
-        // oy valid iff 0 <= oy*sm + ky - pad < H
-        const int ylo = ky >= pad ? 0 : (pad - ky + sm - 1) / sm;
-        const int yhi = (H - 1 + pad - ky) >= 0 ? min(Ho - 1, (H - 1 + pad - ky) / sm) : -1;
-        const int xlo = kx >= pad ? 0 : (pad - kx + sm - 1) / sm;
-        const int xhi = (W - 1 + pad - kx) >= 0 ? min(Wo - 1, (W - 1 + pad - kx) / sm) : -1;
-        if (yhi < ylo || xhi < xlo) return Col{1 << 30, 0, 0u, 0u, 0u};
-        return Col{ylo, xlo, (unsigned)(yhi - ylo), (unsigned)(xhi - xlo),
-                   (unsigned)(ky - pad) * rowb + (unsigned)(kx - pad) * pix + (unsigned)c * (unsigned)sizeof(T)};
+        return Col{(unsigned)(ky - pad) * rowb + (unsigned)(kx - pad) * pix + (unsigned)c * (unsigned)sizeof(T),
+                   (1u << ky) | (1u << (16 + kx))};
     }
     __device__ __forceinline__ KState kstate(int m) const
     {
@@ -268,11 +289,17 @@ template <typename T> struct GatherT {
         ks.oy -= q2 * Ho;
         ks.n += q2;
     }
-    __device__ __forceinline__ uint4 load(const Col &c, const KState &ks) const
+    __device__ __forceinline__ Pixel pixel(const KState &ks) const
     {
-        const bool ok = ks.m < M && (unsigned)(ks.oy - c.ylo) <= c.yspan && (unsigned)(ks.ox - c.xlo) <= c.xspan;
-        const unsigned off = c.off + (unsigned)(ks.n * H + ks.oy * sm) * rowb + (unsigned)(ks.ox * sm) * pix;
-        return ld16(x + (ok ? off : zero_off));
+        const int y0 = ks.oy * sm - pad, x0 = ks.ox * sm - pad;
+        const int ylo = max(0, -y0), yhi = max(ylo, min(kh, H - y0));
+        const int xlo = max(0, -x0), xhi = max(xlo, min(kw, W - x0));
+        const unsigned ym = ((1u << yhi) - 1u) & ~((1u << ylo) - 1u), xm = ((1u << xhi) - 1u) & ~((1u << xlo) - 1u);
+        return Pixel{(unsigned)(ks.n * H + ks.oy * sm) * rowb + (unsigned)(ks.ox * sm) * pix, ks.m < M ? (ym | (xm << 16)) : 0u};
+    }
+    __device__ __forceinline__ unsigned voff(const Col &c, unsigned base, unsigned mask) const
+    {
+        return (mask & c.bits) == c.bits ? c.off + base : kInv;
     }
 };
 
@@ -297,7 +324,8 @@ template <typename T, class L, int ROWS, int NT, int DEPTH> struct Stage<T, L, R
     // fetch the K tile at the cursor into register set RB and advance the cursor
     template <int RB> __device__ __forceinline__ void load(const L &l)
     {
-        static_for<0, SLOTS>([&](auto s) ASGD_INLINE { r[RB][s] = l.load(rows[s], kp); });
+        const __amdgpu_buffer_rsrc_t rs = l.op.rsrc();
+        static_for<0, SLOTS>([&](auto s) ASGD_INLINE { r[RB][s] = buf_ld16(rs, l.voff(rows[s], kp)); });
         l.advance(kp, Geo<T>::BK);
     }
     template <int RB> __device__ __forceinline__ void store(uint4 *sm, int tid) const
@@ -310,10 +338,10 @@ template <typename T, class L, int ROWS, int NT, int DEPTH> struct Stage<T, L, R
     }
 };
 
-// LDS tile of a row-contiguous operand: BK lines of ROWS elements, each line padded by 32 bytes so that the
-// four K lines a transposing read touches fall into different banks.
+// LDS tile of a row-contiguous operand: BK lines of ROWS elements.  A transposing read makes half a wave touch
+// 4 K lines x 64 bytes; with lines 64 bytes (mod 256) apart those eight 32-byte groups cover all banks once.
 template <typename T, int ROWS> struct TransTile {
-    static constexpr int LINE = ROWS * (int)sizeof(T) + 32;   // bytes
+    static constexpr int LINE = ROWS * (int)sizeof(T) + (sizeof(T) == 2 ? 64 : 32);   // bytes
     static constexpr int BYTES = Geo<T>::BK * LINE;
 };
 
@@ -321,24 +349,36 @@ template <typename T, class L, int ROWS, int NT, int DEPTH> struct Stage<T, L, R
     static constexpr int CPL = ROWS * (int)sizeof(T) / 16;   // 16-byte pieces per K line
     static constexpr int LPP = NT / CPL;                     // K lines covered by one pass of the workgroup
     static constexpr int SLOTS = Geo<T>::BK / LPP;
+    static constexpr int NKS = L::kShared ? 1 : SLOTS;
     static_assert(NT % CPL == 0 && Geo<T>::BK % LPP == 0, "tile / thread-count mismatch");
+    static_assert(!L::kShared || (SLOTS == 4 && CPL % 4 == 0), "a quad shares one column and owns four K lines");
     typename L::Col c;
-    typename L::KState ks[SLOTS];
+    typename L::KState ks[NKS];   // shared form: the K line of slot (tid & 3) only
     uint4 r[DEPTH][SLOTS];
     unsigned wo;   // LDS byte offset of slot 0
     __device__ __forceinline__ void init(const L &l, int row0, int k0, int tid, int)
     {
         const int cc = tid % CPL, line = tid / CPL;
         c = l.col(row0 + cc * (16 / (int)sizeof(T)));
-        static_for<0, SLOTS>([&](auto s) ASGD_INLINE { ks[s] = l.kstate(k0 + line + s * LPP); });
+        if constexpr (L::kShared) ks[0] = l.kstate(k0 + line + (tid & 3) * LPP);
+        else static_for<0, SLOTS>([&](auto s) ASGD_INLINE { ks[s] = l.kstate(k0 + line + s * LPP); });
         wo = (unsigned)(line * TransTile<T, ROWS>::LINE + cc * 16);
     }
     template <int RB> __device__ __forceinline__ void load(const L &l)
     {
-        static_for<0, SLOTS>([&](auto s) ASGD_INLINE {
-            r[RB][s] = l.load(c, ks[s]);
-            l.advance(ks[s], Geo<T>::BK);
-        });
+        const __amdgpu_buffer_rsrc_t rs = l.op.rsrc();
+        if constexpr (L::kShared) {
+            const auto px = l.pixel(ks[0]);
+            l.advance(ks[0], Geo<T>::BK);
+            static_for<0, SLOTS>([&](auto s) ASGD_INLINE {
+                r[RB][s] = buf_ld16(rs, l.voff(c, quad_bcast<s>(px.base), quad_bcast<s>(px.mask)));
+            });
+        } else {
+            static_for<0, SLOTS>([&](auto s) ASGD_INLINE {
+                r[RB][s] = buf_ld16(rs, l.voff(c, ks[s]));
+                l.advance(ks[s], Geo<T>::BK);
+            });
+        }
     }
     template <int RB> __device__ __forceinline__ void store(uint4 *sm, int) const
     {
@@ -612,15 +652,15 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
     for (int t = 0; t < nt; t += 2) {
         // step t (even): multiply out of LDS stage 0, fetch tile t+DEPTH, then move tile t+1 into stage 1
         __syncthreads();
-        if (!(dbg & 1)) { stA.template load<0>(la); stB.template load<0>(lb); }   // past the last tile this fetches zeros, which nothing consumes
+        stA.template load<0>(la); stB.template load<0>(lb);   // past the last tile this fetches zeros, which nothing consumes
         if (!(dbg & 4)) compute_tile<T, MB, NB>(sA[0], sB[0], acc, foA, foB);
         if (t + 1 < nt) {
-            if (!(dbg & 2)) { stA.template store<DEPTH - 1>(sA[1], tid); stB.template store<DEPTH - 1>(sB[1], tid); }
+            stA.template store<DEPTH - 1>(sA[1], tid); stB.template store<DEPTH - 1>(sB[1], tid);
             // step t+1 (odd): multiply out of LDS stage 1, fetch tile t+1+DEPTH, then move tile t+2 into stage 0
             __syncthreads();
-            if (!(dbg & 1)) { stA.template load<DEPTH - 1>(la); stB.template load<DEPTH - 1>(lb); }
+            stA.template load<DEPTH - 1>(la); stB.template load<DEPTH - 1>(lb);
             if (!(dbg & 4)) compute_tile<T, MB, NB>(sA[1], sB[1], acc, foA, foB);
-            if (t + 2 < nt && !(dbg & 2)) { stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid); }
+            if (t + 2 < nt) { stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid); }
         }
     }
 
@@ -678,17 +718,8 @@ template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_kerne
 }
 
 // ------------------------------------------------------------------ host side
-// The 256x256 configuration halves the operand traffic per multiply-add but runs one wave per SIMD; measured on
-// the AlexNet-style shapes at batch 128 and 256 it does not beat two 128x128 workgroups per CU yet, so it is
-// only used on request (ASGD_TILE=2 in the environment, for experiments).
-static bool pick_large(long M, long N)
-{
-    static const char *force = getenv("ASGD_TILE");
-    return force && force[0] == '2' && M >= 256 && N >= 256;
-}
-
-// ASGD_DBG in the environment switches phases of the GEMM kernel off (bit 0: global loads, 1: LDS stores,
-// 2: MFMAs, 3: the output phase) to time the others; results are then wrong.  For experiments only.
+// ASGD_DBG in the environment switches phases of the GEMM kernel off (bit 2: the MFMAs, bit 3: the output
+// phase) to time the rest; results are then wrong.  For experiments only.
 static int debug_bits()
 {
     static const int bits = getenv("ASGD_DBG") ? atoi(getenv("ASGD_DBG")) : 0;
@@ -698,13 +729,12 @@ static int debug_bits()
 GemmPlan plan_gemm(long M, long N, long K, int dtype, int max_splits)
 {
     const int BK = dtype == kBF16 ? (int)Geo<bf16_t>::BK : (int)Geo<float>::BK;
-    const bool large = pick_large(M, N);
-    const int BM = large ? 256 : 128, BN = large ? 256 : 128;
+    const int BM = Cfg128::BM, BN = Cfg128::BN;
     const long tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
     const long nkt = (K + BK - 1) / BK;
     // A single row of tiles with a moderate K (the FC layers at batch <= 128) is bound by the partial sums it
     // writes and re-reads: one workgroup per CU with a deeper K range each beats two with half of it.
-    const long target = (large || (M <= BM && nkt <= 256)) ? 256 : 512;
+    const long target = (M <= BM && nkt <= 256) ? 256 : 512;
     long splits = 1;
     if (max_splits > 1 && tiles < target) {
         splits = (target + tiles - 1) / tiles;
@@ -747,14 +777,16 @@ template <typename T, class LA, class LB>
 static int run(const LA &la, const LB &lb, int M, int N, int K, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
     if (M <= 0 || N <= 0 || K <= 0 || (N & 7)) return -1;
-    if (pick_large(M, N)) return run_tile<T, CfgLarge>(la, lb, M, N, K, ep, plan, ws, s);
-    return run_tile<T, CfgSmall>(la, lb, M, N, K, ep, plan, ws, s);
+    if (la.op.bytes == 0 || lb.op.bytes == 0) return -1;   // an operand beyond the 1 GiB the 32-bit offsets cover
+    return run_tile<T, Cfg128>(la, lb, M, N, K, ep, plan, ws, s);
 }
+
+static Operand operand(const void *p, size_t bytes) { return Operand{p, bytes <= kMaxOperandBytes ? (unsigned)bytes : 0u}; }
 
 template <typename T, bool WIDE> static GatherK<T, WIDE> make_gather_k(const Gather &g)
 {
     GatherK<T, WIDE> l;
-    l.x = static_cast<const char *>(g.x); l.zero_off = (unsigned)g.zero_off;
+    l.op = operand(g.x, g.bytes);
     l.pix = g.pix ? (unsigned)g.pix : (unsigned)(g.C * sizeof(T)); l.rowb = g.rowb ? (unsigned)g.rowb : (unsigned)(g.W * g.C * sizeof(T));
     l.H = g.H; l.W = g.W; l.C = g.C; l.Ho = g.Ho; l.Wo = g.Wo; l.kh = g.kh; l.kw = g.kw;
     l.sm = g.sm; l.pad = g.pad; l.M = g.N * g.Ho * g.Wo;
@@ -765,7 +797,7 @@ template <typename T, bool WIDE> static GatherK<T, WIDE> make_gather_k(const Gat
 template <typename T> static GatherKS<T> make_gather_ks(const Gather &g)
 {
     GatherKS<T> l;
-    l.x = static_cast<const T *>(g.x);
+    l.op = operand(g.x, g.bytes);
     l.H = g.H; l.W = g.W; l.C = g.C; l.Ho = g.Ho; l.Wo = g.Wo; l.kh = g.kh; l.kw = g.kw;
     l.sm = g.sm; l.ds = g.ds; l.pad = g.pad; l.M = g.N * g.Ho * g.Wo;
     l.dWo = make_fastdiv(g.Wo); l.dHoWo = make_fastdiv(g.Ho * g.Wo); l.dC = make_fastdiv(g.C); l.dkw = make_fastdiv(g.kw);
@@ -774,73 +806,72 @@ template <typename T> static GatherKS<T> make_gather_ks(const Gather &g)
 template <typename T> static GatherT<T> make_gather_t(const Gather &g)
 {
     GatherT<T> l;
-    l.x = static_cast<const char *>(g.x); l.zero_off = (unsigned)g.zero_off;
+    l.op = operand(g.x, g.bytes);
     l.pix = g.pix ? (unsigned)g.pix : (unsigned)(g.C * sizeof(T)); l.rowb = g.rowb ? (unsigned)g.rowb : (unsigned)(g.W * g.C * sizeof(T));
     l.H = g.H; l.W = g.W; l.C = g.C; l.Ho = g.Ho; l.Wo = g.Wo; l.kh = g.kh; l.kw = g.kw;
     l.sm = g.sm; l.pad = g.pad; l.M = g.N * g.Ho * g.Wo; l.Krows = g.kh * g.kw * g.C;
     l.dWo = make_fastdiv(g.Wo); l.dHo = make_fastdiv(g.Ho); l.dHoWo = make_fastdiv(g.Ho * g.Wo); l.dC = make_fastdiv(g.C); l.dkw = make_fastdiv(g.kw);
     return l;
 }
-template <typename T> static PlainK<T> make_plain_k(const void *p, long ld, int rows, int K, const void *zero)
+// [rows][ld] with K contiguous / [K][ld] with the rows contiguous; the byte range ends with the last element used
+template <typename T> static PlainK<T> make_plain_k(const void *p, long ld, int rows, int K)
 {
-    return PlainK<T>{static_cast<const T *>(p), ld, rows, K, static_cast<const T *>(zero)};
+    return PlainK<T>{operand(p, ((size_t)(rows - 1) * ld + K) * sizeof(T)), (unsigned)(ld * sizeof(T)), rows, K};
 }
-template <typename T> static PlainT<T> make_plain_t(const void *p, long ld, int rows, int K, const void *zero)
+template <typename T> static PlainT<T> make_plain_t(const void *p, long ld, int rows, int K)
 {
-    return PlainT<T>{static_cast<const T *>(p), ld, rows, K, static_cast<const T *>(zero)};
+    return PlainT<T>{operand(p, ((size_t)(K - 1) * ld + rows) * sizeof(T)), (unsigned)(ld * sizeof(T)), rows, K};
 }
 
 template <typename T>
-static int gather_plain_t(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, const void *zero,
-                          hipStream_t s)
+static int gather_plain_t(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
     const int K = a.kh * a.kw * a.C;
     if (a.ds == 1 && a.kh * a.kw <= 32)
-        return run<T>(make_gather_k<T, false>(a), make_plain_k<T>(b, ldb, N, K, zero), a.N * a.Ho * a.Wo, N, K, ep, plan, ws, s);
+        return run<T>(make_gather_k<T, false>(a), make_plain_k<T>(b, ldb, N, K), a.N * a.Ho * a.Wo, N, K, ep, plan, ws, s);
     if (a.ds == 1)
-        return run<T>(make_gather_k<T, true>(a), make_plain_k<T>(b, ldb, N, K, zero), a.N * a.Ho * a.Wo, N, K, ep, plan, ws, s);
-    return run<T>(make_gather_ks<T>(a), make_plain_k<T>(b, ldb, N, K, zero), a.N * a.Ho * a.Wo, N, K, ep, plan, ws, s);
+        return run<T>(make_gather_k<T, true>(a), make_plain_k<T>(b, ldb, N, K), a.N * a.Ho * a.Wo, N, K, ep, plan, ws, s);
+    return run<T>(make_gather_ks<T>(a), make_plain_k<T>(b, ldb, N, K), a.N * a.Ho * a.Wo, N, K, ep, plan, ws, s);
 }
-int gemm_gather_plain(int dtype, const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws,
-                      const void *zero, hipStream_t s)
+int gemm_gather_plain(int dtype, const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
     if (a.ds != 1 && a.sm != 1) return -1;
     if (a.kh > 15 || a.kw > 15) return -1;
-    return dtype == kBF16 ? gather_plain_t<bf16_t>(a, b, ldb, N, ep, plan, ws, zero, s) : gather_plain_t<float>(a, b, ldb, N, ep, plan, ws, zero, s);
+    return dtype == kBF16 ? gather_plain_t<bf16_t>(a, b, ldb, N, ep, plan, ws, s) : gather_plain_t<float>(a, b, ldb, N, ep, plan, ws, s);
 }
 
 int gemm_plain_plain(int dtype, const void *a, long lda, int M, const void *b, long ldb, int N, int b_rows, int K, const Epilogue &ep,
-                     const GemmPlan &plan, float *ws, const void *zero, hipStream_t s)
+                     const GemmPlan &plan, float *ws, hipStream_t s)
 {
     if (b_rows > N) return -1;
     if (dtype == kBF16)
-        return run<bf16_t>(make_plain_k<bf16_t>(a, lda, M, K, zero), make_plain_k<bf16_t>(b, ldb, b_rows, K, zero), M, N, K, ep, plan, ws, s);
-    return run<float>(make_plain_k<float>(a, lda, M, K, zero), make_plain_k<float>(b, ldb, b_rows, K, zero), M, N, K, ep, plan, ws, s);
+        return run<bf16_t>(make_plain_k<bf16_t>(a, lda, M, K), make_plain_k<bf16_t>(b, ldb, b_rows, K), M, N, K, ep, plan, ws, s);
+    return run<float>(make_plain_k<float>(a, lda, M, K), make_plain_k<float>(b, ldb, b_rows, K), M, N, K, ep, plan, ws, s);
 }
 
 int gemm_plain_trans(int dtype, const void *a, long lda, int M, const void *bt, long ldb, int N, int K, const Epilogue &ep,
-                     const GemmPlan &plan, float *ws, const void *zero, hipStream_t s)
+                     const GemmPlan &plan, float *ws, hipStream_t s)
 {
     if (dtype == kBF16)
-        return run<bf16_t>(make_plain_k<bf16_t>(a, lda, M, K, zero), make_plain_t<bf16_t>(bt, ldb, N, K, zero), M, N, K, ep, plan, ws, s);
-    return run<float>(make_plain_k<float>(a, lda, M, K, zero), make_plain_t<float>(bt, ldb, N, K, zero), M, N, K, ep, plan, ws, s);
+        return run<bf16_t>(make_plain_k<bf16_t>(a, lda, M, K), make_plain_t<bf16_t>(bt, ldb, N, K), M, N, K, ep, plan, ws, s);
+    return run<float>(make_plain_k<float>(a, lda, M, K), make_plain_t<float>(bt, ldb, N, K), M, N, K, ep, plan, ws, s);
 }
 
 int gemm_trans_trans(int dtype, const void *at, long lda, int M, const void *bt, long ldb, int N, int K, const Epilogue &ep,
-                     const GemmPlan &plan, float *ws, const void *zero, hipStream_t s)
+                     const GemmPlan &plan, float *ws, hipStream_t s)
 {
     if (dtype == kBF16)
-        return run<bf16_t>(make_plain_t<bf16_t>(at, lda, M, K, zero), make_plain_t<bf16_t>(bt, ldb, N, K, zero), M, N, K, ep, plan, ws, s);
-    return run<float>(make_plain_t<float>(at, lda, M, K, zero), make_plain_t<float>(bt, ldb, N, K, zero), M, N, K, ep, plan, ws, s);
+        return run<bf16_t>(make_plain_t<bf16_t>(at, lda, M, K), make_plain_t<bf16_t>(bt, ldb, N, K), M, N, K, ep, plan, ws, s);
+    return run<float>(make_plain_t<float>(at, lda, M, K), make_plain_t<float>(bt, ldb, N, K), M, N, K, ep, plan, ws, s);
 }
 
 int gemm_trans_gather(int dtype, const void *at, long lda, int M, const Gather &b, const Epilogue &ep, const GemmPlan &plan, float *ws,
-                      const void *zero, hipStream_t s)
+                      hipStream_t s)
 {
-    if (b.ds != 1) return -1;
+    if (b.ds != 1 || b.kh > 15 || b.kw > 15) return -1;
     const int K = b.N * b.Ho * b.Wo, N = b.kh * b.kw * b.C;
-    if (dtype == kBF16) return run<bf16_t>(make_plain_t<bf16_t>(at, lda, M, K, zero), make_gather_t<bf16_t>(b), M, N, K, ep, plan, ws, s);
-    return run<float>(make_plain_t<float>(at, lda, M, K, zero), make_gather_t<float>(b), M, N, K, ep, plan, ws, s);
+    if (dtype == kBF16) return run<bf16_t>(make_plain_t<bf16_t>(at, lda, M, K), make_gather_t<bf16_t>(b), M, N, K, ep, plan, ws, s);
+    return run<float>(make_plain_t<float>(at, lda, M, K), make_gather_t<float>(b), M, N, K, ep, plan, ws, s);
 }
 
 }  // namespace asgd

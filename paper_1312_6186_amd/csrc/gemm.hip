@@ -501,28 +501,22 @@ __device__ __forceinline__ uint64_t mix64(uint64_t z)
     return z;
 }
 
-// Store of 8 consecutive output elements (32 bytes fp32 / 16 bytes bf16), vectorised when aligned.
+// Store of 8 consecutive output elements (32 bytes fp32 / 16 bytes bf16) as 16-byte vectors: every output
+// row starts 16-byte aligned and has a multiple of 8 elements (checked on the host).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 template <typename T> __device__ __forceinline__ void store8(T *p, const float (&v)[8]);
 template <> __device__ __forceinline__ void store8<float>(float *p, const float (&v)[8])
 {
-    if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) {
-        reinterpret_cast<float4 *>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
-        reinterpret_cast<float4 *>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
-    } else {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) p[r] = v[r];
-    }
+    f32x4 *q = reinterpret_cast<f32x4 *>(__builtin_assume_aligned(p, 16));
+    q[0] = f32x4{v[0], v[1], v[2], v[3]};
+    q[1] = f32x4{v[4], v[5], v[6], v[7]};
 }
 template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t *p, const float (&v)[8])
 {
-    union { bf16_t h[8]; uint4 u; } t;
+    union { bf16_t h[8]; u32x4 u; } t;
 #pragma unroll
     for (int r = 0; r < 8; ++r) t.h[r] = (bf16_t)v[r];
-    if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) *reinterpret_cast<uint4 *>(p) = t.u;
-    else {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) p[r] = t.h[r];
-    }
+    *reinterpret_cast<u32x4 *>(__builtin_assume_aligned(p, 16)) = t.u;
 }
 
 template <typename T> struct Vec8;

@@ -79,11 +79,17 @@ struct asgd_net {
     void *arena = nullptr;
     int device = -1;
     void *act0 = nullptr;      // staged input
-    float *scratch = nullptr;  // split-K partials and column-sum partials
+    float *scratch = nullptr;       // split-K partials of the kernels on the caller's stream
+    float *scratch_side = nullptr;  // split-K and column-sum partials of the parameter-gradient kernels (side stream)
+    // The parameter gradients of a layer (and the filter packing of the forward pass) do not feed the next
+    // layer: they run on an internal stream beside the caller's, forked and joined with events.
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    std::vector<hipEvent_t> ev_pack, ev_dy;   // per stage
     float *row_loss = nullptr;
     void *zero_page = nullptr;       // 256 zero bytes, never written
     int *version_counter = nullptr;  // device-side count of applied updates (A-SGD replay)
-    size_t scratch_floats = 0;
+    size_t scratch_floats = 0, scratch_side_floats = 0;
     // key of the last forward pass (for the dropout mask export)
     uint64_t last_seed = 0, last_step = 0;
     uint32_t last_worker = 0;
@@ -140,6 +146,7 @@ size_t carve(asgd_net &n, char *base)
     n.row_loss = static_cast<float *>(at(B * 4));
     n.version_counter = static_cast<int *>(at(256));
     n.scratch = static_cast<float *>(at(n.scratch_floats * 4));
+    n.scratch_side = static_cast<float *>(at(n.scratch_side_floats * 4));
     return c.off;
 }
 
@@ -255,7 +262,7 @@ int plan_net(asgd_net &n)
 
     // sizes, GEMM plans, scratch
     const long B = n.batch;
-    size_t scratch = 0;
+    size_t scratch = 0, scratch_side = 0;
     for (size_t si = 0; si < n.stages.size(); ++si) {
         Stage &s = n.stages[si];
         if (s.kind == ST_CONV) {
@@ -266,19 +273,38 @@ int plan_net(asgd_net &n)
             s.p_fwd = plan_gemm(M, s.outCp, K, n.dtype, 1);
             s.p_dgrad = plan_gemm(Min, s.inCp, (long)s.k * s.k * s.outCp, n.dtype, 1);
             s.p_wgrad = plan_gemm(s.outCp, K, M, n.dtype, 64);
-            scratch = std::max(scratch, s.p_wgrad.ws_floats);
-            scratch = std::max(scratch, colsum_ws_floats(n.dtype, M, s.outCp));
+            scratch_side = std::max(scratch_side, s.p_wgrad.ws_floats);
+            scratch_side = std::max(scratch_side, colsum_ws_floats(n.dtype, M, s.outCp));
         } else if (s.kind == ST_FC) {
             s.p_fwd = plan_gemm(B, s.out_ld, s.in_f, n.dtype, 32);
             s.p_dgrad = plan_gemm(B, s.in_f, s.out_f, n.dtype, 32);
             s.p_wgrad = plan_gemm(s.out_f, s.in_f, B, n.dtype, 1);
             scratch = std::max(scratch, std::max(s.p_fwd.ws_floats, s.p_dgrad.ws_floats));
-            scratch = std::max(scratch, colsum_ws_floats(n.dtype, B, s.out_ld));
+            scratch_side = std::max(scratch_side, colsum_ws_floats(n.dtype, B, s.out_ld));
         }
     }
     n.scratch_floats = scratch + 64;
+    n.scratch_side_floats = scratch_side + 64;
     n.ws_bytes = carve(n, nullptr);
     return ASGD_OK;
+}
+
+// Frees what ensure_prepared made (after waiting for the internal stream).
+int release_device(asgd_net *n)
+{
+    int rc = ASGD_OK;
+    if (n->side) { (void)hipStreamSynchronize(n->side); (void)hipStreamDestroy(n->side); n->side = nullptr; }
+    if (n->ev_fork) { (void)hipEventDestroy(n->ev_fork); n->ev_fork = nullptr; }
+    if (n->ev_join) { (void)hipEventDestroy(n->ev_join); n->ev_join = nullptr; }
+    for (hipEvent_t e : n->ev_pack) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : n->ev_dy) if (e) (void)hipEventDestroy(e);
+    n->ev_pack.clear(); n->ev_dy.clear();
+    if (n->arena) {
+        const hipError_t e = hipFree(n->arena);
+        n->arena = nullptr;
+        if (e != hipSuccess) rc = hip_fail(e, "hipFree");
+    }
+    return rc;
 }
 
 int ensure_prepared(asgd_net *n)
@@ -293,8 +319,24 @@ int ensure_prepared(asgd_net *n)
     if (e != hipSuccess) { (void)hipFree(n->arena); n->arena = nullptr; return hip_fail(e, "hipMemset"); }
     n->device = dev;
     carve(*n, static_cast<char *>(n->arena));
+    e = hipStreamCreateWithFlags(&n->side, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_join, hipEventDisableTiming);
+    n->ev_pack.assign(n->stages.size(), nullptr);
+    n->ev_dy.assign(n->stages.size(), nullptr);
+    for (size_t i = 0; i < n->stages.size() && e == hipSuccess; ++i) {
+        e = hipEventCreateWithFlags(&n->ev_pack[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_dy[i], hipEventDisableTiming);
+    }
+    if (e != hipSuccess) { release_device(n); return hip_fail(e, "creating the internal stream and events"); }
     return ASGD_OK;
 }
+
+#define CHECK_HIP(expr, what)                                   \
+    do {                                                        \
+        const hipError_t e_ = (expr);                           \
+        if (e_ != hipSuccess) return hip_fail(e_, what);        \
+    } while (0)
 
 #define CHECK_LAUNCH(expr, what)                                                             \
     do {                                                                                     \
@@ -350,15 +392,30 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
         if (s0.rw) CHECK_LAUNCH(launch_stage_input_rw(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, s0.pad, s0.rwWp, st), "stage_input");
         else CHECK_LAUNCH(launch_stage_input(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, n->in_cp, st), "stage_input");
     }
+    // filter packing: beside the input staging and the first layers (in line when profiling, to be timed alone)
+    const bool fork = !n->prof_on;
+    hipStream_t sd = fork ? n->side : st;
+    if (fork) {
+        CHECK_HIP(hipEventRecord(n->ev_fork, st), "hipEventRecord");
+        CHECK_HIP(hipStreamWaitEvent(sd, n->ev_fork, 0), "hipStreamWaitEvent");
+    }
+    auto pack = [&](size_t si) -> int {
+        Stage &s = n->stages[si];
+        ProfScope ps(n, sd, ASGD_K_LAYOUT, 0, (double)s.w_cnt * es * (s.wd ? 3 : 2));
+        if (s.rw) CHECK_LAUNCH(launch_pack_conv_rw(dt, param_ptr(n, params, s.w_off), s.wf, s.outC, s.inC, s.k, s.k, s.outCp, s.rwKW, sd), "pack_conv");
+        else CHECK_LAUNCH(launch_pack_conv(dt, param_ptr(n, params, s.w_off), s.wf, s.wd, s.outC, s.inC, s.k, s.k, s.outCp, s.inCp, sd), "pack_conv");
+        if (fork) CHECK_HIP(hipEventRecord(n->ev_pack[si], sd), "hipEventRecord");
+        return ASGD_OK;
+    };
+    if (fork)
+        for (size_t si = 0; si < n->stages.size(); ++si)
+            if (n->stages[si].kind == ST_CONV) { const int rc = pack(si); if (rc != ASGD_OK) return rc; }
     const void *cur = n->act0;
     for (size_t si = 0; si < n->stages.size(); ++si) {
         Stage &s = n->stages[si];
         if (s.kind == ST_CONV) {
-            {
-                ProfScope ps(n, st, ASGD_K_LAYOUT, 0, (double)s.w_cnt * es * (s.wd ? 3 : 2));
-                if (s.rw) CHECK_LAUNCH(launch_pack_conv_rw(dt, param_ptr(n, params, s.w_off), s.wf, s.outC, s.inC, s.k, s.k, s.outCp, s.rwKW, st), "pack_conv");
-                else CHECK_LAUNCH(launch_pack_conv(dt, param_ptr(n, params, s.w_off), s.wf, s.wd, s.outC, s.inC, s.k, s.k, s.outCp, s.inCp, st), "pack_conv");
-            }
+            if (fork) CHECK_HIP(hipStreamWaitEvent(st, n->ev_pack[si], 0), "hipStreamWaitEvent");
+            else { const int rc = pack(si); if (rc != ASGD_OK) return rc; }
             const double Mo = Bd * s.outH * s.outW;
             ProfScope ps(n, st, ASGD_K_CONV_FWD, 2 * Mo * s.outC * s.inC * s.k * s.k,
                          (Bd * s.inH * s.inW * s.inC + (double)s.w_cnt + Mo * s.outC) * es);
@@ -402,22 +459,28 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
 {
     const int B = n->batch, dt = n->dtype;
     const double es = (double)dtype_size(dt), Bd = (double)B;
+    const bool fork = !n->prof_on;
+    hipStream_t sd = fork ? n->side : st;   // parameter gradients go here
     for (int si = (int)n->stages.size() - 1; si >= 0; --si) {
         Stage &s = n->stages[si];
         Stage *prev = si > 0 ? &n->stages[si - 1] : nullptr;
         const void *xin = prev ? prev->out : n->act0;
+        if (fork && s.kind != ST_POOL) {  // the gradient at this stage's output is complete on the caller's stream
+            CHECK_HIP(hipEventRecord(n->ev_dy[si], st), "hipEventRecord");
+            CHECK_HIP(hipStreamWaitEvent(sd, n->ev_dy[si], 0), "hipStreamWaitEvent");
+        }
         if (s.kind == ST_FC) {
             const void *x = s.in_is_spatial ? s.flat_in : xin;
             const long ldx = s.in_is_spatial ? s.in_f : prev->out_ld;
             Epilogue ew;
             ew.out = grads + s.w_off; ew.ld = s.in_f; ew.out_f32 = 1;
             {
-                ProfScope ps(n, st, ASGD_K_FC_WGRAD, 2 * Bd * s.in_f * s.out_f, Bd * (s.in_f + s.out_f) * es + (double)s.w_cnt * 4);
-                CHECK_LAUNCH(gemm_trans_trans(dt, s.dout, s.out_ld, s.out_f, x, ldx, s.in_f, B, ew, s.p_wgrad, n->scratch, st), "fc weight gradient");
+                ProfScope ps(n, sd, ASGD_K_FC_WGRAD, 2 * Bd * s.in_f * s.out_f, Bd * (s.in_f + s.out_f) * es + (double)s.w_cnt * 4);
+                CHECK_LAUNCH(gemm_trans_trans(dt, s.dout, s.out_ld, s.out_f, x, ldx, s.in_f, B, ew, s.p_wgrad, n->scratch_side, sd), "fc weight gradient");
             }
             {
-                ProfScope ps(n, st, ASGD_K_BIAS_GRAD, 0, Bd * s.out_f * es + s.out_f * 4.0);
-                CHECK_LAUNCH(launch_colsum(dt, s.dout, s.out_ld, B, s.out_f, grads + s.b_off, n->scratch, st), "fc bias gradient");
+                ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, Bd * s.out_f * es + s.out_f * 4.0);
+                CHECK_LAUNCH(launch_colsum(dt, s.dout, s.out_ld, B, s.out_f, grads + s.b_off, n->scratch_side, sd), "fc bias gradient");
             }
             if (prev) {
                 Epilogue ed;
@@ -455,12 +518,12 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
             ew.cw_cout = s.outC; ew.cw_cin = s.inC; ew.cw_cinp = s.rw ? s.rwKW : s.inCp; ew.cw_kh = s.k; ew.cw_kw = s.k;
             const double Mo = (double)M, conv_flops = 2 * Mo * s.outC * s.inC * s.k * s.k;
             {
-                ProfScope ps(n, st, ASGD_K_CONV_WGRAD, conv_flops, (Mo * s.outC + Bd * s.inH * s.inW * s.inC) * es + (double)s.w_cnt * 4);
-                CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch, st), "conv filter gradient");
+                ProfScope ps(n, sd, ASGD_K_CONV_WGRAD, conv_flops, (Mo * s.outC + Bd * s.inH * s.inW * s.inC) * es + (double)s.w_cnt * 4);
+                CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch_side, sd), "conv filter gradient");
             }
             {
-                ProfScope ps(n, st, ASGD_K_BIAS_GRAD, 0, Mo * s.outC * es + s.outC * 4.0);
-                CHECK_LAUNCH(launch_colsum(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, n->scratch, st), "conv bias gradient");
+                ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, Mo * s.outC * es + s.outC * 4.0);
+                CHECK_LAUNCH(launch_colsum(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, n->scratch_side, sd), "conv bias gradient");
             }
             if (prev) {
                 Gather d;
@@ -475,6 +538,10 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
                 CHECK_LAUNCH(gemm_gather_plain(dt, d, s.wd, (long)s.k * s.k * s.outCp, s.inCp, ed, s.p_dgrad, n->scratch, st), "conv data gradient");
             }
         }
+    }
+    if (fork) {
+        CHECK_HIP(hipEventRecord(n->ev_join, sd), "hipEventRecord");
+        CHECK_HIP(hipStreamWaitEvent(st, n->ev_join, 0), "hipStreamWaitEvent");
     }
     return ASGD_OK;
 }
@@ -519,10 +586,7 @@ int asgd_net_destroy(asgd_net_t *net)
     if (!net) return ASGD_OK;
     int rc = ASGD_OK;
     for (hipEvent_t e : net->prof_ev) (void)hipEventDestroy(e);
-    if (net->arena) {
-        const hipError_t e = hipFree(net->arena);
-        if (e != hipSuccess) rc = hip_fail(e, "hipFree");
-    }
+    rc = release_device(net);
     delete net;
     return rc;
 }

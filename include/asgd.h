@@ -8,6 +8,7 @@
  *     asgd_snapshot      (a replica fetches the server's parameters)
  *     asgd_fwd_bwd       (one replica's minibatch gradient, Section 2)
  *     asgd_apply_update  (the server applies a pushed gradient)
+ *     asgd_apply_update_snapshot (push and the same replica's next fetch, fused)
  * plus the calls that describe the network and the on-one-GPU A-SGD replay.
  *
  * Conventions
@@ -158,6 +159,16 @@ int asgd_apply_update(float *params, float *momentum, const float *grads, size_t
  *   params : device fp32 [n];  worker_copy : device, n elements of dst_dtype.
  * Errors: ASGD_EINVAL, ASGD_EHIP. */
 int asgd_snapshot(const float *params, void *worker_copy, size_t n, int dst_dtype, void *stream);
+
+/* The push and the next fetch of Section 2.3 in one pass over the parameters:
+ * exactly asgd_apply_update followed by asgd_snapshot of the updated parameters
+ * into `worker_copy` (the same values, bit for bit), without reading the
+ * parameters a second time.  For the replica that fetches right after its own
+ * push; other replicas' copies are untouched.
+ * Errors: ASGD_EINVAL (null with n > 0, unknown dtype), ASGD_EALIGN, ASGD_EHIP. */
+int asgd_apply_update_snapshot(float *params, float *momentum, const float *grads, size_t n,
+                               float lr, float mu, float wd, void *worker_copy, int dst_dtype,
+                               void *stream);
 
 /* Test hook: what the last asgd_fwd_bwd on this plan left behind, converted to
  * canonical layout into a caller-owned device buffer.

@@ -636,6 +636,19 @@ int asgd_apply_update(float *params, float *momentum, const float *grads, size_t
     return ASGD_OK;
 }
 
+int asgd_apply_update_snapshot(float *params, float *momentum, const float *grads, size_t n, float lr, float mu, float wd, void *worker_copy,
+                               int dst_dtype, void *stream)
+{
+    if (dst_dtype != ASGD_F32 && dst_dtype != ASGD_BF16) return fail(ASGD_EINVAL, "asgd_apply_update_snapshot: unknown dtype %d", dst_dtype);
+    if (n == 0) return ASGD_OK;
+    if (!params || !momentum || !grads || !worker_copy) return fail(ASGD_EINVAL, "asgd_apply_update_snapshot: null argument");
+    if ((((uintptr_t)params | (uintptr_t)momentum | (uintptr_t)grads) & 3) || ((uintptr_t)worker_copy & (dst_dtype == ASGD_BF16 ? 1 : 3)))
+        return fail(ASGD_EALIGN, "asgd_apply_update_snapshot: misaligned buffer");
+    if (launch_update_snapshot(params, momentum, grads, n, lr, mu, wd, worker_copy, dst_dtype, static_cast<hipStream_t>(stream)) != 0)
+        return hip_fail(hipGetLastError(), "update kernel");
+    return ASGD_OK;
+}
+
 int asgd_snapshot(const float *params, void *worker_copy, size_t n, int dst_dtype, void *stream)
 {
     if (dst_dtype != ASGD_F32 && dst_dtype != ASGD_BF16) return fail(ASGD_EINVAL, "asgd_snapshot: unknown dtype %d", dst_dtype);

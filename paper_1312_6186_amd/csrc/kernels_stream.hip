@@ -41,9 +41,13 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // Each thread owns 4 float4 per buffer, 256 apart, all loads issued before the arithmetic; gradients are read and
 // parameters / momentum written with non-temporal hints (the 1.2 GB working set of the AlexNet-style net cannot
 // stay in cache between steps anyway).  Measured 5.65 TB/s on 62.4 M parameters.
+// SNAP: 0 = update only, 1 = also write the new parameters to `copy` as fp32, 2 = as bf16 (round to nearest even):
+// the worker copy of the next fetch comes out of the same pass instead of a second read of the parameters.
+__device__ inline uint32_t f32_to_bf16_bits(uint32_t u);
+template <int SNAP>
 __global__ __launch_bounds__(256) void update_kernel(f32x4 *__restrict__ w, f32x4 *__restrict__ v, const f32x4 *__restrict__ g, size_t n4,
                                                      float *ws, float *vs, const float *gs, size_t n, float lr, float mu, float wd,
-                                                     int *version_counter)
+                                                     int *version_counter, void *__restrict__ copy)
 {
     constexpr int U = 4;
     const size_t i0 = (size_t)blockIdx.x * (256 * U) + threadIdx.x;
@@ -61,6 +65,14 @@ __global__ __launch_bounds__(256) void update_kernel(f32x4 *__restrict__ w, f32x
             ww[u] += vv[u];
             __builtin_nontemporal_store(ww[u], &w[i]);
             __builtin_nontemporal_store(vv[u], &v[i]);
+            if constexpr (SNAP == 1) static_cast<f32x4 *>(copy)[i] = ww[u];
+            if constexpr (SNAP == 2) {
+                typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+                u32x2 o;
+                o.x = f32_to_bf16_bits(__float_as_uint(ww[u].x)) | (f32_to_bf16_bits(__float_as_uint(ww[u].y)) << 16);
+                o.y = f32_to_bf16_bits(__float_as_uint(ww[u].z)) | (f32_to_bf16_bits(__float_as_uint(ww[u].w)) << 16);
+                static_cast<u32x2 *>(copy)[i] = o;
+            }
         }
     }
     if (blockIdx.x == 0) {
@@ -68,37 +80,52 @@ __global__ __launch_bounds__(256) void update_kernel(f32x4 *__restrict__ w, f32x
         if (i < n) {
             const float t = mu * vs[i] - lr * (gs[i] + wd * ws[i]);
             vs[i] = t; ws[i] += t;
+            if constexpr (SNAP == 1) static_cast<float *>(copy)[i] = ws[i];
+            if constexpr (SNAP == 2) static_cast<uint16_t *>(copy)[i] = (uint16_t)f32_to_bf16_bits(__float_as_uint(ws[i]));
         }
         if (threadIdx.x == 0 && version_counter) *version_counter += 1;
     }
 }
 
+template <int SNAP>
 __global__ __launch_bounds__(256) void update_scalar_kernel(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd,
-                                                            int *version_counter)
+                                                            int *version_counter, void *copy)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         const float vv = mu * v[i] - lr * (g[i] + wd * w[i]);
         v[i] = vv; w[i] += vv;
+        if constexpr (SNAP == 1) static_cast<float *>(copy)[i] = w[i];
+        if constexpr (SNAP == 2) static_cast<uint16_t *>(copy)[i] = (uint16_t)f32_to_bf16_bits(__float_as_uint(w[i]));
     }
     if (blockIdx.x == 0 && threadIdx.x == 0 && version_counter) *version_counter += 1;
 }
 
-int launch_update(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd, int *version_counter, hipStream_t s)
+template <int SNAP>
+static int launch_update_t(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd, int *version_counter, void *copy, hipStream_t s)
 {
-    const bool aligned = (((uintptr_t)w | (uintptr_t)v | (uintptr_t)g) & 15) == 0;
-    if (aligned) {
+    const unsigned copy_align = SNAP == 1 ? 15u : SNAP == 2 ? 7u : 0u;
+    const bool aligned = (((uintptr_t)w | (uintptr_t)v | (uintptr_t)g) & 15) == 0 && ((uintptr_t)copy & copy_align) == 0;
+    if (aligned && n >= 4) {
         const size_t n4 = n / 4;
         const size_t blocks = (n4 + 1023) / 1024 ? (n4 + 1023) / 1024 : 1;
         if (blocks > 0x7fffffffu) return -1;
-        hipLaunchKernelGGL(update_kernel, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<f32x4 *>(w), reinterpret_cast<f32x4 *>(v),
-                           reinterpret_cast<const f32x4 *>(g), n4, w, v, g, n, lr, mu, wd, version_counter);
+        hipLaunchKernelGGL(update_kernel<SNAP>, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<f32x4 *>(w), reinterpret_cast<f32x4 *>(v),
+                           reinterpret_cast<const f32x4 *>(g), n4, w, v, g, n, lr, mu, wd, version_counter, copy);
     } else {
         unsigned blocks = blocks_for(n ? n : 1, 256);
         if (blocks > 8192) blocks = 8192;
-        hipLaunchKernelGGL(update_scalar_kernel, dim3(blocks), dim3(256), 0, s, w, v, g, n, lr, mu, wd, version_counter);
+        hipLaunchKernelGGL(update_scalar_kernel<SNAP>, dim3(blocks), dim3(256), 0, s, w, v, g, n, lr, mu, wd, version_counter, copy);
     }
     return launch_ok();
+}
+int launch_update(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd, int *version_counter, hipStream_t s)
+{
+    return launch_update_t<0>(w, v, g, n, lr, mu, wd, version_counter, nullptr, s);
+}
+int launch_update_snapshot(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd, void *copy, int dst_dtype, hipStream_t s)
+{
+    return dst_dtype == kBF16 ? launch_update_t<2>(w, v, g, n, lr, mu, wd, nullptr, copy, s) : launch_update_t<1>(w, v, g, n, lr, mu, wd, nullptr, copy, s);
 }
 
 // ---------------------------------------------------------------- snapshot

@@ -59,6 +59,39 @@ def test_snapshot_is_bit_exact(n, offset):
     np.testing.assert_array_equal(dst32.cpu().numpy()[offset:].view(np.uint32), a[offset:].view(np.uint32))
 
 
+@pytest.mark.parametrize("dst", [B.BF16, B.F32])
+@pytest.mark.parametrize("n,offset", [(1, 0), (1023, 0), (4099, 0), (100003, 1), (100003, 4), (1 << 20, 8)])
+def test_fused_update_snapshot_matches_oracle_and_the_two_calls(n, offset, dst):
+    rng = np.random.default_rng(n + 7)
+    w0, v0, g = (rng.standard_normal(n + offset).astype(np.float32) for _ in range(3))
+    lr, mu, wd = 0.01, 0.9, 5e-4
+    w, v, gd = (torch.from_numpy(a).to(DEV) for a in (w0, v0, g))
+    tdt = torch.bfloat16 if dst == B.BF16 else torch.float32
+    copy = torch.zeros(n + offset + 8, dtype=tdt, device=DEV)
+    for _ in range(2):
+        B.asgd_apply_update_snapshot(w[offset:], v[offset:], gd[offset:], lr, mu, wd, copy[offset:offset + n], dst)
+    torch.cuda.synchronize()
+    # against the oracle: update in fp64 twice, then the fetch
+    wr, vr = w0[offset:].astype(np.float64), v0[offset:].astype(np.float64)
+    for _ in range(2):
+        oops.apply_update(wr, vr, g[offset:], np.float32(lr), np.float32(mu), np.float32(wd))
+    assert rel_l2(w.cpu().numpy()[offset:], wr) < 1e-6 and rel_l2(v.cpu().numpy()[offset:], vr) < 1e-6
+    got = copy.float().cpu().numpy()
+    if dst == B.BF16:
+        ref = oops.round_bf16(wr.astype(np.float32).astype(np.float64))
+        # fp32 update arithmetic (operands of order 1, so errors of order 1e-7) may land on the other side of a
+        # rounding boundary: one bf16 step at most, plus that absolute error where the result nearly cancels
+        assert np.all(np.abs(got[offset:offset + n] - ref) <= 2.0 ** -7 * np.abs(ref) + 1e-6)
+    else:
+        assert rel_l2(got[offset:offset + n], wr) < 1e-6
+    assert (got[:offset] == 0).all() and (got[offset + n:] == 0).all()
+    # consistency of the library with itself: the copy is what the separate fetch of the same parameters gives
+    sep = torch.zeros(n, dtype=tdt, device=DEV)
+    B.asgd_snapshot(w[offset:], sep, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(sep.view(torch.int16 if dst == B.BF16 else torch.int32), copy[offset:offset + n].view(torch.int16 if dst == B.BF16 else torch.int32))
+
+
 # ---------------------------------------------------------------- whole-network gradient
 def _net_case(cfg, batch, dtype, seed=0, step=0, worker=0, bias_noise=0.05):
     layers, in_shape = cfg["layers"], cfg["in_shape"]

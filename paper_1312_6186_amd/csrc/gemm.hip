@@ -524,7 +524,20 @@ template <> struct Vec8<float> { union { float4 u[2]; float e[8]; }; };
 template <> struct Vec8<bf16_t> { union { uint4 u[1]; bf16_t e[8]; }; };
 
 // Eight consecutive columns n0..n0+7 of row m (n0 a multiple of 8, all in range).
-template <typename T> __device__ __forceinline__ void epilogue8(const Epilogue &ep, int m, int n0, float (&v)[8])
+// The bias of these 8 columns, as fp32 (zeros past bias_n or without a bias).
+template <typename T> __device__ __forceinline__ void load_bias8(const Epilogue &ep, int n0, float (&b8)[8])
+{
+#pragma unroll
+    for (int r = 0; r < 8; ++r) b8[r] = 0.f;
+    if (ep.bias) {
+        const T *b = static_cast<const T *>(ep.bias);
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            if (n0 + r < ep.bias_n) b8[r] = to_f32(b[n0 + r]);
+    }
+}
+
+template <typename T> __device__ __forceinline__ void epilogue8(const Epilogue &ep, int m, int n0, float (&v)[8], const float (&b8)[8])
 {
     if (ep.mode == 1) {  // conv filter gradient: (cout, (ky,kx,ci_padded)) -> canonical [cout][cin][kh][kw]
         if (m >= ep.cw_cout) return;
@@ -548,10 +561,8 @@ template <typename T> __device__ __forceinline__ void epilogue8(const Epilogue &
         return;
     }
     if (ep.bias) {
-        const T *b = static_cast<const T *>(ep.bias);
 #pragma unroll
-        for (int r = 0; r < 8; ++r)
-            if (n0 + r < ep.bias_n) v[r] += to_f32(b[n0 + r]);
+        for (int r = 0; r < 8; ++r) v[r] += b8[r];
     }
     if (ep.relu) {
 #pragma unroll
@@ -639,6 +650,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
     foA.init(wm, lane);
     foB.init(wn, lane);
 
+    // every output row this thread writes has the same 8 columns: fetch their bias now, behind the first tiles
+    float bias8[8];
+    load_bias8<T>(ep, tn * BN + (tid % (BN / 8)) * 8, bias8);
+
     // register set that receives tile j is j % DEPTH (tile 0 goes through set 0 straight into LDS stage 0)
     stA.template load<0>(la); stB.template load<0>(lb);
     if constexpr (DEPTH == 2) { stA.template load<1>(la); stB.template load<1>(lb); }
@@ -689,7 +704,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
                 const float4 hi = *reinterpret_cast<const float4 *>(stg + row * PITCH + col + 4);
                 float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
                 if (ws) store8<float>(ws + ((long)split * M + m) * N + n0, v);
-                else epilogue8<T>(ep, m, n0, v);
+                else epilogue8<T>(ep, m, n0, v, bias8);
             }
         });
     });
@@ -708,7 +723,9 @@ template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_kerne
         v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
         v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
     }
-    epilogue8<T>(ep, m, n0, v);
+    float b8[8];
+    load_bias8<T>(ep, n0, b8);
+    epilogue8<T>(ep, m, n0, v, b8);
 }
 
 // ------------------------------------------------------------------ host side

@@ -362,6 +362,15 @@ struct ProfScope {
     ~ProfScope() { if (stop) (void)hipEventRecord(stop, st); }
 };
 
+// ReLU commutes with max pooling, and the pooled value is the value at the recorded maximum: where a pooling
+// stage sits on a CONV+RELU, the ReLU mask of that convolution is applied to the gradient at the pool's OUTPUT
+// (mask = pooled activation > 0) by whoever produces that gradient, and the pooling backward pass then has
+// nothing to read but the gradient and the positions.
+bool relu_under_pool(const std::vector<Stage> &st, int pool_idx)
+{
+    return pool_idx > 0 && st[pool_idx].kind == ST_POOL && st[pool_idx - 1].kind == ST_CONV && st[pool_idx - 1].relu;
+}
+
 // The input side of a convolution stage as a gather over its (possibly bordered) input tensor x.
 Gather conv_gather(const Stage &s, const void *x, int B, int dt)
 {
@@ -498,17 +507,19 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
                 }
                 ProfScope ps(n, st, ASGD_K_LAYOUT, 0, s.in_is_spatial ? 3 * Bd * s.in_f * es : 0);
                 if (s.in_is_spatial)
-                    CHECK_LAUNCH(launch_unflatten(dt, s.dflat_in, prev->out, prev->kind == ST_CONV && prev->relu, prev->dout, B, s.inH, s.inW, s.inC,
-                                                  s.inCp, st),
+                    CHECK_LAUNCH(launch_unflatten(dt, s.dflat_in, prev->out, (prev->kind == ST_CONV && prev->relu) || relu_under_pool(n->stages, si - 1),
+                                                  prev->dout, B, s.inH, s.inW, s.inC, s.inCp, st),
                                  "unflatten");
             }
         } else if (s.kind == ST_POOL) {
             // prev exists: a pool cannot be first... unless the net starts with a pool, which feeds no parameters
+            // a ReLU below has been applied to s.dout already by a CONV or FC above (relu_under_pool); only a pool
+            // on top of this pool leaves it to be done here
+            const bool relu_here = prev && prev->kind == ST_CONV && prev->relu && si + 1 < (int)n->stages.size() && n->stages[si + 1].kind == ST_POOL;
             ProfScope ps(n, st, ASGD_K_POOL_BWD, 0,
-                         Bd * s.outC * ((double)s.outH * s.outW * (es + 1) + (double)s.inH * s.inW * es * (prev && prev->relu ? 2 : 1)));
+                         Bd * s.outC * ((double)s.outH * s.outW * (es + 1) + (double)s.inH * s.inW * es * (relu_here ? 2 : 1)));
             if (prev)
-                CHECK_LAUNCH(launch_pool_bwd(dt, s.dout, s.argmax, prev->out, prev->kind == ST_CONV && prev->relu, prev->dout, B, s.inH, s.inW, s.inCp,
-                                             s.k, s.stride, st),
+                CHECK_LAUNCH(launch_pool_bwd(dt, s.dout, s.argmax, prev->out, relu_here, prev->dout, B, s.inH, s.inW, s.inCp, s.k, s.stride, st),
                              "pool backward");
         } else {
             const long M = (long)B * s.outH * s.outW;
@@ -532,7 +543,9 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
                 d.bytes = (size_t)B * s.outH * s.outW * s.outCp * dtype_size(dt);
                 Epilogue ed;
                 ed.out = prev->dout; ed.ld = s.inCp;
-                if (prev->kind == ST_CONV && prev->relu) { ed.mask_src = prev->out; ed.mask_ld = s.inCp; ed.mask_scale = 1.f; }
+                if ((prev->kind == ST_CONV && prev->relu) || relu_under_pool(n->stages, si - 1)) {
+                    ed.mask_src = prev->out; ed.mask_ld = s.inCp; ed.mask_scale = 1.f;
+                }
                 ProfScope ps(n, st, ASGD_K_CONV_DGRAD, conv_flops,
                              (Mo * s.outC + (double)s.w_cnt + Bd * s.inH * s.inW * s.inC * (ed.mask_src ? 2 : 1)) * es);
                 CHECK_LAUNCH(gemm_gather_plain(dt, d, s.wd, (long)s.k * s.k * s.outCp, s.inCp, ed, s.p_dgrad, n->scratch, st), "conv data gradient");

@@ -748,7 +748,7 @@ GemmPlan plan_gemm(long M, long N, long K, int dtype, int max_splits)
     const long target = (M <= BM && nkt <= 256) ? 256 : 512;
     long splits = 1;
     if (max_splits > 1 && tiles < target) {
-        splits = (target + tiles - 1) / tiles;
+        splits = target / tiles;                  // never more workgroups than run at once: a second, nearly empty round would double the time
         if (splits > nkt / 4) splits = nkt / 4;   // at least four K tiles per split
         if (splits > max_splits) splits = max_splits;
         if (splits < 1) splits = 1;

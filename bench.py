@@ -107,7 +107,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="alexnet_bf16_bs128", choices=sorted(WORKLOADS))
     ap.add_argument("--cpu-sample", type=int, default=64, help="images in the oracle's timed sample (0 = skip)")
+    ap.add_argument("--serial", action="store_true",
+                    help="keep every kernel on one stream (for profiler runs: per-kernel durations are then those of kernels running alone)")
     args = ap.parse_args()
+    if args.serial:
+        os.environ["ASGD_SERIAL"] = "1"
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported" % args.gpus,
               file=sys.stderr)
@@ -229,7 +233,7 @@ def main():
         "roofline": roofline,
         "mfma_all_gemms": {"achieved": mfma_flops / (mfma_ms * 1e-3) / 1e12, "peak": PEAK["mfma_" + dtname], "unit": "TFLOP/s",
                            "frac": mfma_flops / (mfma_ms * 1e-3) / 1e12 / PEAK["mfma_" + dtname], "ms_per_step": mfma_ms},
-        "profiled_ms_per_step": profiled_ms,
+        "profiled_ms_per_step": profiled_ms, "serial": bool(args.serial),
         "kernel_classes": classes_out,
         "unfused_calls": unfused,
     }

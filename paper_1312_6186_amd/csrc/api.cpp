@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -362,6 +363,14 @@ struct ProfScope {
     ~ProfScope() { if (stop) (void)hipEventRecord(stop, st); }
 };
 
+// ASGD_SERIAL=1 in the environment keeps every kernel on the caller's stream (no internal side stream), so that
+// a profiler sees each kernel running alone.
+bool serial_mode()
+{
+    static const bool on = getenv("ASGD_SERIAL") && getenv("ASGD_SERIAL")[0] == '1';
+    return on;
+}
+
 // ReLU commutes with max pooling, and the pooled value is the value at the recorded maximum: where a pooling
 // stage sits on a CONV+RELU, the ReLU mask of that convolution is applied to the gradient at the pool's OUTPUT
 // (mask = pooled activation > 0) by whoever produces that gradient, and the pooling backward pass then has
@@ -402,7 +411,7 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
         else CHECK_LAUNCH(launch_stage_input(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, n->in_cp, st), "stage_input");
     }
     // filter packing: beside the input staging and the first layers (in line when profiling, to be timed alone)
-    const bool fork = !n->prof_on;
+    const bool fork = !n->prof_on && !serial_mode();
     hipStream_t sd = fork ? n->side : st;
     if (fork) {
         CHECK_HIP(hipEventRecord(n->ev_fork, st), "hipEventRecord");
@@ -468,7 +477,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
 {
     const int B = n->batch, dt = n->dtype;
     const double es = (double)dtype_size(dt), Bd = (double)B;
-    const bool fork = !n->prof_on;
+    const bool fork = !n->prof_on && !serial_mode();
     hipStream_t sd = fork ? n->side : st;   // parameter gradients go here
     for (int si = (int)n->stages.size() - 1; si >= 0; --si) {
         Stage &s = n->stages[si];

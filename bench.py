@@ -148,6 +148,8 @@ def main():
 
     # One step of the single-replica loop: the replica's gradient on its copy, then the push, which applies the
     # update and leaves the replica's next fetch in `copy` in the same pass (asgd_apply_update_snapshot).
+    # (asgd_train_step, which starts each layer's push as soon as its gradient is complete, gives the same results
+    # but is not faster here: the GEMM workgroups fill the register file, so the update cannot run beside them.)
     def step(i):
         B.asgd_fwd_bwd(net, copy, images, labels, cfg["seeds"]["dropout"], i, 0, loss, grads, stream)
         B.asgd_apply_update_snapshot(master, momentum, grads, lr, mu, wd, copy, dtype, stream)

@@ -9,6 +9,7 @@
  *     asgd_fwd_bwd       (one replica's minibatch gradient, Section 2)
  *     asgd_apply_update  (the server applies a pushed gradient)
  *     asgd_apply_update_snapshot (push and the same replica's next fetch, fused)
+ *     asgd_train_step    (gradient, push and fetch of one replica, pipelined by layer)
  * plus the calls that describe the network and the on-one-GPU A-SGD replay.
  *
  * Conventions
@@ -170,6 +171,25 @@ int asgd_apply_update_snapshot(float *params, float *momentum, const float *grad
                                float lr, float mu, float wd, void *worker_copy, int dst_dtype,
                                void *stream);
 
+/* One whole cycle of a replica that shares the GPU with the server (the
+ * single-replica loop of Section 2.3): asgd_fwd_bwd on `worker_copy`, then
+ * asgd_apply_update_snapshot on every layer's slice of the parameters.  Results
+ * are those of the two calls, bit for bit; the difference is the schedule: a
+ * layer's slice is pushed as soon as its gradient is complete and its data
+ * gradient (the last reader of the old values) has been queued, so the update
+ * can run beside the rest of the backward pass wherever the GPU has room for it.
+ *   master, momentum : device fp32 [P], updated in place.
+ *   worker_copy : device [P] in the plan's compute dtype, 16-byte aligned; the
+ *             parameters the gradient is computed on; holds the updated
+ *             parameters (the next fetch) when the call completes.
+ *   grads       : device fp32 [P]; holds this step's gradient afterwards.
+ *   other arguments as for asgd_fwd_bwd / asgd_apply_update.
+ * Errors: as asgd_fwd_bwd. */
+int asgd_train_step(asgd_net_t *net, float *master, float *momentum, void *worker_copy,
+                    const void *images, const int32_t *labels, uint64_t dropout_seed, uint64_t step,
+                    uint32_t worker, float *loss, float *grads, float lr, float mu, float wd,
+                    void *stream);
+
 /* Test hook: what the last asgd_fwd_bwd on this plan left behind, converted to
  * canonical layout into a caller-owned device buffer.
  *   what = ASGD_DEBUG_OUTPUT : fp32 [B,C,H,W] (or [B,F]) output of `layer`,
@@ -196,7 +216,7 @@ typedef enum {
     ASGD_K_CONV_FWD = 0, ASGD_K_CONV_DGRAD = 1, ASGD_K_CONV_WGRAD = 2,
     ASGD_K_FC_FWD = 3, ASGD_K_FC_DGRAD = 4, ASGD_K_FC_WGRAD = 5,
     ASGD_K_POOL_FWD = 6, ASGD_K_POOL_BWD = 7, ASGD_K_BIAS_GRAD = 8,
-    ASGD_K_SOFTMAX_CE = 9, ASGD_K_LAYOUT = 10, ASGD_K_COUNT = 11
+    ASGD_K_SOFTMAX_CE = 9, ASGD_K_LAYOUT = 10, ASGD_K_UPDATE = 11, ASGD_K_COUNT = 12
 } asgd_kernel_class_t;
 typedef struct {
     int32_t kclass;

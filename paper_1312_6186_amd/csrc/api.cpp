@@ -86,7 +86,7 @@ struct asgd_net {
     // layer: they run on an internal stream beside the caller's, forked and joined with events.
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-    std::vector<hipEvent_t> ev_pack, ev_dy;   // per stage
+    std::vector<hipEvent_t> ev_pack, ev_dy, ev_dg;   // per stage: filters packed, output gradient ready, data gradient issued
     float *row_loss = nullptr;
     void *zero_page = nullptr;       // 256 zero bytes, never written
     int *version_counter = nullptr;  // device-side count of applied updates (A-SGD replay)
@@ -299,7 +299,8 @@ int release_device(asgd_net *n)
     if (n->ev_join) { (void)hipEventDestroy(n->ev_join); n->ev_join = nullptr; }
     for (hipEvent_t e : n->ev_pack) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : n->ev_dy) if (e) (void)hipEventDestroy(e);
-    n->ev_pack.clear(); n->ev_dy.clear();
+    for (hipEvent_t e : n->ev_dg) if (e) (void)hipEventDestroy(e);
+    n->ev_pack.clear(); n->ev_dy.clear(); n->ev_dg.clear();
     if (n->arena) {
         const hipError_t e = hipFree(n->arena);
         n->arena = nullptr;
@@ -325,9 +326,11 @@ int ensure_prepared(asgd_net *n)
     if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_join, hipEventDisableTiming);
     n->ev_pack.assign(n->stages.size(), nullptr);
     n->ev_dy.assign(n->stages.size(), nullptr);
+    n->ev_dg.assign(n->stages.size(), nullptr);
     for (size_t i = 0; i < n->stages.size() && e == hipSuccess; ++i) {
         e = hipEventCreateWithFlags(&n->ev_pack[i], hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_dy[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_dg[i], hipEventDisableTiming);
     }
     if (e != hipSuccess) { release_device(n); return hip_fail(e, "creating the internal stream and events"); }
     return ASGD_OK;
@@ -473,12 +476,35 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
     return ASGD_OK;
 }
 
-int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
+// The server side of a whole training step: where a replica and the server share the GPU, a layer's slice of
+// the parameters is updated (and the replica's copy of it refreshed) as soon as that layer's gradient is complete
+// and its data gradient, the last reader of the old values, has been issued.
+struct ServerArgs {
+    float *master, *momentum;
+    void *copy;          // the replica's parameters (== params of the step), compute dtype
+    float lr, mu, wd;
+};
+
+int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, const ServerArgs *srv)
 {
     const int B = n->batch, dt = n->dtype;
     const double es = (double)dtype_size(dt), Bd = (double)B;
     const bool fork = !n->prof_on && !serial_mode();
     hipStream_t sd = fork ? n->side : st;   // parameter gradients go here
+    auto push = [&](int si) -> int {      // after the stage's gradients are queued on sd and its data gradient on st
+        Stage &s = n->stages[si];
+        if (!srv || s.kind == ST_POOL) return ASGD_OK;
+        if (fork) {
+            CHECK_HIP(hipEventRecord(n->ev_dg[si], st), "hipEventRecord");
+            CHECK_HIP(hipStreamWaitEvent(sd, n->ev_dg[si], 0), "hipStreamWaitEvent");
+        }
+        const size_t off = s.w_off, cnt = s.w_cnt + s.b_cnt;   // weights and bias of a layer are adjacent
+        ProfScope ps(n, sd, ASGD_K_UPDATE, 0, (double)cnt * (20.0 + es));
+        if (launch_update_snapshot(srv->master + off, srv->momentum + off, grads + off, cnt, srv->lr, srv->mu, srv->wd,
+                                   static_cast<char *>(srv->copy) + off * dtype_size(dt), dt, sd) != 0)
+            return hip_fail(hipGetLastError(), "update kernel");
+        return ASGD_OK;
+    };
     for (int si = (int)n->stages.size() - 1; si >= 0; --si) {
         Stage &s = n->stages[si];
         Stage *prev = si > 0 ? &n->stages[si - 1] : nullptr;
@@ -560,6 +586,8 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st)
                 CHECK_LAUNCH(gemm_gather_plain(dt, d, s.wd, (long)s.k * s.k * s.outCp, s.inCp, ed, s.p_dgrad, n->scratch, st), "conv data gradient");
             }
         }
+        const int prc = push(si);
+        if (prc != ASGD_OK) return prc;
     }
     if (fork) {
         CHECK_HIP(hipEventRecord(n->ev_join, sd), "hipEventRecord");
@@ -645,7 +673,24 @@ int asgd_fwd_bwd(asgd_net_t *net, const void *params, const void *images, const 
     rc = forward(net, params, images, labels, dropout_seed, step, worker, loss, st);
     if (rc != ASGD_OK) return rc;
     net->last_seed = dropout_seed; net->last_step = step; net->last_worker = worker; net->ran = true;
-    return backward(net, params, grads, st);
+    return backward(net, params, grads, st, nullptr);
+}
+
+int asgd_train_step(asgd_net_t *net, float *master, float *momentum, void *worker_copy, const void *images, const int32_t *labels,
+                    uint64_t dropout_seed, uint64_t step, uint32_t worker, float *loss, float *grads, float lr, float mu, float wd, void *stream)
+{
+    if (!net || !master || !momentum || !worker_copy || !images || !labels || !loss || !grads) return fail(ASGD_EINVAL, "asgd_train_step: null argument");
+    if (((uintptr_t)master | (uintptr_t)momentum | (uintptr_t)worker_copy | (uintptr_t)grads | (uintptr_t)images) & 15)
+        return fail(ASGD_EALIGN, "asgd_train_step: master, momentum, worker_copy, images and grads must be 16-byte aligned");
+    if (((uintptr_t)labels | (uintptr_t)loss) & 3) return fail(ASGD_EALIGN, "asgd_train_step: labels and loss must be 4-byte aligned");
+    int rc = ensure_prepared(net);
+    if (rc != ASGD_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = forward(net, worker_copy, images, labels, dropout_seed, step, worker, loss, st);
+    if (rc != ASGD_OK) return rc;
+    net->last_seed = dropout_seed; net->last_step = step; net->last_worker = worker; net->ran = true;
+    const ServerArgs srv{master, momentum, worker_copy, lr, mu, wd};
+    return backward(net, worker_copy, grads, st, &srv);
 }
 
 int asgd_apply_update(float *params, float *momentum, const float *grads, size_t n, float lr, float mu, float wd, void *stream)

@@ -41,6 +41,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // Each thread owns 4 float4 per buffer, 256 apart, all loads issued before the arithmetic; gradients are read and
 // parameters / momentum written with non-temporal hints (the 1.2 GB working set of the AlexNet-style net cannot
 // stay in cache between steps anyway).  Measured 5.65 TB/s on 62.4 M parameters.
+// One element of the update, with the contractions written out so that every code path (vector body, scalar
+// tail, unaligned fallback) rounds identically: t = g + wd*w;  v = mu*v - lr*t;  w = w + v.
+__device__ __forceinline__ void update1(float &w, float &v, float g, float lr, float mu, float wd)
+{
+    const float t = __builtin_fmaf(wd, w, g);
+    v = __builtin_fmaf(mu, v, -(lr * t));
+    w = w + v;
+}
+
 // SNAP: 0 = update only, 1 = also write the new parameters to `copy` as fp32, 2 = as bf16 (round to nearest even):
 // the worker copy of the next fetch comes out of the same pass instead of a second read of the parameters.
 __device__ inline uint32_t f32_to_bf16_bits(uint32_t u);
@@ -61,8 +70,12 @@ __global__ __launch_bounds__(256) void update_kernel(f32x4 *__restrict__ w, f32x
     for (int u = 0; u < U; ++u) {
         const size_t i = i0 + (size_t)u * 256;
         if (i < n4) {
-            vv[u] = mu * vv[u] - lr * (gg[u] + wd * ww[u]);
-            ww[u] += vv[u];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float wn = ww[u][e], vn = vv[u][e];
+                update1(wn, vn, gg[u][e], lr, mu, wd);
+                ww[u][e] = wn; vv[u][e] = vn;
+            }
             __builtin_nontemporal_store(ww[u], &w[i]);
             __builtin_nontemporal_store(vv[u], &v[i]);
             if constexpr (SNAP == 1) static_cast<f32x4 *>(copy)[i] = ww[u];
@@ -78,10 +91,11 @@ __global__ __launch_bounds__(256) void update_kernel(f32x4 *__restrict__ w, f32x
     if (blockIdx.x == 0) {
         const size_t i = n4 * 4 + threadIdx.x;
         if (i < n) {
-            const float t = mu * vs[i] - lr * (gs[i] + wd * ws[i]);
-            vs[i] = t; ws[i] += t;
-            if constexpr (SNAP == 1) static_cast<float *>(copy)[i] = ws[i];
-            if constexpr (SNAP == 2) static_cast<uint16_t *>(copy)[i] = (uint16_t)f32_to_bf16_bits(__float_as_uint(ws[i]));
+            float wn = ws[i], vn = vs[i];
+            update1(wn, vn, gs[i], lr, mu, wd);
+            vs[i] = vn; ws[i] = wn;
+            if constexpr (SNAP == 1) static_cast<float *>(copy)[i] = wn;
+            if constexpr (SNAP == 2) static_cast<uint16_t *>(copy)[i] = (uint16_t)f32_to_bf16_bits(__float_as_uint(wn));
         }
         if (threadIdx.x == 0 && version_counter) *version_counter += 1;
     }
@@ -93,10 +107,11 @@ __global__ __launch_bounds__(256) void update_scalar_kernel(float *w, float *v, 
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-        const float vv = mu * v[i] - lr * (g[i] + wd * w[i]);
-        v[i] = vv; w[i] += vv;
-        if constexpr (SNAP == 1) static_cast<float *>(copy)[i] = w[i];
-        if constexpr (SNAP == 2) static_cast<uint16_t *>(copy)[i] = (uint16_t)f32_to_bf16_bits(__float_as_uint(w[i]));
+        float wn = w[i], vn = v[i];
+        update1(wn, vn, g[i], lr, mu, wd);
+        v[i] = vn; w[i] = wn;
+        if constexpr (SNAP == 1) static_cast<float *>(copy)[i] = wn;
+        if constexpr (SNAP == 2) static_cast<uint16_t *>(copy)[i] = (uint16_t)f32_to_bf16_bits(__float_as_uint(wn));
     }
     if (blockIdx.x == 0 && threadIdx.x == 0 && version_counter) *version_counter += 1;
 }

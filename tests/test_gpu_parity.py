@@ -256,6 +256,52 @@ def test_small_cnn_twenty_sgd_steps(dtype):
         g.close()
 
 
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("cfg", [wl.SMALL, RAGGED], ids=["small", "ragged"])
+def test_train_step_is_the_three_calls_bit_for_bit_and_matches_the_oracle(cfg, dtype):
+    """asgd_train_step pipelines the push by layer; its results must be those of fwd_bwd + update + fetch."""
+    layers, in_shape, batch = cfg["layers"], cfg["in_shape"], 12
+    lr, mu, wd = 0.01, 0.9, 5e-4
+    params0 = wl.make_params(layers, in_shape, 2002)
+    tdt = torch.bfloat16 if dtype == B.BF16 else torch.float32
+    onet = oracle.OracleNet(layers, in_shape)
+    runs = []
+    for fused in (False, True):
+        g = GpuNet(layers, in_shape, batch, dtype)
+        try:
+            w = torch.from_numpy(params0).to(DEV); v = torch.zeros_like(w)
+            copy = torch.empty(g.P, dtype=tdt, device=DEV)
+            B.asgd_snapshot(w, copy, dtype)
+            losses, first = [], None
+            for a in range(3):
+                images, labels = wl.make_batch(in_shape, batch, cfg["classes"], 1002 + a)
+                img, lab = g.to_device_images(images), torch.from_numpy(labels.astype(np.int32)).to(DEV)
+                if fused:
+                    B.asgd_train_step(g.net, w, v, copy, img, lab, 77, a, 0, g.loss, g.grads, lr, mu, wd)
+                else:
+                    B.asgd_fwd_bwd(g.net, copy, img, lab, 77, a, 0, g.loss, g.grads)
+                    B.asgd_apply_update(w, v, g.grads, lr, mu, wd)
+                    B.asgd_snapshot(w, copy, dtype)
+                torch.cuda.synchronize()
+                losses.append(float(g.loss.item()))
+                if a == 0:
+                    first = (w.cpu().numpy().copy(), v.cpu().numpy().copy(), g.grads.cpu().numpy().copy(), images, labels)
+            runs.append((w.cpu(), v.cpu(), copy.cpu(), g.grads.cpu(), losses, first))
+        finally:
+            g.close()
+    (w0, v0, c0, g0, l0, _), (w1, v1, c1, g1, l1, first) = runs
+    assert torch.equal(w0, w1) and torch.equal(v0, v1) and torch.equal(g0, g1) and l0 == l1
+    assert torch.equal(c0.view(torch.int16 if dtype == B.BF16 else torch.int32), c1.view(torch.int16 if dtype == B.BF16 else torch.int32))
+    # first step against the oracle (later steps start from parameters the two sides no longer share exactly)
+    wg, vg, gg, images, labels = first
+    p64, i64 = oracle_inputs(params0, images, dtype)
+    _, ref_grads, _ = onet.fwd_bwd(p64, i64, labels, 77, 0, 0, act_dtype=ACT[dtype])
+    w_ref, v_ref = params0.astype(np.float64), np.zeros(params0.size)
+    oops.apply_update(w_ref, v_ref, ref_grads, np.float32(lr), np.float32(mu), np.float32(wd))
+    # a near-tie decision may differ (see the gradient tests, which validate them one by one); this net and seed have none
+    assert rel_l2(gg, ref_grads) < TOL[dtype] and rel_l2(wg, w_ref) < TOL[dtype] and rel_l2(vg, v_ref) < TOL[dtype]
+
+
 # ---------------------------------------------------------------- A-SGD replay
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 def test_asgd_replay_matches_oracle_and_logs_the_schedule(dtype):

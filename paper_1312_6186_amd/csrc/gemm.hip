@@ -39,9 +39,10 @@ template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int DEPTH_, int MINB_> s
     static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, DEPTH = DEPTH_, MINB = MINB_;
     static constexpr int NT = 64 * WAVES_M_ * WAVES_N_;
     static constexpr int MB = BM_ / WAVES_M_ / 32, NB = BN_ / WAVES_N_ / 32;   // MFMA 32x32 blocks per wave
-    static_assert((BM_ / WAVES_M_) % 64 == 0 && (BN_ / WAVES_N_) % 64 == 0, "wave tiles are multiples of 64");
+    static_assert((BM_ / WAVES_M_) % 64 == 0 && (BN_ / WAVES_N_) % 32 == 0, "wave tiles: rows in 64s, columns in 32s");
 };
-using Cfg128 = TileCfg<128, 128, 2, 2, 2, 2>;   // 256 threads, two workgroups per CU
+using Cfg128 = TileCfg<128, 128, 2, 2, 2, 2>;   // 256 threads (wave tile 64x64), two workgroups per CU: two waves per SIMD
+using Cfg128w8 = TileCfg<128, 128, 2, 4, 2, 2>; // 512 threads (wave tile 64x32), two workgroups per CU: four waves per SIMD
 #define ASGD_INLINE __attribute__((always_inline))
 
 // Compile-time loop: indices reach the body as constants, so register arrays are never addressed dynamically.
@@ -351,7 +352,7 @@ template <typename T, class L, int ROWS, int NT, int DEPTH> struct Stage<T, L, R
     static constexpr int SLOTS = Geo<T>::BK / LPP;
     static constexpr int NKS = L::kShared ? 1 : SLOTS;
     static_assert(NT % CPL == 0 && Geo<T>::BK % LPP == 0, "tile / thread-count mismatch");
-    static_assert(!L::kShared || (SLOTS == 4 && CPL % 4 == 0), "a quad shares one column and owns four K lines");
+    static_assert(!L::kShared || ((SLOTS == 4 || SLOTS == 2) && CPL % 4 == 0), "a quad shares one column and owns its K lines");
     typename L::Col c;
     typename L::KState ks[NKS];   // shared form: the K line of slot (tid & 3) only
     uint4 r[DEPTH][SLOTS];
@@ -360,7 +361,7 @@ template <typename T, class L, int ROWS, int NT, int DEPTH> struct Stage<T, L, R
     {
         const int cc = tid % CPL, line = tid / CPL;
         c = l.col(row0 + cc * (16 / (int)sizeof(T)));
-        if constexpr (L::kShared) ks[0] = l.kstate(k0 + line + (tid & 3) * LPP);
+        if constexpr (L::kShared) ks[0] = l.kstate(k0 + line + (tid & (SLOTS - 1)) * LPP);
         else static_for<0, SLOTS>([&](auto s) ASGD_INLINE { ks[s] = l.kstate(k0 + line + s * LPP); });
         wo = (unsigned)(line * TransTile<T, ROWS>::LINE + cc * 16);
     }
@@ -789,7 +790,11 @@ static int run(const LA &la, const LB &lb, int M, int N, int K, const Epilogue &
 {
     if (M <= 0 || N <= 0 || K <= 0 || (N & 7)) return -1;
     if (la.op.bytes == 0 || lb.op.bytes == 0) return -1;   // an operand beyond the 1 GiB the 32-bit offsets cover
-    return run_tile<T, Cfg128>(la, lb, M, N, K, ep, plan, ws, s);
+    // Measured on the AlexNet-style shapes: the 8-wave form (four waves per SIMD hide more latency) wins
+    // everywhere except the convolution filter gradient, whose two transposing operands make it bound by LDS
+    // reads, of which the narrower wave tile needs half as many again.
+    if constexpr (std::is_same<LB, GatherT<T>>::value) return run_tile<T, Cfg128>(la, lb, M, N, K, ep, plan, ws, s);
+    else return run_tile<T, Cfg128w8>(la, lb, M, N, K, ep, plan, ws, s);
 }
 
 static Operand operand(const void *p, size_t bytes) { return Operand{p, bytes <= kMaxOperandBytes ? (unsigned)bytes : 0u}; }

@@ -323,37 +323,65 @@ int launch_pack_conv(int dtype, const void *w, void *wf, void *wd, int cout, int
 }
 
 // ---------------------------------------------------------------- max pooling
+__device__ __forceinline__ uint32_t fdiv32(uint32_t n, const FastDiv &f) { return (__umulhi(n, f.mul) + n) >> f.sh; }
+// thread index -> (channel group, x, y, image) by three multiply-shift divisions (the index fits 31 bits)
+struct PoolIndex { FastDiv dcv, dw, dh; int cv, w, h; };
+static PoolIndex make_pool_index(int cv, int w, int h)
+{
+    return PoolIndex{make_fastdiv((uint32_t)cv), make_fastdiv((uint32_t)w), make_fastdiv((uint32_t)h), cv, w, h};
+}
+__device__ __forceinline__ void pool_decode(uint32_t i, const PoolIndex &p, int &cg, int &x, int &y, int &n)
+{
+    uint32_t t = fdiv32(i, p.dcv); cg = (int)(i - t * p.cv);
+    uint32_t u = fdiv32(t, p.dw); x = (int)(t - u * p.w);
+    n = (int)fdiv32(u, p.dh); y = (int)(u - (uint32_t)n * p.h);
+}
 // One thread owns VEC consecutive channels (16 bytes) of one output pixel.
 template <typename T> struct Vec16 {
     static constexpr int N = 16 / sizeof(T);
     union { uint4 u; T e[16 / sizeof(T)]; };
 };
 
-template <typename T>
+// KC > 0: window size known at compile time, so the k*k loads of a thread are all issued before the first compare.
+template <typename T, int KC>
 __global__ __launch_bounds__(256) void pool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, uint8_t *__restrict__ arg, int B, int H, int W,
-                                                     int Cp, int k, int stride, int Ho, int Wo)
+                                                     int Cp, int k_rt, int stride, int Ho, int Wo, PoolIndex pi)
 {
     constexpr int V = Vec16<T>::N;
-    const int cv = Cp / V;
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (long)B * Ho * Wo * cv) return;
-    const int c0 = (int)(i % cv) * V; long t = i / cv;
-    const int px = (int)(t % Wo); t /= Wo;
-    const int py = (int)(t % Ho);
-    const int n = (int)(t / Ho);
+    const int k = KC > 0 ? KC : k_rt;
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= (uint32_t)B * Ho * Wo * pi.cv) return;
+    int cg, px, py, n;
+    pool_decode(i, pi, cg, px, py, n);
+    const int c0 = cg * V;
+    const T *win = x + (((long)n * H + py * stride) * W + px * stride) * Cp + c0;
     float best[V];
     uint8_t a[V];
-    for (int ky = 0; ky < k; ++ky)
-        for (int kx = 0; kx < k; ++kx) {
-            Vec16<T> v;
-            v.u = *reinterpret_cast<const uint4 *>(x + (((long)n * H + py * stride + ky) * W + px * stride + kx) * Cp + c0);
-            const int pos = ky * k + kx;
+    if constexpr (KC > 0) {
+        Vec16<T> v[KC * KC];
+#pragma unroll
+        for (int p = 0; p < KC * KC; ++p) v[p].u = *reinterpret_cast<const uint4 *>(win + ((long)(p / KC) * W + (p % KC)) * Cp);
+#pragma unroll
+        for (int p = 0; p < KC * KC; ++p) {
 #pragma unroll
             for (int e = 0; e < V; ++e) {
-                const float f = ldf(&v.e[e]);
-                if (pos == 0 || f > best[e]) { best[e] = f; a[e] = (uint8_t)pos; }
+                const float f = ldf(&v[p].e[e]);
+                if (p == 0 || f > best[e]) { best[e] = f; a[e] = (uint8_t)p; }
             }
         }
+    } else {
+        for (int ky = 0; ky < k; ++ky)
+            for (int kx = 0; kx < k; ++kx) {
+                Vec16<T> v;
+                v.u = *reinterpret_cast<const uint4 *>(win + ((long)ky * W + kx) * Cp);
+                const int pos = ky * k + kx;
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    const float f = ldf(&v.e[e]);
+                    if (pos == 0 || f > best[e]) { best[e] = f; a[e] = (uint8_t)pos; }
+                }
+            }
+    }
     Vec16<T> o;
 #pragma unroll
     for (int e = 0; e < V; ++e) stf(&o.e[e], best[e]);
@@ -366,53 +394,83 @@ __global__ __launch_bounds__(256) void pool_fwd_kernel(const T *__restrict__ x, 
     else *reinterpret_cast<uint32_t *>(arg + off) = (uint32_t)packed;
 }
 
+template <typename T>
+static void launch_pool_fwd_t(const void *x, void *y, uint8_t *arg, int B, int H, int W, int Cp, int k, int stride, int Ho, int Wo, unsigned blocks,
+                              hipStream_t s)
+{
+    const T *xx = static_cast<const T *>(x); T *yy = static_cast<T *>(y);
+    const PoolIndex pi = make_pool_index(Cp / (16 / (int)sizeof(T)), Wo, Ho);
+    if (k == 3) hipLaunchKernelGGL((pool_fwd_kernel<T, 3>), dim3(blocks), dim3(256), 0, s, xx, yy, arg, B, H, W, Cp, k, stride, Ho, Wo, pi);
+    else if (k == 2) hipLaunchKernelGGL((pool_fwd_kernel<T, 2>), dim3(blocks), dim3(256), 0, s, xx, yy, arg, B, H, W, Cp, k, stride, Ho, Wo, pi);
+    else hipLaunchKernelGGL((pool_fwd_kernel<T, 0>), dim3(blocks), dim3(256), 0, s, xx, yy, arg, B, H, W, Cp, k, stride, Ho, Wo, pi);
+}
 int launch_pool_fwd(int dtype, const void *x, void *y, uint8_t *arg, int B, int H, int W, int Cp, int k, int stride, hipStream_t s)
 {
     const int Ho = (H - k) / stride + 1, Wo = (W - k) / stride + 1;
     const int V = dtype == kBF16 ? 8 : 4;
+    if ((size_t)B * Ho * Wo * (Cp / V) > 0x7fffffffu) return -1;
     const unsigned blocks = blocks_for((size_t)B * Ho * Wo * (Cp / V), 256);
-    if (dtype == kBF16)
-        hipLaunchKernelGGL(pool_fwd_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(x), static_cast<bf16_t *>(y), arg, B, H, W,
-                           Cp, k, stride, Ho, Wo);
-    else
-        hipLaunchKernelGGL(pool_fwd_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(x), static_cast<float *>(y), arg, B, H, W, Cp, k,
-                           stride, Ho, Wo);
+    if (dtype == kBF16) launch_pool_fwd_t<bf16_t>(x, y, arg, B, H, W, Cp, k, stride, Ho, Wo, blocks, s);
+    else launch_pool_fwd_t<float>(x, y, arg, B, H, W, Cp, k, stride, Ho, Wo, blocks, s);
     return launch_ok();
 }
 
 // Gather form: an input pixel sums, in (py, px) order, the gradients of the
-// windows whose recorded maximum it is; then the ReLU mask of the layer below.
-template <typename T>
+// windows whose recorded maximum it is; then, if asked, the ReLU mask of the layer below.
+// TWO: at most two windows per axis cover a pixel (k <= 2*stride); the four candidate windows are then
+// fetched up front, with the out-of-range ones masked, instead of in a loop whose loads wait for each other.
+template <typename T, bool TWO>
 __global__ __launch_bounds__(256) void pool_bwd_kernel(const T *__restrict__ dy, const uint8_t *__restrict__ arg, const T *__restrict__ x, int relu,
-                                                     T *__restrict__ dx, int B, int H, int W, int Cp, int k, int stride, int Ho, int Wo)
+                                                     T *__restrict__ dx, int B, int H, int W, int Cp, int k, int stride, int Ho, int Wo,
+                                                     PoolIndex pi, FastDiv dstride)
 {
     constexpr int V = Vec16<T>::N;
-    const int cv = Cp / V;
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (long)B * H * W * cv) return;
-    const int c0 = (int)(i % cv) * V; long t = i / cv;
-    const int ix = (int)(t % W); t /= W;
-    const int iy = (int)(t % H);
-    const int n = (int)(t / H);
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= (uint32_t)B * H * W * pi.cv) return;
+    int cg, ix, iy, n;
+    pool_decode(i, pi, cg, ix, iy, n);
+    const int c0 = cg * V;
     float acc[V];
 #pragma unroll
     for (int e = 0; e < V; ++e) acc[e] = 0.f;
-    int py0 = iy - k + 1; py0 = py0 <= 0 ? 0 : (py0 + stride - 1) / stride;
-    int px0 = ix - k + 1; px0 = px0 <= 0 ? 0 : (px0 + stride - 1) / stride;
-    const int py1 = min(iy / stride, Ho - 1), px1 = min(ix / stride, Wo - 1);
-    for (int py = py0; py <= py1; ++py)
-        for (int px = px0; px <= px1; ++px) {
-            const int pos = (iy - py * stride) * k + (ix - px * stride);
-            const long off = (((long)n * Ho + py) * Wo + px) * Cp + c0;
-            Vec16<T> g;
-            g.u = *reinterpret_cast<const uint4 *>(dy + off);
-            uint64_t a8;   // the V recorded positions of this window, one byte each
-            if (V == 8) a8 = *reinterpret_cast<const uint64_t *>(arg + off);
-            else a8 = *reinterpret_cast<const uint32_t *>(arg + off);
+    int py0 = iy - k + 1; py0 = py0 <= 0 ? 0 : (int)fdiv32((uint32_t)(py0 + stride - 1), dstride);
+    int px0 = ix - k + 1; px0 = px0 <= 0 ? 0 : (int)fdiv32((uint32_t)(px0 + stride - 1), dstride);
+    const int py1 = min((int)fdiv32((uint32_t)iy, dstride), Ho - 1), px1 = min((int)fdiv32((uint32_t)ix, dstride), Wo - 1);
+    auto add = [&](const Vec16<T> &g, uint64_t a8, int pos, bool ok) {
 #pragma unroll
-            for (int e = 0; e < V; ++e)
-                if ((int)((a8 >> (8 * e)) & 0xff) == pos) acc[e] += ldf(&g.e[e]);
+        for (int e = 0; e < V; ++e)
+            if (ok && (int)((a8 >> (8 * e)) & 0xff) == pos) acc[e] += ldf(&g.e[e]);
+    };
+    if constexpr (TWO) {
+        Vec16<T> g[4];
+        uint64_t a8[4];
+        int pos[4];
+        bool ok[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {   // (py0, px0), (py0, px0+1), (py0+1, px0), (py0+1, px0+1)
+            const int py = py0 + (q >> 1), px = px0 + (q & 1);
+            ok[q] = py <= py1 && px <= px1;
+            const int pyc = min(py, Ho - 1), pxc = min(px, Wo - 1);   // a readable address either way
+            pos[q] = (iy - py * stride) * k + (ix - px * stride);
+            const long off = (((long)n * Ho + pyc) * Wo + pxc) * Cp + c0;
+            g[q].u = *reinterpret_cast<const uint4 *>(dy + off);
+            if (V == 8) a8[q] = *reinterpret_cast<const uint64_t *>(arg + off);
+            else a8[q] = *reinterpret_cast<const uint32_t *>(arg + off);
         }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) add(g[q], a8[q], pos[q], ok[q]);
+    } else {
+        for (int py = py0; py <= py1; ++py)
+            for (int px = px0; px <= px1; ++px) {
+                const long off = (((long)n * Ho + py) * Wo + px) * Cp + c0;
+                Vec16<T> g;
+                g.u = *reinterpret_cast<const uint4 *>(dy + off);
+                uint64_t a8;   // the V recorded positions of this window, one byte each
+                if (V == 8) a8 = *reinterpret_cast<const uint64_t *>(arg + off);
+                else a8 = *reinterpret_cast<const uint32_t *>(arg + off);
+                add(g, a8, (iy - py * stride) * k + (ix - px * stride), true);
+            }
+    }
     const long off = (((long)n * H + iy) * W + ix) * Cp + c0;
     Vec16<T> o;
     if (relu) {
@@ -427,18 +485,25 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const T *__restrict__ dy,
     *reinterpret_cast<uint4 *>(dx + off) = o.u;
 }
 
+template <typename T>
+static void launch_pool_bwd_t(const void *dy, const uint8_t *arg, const void *x, int relu, void *dx, int B, int H, int W, int Cp, int k, int stride,
+                              int Ho, int Wo, unsigned blocks, hipStream_t s)
+{
+    const T *d = static_cast<const T *>(dy), *xx = static_cast<const T *>(x); T *o = static_cast<T *>(dx);
+    const PoolIndex pi = make_pool_index(Cp / (16 / (int)sizeof(T)), W, H);
+    const FastDiv ds = make_fastdiv((uint32_t)stride);
+    if (k <= 2 * stride) hipLaunchKernelGGL((pool_bwd_kernel<T, true>), dim3(blocks), dim3(256), 0, s, d, arg, xx, relu, o, B, H, W, Cp, k, stride, Ho, Wo, pi, ds);
+    else hipLaunchKernelGGL((pool_bwd_kernel<T, false>), dim3(blocks), dim3(256), 0, s, d, arg, xx, relu, o, B, H, W, Cp, k, stride, Ho, Wo, pi, ds);
+}
 int launch_pool_bwd(int dtype, const void *dy, const uint8_t *arg, const void *x, int relu, void *dx, int B, int H, int W, int Cp, int k, int stride,
                     hipStream_t s)
 {
     const int Ho = (H - k) / stride + 1, Wo = (W - k) / stride + 1;
     const int V = dtype == kBF16 ? 8 : 4;
+    if ((size_t)B * H * W * (Cp / V) > 0x7fffffffu) return -1;
     const unsigned blocks = blocks_for((size_t)B * H * W * (Cp / V), 256);
-    if (dtype == kBF16)
-        hipLaunchKernelGGL(pool_bwd_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(dy), arg, static_cast<const bf16_t *>(x), relu,
-                           static_cast<bf16_t *>(dx), B, H, W, Cp, k, stride, Ho, Wo);
-    else
-        hipLaunchKernelGGL(pool_bwd_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(dy), arg, static_cast<const float *>(x), relu,
-                           static_cast<float *>(dx), B, H, W, Cp, k, stride, Ho, Wo);
+    if (dtype == kBF16) launch_pool_bwd_t<bf16_t>(dy, arg, x, relu, dx, B, H, W, Cp, k, stride, Ho, Wo, blocks, s);
+    else launch_pool_bwd_t<float>(dy, arg, x, relu, dx, B, H, W, Cp, k, stride, Ho, Wo, blocks, s);
     return launch_ok();
 }
 

@@ -51,7 +51,7 @@ typedef enum {
     ASGD_LAYER_RELU = 2,       /* must follow a CONV or an FC                  */
     ASGD_LAYER_MAXPOOL = 3,    /* k, stride (unpadded, floor rule)             */
     ASGD_LAYER_FC = 4,         /* out                                          */
-    ASGD_LAYER_DROPOUT = 5,    /* p, scale; must follow FC or FC+RELU          */
+    ASGD_LAYER_DROPOUT = 5,    /* p, scale; must directly follow FC + RELU      */
     ASGD_LAYER_SOFTMAX_CE = 6  /* last layer; follows an FC                    */
 } asgd_layer_kind_t;
 

@@ -88,7 +88,6 @@ struct asgd_net {
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     std::vector<hipEvent_t> ev_pack, ev_dy, ev_dg;   // per stage: filters packed, output gradient ready, data gradient issued
     float *row_loss = nullptr;
-    void *zero_page = nullptr;       // 256 zero bytes, never written
     int *version_counter = nullptr;  // device-side count of applied updates (A-SGD replay)
     size_t scratch_floats = 0, scratch_side_floats = 0;
     // key of the last forward pass (for the dropout mask export)
@@ -124,11 +123,10 @@ size_t carve(asgd_net &n, char *base)
         const size_t o = c.take(bytes);
         return base ? base + o : nullptr;
     };
-    // every activation / gradient tensor is followed by 256 zero bytes (the arena is cleared once and the
-    // tail is never written): the gathers read out-of-image pieces from there
+    // the arena is cleared once when it is allocated: the zero border of a bordered input is never written
+    // afterwards; tensors are spaced by 256 spare bytes
     const Stage *s0 = n.stages.empty() ? nullptr : &n.stages[0];
     n.act0 = at((s0 && s0->rw ? B * s0->rwHp * s0->rwWp * 4 : B * n.in_h * n.in_w * n.in_cp) * es + 256);
-    n.zero_page = at(256);
     for (size_t i = 0; i < n.stages.size(); ++i) {
         Stage &s = n.stages[i];
         const size_t oe = B * s.out_elems();

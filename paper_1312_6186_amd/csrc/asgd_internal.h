@@ -1,7 +1,9 @@
 // Internal declarations shared by the host orchestration (api.cpp) and the
 // kernel files.  Activations live channel-last, [B][H][W][Cp] with the channel
 // count rounded up to a multiple of 8 (padding channels hold zeros); FC-side
-// activations are [B][ld] row-major.  All kernels target gfx950 only.
+// activations are [B][ld] row-major.  The input of a first convolution over at
+// most 4 channels is instead kept with 4 channels per pixel and its zero border
+// (see Gather).  All kernels target gfx950 only.
 #pragma once
 #include <hip/hip_runtime_api.h>
 #include <stddef.h>

@@ -324,6 +324,13 @@ int launch_pack_conv(int dtype, const void *w, void *wf, void *wd, int cout, int
 
 // ---------------------------------------------------------------- max pooling
 __device__ __forceinline__ uint32_t fdiv32(uint32_t n, const FastDiv &f) { return (__umulhi(n, f.mul) + n) >> f.sh; }
+// Workgroup ids go round-robin over the 8 XCDs; neighbouring pixels share pooling windows, so each XCD is given a
+// contiguous range of blocks (and its L2 fetches a window row once instead of every XCD fetching it).
+__device__ __forceinline__ uint32_t xcd_block()
+{
+    const uint32_t nb = gridDim.x, q = nb >> 3, r = nb & 7, x = blockIdx.x & 7;
+    return x * q + (x < r ? x : r) + (blockIdx.x >> 3);
+}
 // thread index -> (channel group, x, y, image) by three multiply-shift divisions (the index fits 31 bits)
 struct PoolIndex { FastDiv dcv, dw, dh; int cv, w, h; };
 static PoolIndex make_pool_index(int cv, int w, int h)
@@ -349,7 +356,7 @@ __global__ __launch_bounds__(256) void pool_fwd_kernel(const T *__restrict__ x, 
 {
     constexpr int V = Vec16<T>::N;
     const int k = KC > 0 ? KC : k_rt;
-    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    const uint32_t i = xcd_block() * 256u + threadIdx.x;
     if (i >= (uint32_t)B * Ho * Wo * pi.cv) return;
     int cg, px, py, n;
     pool_decode(i, pi, cg, px, py, n);
@@ -425,7 +432,7 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const T *__restrict__ dy,
                                                      PoolIndex pi, FastDiv dstride)
 {
     constexpr int V = Vec16<T>::N;
-    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    const uint32_t i = xcd_block() * 256u + threadIdx.x;
     if (i >= (uint32_t)B * H * W * pi.cv) return;
     int cg, ix, iy, n;
     pool_decode(i, pi, cg, ix, iy, n);

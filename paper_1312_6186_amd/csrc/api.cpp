@@ -85,6 +85,7 @@ struct asgd_net {
     // The parameter gradients of a layer (and the filter packing of the forward pass) do not feed the next
     // layer: they run on an internal stream beside the caller's, forked and joined with events.
     hipStream_t side = nullptr;
+    bool in_replay = false;   // replicas of a replay already run beside each other: no side stream then (measured slower)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     std::vector<hipEvent_t> ev_pack, ev_dy, ev_dg;   // per stage: filters packed, output gradient ready, data gradient issued
     float *row_loss = nullptr;
@@ -412,7 +413,7 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
         else CHECK_LAUNCH(launch_stage_input(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, n->in_cp, st), "stage_input");
     }
     // filter packing: beside the input staging and the first layers (in line when profiling, to be timed alone)
-    const bool fork = !n->prof_on && !serial_mode();
+    const bool fork = !n->prof_on && !n->in_replay && !serial_mode();
     hipStream_t sd = fork ? n->side : st;
     if (fork) {
         CHECK_HIP(hipEventRecord(n->ev_fork, st), "hipEventRecord");
@@ -487,7 +488,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
 {
     const int B = n->batch, dt = n->dtype;
     const double es = (double)dtype_size(dt), Bd = (double)B;
-    const bool fork = !n->prof_on && !serial_mode();
+    const bool fork = !n->prof_on && !n->in_replay && !serial_mode();
     hipStream_t sd = fork ? n->side : st;   // parameter gradients go here
     auto push = [&](int si) -> int {      // after the stage's gradients are queued on sd and its data gradient on st
         Stage &s = n->stages[si];
@@ -841,6 +842,7 @@ int asgd_replay_run(asgd_net_t *const *nets, int n_workers, float *params, float
         last_push[worker[a]] = a;
     }
     for (int w = 0; w < n_workers; ++w) {
+        nets[w]->in_replay = n_workers > 1;
         const int rc = ensure_prepared(nets[w]);
         if (rc != ASGD_OK) return rc;
     }

@@ -218,8 +218,17 @@ def main():
                          "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK["hbm"]}
     dominant = max(classes_out, key=lambda k: classes_out[k]["ms_per_step"])
     d = classes_out[dominant]
+    # HBM bytes per launch of that class, from the committed rocprofv3 counter summary of this workload (null if there is none)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", args.workload + "_hbm_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            t = json.load(f).get("classes", {}).get(dominant)
+        if t:
+            traffic = (t["hbm_read_bytes"] + t["hbm_written_bytes"]) / t["launches"]
     roofline = {"kernel": dominant, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"], "unit": d["unit"],
-                "frac": d["frac"], "traffic": None, "ms_per_launch": d["ms_per_step"] / d["launches_per_step"]}
+                "frac": d["frac"], "traffic": traffic, "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
+                "launches_per_step": d["launches_per_step"], "ms_per_launch": d["ms_per_step"] / d["launches_per_step"]}
     mfma_ms = sum(c["ms_per_step"] for n, c in classes_out.items() if n in MFMA_CLASSES)
     mfma_flops = sum(prof[n]["flops"] for n in MFMA_CLASSES) / K
     B.asgd_net_destroy(net)

@@ -21,6 +21,13 @@ RAGGED = dict(name="ragged", in_shape=(3, 37, 29), classes=10,
                       ("softmax_ce",)])
 
 
+# six input channels and 7x7 windows: the channel-padded first layer and the two-mask form of the window gather
+# (more than 32 window positions), forward, data gradient and filter gradient; a 1x1 convolution; pool 3/1
+WIDE = dict(name="wide", in_shape=(6, 21, 19), classes=10,
+            layers=[("conv", 8, 7, 2, 3), ("relu",), ("conv", 12, 7, 1, 3), ("relu",), ("conv", 12, 1, 1, 0), ("relu",),
+                    ("maxpool", 3, 1), ("fc", 24), ("relu",), ("fc", 10), ("softmax_ce",)])
+
+
 # ---------------------------------------------------------------- update / snapshot
 @pytest.mark.parametrize("n,offset", [(1, 0), (1023, 0), (4099, 0), (15898, 0), (100003, 1), (1 << 20, 4)])
 def test_apply_update_matches_oracle(n, offset):
@@ -113,8 +120,8 @@ def _net_case(cfg, batch, dtype, seed=0, step=0, worker=0, bias_noise=0.05):
 
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
-@pytest.mark.parametrize("cfg,batch", [(wl.TINY, 8), (RAGGED, 5), (RAGGED, 131), (wl.SMALL, 128)],
-                         ids=["tiny", "ragged5", "ragged131", "small"])
+@pytest.mark.parametrize("cfg,batch", [(wl.TINY, 8), (wl.TINY, 1), (RAGGED, 5), (RAGGED, 131), (WIDE, 3), (wl.SMALL, 128)],
+                         ids=["tiny", "tiny-batch1", "ragged5", "ragged131", "wide", "small"])
 def test_minibatch_gradient_matches_oracle(cfg, batch, dtype):
     g, onet, (loss, grads), (ref_loss, ref_grads, trace), _ = _net_case(cfg, batch, dtype, seed=3002, step=4, worker=1)
     try:

@@ -61,6 +61,7 @@ struct Stage {
     uint8_t *argmax = nullptr;
     void *wf = nullptr, *wd = nullptr;
     void *flat_in = nullptr, *dflat_in = nullptr;
+    float *colsum_ws = nullptr; size_t colsum_floats = 0;   // band sums of the bias gradient
     GemmPlan p_fwd, p_dgrad, p_wgrad;
     size_t out_elems() const { return kind == ST_FC ? (size_t)out_ld : (size_t)outH * outW * outCp; }
 };
@@ -138,6 +139,7 @@ size_t carve(asgd_net &n, char *base)
             s.wf = at((size_t)s.outCp * s.k * (s.rw ? s.rwKW : s.k * s.inCp) * es);
             s.wd = i > 0 ? at((size_t)s.inCp * s.k * s.k * s.outCp * es) : nullptr;
         }
+        if (s.kind != ST_POOL) s.colsum_ws = static_cast<float *>(at(s.colsum_floats * 4));
         if (s.kind == ST_FC && s.in_is_spatial) {
             s.flat_in = at(B * s.in_f * es);
             s.dflat_in = at(B * s.in_f * es);
@@ -274,13 +276,13 @@ int plan_net(asgd_net &n)
             s.p_dgrad = plan_gemm(Min, s.inCp, (long)s.k * s.k * s.outCp, n.dtype, 1);
             s.p_wgrad = plan_gemm(s.outCp, K, M, n.dtype, 64);
             scratch_side = std::max(scratch_side, s.p_wgrad.ws_floats);
-            scratch_side = std::max(scratch_side, colsum_ws_floats(n.dtype, M, s.outCp));
+            s.colsum_floats = colsum_ws_floats(n.dtype, M, s.outCp);
         } else if (s.kind == ST_FC) {
             s.p_fwd = plan_gemm(B, s.out_ld, s.in_f, n.dtype, 32);
             s.p_dgrad = plan_gemm(B, s.in_f, s.out_f, n.dtype, 32);
             s.p_wgrad = plan_gemm(s.out_f, s.in_f, B, n.dtype, 1);
             scratch = std::max(scratch, std::max(s.p_fwd.ws_floats, s.p_dgrad.ws_floats));
-            scratch_side = std::max(scratch_side, colsum_ws_floats(n.dtype, B, s.out_ld));
+            s.colsum_floats = colsum_ws_floats(n.dtype, B, s.out_ld);
         }
     }
     n.scratch_floats = scratch + 64;
@@ -419,23 +421,36 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
         CHECK_HIP(hipEventRecord(n->ev_fork, st), "hipEventRecord");
         CHECK_HIP(hipStreamWaitEvent(sd, n->ev_fork, 0), "hipStreamWaitEvent");
     }
-    auto pack = [&](size_t si) -> int {
-        Stage &s = n->stages[si];
-        ProfScope ps(n, sd, ASGD_K_LAYOUT, 0, (double)s.w_cnt * es * (s.wd ? 3 : 2));
-        if (s.rw) CHECK_LAUNCH(launch_pack_conv_rw(dt, param_ptr(n, params, s.w_off), s.wf, s.outC, s.inC, s.k, s.k, s.outCp, s.rwKW, sd), "pack_conv");
-        else CHECK_LAUNCH(launch_pack_conv(dt, param_ptr(n, params, s.w_off), s.wf, s.wd, s.outC, s.inC, s.k, s.k, s.outCp, s.inCp, sd), "pack_conv");
-        if (fork) CHECK_HIP(hipEventRecord(n->ev_pack[si], sd), "hipEventRecord");
-        return ASGD_OK;
-    };
-    if (fork)
-        for (size_t si = 0; si < n->stages.size(); ++si)
-            if (n->stages[si].kind == ST_CONV) { const int rc = pack(si); if (rc != ASGD_OK) return rc; }
+    {   // all layers' filters in one launch (twelve layers per launch at most)
+        PackJobs jobs; jobs.n = 0; jobs.total = 0;
+        double bytes = 0;
+        auto flush = [&]() -> int {
+            if (jobs.n == 0) return ASGD_OK;
+            ProfScope ps(n, sd, ASGD_K_LAYOUT, 0, bytes);
+            CHECK_LAUNCH(launch_pack_conv(dt, jobs, sd), "pack_conv");
+            jobs.n = 0; bytes = 0;
+            return ASGD_OK;
+        };
+        for (size_t si = 0; si < n->stages.size(); ++si) {
+            Stage &s = n->stages[si];
+            if (s.kind != ST_CONV) continue;
+            PackJob &J = jobs.j[jobs.n++];
+            J.w = param_ptr(n, params, s.w_off); J.wf = s.wf; J.wd = s.rw ? nullptr : s.wd;
+            J.cout = s.outC; J.cin = s.inC; J.k = s.k; J.coutp = s.outCp; J.cinp = s.inCp; J.rw = s.rw; J.KW = s.rwKW;
+            bytes += (double)s.w_cnt * es * (J.wd ? 3 : 2);
+            if (jobs.n == 12) { const int rc = flush(); if (rc != ASGD_OK) return rc; }
+        }
+        const int rc = flush();
+        if (rc != ASGD_OK) return rc;
+        if (fork) CHECK_HIP(hipEventRecord(n->ev_pack[0], sd), "hipEventRecord");
+    }
+    bool packed_seen = false;
     const void *cur = n->act0;
     for (size_t si = 0; si < n->stages.size(); ++si) {
         Stage &s = n->stages[si];
         if (s.kind == ST_CONV) {
-            if (fork) CHECK_HIP(hipStreamWaitEvent(st, n->ev_pack[si], 0), "hipStreamWaitEvent");
-            else { const int rc = pack(si); if (rc != ASGD_OK) return rc; }
+            if (fork && !packed_seen) CHECK_HIP(hipStreamWaitEvent(st, n->ev_pack[0], 0), "hipStreamWaitEvent");
+            packed_seen = true;
             const double Mo = Bd * s.outH * s.outW;
             ProfScope ps(n, st, ASGD_K_CONV_FWD, 2 * Mo * s.outC * s.inC * s.k * s.k,
                          (Bd * s.inH * s.inW * s.inC + (double)s.w_cnt + Mo * s.outC) * es);
@@ -490,6 +505,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
     const double es = (double)dtype_size(dt), Bd = (double)B;
     const bool fork = !n->prof_on && !n->in_replay && !serial_mode();
     hipStream_t sd = fork ? n->side : st;   // parameter gradients go here
+    ColsumJobs bias_jobs; bias_jobs.n = 0;  // second stage of the bias gradients: one launch at the end, or per layer when pushing by layer
     auto push = [&](int si) -> int {      // after the stage's gradients are queued on sd and its data gradient on st
         Stage &s = n->stages[si];
         if (!srv || s.kind == ST_POOL) return ASGD_OK;
@@ -523,7 +539,8 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
             }
             {
                 ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, Bd * s.out_f * es + s.out_f * 4.0);
-                CHECK_LAUNCH(launch_colsum(dt, s.dout, s.out_ld, B, s.out_f, grads + s.b_off, n->scratch_side, sd), "fc bias gradient");
+                CHECK_LAUNCH(launch_colsum_partial(dt, s.dout, s.out_ld, B, s.out_f, grads + s.b_off, s.colsum_ws, bias_jobs, sd), "fc bias gradient");
+                if (srv || bias_jobs.n == 12) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "fc bias gradient");
             }
             if (prev) {
                 Epilogue ed;
@@ -568,7 +585,8 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
             }
             {
                 ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, Mo * s.outC * es + s.outC * 4.0);
-                CHECK_LAUNCH(launch_colsum(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, n->scratch_side, sd), "conv bias gradient");
+                CHECK_LAUNCH(launch_colsum_partial(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, s.colsum_ws, bias_jobs, sd), "conv bias gradient");
+                if (srv || bias_jobs.n == 12) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "conv bias gradient");
             }
             if (prev) {
                 Gather d;
@@ -587,6 +605,10 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
         }
         const int prc = push(si);
         if (prc != ASGD_OK) return prc;
+    }
+    {
+        ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, 0);
+        CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "bias gradients");
     }
     if (fork) {
         CHECK_HIP(hipEventRecord(n->ev_join, sd), "hipEventRecord");

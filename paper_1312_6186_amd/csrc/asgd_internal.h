@@ -97,11 +97,16 @@ int launch_snapshot(const float *src, void *dst, size_t n, int dst_dtype, const 
 int launch_stage_input(int dtype, const void *src, void *dst, int B, int C, int H, int W, int Cp, hipStream_t s);
 // the same into the interior of a bordered [B][H+2*pad][Wp][4] tensor (C <= 4; the border is not written)
 int launch_stage_input_rw(int dtype, const void *src, void *dst, int B, int C, int H, int W, int pad, int Wp, hipStream_t s);
-// canonical conv filters -> window-row pack [coutp][kh][KW], element (ky, kx*4 + ci), zeros elsewhere
-int launch_pack_conv_rw(int dtype, const void *w, void *wf, int cout, int cin, int kh, int kw, int coutp, int KW, hipStream_t s);
-// canonical conv filters -> forward pack [coutp][kh][kw][cinp] and flipped data-gradient pack [cinp][kh][kw][coutp]
-int launch_pack_conv(int dtype, const void *w, void *wf, void *wd, int cout, int cin, int kh, int kw, int coutp,
-                     int cinp, hipStream_t s);
+// Filter packing for all convolution layers of a net in one launch.  Per layer: canonical filters
+// [cout][cin][k][k] -> forward pack wf [coutp][k][k][cinp] and, if wd is given, the flipped data-gradient pack
+// wd [cinp][k][k][coutp]; or (rw) the window-row pack wf [coutp][k][KW], element (ky, kx*4 + ci), zeros elsewhere.
+struct PackJob {
+    const void *w; void *wf; void *wd;
+    int cout, cin, k, coutp, cinp, rw, KW;
+    unsigned start, nf;   // filled by launch_pack_conv
+};
+struct PackJobs { PackJob j[12]; int n; unsigned total; };
+int launch_pack_conv(int dtype, PackJobs &jobs, hipStream_t s);
 int launch_pool_fwd(int dtype, const void *x, void *y, uint8_t *arg, int B, int H, int W, int Cp, int k, int stride,
                     hipStream_t s);
 // dx[pixel] = sum of dy over the windows whose recorded maximum is this pixel; times [x > 0] if relu
@@ -111,8 +116,13 @@ int launch_pool_bwd(int dtype, const void *dy, const uint8_t *arg, const void *x
 int launch_flatten(int dtype, const void *x, void *flat, int B, int H, int W, int C, int Cp, hipStream_t s);
 int launch_unflatten(int dtype, const void *dflat, const void *x_for_mask, int relu, void *dx, int B, int H, int W,
                      int C, int Cp, hipStream_t s);
-// db[n] = sum_m dy[m][n], n < N, fp32, fixed summation order
-int launch_colsum(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, hipStream_t s);
+// db[n] = sum_m dy[m][n], n < N, fp32, fixed summation order, in two stages: launch_colsum_partial sums bands of
+// rows into ws (colsum_ws_floats floats, not shared with another pending job) and appends a job;
+// launch_colsum_finish adds the bands of all pending jobs (up to 12) in one launch.
+struct ColsumJob { const float *ws; float *db; long ld; int nblk, N; unsigned start_block; };
+struct ColsumJobs { ColsumJob j[12]; int n; };
+int launch_colsum_partial(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, ColsumJobs &jobs, hipStream_t s);
+int launch_colsum_finish(ColsumJobs &jobs, hipStream_t s);
 size_t colsum_ws_floats(int dtype, long M, long ld);
 // softmax cross-entropy over fp32 logits [B][ld]: loss (mean) and dz (compute type, [B][ld], zero padding columns)
 int launch_softmax_ce(int dtype, const float *z, long ld, const int32_t *labels, int B, int C, void *dz, float *loss,

@@ -267,58 +267,51 @@ int launch_stage_input_rw(int dtype, const void *src, void *dst, int B, int C, i
     return launch_ok();
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void pack_conv_rw_kernel(const T *__restrict__ w, T *__restrict__ wf, int cout, int cin, int kh, int kw, int coutp, int KW)
+// All convolution layers of a net in one launch: element i belongs to the job whose range holds it.
+template <typename T> __global__ __launch_bounds__(256) void pack_conv_kernel(PackJobs jobs)
 {
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (long)coutp * kh * KW) return;
-    const int j = (int)(i % KW); long t = i / KW;
-    const int ky = (int)(t % kh), co = (int)(t / kh);
-    const int kx = j >> 2, ci = j & 3;
-    wf[i] = (co < cout && ci < cin && kx < kw) ? w[(((long)co * cin + ci) * kh + ky) * kw + kx] : (T)0.f;
-}
-int launch_pack_conv_rw(int dtype, const void *w, void *wf, int cout, int cin, int kh, int kw, int coutp, int KW, hipStream_t s)
-{
-    const unsigned blocks = blocks_for((size_t)coutp * kh * KW, 256);
-    if (dtype == kBF16)
-        hipLaunchKernelGGL(pack_conv_rw_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(w), static_cast<bf16_t *>(wf), cout, cin, kh, kw, coutp, KW);
-    else
-        hipLaunchKernelGGL(pack_conv_rw_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(w), static_cast<float *>(wf), cout, cin, kh, kw, coutp, KW);
-    return launch_ok();
-}
-
-template <typename T>
-__global__ __launch_bounds__(256) void pack_conv_kernel(const T *__restrict__ w, T *__restrict__ wf, T *__restrict__ wd, int cout, int cin, int kh,
-                                                      int kw, int coutp, int cinp)
-{
-    const long nf = (long)coutp * kh * kw * cinp;
-    const long nd = wd ? (long)cinp * kh * kw * coutp : 0;
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i < nf) {  // wf[co][ky][kx][ci]
-        const int ci = (int)(i % cinp); long t = i / cinp;
-        const int kx = (int)(t % kw); t /= kw;
-        const int ky = (int)(t % kh);
-        const int co = (int)(t / kh);
-        wf[i] = (co < cout && ci < cin) ? w[(((long)co * cin + ci) * kh + ky) * kw + kx] : (T)0.f;
-    } else if (i < nf + nd) {  // wd[ci][ky'][kx'][co] = w[co][ci][kh-1-ky'][kw-1-kx']
-        const long j = i - nf;
-        const int co = (int)(j % coutp); long t = j / coutp;
-        const int kx = (int)(t % kw); t /= kw;
-        const int ky = (int)(t % kh);
-        const int ci = (int)(t / kh);
-        wd[j] = (co < cout && ci < cin) ? w[(((long)co * cin + ci) * kh + (kh - 1 - ky)) * kw + (kw - 1 - kx)] : (T)0.f;
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= jobs.total) return;
+    int q = 0;
+    while (q + 1 < jobs.n && i >= jobs.j[q + 1].start) ++q;
+    const PackJob &J = jobs.j[q];
+    const T *w = static_cast<const T *>(J.w);
+    unsigned li = i - J.start;
+    const int k = J.k;
+    if (J.rw) {  // wf[co][ky][j], j = kx*4 + ci over a padded window row of KW elements
+        const int jj = (int)(li % (unsigned)J.KW); unsigned t = li / (unsigned)J.KW;
+        const int ky = (int)(t % (unsigned)k), co = (int)(t / (unsigned)k);
+        const int kx = jj >> 2, ci = jj & 3;
+        static_cast<T *>(J.wf)[li] = (co < J.cout && ci < J.cin && kx < k) ? w[(((long)co * J.cin + ci) * k + ky) * k + kx] : (T)0.f;
+    } else if (li < J.nf) {  // wf[co][ky][kx][ci]
+        const int ci = (int)(li % (unsigned)J.cinp); unsigned t = li / (unsigned)J.cinp;
+        const int kx = (int)(t % (unsigned)k); t /= (unsigned)k;
+        const int ky = (int)(t % (unsigned)k), co = (int)(t / (unsigned)k);
+        static_cast<T *>(J.wf)[li] = (co < J.cout && ci < J.cin) ? w[(((long)co * J.cin + ci) * k + ky) * k + kx] : (T)0.f;
+    } else {  // wd[ci][ky'][kx'][co] = w[co][ci][k-1-ky'][k-1-kx']
+        li -= J.nf;
+        const int co = (int)(li % (unsigned)J.coutp); unsigned t = li / (unsigned)J.coutp;
+        const int kx = (int)(t % (unsigned)k); t /= (unsigned)k;
+        const int ky = (int)(t % (unsigned)k), ci = (int)(t / (unsigned)k);
+        static_cast<T *>(J.wd)[li] = (co < J.cout && ci < J.cin) ? w[(((long)co * J.cin + ci) * k + (k - 1 - ky)) * k + (k - 1 - kx)] : (T)0.f;
     }
 }
-int launch_pack_conv(int dtype, const void *w, void *wf, void *wd, int cout, int cin, int kh, int kw, int coutp, int cinp, hipStream_t s)
+int launch_pack_conv(int dtype, PackJobs &jobs, hipStream_t s)
 {
-    const size_t total = (size_t)coutp * kh * kw * cinp * (wd ? 2 : 1);
+    size_t total = 0;
+    for (int q = 0; q < jobs.n; ++q) {
+        PackJob &J = jobs.j[q];
+        const size_t nf = J.rw ? (size_t)J.coutp * J.k * J.KW : (size_t)J.coutp * J.k * J.k * J.cinp;
+        const size_t nd = (!J.rw && J.wd) ? nf : 0;
+        if (total + nf + nd > 0xffffffffull) return -1;
+        J.start = (unsigned)total; J.nf = (unsigned)nf;
+        total += nf + nd;
+    }
+    if (total == 0) return 0;
+    jobs.total = (unsigned)total;
     const unsigned blocks = blocks_for(total, 256);
-    if (dtype == kBF16)
-        hipLaunchKernelGGL(pack_conv_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(w), static_cast<bf16_t *>(wf),
-                           static_cast<bf16_t *>(wd), cout, cin, kh, kw, coutp, cinp);
-    else
-        hipLaunchKernelGGL(pack_conv_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(w), static_cast<float *>(wf),
-                           static_cast<float *>(wd), cout, cin, kh, kw, coutp, cinp);
+    if (dtype == kBF16) hipLaunchKernelGGL(pack_conv_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, jobs);
+    else hipLaunchKernelGGL(pack_conv_kernel<float>, dim3(blocks), dim3(256), 0, s, jobs);
     return launch_ok();
 }
 
@@ -602,13 +595,19 @@ __global__ __launch_bounds__(256) void colsum_stage1(const T *__restrict__ dy, l
         }
     }
 }
-__global__ __launch_bounds__(256) void colsum_stage2(const float *__restrict__ ws, int nblk, long ld, int N, float *__restrict__ db)
+// Stage 2 for several layers in one launch: a block owns 8 columns of one job.
+__global__ __launch_bounds__(256) void colsum_stage2(ColsumJobs jobs)
 {
-    // 8 columns per block, 32 lanes per column; a lane adds bands lane, lane+32, ... (four loads in flight),
-    // then the lanes are added in order
+    // 32 lanes per column; a lane adds bands lane, lane+32, ... (four loads in flight), then the lanes are added in order
     __shared__ float part[32][8];
+    int q = 0;
+    while (q + 1 < jobs.n && blockIdx.x >= jobs.j[q + 1].start_block) ++q;
+    const ColsumJob &J = jobs.j[q];
+    const float *ws = J.ws;
+    const long ld = J.ld;
+    const int nblk = J.nblk, N = J.N;
     const int tx = threadIdx.x & 7, ty = threadIdx.x >> 3;
-    const int n = blockIdx.x * 8 + tx;
+    const int n = (int)(blockIdx.x - J.start_block) * 8 + tx;
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
     if (n < N) {
         int b = ty;
@@ -623,7 +622,7 @@ __global__ __launch_bounds__(256) void colsum_stage2(const float *__restrict__ w
     if (ty == 0 && n < N) {
         float t = 0.f;
         for (int j = 0; j < 32; ++j) t += part[j][tx];
-        db[n] = t;
+        J.db[n] = t;
     }
 }
 static void colsum_geometry(int dtype, long ld, long M, int &chunks, int &cpb, int &rl, long &rows_per_block, int &nblk)
@@ -643,15 +642,27 @@ size_t colsum_ws_floats(int dtype, long M, long ld)
     colsum_geometry(dtype, ld, M, chunks, cpb, rl, rpb, nblk);
     return (size_t)nblk * (size_t)ld;
 }
-// dy is [M][ld] with ld a multiple of 8 and columns N..ld-1 zero or ignorable
-int launch_colsum(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, hipStream_t s)
+// dy is [M][ld] with ld a multiple of 8 and columns N..ld-1 zero or ignorable.  Stage 1 leaves the band sums in
+// ws (colsum_ws_floats) and appends the job that finishes them; launch_colsum_finish runs all appended jobs.
+int launch_colsum_partial(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, ColsumJobs &jobs, hipStream_t s)
 {
+    if (jobs.n >= 12) return -1;
     int chunks, cpb, rl, nblk; long rpb;
     colsum_geometry(dtype, ld, M, chunks, cpb, rl, rpb, nblk);
     const dim3 grid((chunks + cpb - 1) / cpb, nblk);
     if (dtype == kBF16) hipLaunchKernelGGL(colsum_stage1<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(dy), ld, M, chunks, cpb, rl, rpb, ws);
     else hipLaunchKernelGGL(colsum_stage1<float>, grid, dim3(256), 0, s, static_cast<const float *>(dy), ld, M, chunks, cpb, rl, rpb, ws);
-    hipLaunchKernelGGL(colsum_stage2, dim3((N + 7) / 8), dim3(256), 0, s, ws, nblk, ld, N, db);
+    ColsumJob &J = jobs.j[jobs.n++];
+    J.ws = ws; J.nblk = nblk; J.ld = ld; J.N = N; J.db = db; J.start_block = 0;
+    return launch_ok();
+}
+int launch_colsum_finish(ColsumJobs &jobs, hipStream_t s)
+{
+    if (jobs.n == 0) return 0;
+    unsigned blocks = 0;
+    for (int q = 0; q < jobs.n; ++q) { jobs.j[q].start_block = blocks; blocks += (unsigned)((jobs.j[q].N + 7) / 8); }
+    hipLaunchKernelGGL(colsum_stage2, dim3(blocks), dim3(256), 0, s, jobs);
+    jobs.n = 0;
     return launch_ok();
 }
 

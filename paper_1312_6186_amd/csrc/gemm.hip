@@ -723,8 +723,24 @@ template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_kerne
     if (g >= (long)M * n8) return;
     const int m = (int)(g / n8), n0 = (int)(g - (long)m * n8) * 8;
     float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < splits; ++s) {
-        const float4 *p = reinterpret_cast<const float4 *>(ws + ((long)s * M + m) * N + n0);
+    const long stride = (long)M * N;
+    const float *p0 = ws + (long)m * N + n0;
+    int s = 0;
+    for (; s + 4 <= splits; s += 4) {   // four partials in flight; added in split order all the same
+        float4 a[4], b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float4 *p = reinterpret_cast<const float4 *>(p0 + (s + u) * stride);
+            a[u] = p[0]; b[u] = p[1];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            v[0] += a[u].x; v[1] += a[u].y; v[2] += a[u].z; v[3] += a[u].w;
+            v[4] += b[u].x; v[5] += b[u].y; v[6] += b[u].z; v[7] += b[u].w;
+        }
+    }
+    for (; s < splits; ++s) {
+        const float4 *p = reinterpret_cast<const float4 *>(p0 + s * stride);
         const float4 a = p[0], b = p[1];
         v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
         v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;

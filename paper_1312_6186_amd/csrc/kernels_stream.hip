@@ -267,34 +267,54 @@ int launch_stage_input_rw(int dtype, const void *src, void *dst, int B, int C, i
     return launch_ok();
 }
 
-// All convolution layers of a net in one launch: element i belongs to the job whose range holds it.
+// All convolution layers of a net in one launch.  A thread produces 8 consecutive packed elements (the innermost
+// packed index is a multiple of 8 wide in every pack) and stores them as one or two 16-byte vectors; group g
+// belongs to the job whose range holds it.
 template <typename T> __global__ __launch_bounds__(256) void pack_conv_kernel(PackJobs jobs)
 {
-    const unsigned i = blockIdx.x * 256u + threadIdx.x;
-    if (i >= jobs.total) return;
+    const unsigned g = blockIdx.x * 256u + threadIdx.x;
+    if (g >= jobs.total) return;
     int q = 0;
-    while (q + 1 < jobs.n && i >= jobs.j[q + 1].start) ++q;
+    while (q + 1 < jobs.n && g >= jobs.j[q + 1].start) ++q;
     const PackJob &J = jobs.j[q];
     const T *w = static_cast<const T *>(J.w);
-    unsigned li = i - J.start;
+    unsigned li = (g - J.start) * 8u;     // first of this thread's 8 elements
     const int k = J.k;
+    const long kk = (long)k * k;
+    __attribute__((aligned(16))) T out[8];
+    T *dst;
     if (J.rw) {  // wf[co][ky][j], j = kx*4 + ci over a padded window row of KW elements
-        const int jj = (int)(li % (unsigned)J.KW); unsigned t = li / (unsigned)J.KW;
+        const int j0 = (int)(li % (unsigned)J.KW); unsigned t = li / (unsigned)J.KW;
         const int ky = (int)(t % (unsigned)k), co = (int)(t / (unsigned)k);
-        const int kx = jj >> 2, ci = jj & 3;
-        static_cast<T *>(J.wf)[li] = (co < J.cout && ci < J.cin && kx < k) ? w[(((long)co * J.cin + ci) * k + ky) * k + kx] : (T)0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int kx = (j0 + e) >> 2, ci = (j0 + e) & 3;
+            out[e] = (co < J.cout && ci < J.cin && kx < k) ? w[((long)co * J.cin + ci) * kk + ky * k + kx] : (T)0.f;
+        }
+        dst = static_cast<T *>(J.wf) + li;
     } else if (li < J.nf) {  // wf[co][ky][kx][ci]
-        const int ci = (int)(li % (unsigned)J.cinp); unsigned t = li / (unsigned)J.cinp;
+        const int ci0 = (int)(li % (unsigned)J.cinp); unsigned t = li / (unsigned)J.cinp;
         const int kx = (int)(t % (unsigned)k); t /= (unsigned)k;
         const int ky = (int)(t % (unsigned)k), co = (int)(t / (unsigned)k);
-        static_cast<T *>(J.wf)[li] = (co < J.cout && ci < J.cin) ? w[(((long)co * J.cin + ci) * k + ky) * k + kx] : (T)0.f;
+        const T *src = w + ((long)co * J.cin + ci0) * kk + ky * k + kx;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = (co < J.cout && ci0 + e < J.cin) ? src[e * kk] : (T)0.f;
+        dst = static_cast<T *>(J.wf) + li;
     } else {  // wd[ci][ky'][kx'][co] = w[co][ci][k-1-ky'][k-1-kx']
         li -= J.nf;
-        const int co = (int)(li % (unsigned)J.coutp); unsigned t = li / (unsigned)J.coutp;
+        const int co0 = (int)(li % (unsigned)J.coutp); unsigned t = li / (unsigned)J.coutp;
         const int kx = (int)(t % (unsigned)k); t /= (unsigned)k;
         const int ky = (int)(t % (unsigned)k), ci = (int)(t / (unsigned)k);
-        static_cast<T *>(J.wd)[li] = (co < J.cout && ci < J.cin) ? w[(((long)co * J.cin + ci) * k + (k - 1 - ky)) * k + (k - 1 - kx)] : (T)0.f;
+        const T *src = w + ((long)co0 * J.cin + ci) * kk + (k - 1 - ky) * k + (k - 1 - kx);
+        const long cstride = (long)J.cin * kk;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = (co0 + e < J.cout && ci < J.cin) ? src[e * cstride] : (T)0.f;
+        dst = static_cast<T *>(J.wd) + li;
     }
+    uint4 *d4 = reinterpret_cast<uint4 *>(dst);
+    const uint4 *o4 = reinterpret_cast<const uint4 *>(out);
+#pragma unroll
+    for (int v = 0; v < (int)(8 * sizeof(T) / 16); ++v) d4[v] = o4[v];
 }
 int launch_pack_conv(int dtype, PackJobs &jobs, hipStream_t s)
 {
@@ -303,9 +323,9 @@ int launch_pack_conv(int dtype, PackJobs &jobs, hipStream_t s)
         PackJob &J = jobs.j[q];
         const size_t nf = J.rw ? (size_t)J.coutp * J.k * J.KW : (size_t)J.coutp * J.k * J.k * J.cinp;
         const size_t nd = (!J.rw && J.wd) ? nf : 0;
-        if (total + nf + nd > 0xffffffffull) return -1;
+        if (nf + nd > 0xffffffffull || (nf & 7)) return -1;   // cinp, coutp and KW are multiples of 8
         J.start = (unsigned)total; J.nf = (unsigned)nf;
-        total += nf + nd;
+        total += (nf + nd) / 8;                                 // in groups of 8 elements
     }
     if (total == 0) return 0;
     jobs.total = (unsigned)total;

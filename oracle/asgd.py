@@ -4,6 +4,10 @@
 parameter versions, update a is computed by its worker on version
 ``read_version[a]`` and applied to version a, giving version a+1.  Each push is
 one raw minibatch-mean gradient; the server owns the momentum buffer.
+
+``replay_nsync`` is the regime the paper runs (Section 2.3, n_fetch = n_push =
+n_sync): a replica updates its own parameters on its GPU for n_sync steps
+between two exchanges with the server.
 """
 import numpy as np
 
@@ -58,3 +62,51 @@ def replay(net, params0, worker, read_version, batch_fn, lr, mu, wd, dropout_see
         losses.append(loss)
         log.append((a, int(worker[a]), r))
     return w, v, losses, np.array(log, dtype=np.int32)
+
+
+def replay_nsync(net, params0, worker, read_version, batch_fn, n_sync, lr, mu, wd, dropout_seed=0,
+                 worker_dtype="f64", act_dtype="f64"):
+    """A-SGD with n_fetch = n_push = n_sync (Section 2.3).
+
+    Reading of the paper's one sentence on it: cycle a belongs to replica
+    worker[a].  The replica fetches version read_version[a] of the server's
+    parameters into its own fp32 parameters, then runs n_sync ordinary
+    momentum-SGD steps on them (same rule and hyper-parameters as the server; its
+    own momentum buffer, zero at the start and kept across fetches), computing
+    each gradient on its parameters as it holds them for compute (worker_dtype).
+    It pushes the SUM of those n_sync minibatch gradients, which the server
+    applies as one gradient, giving version a+1.  Minibatch i of cycle a is
+    batch_fn(a, i); its dropout step is a*n_sync + i.  n_sync = 1 is ``replay``.
+
+    Returns final server params and momentum, the losses [T][n_sync], the log of
+    (update, worker, version read) and the replicas' (params, momentum)."""
+    T = len(worker)
+    W = int(max(worker)) + 1 if T else 0
+    w = np.array(params0, dtype=np.float64)
+    v = np.zeros_like(w)
+    versions = {0: w.copy()}
+    local_w = [None] * W
+    local_v = [np.zeros_like(w) for _ in range(W)]
+    losses, log = [], []
+    for a in range(T):
+        r, k = int(read_version[a]), int(worker[a])
+        assert 0 <= r <= a
+        # fetch: fp32 values of the server's parameters
+        local_w[k] = versions[r].astype(np.float32).astype(np.float64) if worker_dtype != "f64" else versions[r].copy()
+        pushed = np.zeros_like(w)
+        row = []
+        for i in range(n_sync):
+            images, labels = batch_fn(a, i)
+            loss, g, _ = net.fwd_bwd(worker_copy(local_w[k], worker_dtype), images, labels, dropout_seed,
+                                     a * n_sync + i, k, act_dtype=act_dtype)
+            pushed += g
+            ops.apply_update(local_w[k], local_v[k], g, lr, mu, wd)
+            row.append(loss)
+        ops.apply_update(w, v, pushed, lr, mu, wd)
+        versions[a + 1] = w.copy()
+        oldest_needed = min([int(read_version[b]) for b in range(a + 1, T)] + [a + 1])
+        for key in [q for q in versions if q < oldest_needed]:
+            del versions[key]
+        losses.append(row)
+        log.append((a, k, r))
+    return w, v, losses, np.array(log, dtype=np.int32), list(zip(local_w, local_v))

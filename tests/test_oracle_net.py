@@ -148,6 +148,79 @@ def test_stale_reads_change_the_trajectory_and_replay_is_reproducible():
         assert w.tobytes() == w2.tobytes()
 
 
+def test_nsync_one_is_the_plain_replay():
+    net, params, _, _ = _setup(NET_B, 4, 11)
+    T = 6
+    bf = _batch_fn(NET_B, 4, 100)
+    worker, rv = ops.schedule(T, 4005, 3, 2)
+    wa, va, la, loga = asgd.replay(net, params, worker, rv, bf, 0.05, 0.9, 1e-3, dropout_seed=5)
+    wb, vb, lb, logb, _ = asgd.replay_nsync(net, params, worker, rv, lambda a, i: bf(a), 1, 0.05, 0.9, 1e-3, dropout_seed=5)
+    assert wa.tobytes() == wb.tobytes() and va.tobytes() == vb.tobytes() and la == [r[0] for r in lb] and (loga == logb).all()
+
+
+def test_nsync_single_cycle_is_local_sgd_plus_one_push_of_the_summed_gradient():
+    net, params, _, _ = _setup(NET_B, 4, 11)
+    k, lr, mu, wd = 3, 0.05, 0.9, 1e-3
+    bf = _batch_fn(NET_B, 4, 200)
+    w, v, losses, log, local = asgd.replay_nsync(net, params, np.zeros(1, np.int32), np.zeros(1, np.int32), lambda a, i: bf(i), k,
+                                                 lr, mu, wd)
+    # the replica's own trajectory over the cycle is plain momentum SGD from the fetched parameters
+    w_loc, v_loc, l_loc = asgd.sgd_loop(net, params, bf, k, lr, mu, wd)
+    assert local[0][0].tobytes() == w_loc.tobytes() and local[0][1].tobytes() == v_loc.tobytes() and losses[0] == l_loc
+    # the server saw one gradient: the sum of the k gradients along that trajectory
+    ws, vs, total = params.copy(), np.zeros_like(params), np.zeros_like(params)
+    for i in range(k):
+        _, g, _ = net.fwd_bwd(ws, *bf(i), 0, i, 0)
+        total += g
+        ops.apply_update(ws, vs, g, lr, mu, wd)
+    t = total + wd * params
+    assert np.allclose(v, -lr * t, rtol=1e-13, atol=0) and np.allclose(w, params - lr * t, rtol=1e-13, atol=1e-300)
+
+
+def test_nsync_protocol_against_a_closed_model_simulated_independently():
+    """With all-zero images the logits are the biases, so the whole protocol runs on a C-vector:
+    gradient = softmax(b) - onehot(label) for the biases and exactly zero for the weights (which start at zero).
+    The recurrences below are written out directly (per replica: b, m; server: b, m, history) and know nothing
+    of the oracle's code."""
+    C, W, n_sync, T, lr, mu, wd = 5, 2, 3, 7, 0.3, 0.8, 0.01
+    layers, in_shape = [("fc", C), ("softmax_ce",)], (1, 2, 4)
+    net = oracle.OracleNet(layers, in_shape)
+    rng = np.random.default_rng(3)
+    params0 = np.zeros(net.param_count)
+    (w_off, w_shape, b_off, b_len), = [net.param_slices[k] for k in net.param_slices]
+    params0[b_off:b_off + C] = rng.standard_normal(C)
+    labels = rng.integers(0, C, size=(T, n_sync))
+    worker = np.array([a % W for a in range(T)], np.int32)
+    rv = np.array([0, 0, 2, 2, 4, 4, 6], np.int32)           # stale by 0 or 1, causally possible for two replicas
+    zeros = np.zeros((1,) + in_shape)
+    w, v, losses, log, local = asgd.replay_nsync(net, params0, worker, rv, lambda a, i: (zeros, labels[a, i:i + 1]), n_sync,
+                                                 lr, mu, wd)
+
+    def grad(b, y):
+        e = np.exp(b - b.max()); p = e / e.sum(); p[y] -= 1.0
+        return p, float(np.log(e.sum()) + b.max() - b[y])
+    hist = [params0[b_off:b_off + C].copy()]
+    sb, sm = hist[0].copy(), np.zeros(C)
+    lb, lm = [None] * W, [np.zeros(C) for _ in range(W)]
+    want_losses = []
+    for a in range(T):
+        k = a % W
+        lb[k] = hist[rv[a]].copy()
+        acc, row = np.zeros(C), []
+        for i in range(n_sync):
+            g, loss = grad(lb[k], labels[a, i])
+            acc += g; row.append(loss)
+            lm[k] = mu * lm[k] - lr * (g + wd * lb[k]); lb[k] = lb[k] + lm[k]
+        sm = mu * sm - lr * (acc + wd * sb); sb = sb + sm
+        hist.append(sb.copy()); want_losses.append(row)
+    assert np.allclose(w[b_off:b_off + C], sb, rtol=1e-12) and np.allclose(v[b_off:b_off + C], sm, rtol=1e-12)
+    assert np.all(w[w_off:w_off + C * 8] == 0)
+    assert np.allclose(losses, want_losses, rtol=1e-12)
+    for k in range(W):
+        assert np.allclose(local[k][0][b_off:b_off + C], lb[k], rtol=1e-12) and np.allclose(local[k][1][b_off:b_off + C], lm[k], rtol=1e-12)
+    np.testing.assert_array_equal(log, np.stack([np.arange(T), worker, rv], 1))
+
+
 def test_worker_copy_rounding():
     p = np.array([1.0 + 2.0**-8, 1.0 + 2.0**-30, -3.5])
     np.testing.assert_array_equal(asgd.worker_copy(p, "bf16"), [1.0, 1.0, -3.5])

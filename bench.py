@@ -29,6 +29,9 @@ WORKLOADS = {
     # A-SGD on one GPU: 4 workers as concurrent streams, batch 32 each, snapshots up to 3 updates stale;
     # a step is one pushed gradient (snapshot + fwd_bwd + server update)
     "asgd_4x32_bf16": (32, "bf16"),
+    # the same replicas in the paper's n_sync regime: 4 local momentum-SGD steps between exchanges, the sum of the
+    # 4 gradients pushed; a step is one cycle (4 minibatches of 32)
+    "asgd_nsync4_4x32_bf16": (32, "bf16"),
 }
 PEAK = {"hbm": 8000.0, "mfma_bf16": 2500.0, "mfma_f32": 157.3}   # GB/s, TFLOP/s (MI355X, dense)
 MFMA_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad", "fc_fwd", "fc_dgrad", "fc_wgrad")
@@ -52,8 +55,9 @@ def cpu_baseline(layers, in_shape, classes, sample_batch, hp):
             "sample": "one fwd+bwd+update of the same AlexNet-style net on %d images (%.1f s)" % (sample_batch, dt)}
 
 
-def bench_asgd(args, batch):
-    """Replay of a seeded staleness schedule: `steps` pushed gradients, 4 worker streams + a server stream."""
+def bench_asgd(args, batch, n_sync=0):
+    """Replay of a seeded staleness schedule: `steps` pushed gradients, 4 worker streams + a server stream.
+    n_sync > 0: the n_sync regime (each push is the sum of n_sync local steps' gradients)."""
     import numpy as np
     import torch
     from paper_1312_6186_amd import binding as B
@@ -68,7 +72,10 @@ def bench_asgd(args, batch):
     mom = torch.zeros_like(params)
     copies = [torch.empty(P, dtype=torch.bfloat16, device=dev) for _ in range(W)]
     grads = [torch.empty(P, dtype=torch.float32, device=dev) for _ in range(W)]
-    nb = max(args.steps, args.warmup, 1)
+    per = max(n_sync, 1)                      # minibatches per pushed gradient
+    nb = max(args.steps, args.warmup, 1) * per
+    f32 = lambda: [torch.zeros(P, dtype=torch.float32, device=dev) for _ in range(W)]
+    wp, wm, wa = (f32(), f32(), f32()) if n_sync else (None, None, None)
     rng = np.random.default_rng(1005)
     images = torch.from_numpy(rng.standard_normal((nb, batch) + tuple(in_shape), dtype=np.float32)).to(dev).to(torch.bfloat16)
     labels = torch.from_numpy(rng.integers(0, classes, size=(nb, batch), dtype=np.int32)).to(dev)
@@ -77,7 +84,11 @@ def bench_asgd(args, batch):
 
     def run(T):
         worker, rv = B.asgd_schedule_generate(T, 4005, W, 3)
-        B.asgd_replay_run(nets, params, mom, copies, grads, images, labels, worker, rv, lr, mu, wd, 3003, losses, log)
+        if n_sync:
+            B.asgd_replay_nsync_run(nets, n_sync, params, mom, wp, wm, wa, copies, grads, images, labels, worker, rv, lr, mu, wd, 3003,
+                                    losses, log)
+        else:
+            B.asgd_replay_run(nets, params, mom, copies, grads, images, labels, worker, rv, lr, mu, wd, 3003, losses, log)
         torch.cuda.synchronize()
         return worker, rv
 
@@ -91,12 +102,14 @@ def bench_asgd(args, batch):
         B.asgd_net_destroy(n)
     print(json.dumps({
         "metric": "images/sec fwd+bwd+update, AlexNet-style bs128; % MFMA peak (conv/FC)",
-        "value": batch * args.steps / elapsed, "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": batch * per * args.steps / elapsed, "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "net": "AlexNet-style single column (62378344 parameters)", "workers": W,
-                   "batch_per_worker": batch, "max_staleness": 3, "schedule_seed": 4005,
-                   "step": "one pushed gradient: snapshot + fwd_bwd on a worker stream, update on the server stream"},
+                   "batch_per_worker": batch, "max_staleness": 3, "schedule_seed": 4005, "n_sync": per,
+                   "step": ("one cycle: fetch, %d local steps (fwd_bwd, accumulate, local update) on a worker stream, "
+                            "update with the summed gradient on the server stream" % per) if n_sync else
+                           "one pushed gradient: snapshot + fwd_bwd on a worker stream, update on the server stream"},
         "schedule_log_matches": ok, "roofline": None, "cpu_baseline": None}))
 
 
@@ -123,6 +136,8 @@ def main():
     from paper_1312_6186_amd import workloads as wl
 
     batch, dtname = WORKLOADS[args.workload]
+    if args.workload.startswith("asgd_nsync4"):
+        return bench_asgd(args, batch, n_sync=4)
     if args.workload.startswith("asgd"):
         return bench_asgd(args, batch)
     dtype = B.BF16 if dtname == "bf16" else B.F32

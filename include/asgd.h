@@ -262,6 +262,38 @@ int asgd_replay_run(asgd_net_t *const *nets, int n_workers, float *params, float
                     float lr, float mu, float wd, uint64_t dropout_seed, float *losses, int32_t *log,
                     void *stream);
 
+/* The regime the paper runs, n_fetch = n_push = n_sync (Section 2.3: the
+ * parameters are updated on the GPU for n_sync steps between two exchanges with
+ * the server).  The paper gives one sentence; the reading implemented here:
+ * cycle a belongs to replica worker[a].  The replica fetches the server's
+ * parameters when exactly read_version[a] updates have been applied, into its
+ * own fp32 parameters (and its compute copy), runs n_sync momentum-SGD steps on
+ * them with its own momentum buffer (same rule and hyper-parameters as the
+ * server; the momentum persists across fetches), and pushes the SUM of the
+ * n_sync minibatch gradients, which the server applies as one gradient
+ * (update a).  Local step i of cycle a uses minibatch a*n_sync + i, which is
+ * also its dropout step.  n_sync = 1 gives asgd_replay_run's results.
+ *   worker_params, worker_momentum, worker_accum : host arrays of n_workers
+ *             device fp32 [param_count] buffers: each replica's parameters
+ *             (overwritten by every fetch), momentum (read and updated; zero it
+ *             before the first call) and gradient accumulator (scratch).
+ *   images, labels : device, T*n_sync minibatches back to back.
+ *   losses  : device fp32 [T*n_sync].
+ *   everything else as for asgd_replay_run.
+ * Errors: as asgd_replay_run; ASGD_EINVAL for n_sync < 1. */
+int asgd_replay_nsync_run(asgd_net_t *const *nets, int n_workers, int n_sync, float *params,
+                          float *momentum, float *const *worker_params,
+                          float *const *worker_momentum, float *const *worker_accum,
+                          void *const *worker_copy, float *const *worker_grads, const void *images,
+                          const int32_t *labels, const int32_t *worker,
+                          const int32_t *read_version, int T, float lr, float mu, float wd,
+                          uint64_t dropout_seed, float *losses, int32_t *log, void *stream);
+
+/* The replica's gradient accumulator of that regime: accum = grads (first != 0)
+ * or accum + grads, device fp32 [n].
+ * Errors: ASGD_EINVAL (null with n > 0), ASGD_EALIGN, ASGD_EHIP. */
+int asgd_accumulate(float *accum, const float *grads, size_t n, int first, void *stream);
+
 /* Text of the last error on the calling thread ("" if none). */
 const char *asgd_last_error(void);
 

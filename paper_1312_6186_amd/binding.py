@@ -19,7 +19,7 @@ OK, EINVAL, ESHAPE, ENOMEM, EHIP, EALIGN = 0, -1, -2, -3, -4, -5
 EXPORTS = ["asgd_net_create", "asgd_net_prepare", "asgd_net_destroy", "asgd_param_count", "asgd_param_layout",
            "asgd_layer_shape", "asgd_workspace_bytes", "asgd_fwd_bwd", "asgd_apply_update", "asgd_snapshot",
            "asgd_apply_update_snapshot", "asgd_train_step",
-           "asgd_debug_get", "asgd_profile_begin", "asgd_profile_end", "asgd_schedule_generate", "asgd_replay_run",
+           "asgd_debug_get", "asgd_profile_begin", "asgd_profile_end", "asgd_schedule_generate", "asgd_replay_run", "asgd_replay_nsync_run", "asgd_accumulate",
            "asgd_last_error"]
 KERNEL_CLASSES = ["conv_fwd", "conv_dgrad", "conv_wgrad", "fc_fwd", "fc_dgrad", "fc_wgrad", "pool_fwd", "pool_bwd",
                   "bias_grad", "softmax_ce", "layout", "update"]
@@ -82,6 +82,10 @@ def lib():
         L.asgd_replay_run.argtypes = [ctypes.POINTER(vp), ctypes.c_int, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp,
                                       i32p, i32p, ctypes.c_int, ctypes.c_float, ctypes.c_float, ctypes.c_float,
                                       ctypes.c_uint64, vp, vp, vp]
+        L.asgd_replay_nsync_run.argtypes = [ctypes.POINTER(vp), ctypes.c_int, ctypes.c_int, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                            ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, i32p, i32p, ctypes.c_int,
+                                            ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_uint64, vp, vp, vp]
+        L.asgd_accumulate.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
         L.asgd_last_error.restype = ctypes.c_char_p
         _lib = L
     return _lib
@@ -230,3 +234,23 @@ def asgd_replay_run(nets, params, momentum, worker_copy, worker_grads, images, l
     _check(lib().asgd_replay_run(net_arr, W, _ptr(params), _ptr(momentum), copy_arr, grad_arr, _ptr(images), _ptr(labels),
                                  worker.ctypes.data_as(i32p), read_version.ctypes.data_as(i32p), len(worker), lr, mu, wd,
                                  dropout_seed, _ptr(losses), _ptr(log), _stream(stream)))
+
+
+def asgd_replay_nsync_run(nets, n_sync, params, momentum, worker_params, worker_momentum, worker_accum, worker_copy, worker_grads, images,
+                          labels, worker, read_version, lr, mu, wd, dropout_seed, losses, log, stream=None):
+    import numpy as np
+    W = len(nets)
+    vp = ctypes.c_void_p
+    arr = lambda ts: (vp * W)(*[t.data_ptr() for t in ts])
+    net_arr = (vp * W)(*[n.value for n in nets])
+    worker = np.ascontiguousarray(worker, dtype=np.int32)
+    read_version = np.ascontiguousarray(read_version, dtype=np.int32)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    _check(lib().asgd_replay_nsync_run(net_arr, W, n_sync, _ptr(params), _ptr(momentum), arr(worker_params), arr(worker_momentum),
+                                       arr(worker_accum), arr(worker_copy), arr(worker_grads), _ptr(images), _ptr(labels),
+                                       worker.ctypes.data_as(i32p), read_version.ctypes.data_as(i32p), len(worker), lr, mu, wd,
+                                       dropout_seed, _ptr(losses), _ptr(log), _stream(stream)))
+
+
+def asgd_accumulate(accum, grads, first, stream=None, n=None):
+    _check(lib().asgd_accumulate(_ptr(accum), _ptr(grads), accum.numel() if n is None else n, 1 if first else 0, _stream(stream)))

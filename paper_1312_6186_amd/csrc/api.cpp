@@ -837,17 +837,26 @@ int asgd_schedule_generate(int32_t *worker, int32_t *read_version, int T, uint64
     return ASGD_OK;
 }
 
-int asgd_replay_run(asgd_net_t *const *nets, int n_workers, float *params, float *momentum, void *const *worker_copy,
-                    float *const *worker_grads, const void *images, const int32_t *labels, const int32_t *worker,
-                    const int32_t *read_version, int T, float lr, float mu, float wd, uint64_t dropout_seed, float *losses, int32_t *log,
-                    void *stream)
+// Replica-side state of the n_sync regime: each replica's own fp32 parameters, momentum and gradient accumulator.
+struct LocalState {
+    int n_sync;
+    float *const *params, *const *momentum, *const *accum;
+};
+
+static int replay_impl(asgd_net_t *const *nets, int n_workers, float *params, float *momentum, void *const *worker_copy,
+                       float *const *worker_grads, const void *images, const int32_t *labels, const int32_t *worker,
+                       const int32_t *read_version, int T, float lr, float mu, float wd, uint64_t dropout_seed, float *losses, int32_t *log,
+                       void *stream, const LocalState *loc)
 {
     if (!nets || !params || !momentum || !worker_copy || !worker_grads || !images || !labels || !worker || !read_version || !losses || !log)
         return fail(ASGD_EINVAL, "asgd_replay_run: null argument");
+    if (loc && (loc->n_sync < 1 || !loc->params || !loc->momentum || !loc->accum)) return fail(ASGD_EINVAL, "asgd_replay_nsync_run: bad n_sync or null argument");
+    const int n_sync = loc ? loc->n_sync : 1;
     if (n_workers <= 0 || n_workers > 64 || T < 0) return fail(ASGD_EINVAL, "asgd_replay_run: bad worker count or length");
     if (T == 0) return ASGD_OK;
     for (int w = 0; w < n_workers; ++w) {
         if (!nets[w] || !worker_copy[w] || !worker_grads[w]) return fail(ASGD_EINVAL, "asgd_replay_run: null entry for worker %d", w);
+        if (loc && (!loc->params[w] || !loc->momentum[w] || !loc->accum[w])) return fail(ASGD_EINVAL, "asgd_replay_nsync_run: null entry for worker %d", w);
         if (nets[w]->param_count != nets[0]->param_count || nets[w]->batch != nets[0]->batch || nets[w]->dtype != nets[0]->dtype)
             return fail(ASGD_EINVAL, "asgd_replay_run: worker %d has a different network", w);
         for (int u = 0; u < w; ++u)
@@ -913,16 +922,27 @@ int asgd_replay_run(asgd_net_t *const *nets, int n_workers, float *params, float
             RP(hipStreamWaitEvent(ws[w], v > 0 ? ev_upd[v - 1] : ev_reset, 0));
             if (launch_snapshot(params, worker_copy[w], P, n0->dtype, counter, log + 3 * (size_t)a, a, w, ws[w]) != 0 && rc == ASGD_OK)
                 rc = hip_fail(hipGetLastError(), "snapshot kernel");
+            if (loc && launch_snapshot(params, loc->params[w], P, kF32, nullptr, nullptr, 0, 0, ws[w]) != 0 && rc == ASGD_OK)
+                rc = hip_fail(hipGetLastError(), "snapshot kernel");   // the replica's own fp32 parameters
             RP(hipEventRecord(ev_snap[a], ws[w]));
-            if (rc == ASGD_OK)
-                rc = asgd_fwd_bwd(nets[w], worker_copy[w], static_cast<const char *>(images) + (size_t)a * img_bytes,
-                                  labels + (size_t)a * n0->batch, dropout_seed, (uint64_t)a, (uint32_t)w, losses + a, worker_grads[w], ws[w]);
+            for (int i = 0; i < n_sync && rc == ASGD_OK; ++i) {
+                const size_t b = (size_t)a * n_sync + i;   // minibatch and dropout step of local step i of cycle a
+                rc = asgd_fwd_bwd(nets[w], worker_copy[w], static_cast<const char *>(images) + b * img_bytes, labels + b * n0->batch,
+                                  dropout_seed, (uint64_t)b, (uint32_t)w, losses + b, worker_grads[w], ws[w]);
+                if (loc && rc == ASGD_OK) {
+                    // the push is the sum of the cycle's gradients; the replica keeps training on its own parameters
+                    if (launch_accumulate(loc->accum[w], worker_grads[w], P, i == 0, ws[w]) != 0) rc = hip_fail(hipGetLastError(), "accumulate kernel");
+                    else if (launch_update_snapshot(loc->params[w], loc->momentum[w], worker_grads[w], P, lr, mu, wd, worker_copy[w], n0->dtype,
+                                                    ws[w]) != 0)
+                        rc = hip_fail(hipGetLastError(), "update kernel");
+                }
+            }
             RP(hipEventRecord(ev_grad[a], ws[w]));
         }
         for (int a = v; a < T && rc == ASGD_OK; ++a)
             if (read_version[a] == v) RP(hipStreamWaitEvent(server, ev_snap[a], 0));
         RP(hipStreamWaitEvent(server, ev_grad[v], 0));
-        if (rc == ASGD_OK && launch_update(params, momentum, worker_grads[worker[v]], P, lr, mu, wd, counter, server) != 0)
+        if (rc == ASGD_OK && launch_update(params, momentum, loc ? loc->accum[worker[v]] : worker_grads[worker[v]], P, lr, mu, wd, counter, server) != 0)
             rc = hip_fail(hipGetLastError(), "update kernel");
         RP(hipEventRecord(ev_upd[v], server));
     }
@@ -937,6 +957,34 @@ int asgd_replay_run(asgd_net_t *const *nets, int n_workers, float *params, float
     if (server) (void)hipStreamDestroy(server);
 #undef RP
     return rc;
+}
+
+int asgd_replay_run(asgd_net_t *const *nets, int n_workers, float *params, float *momentum, void *const *worker_copy,
+                    float *const *worker_grads, const void *images, const int32_t *labels, const int32_t *worker,
+                    const int32_t *read_version, int T, float lr, float mu, float wd, uint64_t dropout_seed, float *losses, int32_t *log,
+                    void *stream)
+{
+    return replay_impl(nets, n_workers, params, momentum, worker_copy, worker_grads, images, labels, worker, read_version, T, lr, mu, wd,
+                       dropout_seed, losses, log, stream, nullptr);
+}
+
+int asgd_replay_nsync_run(asgd_net_t *const *nets, int n_workers, int n_sync, float *params, float *momentum, float *const *worker_params,
+                          float *const *worker_momentum, float *const *worker_accum, void *const *worker_copy, float *const *worker_grads,
+                          const void *images, const int32_t *labels, const int32_t *worker, const int32_t *read_version, int T, float lr,
+                          float mu, float wd, uint64_t dropout_seed, float *losses, int32_t *log, void *stream)
+{
+    const LocalState loc{n_sync, worker_params, worker_momentum, worker_accum};
+    return replay_impl(nets, n_workers, params, momentum, worker_copy, worker_grads, images, labels, worker, read_version, T, lr, mu, wd,
+                       dropout_seed, losses, log, stream, &loc);
+}
+
+int asgd_accumulate(float *accum, const float *grads, size_t n, int first, void *stream)
+{
+    if (n == 0) return ASGD_OK;
+    if (!accum || !grads) return fail(ASGD_EINVAL, "asgd_accumulate: null argument");
+    if (((uintptr_t)accum | (uintptr_t)grads) & 3) return fail(ASGD_EALIGN, "asgd_accumulate: buffers must be 4-byte aligned");
+    if (launch_accumulate(accum, grads, n, first != 0, static_cast<hipStream_t>(stream)) != 0) return hip_fail(hipGetLastError(), "accumulate kernel");
+    return ASGD_OK;
 }
 
 }  // extern "C"

@@ -91,6 +91,8 @@ int launch_update(float *w, float *v, const float *g, size_t n, float lr, float 
 // the update, and the updated parameters written to `copy` (fp32 or bf16) in the same pass
 int launch_update_snapshot(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd, void *copy,
                            int dst_dtype, hipStream_t s);
+// acc = g (first) or acc + g
+int launch_accumulate(float *acc, const float *g, size_t n, bool first, hipStream_t s);
 int launch_snapshot(const float *src, void *dst, size_t n, int dst_dtype, const int *version_counter,
                     int32_t *log_slot, int log_update, int log_worker, hipStream_t s);
 // images [B][C][H][W] (compute type) -> channel-last [B][H][W][Cp], zero padding channels

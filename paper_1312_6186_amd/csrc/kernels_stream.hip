@@ -143,6 +143,29 @@ int launch_update_snapshot(float *w, float *v, const float *g, size_t n, float l
     return dst_dtype == kBF16 ? launch_update_t<2>(w, v, g, n, lr, mu, wd, nullptr, copy, s) : launch_update_t<1>(w, v, g, n, lr, mu, wd, nullptr, copy, s);
 }
 
+// ---------------------------------------------------------------- gradient accumulator (n_push > 1)
+// acc = g (first) or acc + g; 16-byte vectors when both are aligned, the same arithmetic either way.
+__global__ __launch_bounds__(256) void accumulate_kernel(float *__restrict__ acc, const float *__restrict__ g, size_t n, int first, int vec)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t t0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t n4 = vec ? n / 4 : 0;
+    for (size_t i = t0; i < n4; i += stride) {
+        f32x4 a = __builtin_nontemporal_load(&reinterpret_cast<const f32x4 *>(g)[i]);
+        if (!first) a += reinterpret_cast<f32x4 *>(acc)[i];
+        reinterpret_cast<f32x4 *>(acc)[i] = a;
+    }
+    for (size_t i = n4 * 4 + t0; i < n; i += stride) acc[i] = first ? g[i] : acc[i] + g[i];
+}
+int launch_accumulate(float *acc, const float *g, size_t n, bool first, hipStream_t s)
+{
+    const int vec = ((((uintptr_t)acc | (uintptr_t)g) & 15) == 0) ? 1 : 0;
+    unsigned blocks = blocks_for(vec ? (n + 3) / 4 : n, 256);
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(accumulate_kernel, dim3(blocks), dim3(256), 0, s, acc, g, n, first ? 1 : 0, vec);
+    return launch_ok();
+}
+
 // ---------------------------------------------------------------- snapshot
 __device__ inline uint32_t f32_to_bf16_bits(uint32_t u)  // round to nearest even; NaN -> quiet NaN
 {

@@ -353,6 +353,76 @@ def test_asgd_replay_matches_oracle_and_logs_the_schedule(dtype):
             B.asgd_net_destroy(n)
 
 
+@pytest.mark.parametrize("n,offset", [(1, 0), (4099, 0), (100003, 1), (1 << 20, 4)])
+def test_accumulate_matches_numpy(n, offset):
+    rng = np.random.default_rng(n)
+    g = [rng.standard_normal(n + offset).astype(np.float32) for _ in range(3)]
+    acc = torch.full((n + offset,), 7.0, dtype=torch.float32, device=DEV)
+    for i, gi in enumerate(g):
+        B.asgd_accumulate(acc[offset:], torch.from_numpy(gi).to(DEV)[offset:], first=(i == 0))
+    torch.cuda.synchronize()
+    want = (g[0][offset:] + g[1][offset:]) + g[2][offset:]      # fp32, in push order
+    np.testing.assert_array_equal(acc.cpu().numpy()[offset:], want)
+    assert (acc.cpu().numpy()[:offset] == 7.0).all()
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("n_sync", [1, 3])
+def test_nsync_replay_matches_oracle_and_logs_the_schedule(n_sync, dtype):
+    cfg = wl.TINY
+    layers, in_shape, batch = cfg["layers"], cfg["in_shape"], 8
+    W, T, lr, mu, wd = 3, 9, 0.0005, 0.9, 5e-4
+    worker, rv = B.asgd_schedule_generate(T, 4005, W, 2)
+    params0 = wl.make_params(layers, in_shape, 2001)
+    batches = [wl.make_batch(in_shape, batch, 10, 1105 + b) for b in range(T * n_sync)]
+    if dtype == B.BF16:
+        batches = [(wl.round_to_bf16(i), l) for i, l in batches]
+    onet = oracle.OracleNet(layers, in_shape)
+    wdt = "bf16" if dtype == B.BF16 else "f32"
+    w_ref, v_ref, losses_ref, log_ref, local_ref = oasgd.replay_nsync(
+        onet, params0, worker, rv, lambda a, i: batches[a * n_sync + i], n_sync, np.float32(lr), np.float32(mu), np.float32(wd),
+        dropout_seed=9, worker_dtype=wdt, act_dtype=ACT[dtype])
+    tdt = torch.bfloat16 if dtype == B.BF16 else torch.float32
+    nets = [B.asgd_net_create(layers, batch, in_shape, dtype) for _ in range(W)]
+    P = B.asgd_param_count(nets[0])
+    try:
+        results = []
+        for rep in range(2):
+            params = torch.from_numpy(params0).to(DEV); mom = torch.zeros_like(params)
+            f32 = lambda: [torch.zeros(P, dtype=torch.float32, device=DEV) for _ in range(W)]
+            wp, wm, wa, grads = f32(), f32(), f32(), f32()
+            copies = [torch.empty(P, dtype=tdt, device=DEV) for _ in range(W)]
+            images = torch.from_numpy(np.stack([b[0] for b in batches])).to(DEV).to(tdt).contiguous()
+            labels = torch.from_numpy(np.stack([b[1] for b in batches]).astype(np.int32)).to(DEV)
+            losses = torch.zeros(T * n_sync, dtype=torch.float32, device=DEV)
+            log = torch.full((T, 3), -7, dtype=torch.int32, device=DEV)
+            B.asgd_replay_nsync_run(nets, n_sync, params, mom, wp, wm, wa, copies, grads, images, labels, worker, rv, lr, mu, wd, 9,
+                                    losses, log)
+            torch.cuda.synchronize()
+            results.append([params.cpu().numpy(), mom.cpu().numpy(), losses.cpu().numpy(), log.cpu().numpy()]
+                           + [t.cpu().numpy() for t in wp + wm])
+        p, m, ls, lg = results[0][:4]
+        np.testing.assert_array_equal(lg, log_ref)
+        tol = TOL[dtype]
+        assert rel_l2(ls, np.array(losses_ref).ravel()) < tol and rel_l2(p, w_ref) < tol and rel_l2(m, v_ref) < tol
+        for k in range(W):                                       # the replicas' own parameters and momentum
+            assert rel_l2(results[0][4 + k], local_ref[k][0]) < tol and rel_l2(results[0][4 + W + k], local_ref[k][1]) < tol
+        for a, b in zip(results[0], results[1]):                  # reproducible bit for bit
+            assert a.tobytes() == b.tobytes()
+        if n_sync == 1:                                           # the plain replay, bit for bit
+            params = torch.from_numpy(params0).to(DEV); mom = torch.zeros_like(params)
+            copies = [torch.empty(P, dtype=tdt, device=DEV) for _ in range(W)]
+            grads = [torch.empty(P, dtype=torch.float32, device=DEV) for _ in range(W)]
+            losses = torch.zeros(T, dtype=torch.float32, device=DEV)
+            log = torch.full((T, 3), -7, dtype=torch.int32, device=DEV)
+            B.asgd_replay_run(nets, params, mom, copies, grads, images, labels, worker, rv, lr, mu, wd, 9, losses, log)
+            torch.cuda.synchronize()
+            assert params.cpu().numpy().tobytes() == p.tobytes() and losses.cpu().numpy().tobytes() == ls.tobytes()
+    finally:
+        for n in nets:
+            B.asgd_net_destroy(n)
+
+
 # ---------------------------------------------------------------- full size, in the configuration bench.py times
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 def test_alexnet_full_batch_sampled_against_oracle(dtype):

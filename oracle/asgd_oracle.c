@@ -229,6 +229,54 @@ void oracle_maxpool_bwd(const double *dp, const uint8_t *idx, double *dr,
 }
 
 /* ---------------------------------------------------------------------------
+ * Local response normalisation across channels (part of the cited architecture,
+ * Section 3: "the same architecture as described in" Krizhevsky et al. 2012,
+ * whose Section 3.3 defines it):
+ *   s[n,c,h,w] = k + alpha * sum_{c' = max(0, c - size/2)}^{min(C-1, c + size/2)} a[n,c',h,w]^2
+ *   b = a * s^(-beta)
+ *   da[i] = db[i] * s[i]^(-beta) - 2*alpha*beta * a[i] * sum_{j : |i-j| <= size/2} db[j] * a[j] * s[j]^(-beta-1)
+ * ------------------------------------------------------------------------ */
+void oracle_lrn_fwd(const double *a, double *b, int N, int C, int H, int W, int size, double alpha, double beta, double k)
+{
+    const int half = size / 2;
+    const size_t HW = (size_t)H * W;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (size_t p = 0; p < HW; ++p) {
+                double sum = 0.0;
+                for (int j = c - half; j <= c + half; ++j)
+                    if (j >= 0 && j < C) { const double v = a[((size_t)n * C + j) * HW + p]; sum += v * v; }
+                b[((size_t)n * C + c) * HW + p] = a[((size_t)n * C + c) * HW + p] * pow(k + alpha * sum, -beta);
+            }
+}
+
+void oracle_lrn_bwd(const double *a, const double *db, double *da, int N, int C, int H, int W, int size, double alpha, double beta,
+                    double k)
+{
+    const int half = size / 2;
+    const size_t HW = (size_t)H * W;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (size_t p = 0; p < HW; ++p) {
+            for (int i = 0; i < C; ++i) {
+                double acc = 0.0, s_i = 0.0;
+                for (int j = i - half; j <= i + half; ++j) {
+                    if (j < 0 || j >= C) continue;
+                    double s_j = 0.0;
+                    for (int q = j - half; q <= j + half; ++q)
+                        if (q >= 0 && q < C) { const double v = a[((size_t)n * C + q) * HW + p]; s_j += v * v; }
+                    s_j = k + alpha * s_j;
+                    if (j == i) s_i = s_j;
+                    acc += db[((size_t)n * C + j) * HW + p] * a[((size_t)n * C + j) * HW + p] * pow(s_j, -beta - 1.0);
+                }
+                const size_t o = ((size_t)n * C + i) * HW + p;
+                da[o] = db[o] * pow(s_i, -beta) - 2.0 * alpha * beta * a[o] * acc;
+            }
+        }
+}
+
+/* ---------------------------------------------------------------------------
  * Fully connected layer.   y[n,o] = b[o] + sum_i x[n,i] * w[o,i]
  *   dx[n,i] = sum_o dy[n,o] * w[o,i]
  *   dw[o,i] = sum_n dy[n,o] * x[n,i]        db[o] = sum_n dy[n,o]

@@ -45,7 +45,7 @@ class OracleNet:
                 self.param_slices[li] = (off, wshape, off + l[1] * nin, l[1])
                 off += l[1] * nin + l[1]
                 shape = (l[1],)
-            elif kind in ("relu", "dropout", "softmax_ce"):
+            elif kind in ("relu", "dropout", "softmax_ce", "lrn"):
                 pass
             else:
                 raise ValueError(kind)
@@ -102,6 +102,8 @@ class OracleNet:
                     x = ops.maxpool_gather(x, t["argmax"], l[1], l[2])
                 else:
                     x, t["argmax"] = ops.maxpool_fwd(x, l[1], l[2])
+            elif kind == "lrn":   # ("lrn", size, alpha, beta, k)
+                x = ops.lrn_fwd(x, l[1], l[2], l[3], l[4])
             elif kind == "fc":
                 w, b = self.split(params, li)
                 x = ops.fc_fwd(x.reshape(N, -1), w, b)
@@ -120,7 +122,7 @@ class OracleNet:
             if act_dtype == "bf16" and kind != "softmax_ce":
                 nxt = self.layers[li + 1][0]
                 stored = ((kind in ("conv", "fc") and nxt not in ("relu", "softmax_ce"))
-                          or (kind == "relu" and nxt != "dropout") or kind == "dropout")
+                          or (kind == "relu" and nxt != "dropout") or kind in ("dropout", "lrn"))
                 if stored:
                     x = ops.round_bf16(x)
             t["out"] = x
@@ -150,6 +152,8 @@ class OracleNet:
             elif kind == "maxpool":
                 d = ops.maxpool_bwd(d.reshape(trace[li]["out"].shape), trace[li]["argmax"], xin.shape[2:],
                                     l[1], l[2])
+            elif kind == "lrn":
+                d = ops.lrn_bwd(xin, d.reshape(xin.shape), l[1], l[2], l[3], l[4])
             elif kind == "fc":
                 w, b = self.split(params, li)
                 w_off, w_shape, b_off, b_len = self.param_slices[li]

@@ -136,6 +136,25 @@ def maxpool_bwd(dp, idx, in_hw, k, stride):
     return dr
 
 
+def lrn_fwd(a, size, alpha, beta, k):
+    """Cross-channel local response normalisation of a [N,C,H,W] tensor."""
+    a = _f64(a)
+    N, C, H, W = a.shape
+    b = np.empty_like(a)
+    _load().oracle_lrn_fwd(_d(a), _d(b), N, C, H, W, int(size), ctypes.c_double(alpha), ctypes.c_double(beta), ctypes.c_double(k))
+    return b
+
+
+def lrn_bwd(a, db, size, alpha, beta, k):
+    a, db = _f64(a), _f64(db)
+    N, C, H, W = a.shape
+    assert db.shape == a.shape
+    da = np.empty_like(a)
+    _load().oracle_lrn_bwd(_d(a), _d(db), _d(da), N, C, H, W, int(size), ctypes.c_double(alpha), ctypes.c_double(beta),
+                           ctypes.c_double(k))
+    return da
+
+
 def fc_fwd(x, w, b):
     x, w, b = _f64(x), _f64(w), _f64(b)
     N, nin = x.shape

@@ -160,6 +160,43 @@ def test_maxpool_tie_break_first_in_row_major():
 
 
 # ------------------------------------------------------------------ softmax cross-entropy
+def test_lrn_special_cases_and_library():
+    rng = np.random.default_rng(12)
+    a = rng.standard_normal((2, 7, 3, 4))
+    # window of one channel: elementwise closed form
+    b1 = ops.lrn_fwd(a, 1, 0.3, 0.75, 2.0)
+    np.testing.assert_allclose(b1, a / (2.0 + 0.3 * a * a) ** 0.75, rtol=1e-14)
+    # window covering every channel from anywhere: one sum per pixel
+    b_all = ops.lrn_fwd(a, 13, 0.1, 0.5, 1.0)
+    np.testing.assert_allclose(b_all, a / np.sqrt(1.0 + 0.1 * (a * a).sum(1, keepdims=True)), rtol=1e-14)
+    # window of 5, written out by hand for one element, edges clipped
+    b5 = ops.lrn_fwd(a, 5, 1e-4, 0.75, 2.0)
+    assert abs(b5[1, 0, 2, 1] - a[1, 0, 2, 1] / (2.0 + 1e-4 * (a[1, 0:3, 2, 1] ** 2).sum()) ** 0.75) < 1e-15
+    assert abs(b5[0, 4, 0, 0] - a[0, 4, 0, 0] / (2.0 + 1e-4 * (a[0, 2:7, 0, 0] ** 2).sum()) ** 0.75) < 1e-15
+    # the library routine averages over the window (alpha / size): same thing with alpha * size
+    for size, alpha, beta, k in [(5, 1e-4, 0.75, 2.0), (3, 0.2, 0.6, 1.5)]:
+        t = torch.tensor(a, requires_grad=True)
+        y = torch.nn.functional.local_response_norm(t, size, alpha=alpha * size, beta=beta, k=k)
+        np.testing.assert_allclose(ops.lrn_fwd(a, size, alpha, beta, k), y.detach().numpy(), rtol=1e-12)
+        db = rng.standard_normal(a.shape)
+        y.backward(torch.tensor(db))
+        np.testing.assert_allclose(ops.lrn_bwd(a, db, size, alpha, beta, k), t.grad.numpy(), rtol=1e-10, atol=1e-14)
+
+
+def test_lrn_backward_by_finite_differences():
+    rng = np.random.default_rng(13)
+    a = rng.standard_normal((1, 6, 2, 2))
+    db = rng.standard_normal(a.shape)
+    size, alpha, beta, k = 5, 0.4, 0.75, 2.0      # a large alpha, so that the cross terms matter
+    da = ops.lrn_bwd(a, db, size, alpha, beta, k)
+    h = 1e-6
+    for idx in np.ndindex(a.shape):
+        ap, am = a.copy(), a.copy()
+        ap[idx] += h; am[idx] -= h
+        fd = ((ops.lrn_fwd(ap, size, alpha, beta, k) - ops.lrn_fwd(am, size, alpha, beta, k)) * db).sum() / (2 * h)
+        assert abs(fd - da[idx]) < 1e-8 * (1 + abs(da[idx]))
+
+
 def test_softmax_ce_closed_forms():
     for C in (10, 1000):
         N = 4

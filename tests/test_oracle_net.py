@@ -32,7 +32,11 @@ def test_param_counts_of_the_paper_sized_configs():
     assert net.shapes[2] == (96, 27, 27) and net.shapes[12] == (256, 6, 6)   # FC fan-in 9216
 
 
-@pytest.mark.parametrize("cfg", [NET_A, NET_B])
+NET_LRN = dict(in_shape=(2, 9, 9), classes=3,   # conv - relu - lrn - pool as in the cited architecture, large alpha
+               layers=[("conv", 6, 3, 1, 1), ("relu",), ("lrn", 5, 0.5, 0.75, 2.0), ("maxpool", 3, 2), ("fc", 3), ("softmax_ce",)])
+
+
+@pytest.mark.parametrize("cfg", [NET_A, NET_B, NET_LRN])
 def test_gradient_by_central_finite_differences(cfg):
     net, params, images, labels = _setup(cfg, 3, 5)
     loss, grads, _ = net.fwd_bwd(params, images, labels, dropout_seed=9, step=2, worker=1)

@@ -26,6 +26,7 @@ WORKLOADS = {
     "alexnet_bf16_bs128": (128, "bf16"),   # the headline: AlexNet-style single column, bf16 MFMA, fp32 master weights
     "alexnet_f32_bs128": (128, "f32"),
     "alexnet_bf16_bs256": (256, "bf16"),
+    "alexnet_lrn_bf16_bs128": (128, "bf16"),  # with the response normalisation of the cited architecture after conv1, conv2
     # A-SGD on one GPU: 4 workers as concurrent streams, batch 32 each, snapshots up to 3 updates stale;
     # a step is one pushed gradient (snapshot + fwd_bwd + server update)
     "asgd_4x32_bf16": (32, "bf16"),
@@ -142,7 +143,7 @@ def main():
         return bench_asgd(args, batch)
     dtype = B.BF16 if dtname == "bf16" else B.F32
     tdt = torch.bfloat16 if dtname == "bf16" else torch.float32
-    cfg = wl.ALEXNET
+    cfg = wl.ALEXNET_LRN if "_lrn_" in args.workload else wl.ALEXNET
     layers, in_shape, classes = cfg["layers"], cfg["in_shape"], cfg["classes"]
     lr, mu, wd = cfg["lr"], cfg["mu"], cfg["wd"]
     dev = torch.device("cuda:0")

@@ -52,21 +52,26 @@ typedef enum {
     ASGD_LAYER_MAXPOOL = 3,    /* k, stride (unpadded, floor rule)             */
     ASGD_LAYER_FC = 4,         /* out                                          */
     ASGD_LAYER_DROPOUT = 5,    /* p, scale; must directly follow FC + RELU      */
-    ASGD_LAYER_SOFTMAX_CE = 6  /* last layer; follows an FC                    */
+    ASGD_LAYER_SOFTMAX_CE = 6, /* last layer; follows an FC                    */
+    ASGD_LAYER_LRN = 7         /* k (window, odd, <= 9), p (alpha), scale (beta), bias; must directly follow CONV + RELU */
 } asgd_layer_kind_t;
 
 /* One entry of the network description.  Unused fields are ignored.
  * Dropout (Section 1 cites Hinton et al. 2012): a unit is dropped with
  * probability p; kept units are multiplied by `scale` (0 is read as 1, the
- * cited unscaled form). */
+ * cited unscaled form).
+ * LRN is the cross-channel response normalisation of the architecture the paper
+ * trains (Section 3 cites it):  b[c] = a[c] * (bias + alpha * sum a[c']^2)^(-beta),
+ * the sum over the `k` channels centred on c, clipped at the ends. */
 typedef struct {
     int32_t kind;   /* asgd_layer_kind_t */
     int32_t out;    /* CONV: output channels; FC: output features */
     int32_t k;      /* CONV / MAXPOOL: square window size */
     int32_t stride; /* CONV / MAXPOOL */
     int32_t pad;    /* CONV: zero padding on each side */
-    float p;        /* DROPOUT: drop probability, 0 <= p < 1 */
-    float scale;    /* DROPOUT: factor on kept units */
+    float p;        /* DROPOUT: drop probability, 0 <= p < 1; LRN: alpha */
+    float scale;    /* DROPOUT: factor on kept units; LRN: beta */
+    float bias;     /* LRN: the additive constant k of the formula */
 } asgd_layer_desc_t;
 
 /* Where one parameterised layer lives in the flat parameter vector. */
@@ -216,7 +221,7 @@ typedef enum {
     ASGD_K_CONV_FWD = 0, ASGD_K_CONV_DGRAD = 1, ASGD_K_CONV_WGRAD = 2,
     ASGD_K_FC_FWD = 3, ASGD_K_FC_DGRAD = 4, ASGD_K_FC_WGRAD = 5,
     ASGD_K_POOL_FWD = 6, ASGD_K_POOL_BWD = 7, ASGD_K_BIAS_GRAD = 8,
-    ASGD_K_SOFTMAX_CE = 9, ASGD_K_LAYOUT = 10, ASGD_K_UPDATE = 11, ASGD_K_COUNT = 12
+    ASGD_K_SOFTMAX_CE = 9, ASGD_K_LAYOUT = 10, ASGD_K_UPDATE = 11, ASGD_K_LRN = 12, ASGD_K_COUNT = 13
 } asgd_kernel_class_t;
 typedef struct {
     int32_t kclass;

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libasgd_mi355x.so")
 
 F32, BF16 = 0, 1
-LAYER_CONV, LAYER_RELU, LAYER_MAXPOOL, LAYER_FC, LAYER_DROPOUT, LAYER_SOFTMAX_CE = 1, 2, 3, 4, 5, 6
+LAYER_CONV, LAYER_RELU, LAYER_MAXPOOL, LAYER_FC, LAYER_DROPOUT, LAYER_SOFTMAX_CE, LAYER_LRN = 1, 2, 3, 4, 5, 6, 7
 DEBUG_OUTPUT, DEBUG_ARGMAX, DEBUG_MASK = 0, 1, 2
 OK, EINVAL, ESHAPE, ENOMEM, EHIP, EALIGN = 0, -1, -2, -3, -4, -5
 
@@ -22,12 +22,12 @@ EXPORTS = ["asgd_net_create", "asgd_net_prepare", "asgd_net_destroy", "asgd_para
            "asgd_debug_get", "asgd_profile_begin", "asgd_profile_end", "asgd_schedule_generate", "asgd_replay_run", "asgd_replay_nsync_run", "asgd_accumulate",
            "asgd_last_error"]
 KERNEL_CLASSES = ["conv_fwd", "conv_dgrad", "conv_wgrad", "fc_fwd", "fc_dgrad", "fc_wgrad", "pool_fwd", "pool_bwd",
-                  "bias_grad", "softmax_ce", "layout", "update"]
+                  "bias_grad", "softmax_ce", "layout", "update", "lrn"]
 
 
 class LayerDesc(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("out", ctypes.c_int32), ("k", ctypes.c_int32), ("stride", ctypes.c_int32),
-                ("pad", ctypes.c_int32), ("p", ctypes.c_float), ("scale", ctypes.c_float)]
+                ("pad", ctypes.c_int32), ("p", ctypes.c_float), ("scale", ctypes.c_float), ("bias", ctypes.c_float)]
 
 
 class TensorInfo(ctypes.Structure):
@@ -129,6 +129,8 @@ def layer_descs(layers):
             arr[i] = LayerDesc(LAYER_DROPOUT, 0, 0, 0, 0, float(l[1]), float(l[2]) if len(l) > 2 else 0.0)
         elif kind == "softmax_ce":
             arr[i] = LayerDesc(LAYER_SOFTMAX_CE, 0, 0, 0, 0, 0.0, 0.0)
+        elif kind == "lrn":    # ("lrn", size, alpha, beta, k)
+            arr[i] = LayerDesc(LAYER_LRN, 0, l[1], 0, 0, float(l[2]), float(l[3]), float(l[4]))
         else:
             raise ValueError("unknown layer kind %r" % (kind,))
     return arr

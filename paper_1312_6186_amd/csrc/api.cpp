@@ -37,7 +37,7 @@ int hip_fail(hipError_t e, const char *what) { return fail(ASGD_EHIP, "%s: %s", 
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
-enum StageKind { ST_CONV = 1, ST_POOL = 2, ST_FC = 3 };
+enum StageKind { ST_CONV = 1, ST_POOL = 2, ST_FC = 3, ST_LRN = 4 };
 
 struct Stage {
     int kind = 0;
@@ -53,6 +53,8 @@ struct Stage {
     // window-row form (first stage, <= 4 input channels): bordered input [B][rwHp][rwWp][4], K = k * rwKW
     int rw = 0, rwKW = 0, rwHp = 0, rwWp = 0;
     int relu = 0, drop = 0, drop_layer = -1;
+    float lrn_alpha = 0.f, lrn_beta = 0.f, lrn_bias = 0.f;   // ST_LRN (window size in k)
+    bool has_params() const { return kind == ST_CONV || kind == ST_FC; }
     float drop_p = 0.f, drop_scale = 1.f;
     uint32_t drop_thr = 0;
     size_t w_off = 0, w_cnt = 0, b_off = 0, b_cnt = 0;
@@ -139,7 +141,7 @@ size_t carve(asgd_net &n, char *base)
             s.wf = at((size_t)s.outCp * s.k * (s.rw ? s.rwKW : s.k * s.inCp) * es);
             s.wd = i > 0 ? at((size_t)s.inCp * s.k * s.k * s.outCp * es) : nullptr;
         }
-        if (s.kind != ST_POOL) s.colsum_ws = static_cast<float *>(at(s.colsum_floats * 4));
+        if (s.has_params()) s.colsum_ws = static_cast<float *>(at(s.colsum_floats * 4));
         if (s.kind == ST_FC && s.in_is_spatial) {
             s.flat_in = at(B * s.in_f * es);
             s.dflat_in = at(B * s.in_f * es);
@@ -201,6 +203,15 @@ int plan_net(asgd_net &n)
             s.k = l.k; s.stride = l.stride;
             s.outH = (H - l.k) / l.stride + 1; s.outW = (W - l.k) / l.stride + 1;
             H = s.outH; W = s.outW;
+            n.layer_shape[3 * i] = C; n.layer_shape[3 * i + 1] = H; n.layer_shape[3 * i + 2] = W;
+        } else if (l.kind == ASGD_LAYER_LRN) {
+            if (n.stages.empty() || n.stages.back().kind != ST_CONV || !n.stages.back().relu)
+                return fail(ASGD_ESHAPE, "layer %d: LRN must directly follow CONV + RELU", i);
+            if (l.k < 1 || l.k > 9 || !(l.k & 1)) return fail(ASGD_ESHAPE, "layer %d: LRN window must be odd and at most 9", i);
+            if (!(l.bias > 0.f) || !(l.p >= 0.f) || !(l.scale >= 0.f)) return fail(ASGD_ESHAPE, "layer %d: LRN needs bias > 0, alpha >= 0, beta >= 0", i);
+            s.kind = ST_LRN;
+            s.inC = s.outC = C; s.inCp = s.outCp = round_up(C, 8); s.inH = s.outH = H; s.inW = s.outW = W;
+            s.k = l.k; s.lrn_alpha = l.p; s.lrn_beta = l.scale; s.lrn_bias = l.bias;
             n.layer_shape[3 * i] = C; n.layer_shape[3 * i + 1] = H; n.layer_shape[3 * i + 2] = W;
         } else if (l.kind == ASGD_LAYER_FC) {
             if (l.out <= 0) return fail(ASGD_ESHAPE, "layer %d: bad FC size", i);
@@ -458,6 +469,9 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
             Epilogue ep;
             ep.out = s.out; ep.ld = s.outCp; ep.bias = param_ptr(n, params, s.b_off); ep.bias_n = s.outC; ep.relu = s.relu;
             CHECK_LAUNCH(gemm_gather_plain(dt, g, s.wf, (long)g.kh * g.kw * g.C, s.outCp, ep, s.p_fwd, n->scratch, st), "conv forward");
+        } else if (s.kind == ST_LRN) {
+            ProfScope ps(n, st, ASGD_K_LRN, 0, 2 * Bd * s.outC * s.outH * s.outW * es);
+            CHECK_LAUNCH(launch_lrn_fwd(dt, cur, s.out, (size_t)B * s.outH * s.outW, s.outCp, s.k, s.lrn_alpha, s.lrn_beta, s.lrn_bias, st), "lrn forward");
         } else if (s.kind == ST_POOL) {
             ProfScope ps(n, st, ASGD_K_POOL_FWD, 0, Bd * s.outC * ((double)s.inH * s.inW * es + (double)s.outH * s.outW * (es + 1)));
             CHECK_LAUNCH(launch_pool_fwd(dt, cur, s.out, s.argmax, B, s.inH, s.inW, s.inCp, s.k, s.stride, st), "pool forward");
@@ -508,7 +522,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
     ColsumJobs bias_jobs; bias_jobs.n = 0;  // second stage of the bias gradients: one launch at the end, or per layer when pushing by layer
     auto push = [&](int si) -> int {      // after the stage's gradients are queued on sd and its data gradient on st
         Stage &s = n->stages[si];
-        if (!srv || s.kind == ST_POOL) return ASGD_OK;
+        if (!srv || !s.has_params()) return ASGD_OK;
         if (fork) {
             CHECK_HIP(hipEventRecord(n->ev_dg[si], st), "hipEventRecord");
             CHECK_HIP(hipStreamWaitEvent(sd, n->ev_dg[si], 0), "hipStreamWaitEvent");
@@ -524,7 +538,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
         Stage &s = n->stages[si];
         Stage *prev = si > 0 ? &n->stages[si - 1] : nullptr;
         const void *xin = prev ? prev->out : n->act0;
-        if (fork && s.kind != ST_POOL) {  // the gradient at this stage's output is complete on the caller's stream
+        if (fork && s.has_params()) {  // the gradient at this stage's output is complete on the caller's stream
             CHECK_HIP(hipEventRecord(n->ev_dy[si], st), "hipEventRecord");
             CHECK_HIP(hipStreamWaitEvent(sd, n->ev_dy[si], 0), "hipStreamWaitEvent");
         }
@@ -562,11 +576,18 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
                                                   prev->dout, B, s.inH, s.inW, s.inC, s.inCp, st),
                                  "unflatten");
             }
+        } else if (s.kind == ST_LRN) {
+            // prev is the CONV + RELU it normalises: the ReLU mask of that convolution is applied here
+            ProfScope ps(n, st, ASGD_K_LRN, 0, 3 * Bd * s.outC * s.outH * s.outW * es);
+            CHECK_LAUNCH(launch_lrn_bwd(dt, prev->out, s.dout, 1, prev->dout, (size_t)B * s.outH * s.outW, s.outCp, s.k, s.lrn_alpha, s.lrn_beta,
+                                        s.lrn_bias, st),
+                         "lrn backward");
         } else if (s.kind == ST_POOL) {
             // prev exists: a pool cannot be first... unless the net starts with a pool, which feeds no parameters
             // a ReLU below has been applied to s.dout already by a CONV or FC above (relu_under_pool); only a pool
             // on top of this pool leaves it to be done here
-            const bool relu_here = prev && prev->kind == ST_CONV && prev->relu && si + 1 < (int)n->stages.size() && n->stages[si + 1].kind == ST_POOL;
+            const bool masked_above = si + 1 < (int)n->stages.size() && n->stages[si + 1].has_params();
+            const bool relu_here = prev && prev->kind == ST_CONV && prev->relu && !masked_above;
             ProfScope ps(n, st, ASGD_K_POOL_BWD, 0,
                          Bd * s.outC * ((double)s.outH * s.outW * (es + 1) + (double)s.inH * s.inW * es * (relu_here ? 2 : 1)));
             if (prev)

@@ -114,6 +114,11 @@ int launch_pool_fwd(int dtype, const void *x, void *y, uint8_t *arg, int B, int 
 // dx[pixel] = sum of dy over the windows whose recorded maximum is this pixel; times [x > 0] if relu
 int launch_pool_bwd(int dtype, const void *dy, const uint8_t *arg, const void *x, int relu, void *dx, int B, int H,
                     int W, int Cp, int k, int stride, hipStream_t s);
+// cross-channel response normalisation on channel-last tensors: y = a * (bias + alpha * window sum of a^2)^(-beta);
+// backward writes da (times [a > 0], the ReLU of the convolution below, if relu) from a and dy; size odd, <= 9
+int launch_lrn_fwd(int dtype, const void *a, void *y, size_t pixels, int Cp, int size, float alpha, float beta, float bias, hipStream_t s);
+int launch_lrn_bwd(int dtype, const void *a, const void *dy, int relu, void *da, size_t pixels, int Cp, int size, float alpha, float beta,
+                   float bias, hipStream_t s);
 // channel-last [B][H][W][Cp] -> [B][C*H*W] in (c,h,w) order, and back (zero padding channels; optional ReLU mask)
 int launch_flatten(int dtype, const void *x, void *flat, int B, int H, int W, int C, int Cp, hipStream_t s);
 int launch_unflatten(int dtype, const void *dflat, const void *x_for_mask, int relu, void *dx, int B, int H, int W,

@@ -550,6 +550,128 @@ int launch_pool_bwd(int dtype, const void *dy, const uint8_t *arg, const void *x
     return launch_ok();
 }
 
+// ---------------------------------------------------------------- local response normalisation (across channels)
+// One thread owns V consecutive channels (16 bytes) of one pixel and reads the channels up to 8 to either side
+// (padding channels hold zeros, channels outside the tensor count as zeros), so windows of up to 9 channels fit
+// the forward pass and the backward pass, which needs the window sums of the neighbours' windows.
+template <typename T> struct LrnWindow {
+    static constexpr int V = 16 / sizeof(T), R = 8, N = V + 2 * R;
+    float f[N];   // f[R + e] is channel c0 + e
+    __device__ __forceinline__ void load(const T *pix, int c0, int Cp)
+    {
+#pragma unroll
+        for (int q = -(R / V); q <= R / V; ++q) {
+            const int c = c0 + q * V;
+            Vec16<T> v;
+            if (c >= 0 && c < Cp) v.u = *reinterpret_cast<const uint4 *>(pix + c);
+            else v.u = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int e = 0; e < V; ++e) f[R + q * V + e] = ldf(&v.e[e]);
+        }
+    }
+};
+__device__ __forceinline__ float pow_neg(float s, float e) { return exp2f(-e * log2f(s)); }   // s^(-e), s >= bias > 0
+
+template <typename T, int half>   // half = size / 2, a compile-time constant so that the windows stay in registers
+__global__ __launch_bounds__(256) void lrn_fwd_kernel(const T *__restrict__ a, T *__restrict__ y, size_t groups, int Cp, float alpha, float beta,
+                                                    float bias)
+{
+    constexpr int V = LrnWindow<T>::V, R = LrnWindow<T>::R;
+    const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (g >= groups) return;
+    const int cv = Cp / V;
+    const size_t pix = g / cv;
+    const int c0 = (int)(g - pix * cv) * V;
+    LrnWindow<T> w;
+    w.load(a + pix * Cp, c0, Cp);
+    Vec16<T> o;
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        float sum = 0.f;
+#pragma unroll
+        for (int j = -half; j <= half; ++j) sum += w.f[R + e + j] * w.f[R + e + j];
+        stf(&o.e[e], w.f[R + e] * pow_neg(bias + alpha * sum, beta));
+    }
+    *reinterpret_cast<uint4 *>(y + pix * Cp + c0) = o.u;
+}
+
+template <typename T, int half>
+__global__ __launch_bounds__(256) void lrn_bwd_kernel(const T *__restrict__ a, const T *__restrict__ dy, int relu, T *__restrict__ da, size_t groups,
+                                                    int Cp, float alpha, float beta, float bias)
+{
+    constexpr int V = LrnWindow<T>::V, R = LrnWindow<T>::R;
+    const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (g >= groups) return;
+    const int cv = Cp / V;
+    const size_t pix = g / cv;
+    const int c0 = (int)(g - pix * cv) * V;
+    LrnWindow<T> wa, wd;
+    wa.load(a + pix * Cp, c0, Cp);
+    wd.load(dy + pix * Cp, c0, Cp);
+    // for every channel j within `half` of this thread's channels: s_j, and t_j = dy_j * a_j * s_j^(-beta-1)
+    float t[V + 8], sown[V];
+#pragma unroll
+    for (int q = 0; q < V + 8; ++q) {
+        const int j = q - 4;                    // channel c0 + j, j in [-4, V+3] covers half <= 4
+        float sum = 0.f;
+#pragma unroll
+        for (int r = -half; r <= half; ++r) sum += wa.f[R + j + r] * wa.f[R + j + r];
+        const float sj = bias + alpha * sum;
+        t[q] = (j >= -half && j < V + half) ? wd.f[R + j] * wa.f[R + j] * pow_neg(sj, beta + 1.f) : 0.f;
+        if (j >= 0 && j < V) sown[j] = sj;
+    }
+    Vec16<T> o;
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        float acc = 0.f;
+#pragma unroll
+        for (int r = -half; r <= half; ++r) acc += t[e + 4 + r];
+        float v = wd.f[R + e] * pow_neg(sown[e], beta) - 2.f * alpha * beta * wa.f[R + e] * acc;
+        if (relu && !(wa.f[R + e] > 0.f)) v = 0.f;
+        stf(&o.e[e], v);
+    }
+    *reinterpret_cast<uint4 *>(da + pix * Cp + c0) = o.u;
+}
+
+template <typename T, int HALF>
+static void launch_lrn_t(const void *a, const void *dy, int relu, void *out, size_t groups, int Cp, float alpha, float beta, float bias, bool bwd,
+                         hipStream_t s)
+{
+    const unsigned blocks = blocks_for(groups, 256);
+    if (bwd)
+        hipLaunchKernelGGL((lrn_bwd_kernel<T, HALF>), dim3(blocks), dim3(256), 0, s, static_cast<const T *>(a), static_cast<const T *>(dy), relu,
+                           static_cast<T *>(out), groups, Cp, alpha, beta, bias);
+    else
+        hipLaunchKernelGGL((lrn_fwd_kernel<T, HALF>), dim3(blocks), dim3(256), 0, s, static_cast<const T *>(a), static_cast<T *>(out), groups, Cp, alpha,
+                           beta, bias);
+}
+template <typename T>
+static int launch_lrn_any(const void *a, const void *dy, int relu, void *out, size_t pixels, int Cp, int size, float alpha, float beta, float bias,
+                          bool bwd, hipStream_t s)
+{
+    if (size < 1 || size > 9 || !(size & 1) || !(bias > 0.f)) return -1;
+    const size_t groups = pixels * (size_t)(Cp / (16 / (int)sizeof(T)));
+    switch (size / 2) {
+    case 0: launch_lrn_t<T, 0>(a, dy, relu, out, groups, Cp, alpha, beta, bias, bwd, s); break;
+    case 1: launch_lrn_t<T, 1>(a, dy, relu, out, groups, Cp, alpha, beta, bias, bwd, s); break;
+    case 2: launch_lrn_t<T, 2>(a, dy, relu, out, groups, Cp, alpha, beta, bias, bwd, s); break;
+    case 3: launch_lrn_t<T, 3>(a, dy, relu, out, groups, Cp, alpha, beta, bias, bwd, s); break;
+    default: launch_lrn_t<T, 4>(a, dy, relu, out, groups, Cp, alpha, beta, bias, bwd, s); break;
+    }
+    return launch_ok();
+}
+int launch_lrn_fwd(int dtype, const void *a, void *y, size_t pixels, int Cp, int size, float alpha, float beta, float bias, hipStream_t s)
+{
+    return dtype == kBF16 ? launch_lrn_any<bf16_t>(a, nullptr, 0, y, pixels, Cp, size, alpha, beta, bias, false, s)
+                          : launch_lrn_any<float>(a, nullptr, 0, y, pixels, Cp, size, alpha, beta, bias, false, s);
+}
+int launch_lrn_bwd(int dtype, const void *a, const void *dy, int relu, void *da, size_t pixels, int Cp, int size, float alpha, float beta,
+                   float bias, hipStream_t s)
+{
+    return dtype == kBF16 ? launch_lrn_any<bf16_t>(a, dy, relu, da, pixels, Cp, size, alpha, beta, bias, true, s)
+                          : launch_lrn_any<float>(a, dy, relu, da, pixels, Cp, size, alpha, beta, bias, true, s);
+}
+
 // ---------------------------------------------------------------- flatten / unflatten
 template <typename T>
 __global__ __launch_bounds__(256) void flatten_kernel(const T *__restrict__ x, T *__restrict__ flat, int B, int H, int W, int C, int Cp)

@@ -8,13 +8,18 @@ labels stand in for the ILSVRC-2012 data the paper trains on (Section 1).
 
 A network is a list of layer tuples:
     ("conv", cout, k, stride, pad)  ("relu",)  ("maxpool", k, stride)
-    ("fc", out)  ("dropout", p)  ("softmax_ce",)
+    ("fc", out)  ("dropout", p)  ("softmax_ce",)  ("lrn", size, alpha, beta, k)
 """
 import numpy as np
 
 
-def _conv_block(cout, k, stride, pad, pool=None):
+LRN = ("lrn", 5, 1e-4, 0.75, 2.0)   # the constants of the cited architecture (Krizhevsky et al. 2012, Section 3.3)
+
+
+def _conv_block(cout, k, stride, pad, pool=None, lrn=False):
     block = [("conv", cout, k, stride, pad), ("relu",)]
+    if lrn:
+        block.append(LRN)
     if pool:
         block.append(("maxpool",) + pool)
     return block
@@ -43,7 +48,12 @@ ALEXNET = {
     "lr": 0.01, "mu": 0.9, "wd": 5e-4, "seeds": {"data": 1003, "init": 2003, "dropout": 3003},
 }
 
-CONFIGS = {"tiny": TINY, "small": SMALL, "alexnet": ALEXNET}
+# the same net with the response normalisation of the cited architecture after conv1 and conv2 (before the pools)
+ALEXNET_LRN = dict(ALEXNET, name="alexnet_lrn",
+                   layers=(_conv_block(96, 11, 4, 2, (3, 2), lrn=True) + _conv_block(256, 5, 1, 2, (3, 2), lrn=True)
+                           + ALEXNET["layers"][6:]))
+
+CONFIGS = {"tiny": TINY, "small": SMALL, "alexnet": ALEXNET, "alexnet_lrn": ALEXNET_LRN}
 
 
 def param_shapes(layers, in_shape):

@@ -28,6 +28,14 @@ WIDE = dict(name="wide", in_shape=(6, 21, 19), classes=10,
                     ("maxpool", 3, 1), ("fc", 24), ("relu",), ("fc", 10), ("softmax_ce",)])
 
 
+# response normalisation after CONV + RELU: before a pool, and directly under the next convolution; windows 5 and 9;
+# constants far larger than the cited ones so that the cross-channel terms weigh in
+LRNNET = dict(name="lrn", in_shape=(3, 21, 19), classes=10,
+              layers=[("conv", 16, 3, 1, 1), ("relu",), ("lrn", 5, 0.05, 0.75, 2.0), ("maxpool", 3, 2),
+                      ("conv", 24, 3, 1, 1), ("relu",), ("lrn", 9, 0.02, 0.5, 1.0),
+                      ("conv", 8, 3, 1, 1), ("relu",), ("maxpool", 2, 2), ("fc", 10), ("softmax_ce",)])
+
+
 # ---------------------------------------------------------------- update / snapshot
 @pytest.mark.parametrize("n,offset", [(1, 0), (1023, 0), (4099, 0), (15898, 0), (100003, 1), (1 << 20, 4)])
 def test_apply_update_matches_oracle(n, offset):
@@ -120,8 +128,8 @@ def _net_case(cfg, batch, dtype, seed=0, step=0, worker=0, bias_noise=0.05):
 
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
-@pytest.mark.parametrize("cfg,batch", [(wl.TINY, 8), (wl.TINY, 1), (RAGGED, 5), (RAGGED, 131), (WIDE, 3), (wl.SMALL, 128)],
-                         ids=["tiny", "tiny-batch1", "ragged5", "ragged131", "wide", "small"])
+@pytest.mark.parametrize("cfg,batch", [(wl.TINY, 8), (wl.TINY, 1), (RAGGED, 5), (RAGGED, 131), (WIDE, 3), (LRNNET, 7), (wl.SMALL, 128)],
+                         ids=["tiny", "tiny-batch1", "ragged5", "ragged131", "wide", "lrn", "small"])
 def test_minibatch_gradient_matches_oracle(cfg, batch, dtype):
     g, onet, (loss, grads), (ref_loss, ref_grads, trace), _ = _net_case(cfg, batch, dtype, seed=3002, step=4, worker=1)
     try:
@@ -131,7 +139,7 @@ def test_minibatch_gradient_matches_oracle(cfg, batch, dtype):
         # layer outputs, masks and pooling positions
         for li, l in enumerate(cfg["layers"]):
             nxt = cfg["layers"][li + 1][0] if li + 1 < len(cfg["layers"]) else None
-            group_end = (l[0] == "maxpool" or (l[0] == "relu" and nxt != "dropout") or l[0] == "dropout"
+            group_end = (l[0] in ("maxpool", "lrn") or (l[0] == "relu" and nxt != "dropout") or l[0] == "dropout"
                          or (l[0] in ("conv", "fc") and nxt != "relu"))
             if group_end and l[0] != "softmax_ce":
                 out = g.debug(B.DEBUG_OUTPUT, li)
@@ -189,9 +197,11 @@ def test_fwd_bwd_is_reproducible_bit_for_bit(dtype):
 
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
-def test_alexnet_layers_small_batch(dtype):
-    """Every layer shape of the AlexNet-style net, at a batch the oracle finishes in seconds."""
-    g, onet, (loss, grads), (ref_loss, ref_grads, trace), _ = _net_case(wl.ALEXNET, 4, dtype, seed=3003, step=0, worker=0,
+@pytest.mark.parametrize("cfg", [wl.ALEXNET, wl.ALEXNET_LRN], ids=["plain", "lrn"])
+def test_alexnet_layers_small_batch(cfg, dtype):
+    """Every layer shape of the AlexNet-style net (without and with the response normalisation of the cited
+    architecture), at a batch the oracle finishes in seconds."""
+    g, onet, (loss, grads), (ref_loss, ref_grads, trace), _ = _net_case(cfg, 4, dtype, seed=3003, step=0, worker=0,
                                                                        bias_noise=0.0)
     try:
         tol = TOL[dtype]

@@ -72,6 +72,13 @@ def test_bad_descriptors_are_rejected_with_codes():
     assert _rc([("conv", 3, 3, 1, 0), ("fc", 10), ("softmax_ce",)], in_shape=(3, 5, 5)) == B.ESHAPE  # fan-in 27
     assert _rc([("fc", 16), ("dropout", 0.5), ("fc", 10), ("softmax_ce",)]) == B.ESHAPE       # dropout needs FC+ReLU
     assert _rc([("fc", 16), ("relu",), ("dropout", 1.0), ("fc", 10), ("softmax_ce",)]) == B.ESHAPE
+    lrn = [("conv", 8, 3, 1, 1), ("relu",), ("lrn", 5, 1e-4, 0.75, 2.0), ("maxpool", 2, 2), ("fc", 10), ("softmax_ce",)]
+    assert _rc(lrn) == B.OK
+    assert _rc([lrn[0]] + lrn[2:]) == B.ESHAPE                        # LRN needs CONV + RELU right before it
+    assert _rc(lrn[:2] + [lrn[3], lrn[2]] + lrn[4:]) == B.ESHAPE      # not after a pool
+    assert _rc(lrn[:2] + [("lrn", 4, 1e-4, 0.75, 2.0)] + lrn[3:]) == B.ESHAPE    # even window
+    assert _rc(lrn[:2] + [("lrn", 11, 1e-4, 0.75, 2.0)] + lrn[3:]) == B.ESHAPE   # window above 9
+    assert _rc(lrn[:2] + [("lrn", 5, 1e-4, 0.75, 0.0)] + lrn[3:]) == B.ESHAPE    # bias must be positive
     assert _rc(ok, batch=0) == B.ESHAPE
     assert _rc(ok, dt=7) == B.EINVAL
     assert "dtype" in B.asgd_last_error()

@@ -402,6 +402,35 @@ void oracle_apply_update(double *w, double *v, const double *g, size_t count,
 }
 
 /* ---------------------------------------------------------------------------
+ * The two server updates the paper names as the next thing to try (Section 5,
+ * "Future directions": Adagrad and Adadelta), with the same weight-decay
+ * convention as above (t = g + wd*w).
+ *   Adagrad  (Duchi et al. 2011):  h = h + t*t;   w = w - lr * t / (sqrt(h) + eps)
+ *   Adadelta (Zeiler 2012, Algorithm 1):
+ *       a = rho*a + (1-rho)*t*t;   d = -sqrt(b + eps) / sqrt(a + eps) * t;
+ *       b = rho*b + (1-rho)*d*d;   w = w + d
+ * ------------------------------------------------------------------------ */
+void oracle_apply_adagrad(double *w, double *h, const double *g, size_t count, double lr, double eps, double wd)
+{
+    for (size_t i = 0; i < count; ++i) {
+        const double t = g[i] + wd * w[i];
+        h[i] = h[i] + t * t;
+        w[i] = w[i] - lr * t / (sqrt(h[i]) + eps);
+    }
+}
+
+void oracle_apply_adadelta(double *w, double *a, double *b, const double *g, size_t count, double rho, double eps, double wd)
+{
+    for (size_t i = 0; i < count; ++i) {
+        const double t = g[i] + wd * w[i];
+        a[i] = rho * a[i] + (1.0 - rho) * t * t;
+        const double d = -sqrt(b[i] + eps) / sqrt(a[i] + eps) * t;
+        b[i] = rho * b[i] + (1.0 - rho) * d * d;
+        w[i] = w[i] + d;
+    }
+}
+
+/* ---------------------------------------------------------------------------
  * Worker copy of the server's parameters (Section 2.3: a replica "requests
  * updated parameters").  fp32 -> bf16 by round-to-nearest-even on the bit
  * pattern; NaN stays a quiet NaN with its sign.

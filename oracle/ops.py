@@ -218,6 +218,24 @@ def apply_update(w, v, g, lr, mu, wd):
                                 ctypes.c_double(mu), ctypes.c_double(wd))
 
 
+def apply_adagrad(w, h, g, lr, eps, wd):
+    """In place on the float64 arrays ``w`` (parameters) and ``h`` (sum of squared gradients)."""
+    assert w.dtype == h.dtype == np.float64 and w.flags.c_contiguous and h.flags.c_contiguous
+    g = _f64(g)
+    assert w.size == h.size == g.size
+    _load().oracle_apply_adagrad(_d(w), _d(h), _d(g), ctypes.c_size_t(w.size), ctypes.c_double(lr), ctypes.c_double(eps),
+                                 ctypes.c_double(wd))
+
+
+def apply_adadelta(w, a, b, g, rho, eps, wd):
+    """In place on the float64 arrays ``w``, ``a`` (running mean of squared gradients), ``b`` (of squared steps)."""
+    assert w.dtype == a.dtype == b.dtype == np.float64 and w.flags.c_contiguous and a.flags.c_contiguous and b.flags.c_contiguous
+    g = _f64(g)
+    assert w.size == a.size == b.size == g.size
+    _load().oracle_apply_adadelta(_d(w), _d(a), _d(b), _d(g), ctypes.c_size_t(w.size), ctypes.c_double(rho), ctypes.c_double(eps),
+                                  ctypes.c_double(wd))
+
+
 def snapshot_bf16(params_f32):
     """fp32 array -> uint16 array of bf16 bit patterns (round to nearest even)."""
     p = np.ascontiguousarray(params_f32, dtype=np.float32)

@@ -309,6 +309,44 @@ def test_update_closed_forms():
     np.testing.assert_allclose(w, w0 + v, rtol=1e-14)
 
 
+def test_adagrad_and_adadelta_closed_forms_and_library():
+    n = 40
+    w0, g = randn(n), randn(n)
+    # Adagrad, constant gradient, no decay, eps = 0: step t moves by lr * sign(g) / sqrt(t)
+    w, h = w0.copy(), np.zeros(n)
+    T, lr = 12, 0.3
+    for _ in range(T):
+        ops.apply_adagrad(w, h, g, lr, 0.0, 0.0)
+    np.testing.assert_allclose(h, T * g * g, rtol=1e-13)
+    np.testing.assert_allclose(w, w0 - lr * np.sign(g) * sum(1 / np.sqrt(t) for t in range(1, T + 1)), rtol=1e-12)
+    # Adadelta, first step from zero state: d = -sqrt(eps) / sqrt((1-rho) g^2 + eps) * g
+    w, a, b = w0.copy(), np.zeros(n), np.zeros(n)
+    rho, eps = 0.95, 1e-6
+    ops.apply_adadelta(w, a, b, g, rho, eps, 0.0)
+    d = -np.sqrt(eps) / np.sqrt((1 - rho) * g * g + eps) * g
+    np.testing.assert_allclose(w - w0, d, rtol=1e-9)
+    np.testing.assert_allclose(a, (1 - rho) * g * g, rtol=1e-14)
+    np.testing.assert_allclose(b, (1 - rho) * d * d, rtol=1e-9)
+    # both against the library optimisers in float64, several steps with weight decay and fresh gradients
+    gs = [randn(n) for _ in range(6)]
+    for name in ("adagrad", "adadelta"):
+        p = torch.tensor(w0.copy(), requires_grad=True)
+        if name == "adagrad":
+            opt = torch.optim.Adagrad([p], lr=0.05, eps=1e-7, weight_decay=1e-3)
+            w, h = w0.copy(), np.zeros(n)
+        else:
+            opt = torch.optim.Adadelta([p], lr=1.0, rho=0.9, eps=1e-6, weight_decay=1e-3)
+            w, a, b = w0.copy(), np.zeros(n), np.zeros(n)
+        for gi in gs:
+            p.grad = torch.tensor(gi)
+            opt.step()
+            if name == "adagrad":
+                ops.apply_adagrad(w, h, gi, 0.05, 1e-7, 1e-3)
+            else:
+                ops.apply_adadelta(w, a, b, gi, 0.9, 1e-6, 1e-3)
+        np.testing.assert_allclose(w, p.detach().numpy(), rtol=1e-11, atol=1e-15)
+
+
 # ------------------------------------------------------------------ snapshot
 def test_snapshot_bf16_matches_library_cast_and_hand_cases():
     a = np.concatenate([RNG.standard_normal(5000).astype(np.float32) * np.float32(10.0) ** RNG.integers(-30, 30, 5000),

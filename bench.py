@@ -195,7 +195,7 @@ def main():
     torch.cuda.synchronize()
     profiled_ms = 1e3 * (time.perf_counter() - tp0) / args.steps
     prof = B.asgd_profile_end(net)
-    # the two unfused calls, timed on their own (not part of the step)
+    # calls that are not part of the step, timed on their own: the two unfused protocol calls and the adaptive updates
     scratch_copy = torch.empty_like(copy)
     ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(5)]
     zero_grads = torch.zeros_like(grads)
@@ -245,6 +245,22 @@ def main():
     roofline = {"kernel": dominant, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"], "unit": d["unit"],
                 "frac": d["frac"], "traffic": traffic, "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
                 "launches_per_step": d["launches_per_step"], "ms_per_launch": d["ms_per_step"] / d["launches_per_step"]}
+    # the two adaptive server updates on the same buffers (not part of the step; they leave garbage in `scratch_copy`-sized state)
+    state_a, state_b = torch.zeros_like(master), torch.zeros_like(master)
+    w_tmp = master.clone()
+    ev3 = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(5)]
+    for e in ev3:
+        e[0].record(stream)
+        B.asgd_apply_update_adagrad(w_tmp, state_a, zero_grads, 0.01, 1e-7, 5e-4, stream)
+        e[1].record(stream)
+        B.asgd_apply_update_adadelta(w_tmp, state_a, state_b, zero_grads, 0.95, 1e-6, 5e-4, stream)
+        e[2].record(stream)
+    torch.cuda.synchronize()
+    for name, a, b, nbytes in (("update_adagrad", 0, 1, P * 20), ("update_adadelta", 1, 2, P * 28)):
+        ms = sum(e[a].elapsed_time(e[b]) for e in ev3[1:]) / (len(ev3) - 1)
+        unfused[name] = {"bound": "hbm", "ms_per_call": ms, "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK["hbm"], "unit": "GB/s",
+                         "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK["hbm"]}
+    del state_a, state_b, w_tmp
     mfma_ms = sum(c["ms_per_step"] for n, c in classes_out.items() if n in MFMA_CLASSES)
     mfma_flops = sum(prof[n]["flops"] for n in MFMA_CLASSES) / K
     B.asgd_net_destroy(net)
@@ -262,7 +278,7 @@ def main():
                            "frac": mfma_flops / (mfma_ms * 1e-3) / 1e12 / PEAK["mfma_" + dtname], "ms_per_step": mfma_ms},
         "profiled_ms_per_step": profiled_ms, "serial": bool(args.serial),
         "kernel_classes": classes_out,
-        "unfused_calls": unfused,
+        "other_calls": unfused,
     }
     if args.cpu_sample > 0:
         out["cpu_baseline"] = cpu_baseline(layers, in_shape, classes, args.cpu_sample, (lr, mu, wd))

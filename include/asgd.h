@@ -159,6 +159,20 @@ int asgd_fwd_bwd(asgd_net_t *net, const void *params, const void *images, const 
 int asgd_apply_update(float *params, float *momentum, const float *grads, size_t n, float lr,
                       float mu, float wd, void *stream);
 
+/* The two server updates the paper names as future work (Section 5), as the
+ * same kind of single pass over the flat buffers, with t = g + wd*w:
+ *   Adagrad :  h += t*t;  w -= lr * t / (sqrt(h) + eps)
+ *   Adadelta:  a = rho*a + (1-rho)*t*t;  d = -sqrt(b + eps) / sqrt(a + eps) * t;
+ *              b = rho*b + (1-rho)*d*d;  w += d
+ *   params and the state buffers (hist; avg_sq_grad, avg_sq_step): device fp32
+ *   [n], updated in place, state zero before the first update; grads read only.
+ * Errors: ASGD_EINVAL (null with n > 0), ASGD_EALIGN, ASGD_EHIP. */
+int asgd_apply_update_adagrad(float *params, float *hist, const float *grads, size_t n, float lr,
+                              float eps, float wd, void *stream);
+int asgd_apply_update_adadelta(float *params, float *avg_sq_grad, float *avg_sq_step,
+                               const float *grads, size_t n, float rho, float eps, float wd,
+                               void *stream);
+
 /* A replica's fetch (Section 2.3): copy the server's fp32 parameters into the
  * worker's buffer, as fp32 (dst_dtype ASGD_F32) or rounded to bf16, ties to
  * even (ASGD_BF16; NaN stays a quiet NaN).

@@ -19,7 +19,7 @@ OK, EINVAL, ESHAPE, ENOMEM, EHIP, EALIGN = 0, -1, -2, -3, -4, -5
 EXPORTS = ["asgd_net_create", "asgd_net_prepare", "asgd_net_destroy", "asgd_param_count", "asgd_param_layout",
            "asgd_layer_shape", "asgd_workspace_bytes", "asgd_fwd_bwd", "asgd_apply_update", "asgd_snapshot",
            "asgd_apply_update_snapshot", "asgd_train_step",
-           "asgd_debug_get", "asgd_profile_begin", "asgd_profile_end", "asgd_schedule_generate", "asgd_replay_run", "asgd_replay_nsync_run", "asgd_accumulate",
+           "asgd_debug_get", "asgd_profile_begin", "asgd_profile_end", "asgd_schedule_generate", "asgd_replay_run", "asgd_replay_nsync_run", "asgd_accumulate", "asgd_apply_update_adagrad", "asgd_apply_update_adadelta",
            "asgd_last_error"]
 KERNEL_CLASSES = ["conv_fwd", "conv_dgrad", "conv_wgrad", "fc_fwd", "fc_dgrad", "fc_wgrad", "pool_fwd", "pool_bwd",
                   "bias_grad", "softmax_ce", "layout", "update", "lrn"]
@@ -86,6 +86,8 @@ def lib():
                                             ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, i32p, i32p, ctypes.c_int,
                                             ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_uint64, vp, vp, vp]
         L.asgd_accumulate.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
+        L.asgd_apply_update_adagrad.argtypes = [vp, vp, vp, ctypes.c_size_t, ctypes.c_float, ctypes.c_float, ctypes.c_float, vp]
+        L.asgd_apply_update_adadelta.argtypes = [vp, vp, vp, vp, ctypes.c_size_t, ctypes.c_float, ctypes.c_float, ctypes.c_float, vp]
         L.asgd_last_error.restype = ctypes.c_char_p
         _lib = L
     return _lib
@@ -256,3 +258,13 @@ def asgd_replay_nsync_run(nets, n_sync, params, momentum, worker_params, worker_
 
 def asgd_accumulate(accum, grads, first, stream=None, n=None):
     _check(lib().asgd_accumulate(_ptr(accum), _ptr(grads), accum.numel() if n is None else n, 1 if first else 0, _stream(stream)))
+
+
+def asgd_apply_update_adagrad(params, hist, grads, lr, eps, wd, stream=None, n=None):
+    _check(lib().asgd_apply_update_adagrad(_ptr(params), _ptr(hist), _ptr(grads), params.numel() if n is None else n, lr, eps, wd,
+                                           _stream(stream)))
+
+
+def asgd_apply_update_adadelta(params, avg_sq_grad, avg_sq_step, grads, rho, eps, wd, stream=None, n=None):
+    _check(lib().asgd_apply_update_adadelta(_ptr(params), _ptr(avg_sq_grad), _ptr(avg_sq_step), _ptr(grads),
+                                            params.numel() if n is None else n, rho, eps, wd, _stream(stream)))

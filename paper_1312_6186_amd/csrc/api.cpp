@@ -999,6 +999,27 @@ int asgd_replay_nsync_run(asgd_net_t *const *nets, int n_workers, int n_sync, fl
                        dropout_seed, losses, log, stream, &loc);
 }
 
+int asgd_apply_update_adagrad(float *params, float *hist, const float *grads, size_t n, float lr, float eps, float wd, void *stream)
+{
+    if (n == 0) return ASGD_OK;
+    if (!params || !hist || !grads) return fail(ASGD_EINVAL, "asgd_apply_update_adagrad: null argument");
+    if (((uintptr_t)params | (uintptr_t)hist | (uintptr_t)grads) & 3) return fail(ASGD_EALIGN, "asgd_apply_update_adagrad: buffers must be 4-byte aligned");
+    if (launch_adagrad(params, hist, grads, n, lr, eps, wd, static_cast<hipStream_t>(stream)) != 0) return hip_fail(hipGetLastError(), "update kernel");
+    return ASGD_OK;
+}
+
+int asgd_apply_update_adadelta(float *params, float *avg_sq_grad, float *avg_sq_step, const float *grads, size_t n, float rho, float eps, float wd,
+                               void *stream)
+{
+    if (n == 0) return ASGD_OK;
+    if (!params || !avg_sq_grad || !avg_sq_step || !grads) return fail(ASGD_EINVAL, "asgd_apply_update_adadelta: null argument");
+    if (((uintptr_t)params | (uintptr_t)avg_sq_grad | (uintptr_t)avg_sq_step | (uintptr_t)grads) & 3)
+        return fail(ASGD_EALIGN, "asgd_apply_update_adadelta: buffers must be 4-byte aligned");
+    if (launch_adadelta(params, avg_sq_grad, avg_sq_step, grads, n, rho, eps, wd, static_cast<hipStream_t>(stream)) != 0)
+        return hip_fail(hipGetLastError(), "update kernel");
+    return ASGD_OK;
+}
+
 int asgd_accumulate(float *accum, const float *grads, size_t n, int first, void *stream)
 {
     if (n == 0) return ASGD_OK;

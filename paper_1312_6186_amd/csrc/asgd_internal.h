@@ -91,6 +91,9 @@ int launch_update(float *w, float *v, const float *g, size_t n, float lr, float 
 // the update, and the updated parameters written to `copy` (fp32 or bf16) in the same pass
 int launch_update_snapshot(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd, void *copy,
                            int dst_dtype, hipStream_t s);
+// Adagrad / Adadelta server updates (one pass, in place)
+int launch_adagrad(float *w, float *h, const float *g, size_t n, float lr, float eps, float wd, hipStream_t s);
+int launch_adadelta(float *w, float *a, float *b, const float *g, size_t n, float rho, float eps, float wd, hipStream_t s);
 // acc = g (first) or acc + g
 int launch_accumulate(float *acc, const float *g, size_t n, bool first, hipStream_t s);
 int launch_snapshot(const float *src, void *dst, size_t n, int dst_dtype, const int *version_counter,

@@ -143,6 +143,92 @@ int launch_update_snapshot(float *w, float *v, const float *g, size_t n, float l
     return dst_dtype == kBF16 ? launch_update_t<2>(w, v, g, n, lr, mu, wd, nullptr, copy, s) : launch_update_t<1>(w, v, g, n, lr, mu, wd, nullptr, copy, s);
 }
 
+// ---------------------------------------------------------------- Adagrad / Adadelta server updates
+// The same streaming shape as the momentum update: 16-byte vectors where the buffers allow, identical arithmetic
+// (explicit contractions) on every path.
+//   Adagrad :  t = g + wd*w;  h += t*t;  w -= lr * t / (sqrt(h) + eps)
+//   Adadelta:  t = g + wd*w;  a = rho*a + (1-rho)*t*t;  d = -sqrt(b+eps)/sqrt(a+eps)*t;  b = rho*b + (1-rho)*d*d;  w += d
+__device__ __forceinline__ void adagrad1(float &w, float &h, float g, float lr, float eps, float wd)
+{
+    const float t = __builtin_fmaf(wd, w, g);
+    h = __builtin_fmaf(t, t, h);
+    w = w - lr * t / (__builtin_sqrtf(h) + eps);
+}
+__device__ __forceinline__ void adadelta1(float &w, float &a, float &b, float g, float rho, float eps, float wd)
+{
+    const float t = __builtin_fmaf(wd, w, g);
+    a = __builtin_fmaf(rho, a, (1.f - rho) * (t * t));
+    const float d = -(__builtin_sqrtf(b + eps) / __builtin_sqrtf(a + eps)) * t;
+    b = __builtin_fmaf(rho, b, (1.f - rho) * (d * d));
+    w = w + d;
+}
+// KIND 0: Adagrad (s1 = h, s2 unused, c1 = lr); KIND 1: Adadelta (s1 = a, s2 = b, c1 = rho)
+template <int KIND>
+__global__ __launch_bounds__(256) void adaptive_update_kernel(float *__restrict__ w, float *__restrict__ s1, float *__restrict__ s2,
+                                                             const float *__restrict__ g, size_t n, int vec, float c1, float eps, float wd)
+{
+    // vector body: each thread owns U float4 per buffer, 256 apart, all loads issued before the arithmetic
+    constexpr int U = 4;
+    const size_t n4 = vec ? n / 4 : 0;
+    const size_t i0 = (size_t)blockIdx.x * (256 * U) + threadIdx.x;
+    f32x4 ww[U], aa[U], bb[U], gg[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const size_t i = i0 + (size_t)u * 256;
+        if (i < n4) {
+            ww[u] = reinterpret_cast<f32x4 *>(w)[i]; aa[u] = reinterpret_cast<f32x4 *>(s1)[i];
+            if (KIND == 1) bb[u] = reinterpret_cast<f32x4 *>(s2)[i];
+            gg[u] = __builtin_nontemporal_load(&reinterpret_cast<const f32x4 *>(g)[i]);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const size_t i = i0 + (size_t)u * 256;
+        if (i < n4) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float we = ww[u][e], ae = aa[u][e], be = KIND == 1 ? bb[u][e] : 0.f;
+                if (KIND == 0) adagrad1(we, ae, gg[u][e], c1, eps, wd);
+                else adadelta1(we, ae, be, gg[u][e], c1, eps, wd);
+                ww[u][e] = we; aa[u][e] = ae;
+                if (KIND == 1) bb[u][e] = be;
+            }
+            __builtin_nontemporal_store(ww[u], &reinterpret_cast<f32x4 *>(w)[i]);
+            __builtin_nontemporal_store(aa[u], &reinterpret_cast<f32x4 *>(s1)[i]);
+            if (KIND == 1) __builtin_nontemporal_store(bb[u], &reinterpret_cast<f32x4 *>(s2)[i]);
+        }
+    }
+    // scalar tail (everything, if the buffers are not 16-byte aligned), grid-stride
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = n4 * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        float we = w[i], ae = s1[i], be = KIND == 1 ? s2[i] : 0.f;
+        if (KIND == 0) adagrad1(we, ae, g[i], c1, eps, wd);
+        else adadelta1(we, ae, be, g[i], c1, eps, wd);
+        w[i] = we; s1[i] = ae;
+        if (KIND == 1) s2[i] = be;
+    }
+}
+static unsigned adaptive_blocks(size_t n, int vec)
+{
+    if (vec) { const size_t b = (n / 4 + 1023) / 1024; return (unsigned)(b ? b : 1); }
+    unsigned b = blocks_for(n ? n : 1, 256);
+    return b > 32768 ? 32768 : b;
+}
+int launch_adagrad(float *w, float *h, const float *g, size_t n, float lr, float eps, float wd, hipStream_t s)
+{
+    const int vec = ((((uintptr_t)w | (uintptr_t)h | (uintptr_t)g) & 15) == 0) ? 1 : 0;
+    const unsigned blocks = adaptive_blocks(n, vec);
+    hipLaunchKernelGGL(adaptive_update_kernel<0>, dim3(blocks), dim3(256), 0, s, w, h, static_cast<float *>(nullptr), g, n, vec, lr, eps, wd);
+    return launch_ok();
+}
+int launch_adadelta(float *w, float *a, float *b, const float *g, size_t n, float rho, float eps, float wd, hipStream_t s)
+{
+    const int vec = ((((uintptr_t)w | (uintptr_t)a | (uintptr_t)b | (uintptr_t)g) & 15) == 0) ? 1 : 0;
+    const unsigned blocks = adaptive_blocks(n, vec);
+    hipLaunchKernelGGL(adaptive_update_kernel<1>, dim3(blocks), dim3(256), 0, s, w, a, b, g, n, vec, rho, eps, wd);
+    return launch_ok();
+}
+
 // ---------------------------------------------------------------- gradient accumulator (n_push > 1)
 // acc = g (first) or acc + g; 16-byte vectors when both are aligned, the same arithmetic either way.
 __global__ __launch_bounds__(256) void accumulate_kernel(float *__restrict__ acc, const float *__restrict__ g, size_t n, int first, int vec)

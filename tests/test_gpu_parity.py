@@ -54,6 +54,32 @@ def test_apply_update_matches_oracle(n, offset):
     np.testing.assert_array_equal(gd.cpu().numpy(), g)
 
 
+@pytest.mark.parametrize("n,offset", [(1, 0), (4099, 0), (100003, 1), (1 << 20, 4)])
+def test_adagrad_and_adadelta_match_oracle(n, offset):
+    rng = np.random.default_rng(n + 3)
+    w0 = rng.standard_normal(n + offset).astype(np.float32)
+    gs = [rng.standard_normal(n + offset).astype(np.float32) for _ in range(4)]
+    # Adagrad
+    w = torch.from_numpy(w0).to(DEV); h = torch.zeros_like(w)
+    wr, hr = w0[offset:].astype(np.float64), np.zeros(n)
+    for g in gs:
+        B.asgd_apply_update_adagrad(w[offset:], h[offset:], torch.from_numpy(g).to(DEV)[offset:], 0.05, 1e-7, 1e-3)
+        oops.apply_adagrad(wr, hr, g[offset:], np.float32(0.05), np.float32(1e-7), np.float32(1e-3))
+    torch.cuda.synchronize()
+    assert rel_l2(w.cpu().numpy()[offset:], wr) < 1e-6 and rel_l2(h.cpu().numpy()[offset:], hr) < 1e-6
+    np.testing.assert_array_equal(w.cpu().numpy()[:offset], w0[:offset])
+    # Adadelta
+    w = torch.from_numpy(w0).to(DEV); a = torch.zeros_like(w); b = torch.zeros_like(w)
+    wr, ar, br = w0[offset:].astype(np.float64), np.zeros(n), np.zeros(n)
+    for g in gs:
+        B.asgd_apply_update_adadelta(w[offset:], a[offset:], b[offset:], torch.from_numpy(g).to(DEV)[offset:], 0.9, 1e-6, 1e-3)
+        oops.apply_adadelta(wr, ar, br, g[offset:], np.float32(0.9), np.float32(1e-6), np.float32(1e-3))
+    torch.cuda.synchronize()
+    assert rel_l2(w.cpu().numpy()[offset:], wr) < 1e-6 and rel_l2(a.cpu().numpy()[offset:], ar) < 1e-6
+    assert rel_l2(b.cpu().numpy()[offset:], br) < 1e-5       # squares of steps of order sqrt(eps): a few more ulps
+    np.testing.assert_array_equal(w.cpu().numpy()[:offset], w0[:offset])
+
+
 @pytest.mark.parametrize("n,offset", [(1, 0), (7, 0), (4099, 0), (100003, 3), (1 << 20, 0)])
 def test_snapshot_is_bit_exact(n, offset):
     rng = np.random.default_rng(n)

@@ -25,11 +25,12 @@ class OracleNet:
         for li, l in enumerate(self.layers):
             kind = l[0]
             if kind == "conv":
-                _, cout, k, s, p = l
+                cout, k, s, p = l[1:5]
+                groups = l[5] if len(l) > 5 else 1       # ("conv", cout, k, stride, pad[, groups])
                 c, h, w = shape
                 ho, wo = (h + 2 * p - k) // s + 1, (w + 2 * p - k) // s + 1
-                assert ho > 0 and wo > 0
-                wshape = (cout, c, k, k)
+                assert ho > 0 and wo > 0 and c % groups == 0 and cout % groups == 0
+                wshape = (cout, c // groups, k, k)
                 self.param_slices[li] = (off, wshape, off + int(np.prod(wshape)), cout)
                 off += int(np.prod(wshape)) + cout
                 shape = (cout, ho, wo)
@@ -88,7 +89,15 @@ class OracleNet:
             t = {}
             if kind == "conv":
                 w, b = self.split(params, li)
-                x = ops.conv_fwd(x, w, b, l[3], l[4])
+                groups = l[5] if len(l) > 5 else 1
+                if groups == 1:
+                    x = ops.conv_fwd(x, w, b, l[3], l[4])
+                else:
+                    # grouped ("two-column") convolution: group g maps input channels [g*Cg, (g+1)*Cg) to output
+                    # channels [g*Og, (g+1)*Og) and is an ordinary convolution of those slices
+                    cg, og = x.shape[1] // groups, w.shape[0] // groups
+                    x = np.concatenate([ops.conv_fwd(x[:, g * cg:(g + 1) * cg], w[g * og:(g + 1) * og], b[g * og:(g + 1) * og],
+                                                     l[3], l[4]) for g in range(groups)], axis=1)
             elif kind == "relu":
                 t["pre"] = x
                 if li in dec_relu:
@@ -165,9 +174,19 @@ class OracleNet:
                 w, b = self.split(params, li)
                 w_off, w_shape, b_off, b_len = self.param_slices[li]
                 dy = d.reshape(trace[li]["out"].shape)
-                dw, db = ops.conv_bwd_weight(xin, dy, l[2], l[3], l[4])
+                groups = l[5] if len(l) > 5 else 1
+                if groups == 1:
+                    dw, db = ops.conv_bwd_weight(xin, dy, l[2], l[3], l[4])
+                    d = ops.conv_bwd_data(dy, w, xin.shape[2:], l[3], l[4]) if li > 0 else None
+                else:
+                    cg, og = xin.shape[1] // groups, w.shape[0] // groups
+                    parts = [ops.conv_bwd_weight(xin[:, g * cg:(g + 1) * cg], dy[:, g * og:(g + 1) * og], l[2], l[3], l[4])
+                             for g in range(groups)]
+                    dw = np.concatenate([pw for pw, _ in parts], axis=0)
+                    db = np.concatenate([pb for _, pb in parts])
+                    d = np.concatenate([ops.conv_bwd_data(dy[:, g * og:(g + 1) * og], w[g * og:(g + 1) * og], xin.shape[2:], l[3], l[4])
+                                        for g in range(groups)], axis=1) if li > 0 else None
                 grads[w_off:w_off + dw.size] = dw.reshape(-1)
                 grads[b_off:b_off + b_len] = db
-                d = ops.conv_bwd_data(dy, w, xin.shape[2:], l[3], l[4]) if li > 0 else None
             trace["dx"][li] = d
         return loss, grads, trace

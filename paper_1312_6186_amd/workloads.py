@@ -7,7 +7,7 @@ see identical bytes.  Synthetic N(0,1) images of the crop shape and uniform
 labels stand in for the ILSVRC-2012 data the paper trains on (Section 1).
 
 A network is a list of layer tuples:
-    ("conv", cout, k, stride, pad)  ("relu",)  ("maxpool", k, stride)
+    ("conv", cout, k, stride, pad[, groups])  ("relu",)  ("maxpool", k, stride)
     ("fc", out)  ("dropout", p)  ("softmax_ce",)  ("lrn", size, alpha, beta, k)
 """
 import numpy as np
@@ -62,9 +62,10 @@ def param_shapes(layers, in_shape):
     out = []
     for li, l in enumerate(layers):
         if l[0] == "conv":
-            _, cout, k, s, p = l
+            cout, k, s, p = l[1:5]
+            groups = l[5] if len(l) > 5 else 1
             c, h, w = shape
-            out.append((li, (cout, c, k, k), cout, c * k * k))
+            out.append((li, (cout, c // groups, k, k), cout, (c // groups) * k * k))
             shape = (cout, (h + 2 * p - k) // s + 1, (w + 2 * p - k) // s + 1)
         elif l[0] == "maxpool":
             _, k, s = l

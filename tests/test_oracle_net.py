@@ -36,8 +36,9 @@ NET_LRN = dict(in_shape=(2, 9, 9), classes=3,   # conv - relu - lrn - pool as in
                layers=[("conv", 6, 3, 1, 1), ("relu",), ("lrn", 5, 0.5, 0.75, 2.0), ("maxpool", 3, 2), ("fc", 3), ("softmax_ce",)])
 
 
-@pytest.mark.parametrize("cfg", [NET_A, NET_B, NET_LRN])
+@pytest.mark.parametrize("cfg", [NET_A, NET_B, NET_LRN, "grouped"])
 def test_gradient_by_central_finite_differences(cfg):
+    cfg = NET_G if cfg == "grouped" else cfg
     net, params, images, labels = _setup(cfg, 3, 5)
     loss, grads, _ = net.fwd_bwd(params, images, labels, dropout_seed=9, step=2, worker=1)
     h = 1e-5
@@ -61,9 +62,10 @@ def _torch_fwd_bwd(cfg, params, images, labels, masks):
     off = 0
     for li, l in enumerate(cfg["layers"]):
         if l[0] == "conv":
-            cin = x.shape[1]; n = l[1] * cin * l[2] * l[2]
+            groups = l[5] if len(l) > 5 else 1
+            cin = x.shape[1] // groups; n = l[1] * cin * l[2] * l[2]
             w = p[off:off + n].reshape(l[1], cin, l[2], l[2]); b = p[off + n:off + n + l[1]]; off += n + l[1]
-            x = torch.nn.functional.conv2d(x, w, b, stride=l[3], padding=l[4])
+            x = torch.nn.functional.conv2d(x, w, b, stride=l[3], padding=l[4], groups=groups)
         elif l[0] == "relu":
             x = torch.relu(x)
         elif l[0] == "maxpool":
@@ -80,7 +82,11 @@ def _torch_fwd_bwd(cfg, params, images, labels, masks):
     return float(loss.detach()), p.grad.numpy()
 
 
-@pytest.mark.parametrize("cfg,batch", [(NET_A, 4), (NET_B, 4),
+NET_G = dict(in_shape=(4, 9, 8), classes=3,    # grouped convolutions: 2 groups, then 3 groups with a stride
+             layers=[("conv", 6, 3, 1, 1, 2), ("relu",), ("conv", 6, 3, 2, 1, 3), ("relu",), ("maxpool", 2, 2), ("fc", 3), ("softmax_ce",)])
+
+
+@pytest.mark.parametrize("cfg,batch", [(NET_A, 4), (NET_B, 4), (NET_G, 3),
                                        (dict(wl.SMALL, classes=10), 6)])
 def test_whole_net_matches_torch_autograd_in_float64(cfg, batch):
     net, params, images, labels = _setup(cfg, batch, 21)

@@ -27,6 +27,7 @@ WORKLOADS = {
     "alexnet_f32_bs128": (128, "f32"),
     "alexnet_bf16_bs256": (256, "bf16"),
     "alexnet_lrn_bf16_bs128": (128, "bf16"),  # with the response normalisation of the cited architecture after conv1, conv2
+    "alexnet_full_bf16_bs128": (128, "bf16"),  # the cited architecture in full: LRN and two-column conv2 / conv4 / conv5
     # A-SGD on one GPU: 4 workers as concurrent streams, batch 32 each, snapshots up to 3 updates stale;
     # a step is one pushed gradient (snapshot + fwd_bwd + server update)
     "asgd_4x32_bf16": (32, "bf16"),
@@ -143,7 +144,7 @@ def main():
         return bench_asgd(args, batch)
     dtype = B.BF16 if dtname == "bf16" else B.F32
     tdt = torch.bfloat16 if dtname == "bf16" else torch.float32
-    cfg = wl.ALEXNET_LRN if "_lrn_" in args.workload else wl.ALEXNET
+    cfg = wl.ALEXNET_FULL if "_full_" in args.workload else wl.ALEXNET_LRN if "_lrn_" in args.workload else wl.ALEXNET
     layers, in_shape, classes = cfg["layers"], cfg["in_shape"], cfg["classes"]
     lr, mu, wd = cfg["lr"], cfg["mu"], cfg["wd"]
     dev = torch.device("cuda:0")
@@ -270,7 +271,7 @@ def main():
         "value": batch * args.steps / elapsed, "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if dtname == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "net": "AlexNet-style single column (62378344 parameters)", "batch": batch,
+        "config": {"workload": args.workload, "net": "%s (%d parameters)" % (cfg["name"], P), "batch": batch,
                    "step": "fwd_bwd + apply_update_snapshot (push fused with the next fetch)", "lr": lr, "mu": mu, "wd": wd},
         "loss": final_loss,
         "roofline": roofline,

@@ -72,6 +72,9 @@ typedef struct {
     float p;        /* DROPOUT: drop probability, 0 <= p < 1; LRN: alpha */
     float scale;    /* DROPOUT: factor on kept units; LRN: beta */
     float bias;     /* LRN: the additive constant k of the formula */
+    int32_t groups; /* CONV: number of channel groups ("columns"); 0 or 1 = ungrouped.  Group g maps input
+                       channels [g*cin/groups, ...) to output channels [g*out/groups, ...); both per-group
+                       counts must be multiples of 8; filters are [out][cin/groups][k][k] */
 } asgd_layer_desc_t;
 
 /* Where one parameterised layer lives in the flat parameter vector. */

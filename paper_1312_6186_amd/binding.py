@@ -27,7 +27,7 @@ KERNEL_CLASSES = ["conv_fwd", "conv_dgrad", "conv_wgrad", "fc_fwd", "fc_dgrad", 
 
 class LayerDesc(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("out", ctypes.c_int32), ("k", ctypes.c_int32), ("stride", ctypes.c_int32),
-                ("pad", ctypes.c_int32), ("p", ctypes.c_float), ("scale", ctypes.c_float), ("bias", ctypes.c_float)]
+                ("pad", ctypes.c_int32), ("p", ctypes.c_float), ("scale", ctypes.c_float), ("bias", ctypes.c_float), ("groups", ctypes.c_int32)]
 
 
 class TensorInfo(ctypes.Structure):
@@ -120,7 +120,7 @@ def layer_descs(layers):
     for i, l in enumerate(layers):
         kind = l[0]
         if kind == "conv":
-            arr[i] = LayerDesc(LAYER_CONV, l[1], l[2], l[3], l[4], 0.0, 0.0)
+            arr[i] = LayerDesc(LAYER_CONV, l[1], l[2], l[3], l[4], 0.0, 0.0, 0.0, l[5] if len(l) > 5 else 1)
         elif kind == "relu":
             arr[i] = LayerDesc(LAYER_RELU, 0, 0, 0, 0, 0.0, 0.0)
         elif kind == "maxpool":

@@ -50,6 +50,7 @@ struct Stage {
     bool in_is_spatial = false;  // an fc fed by a conv / pool stage (flatten boundary)
     bool last = false;           // produces the fp32 logits
     int k = 0, stride = 1, pad = 0;
+    int groups = 1;   // convolution channel groups
     // window-row form (first stage, <= 4 input channels): bordered input [B][rwHp][rwWp][4], K = k * rwKW
     int rw = 0, rwKW = 0, rwHp = 0, rwWp = 0;
     int relu = 0, drop = 0, drop_layer = -1;
@@ -173,6 +174,9 @@ int plan_net(asgd_net &n)
             if (l.out <= 0 || l.k <= 0 || l.k > 15 || l.stride <= 0 || l.pad < 0) return fail(ASGD_ESHAPE, "layer %d: bad CONV parameters (filter size 1..15)", i);
             if (H + 2 * l.pad < l.k || W + 2 * l.pad < l.k) return fail(ASGD_ESHAPE, "layer %d: filter larger than padded input", i);
             s.kind = ST_CONV;
+            s.groups = l.groups > 1 ? l.groups : 1;
+            if (s.groups > 1 && (C % s.groups || l.out % s.groups || (C / s.groups) % 8 || (l.out / s.groups) % 8))
+                return fail(ASGD_ESHAPE, "layer %d: a grouped CONV needs input and output channels per group in multiples of 8", i);
             s.inC = C; s.inCp = round_up(C, 8); s.inH = H; s.inW = W;
             s.k = l.k; s.stride = l.stride; s.pad = l.pad;
             s.outC = l.out; s.outCp = round_up(l.out, 8);
@@ -181,13 +185,13 @@ int plan_net(asgd_net &n)
             // First layer over <= 4 channels: padding them to 8 would make most of the reduction zeros.  Keep 4 per
             // pixel and merge (kx, c) into one contiguous run instead, if the 16-byte pieces stay aligned.
             const int es0 = (int)dtype_size(n.dtype);
-            if (n.stages.empty() && C <= 4 && (l.stride * 4 * es0) % 16 == 0) {
+            if (n.stages.empty() && C <= 4 && s.groups == 1 && (l.stride * 4 * es0) % 16 == 0) {
                 s.rw = 1;
                 s.rwKW = round_up(l.k * 4, 8);   // the filter-gradient GEMM wants its column count in eights
                 s.rwHp = H + 2 * l.pad;
                 s.rwWp = round_up(std::max(W + 2 * l.pad, (s.outW - 1) * l.stride + s.rwKW / 4), 16 / (4 * es0) > 1 ? 2 : 1);
             }
-            s.w_off = off; s.w_cnt = (size_t)l.out * C * l.k * l.k; s.b_off = off + s.w_cnt; s.b_cnt = l.out;
+            s.w_off = off; s.w_cnt = (size_t)l.out * (C / s.groups) * l.k * l.k; s.b_off = off + s.w_cnt; s.b_cnt = l.out;
             off += s.w_cnt + s.b_cnt;
             C = l.out; H = s.outH; W = s.outW;
             n.layer_shape[3 * i] = C; n.layer_shape[3 * i + 1] = H; n.layer_shape[3 * i + 2] = W;
@@ -263,7 +267,7 @@ int plan_net(asgd_net &n)
             memset(&t, 0, sizeof t);
             t.layer = s.first_layer; t.kind = s.kind == ST_CONV ? ASGD_LAYER_CONV : ASGD_LAYER_FC;
             t.w_offset = s.w_off; t.w_count = s.w_cnt; t.b_offset = s.b_off; t.b_count = s.b_cnt;
-            if (s.kind == ST_CONV) { t.w_shape[0] = s.outC; t.w_shape[1] = s.inC; t.w_shape[2] = s.k; t.w_shape[3] = s.k; }
+            if (s.kind == ST_CONV) { t.w_shape[0] = s.outC; t.w_shape[1] = s.inC / s.groups; t.w_shape[2] = s.k; t.w_shape[3] = s.k; }
             else { t.w_shape[0] = s.out_f; t.w_shape[1] = s.in_f; t.w_shape[2] = 1; t.w_shape[3] = 1; }
             n.tensors.push_back(t);
         }
@@ -283,9 +287,16 @@ int plan_net(asgd_net &n)
             const long K = s.rw ? (long)s.k * s.rwKW : (long)s.k * s.k * s.inCp;
             if (s.rw && (long)B * s.rwHp * s.rwWp * 16 > 0x7fffffffL) return fail(ASGD_ESHAPE, "layer %d: tensor too large", s.first_layer);
             if (M > 0x7fffffffL / 2 || Min > 0x7fffffffL / 2 || M * s.outCp * 4 > 0x7fffffffL || Min * s.inCp * 4 > 0x7fffffffL) return fail(ASGD_ESHAPE, "layer %d: tensor too large", s.first_layer);
-            s.p_fwd = plan_gemm(M, s.outCp, K, n.dtype, 1);
-            s.p_dgrad = plan_gemm(Min, s.inCp, (long)s.k * s.k * s.outCp, n.dtype, 1);
-            s.p_wgrad = plan_gemm(s.outCp, K, M, n.dtype, 64);
+            if (s.groups > 1) {   // one GEMM per group, on that group's channel slices
+                const long Cg = s.inC / s.groups, Og = s.outC / s.groups, Kg = (long)s.k * s.k * Cg;
+                s.p_fwd = plan_gemm(M, Og, Kg, n.dtype, 1);
+                s.p_dgrad = plan_gemm(Min, Cg, (long)s.k * s.k * Og, n.dtype, 1);
+                s.p_wgrad = plan_gemm(Og, Kg, M, n.dtype, 64);
+            } else {
+                s.p_fwd = plan_gemm(M, s.outCp, K, n.dtype, 1);
+                s.p_dgrad = plan_gemm(Min, s.inCp, (long)s.k * s.k * s.outCp, n.dtype, 1);
+                s.p_wgrad = plan_gemm(s.outCp, K, M, n.dtype, 64);
+            }
             scratch_side = std::max(scratch_side, s.p_wgrad.ws_floats);
             s.colsum_floats = colsum_ws_floats(n.dtype, M, s.outCp);
         } else if (s.kind == ST_FC) {
@@ -396,11 +407,19 @@ bool relu_under_pool(const std::vector<Stage> &st, int pool_idx)
 }
 
 // The input side of a convolution stage as a gather over its (possibly bordered) input tensor x.
-Gather conv_gather(const Stage &s, const void *x, int B, int dt)
+Gather conv_gather(const Stage &s, const void *x, int B, int dt, int group = 0)
 {
     const size_t es = dtype_size(dt);
     Gather g;
     g.x = x; g.N = B; g.Ho = s.outH; g.Wo = s.outW; g.sm = s.stride; g.ds = 1;
+    if (s.groups > 1) {   // the group's channels of every pixel: pixels keep the full tensor's strides
+        const int Cg = s.inC / s.groups;
+        g.x = static_cast<const char *>(x) + (size_t)group * Cg * es;
+        g.H = s.inH; g.W = s.inW; g.C = Cg; g.kh = g.kw = s.k; g.pad = s.pad;
+        g.pix = (size_t)s.inCp * es; g.rowb = (size_t)s.inW * s.inCp * es;
+        g.bytes = (size_t)B * s.inH * s.inW * s.inCp * es - (size_t)group * Cg * es;
+        return g;
+    }
     if (s.rw) {
         g.H = s.rwHp; g.W = s.rwWp; g.C = s.rwKW; g.kh = s.k; g.kw = 1; g.pad = 0;
         g.pix = 4 * es; g.rowb = (size_t)s.rwWp * 4 * es;
@@ -445,6 +464,27 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
         for (size_t si = 0; si < n->stages.size(); ++si) {
             Stage &s = n->stages[si];
             if (s.kind != ST_CONV) continue;
+            if (s.groups > 1) {
+                // forward pack of all groups at once (rows are output channels, each over its group's Cg inputs);
+                // one flipped data-gradient pack per group
+                const int Cg = s.inC / s.groups, Og = s.outC / s.groups;
+                const size_t gw = (size_t)Og * Cg * s.k * s.k;          // canonical filters / packed elements of one group
+                {
+                    PackJob &J = jobs.j[jobs.n++];
+                    J.w = param_ptr(n, params, s.w_off); J.wf = s.wf; J.wd = nullptr;
+                    J.cout = s.outC; J.cin = Cg; J.k = s.k; J.coutp = s.outC; J.cinp = Cg; J.rw = 0; J.KW = 0;
+                    bytes += (double)s.w_cnt * es * 2;
+                    if (jobs.n == 12) { const int rc = flush(); if (rc != ASGD_OK) return rc; }
+                }
+                for (int g = 0; g < s.groups && s.wd; ++g) {
+                    PackJob &J = jobs.j[jobs.n++];
+                    J.w = param_ptr(n, params, s.w_off + g * gw); J.wf = nullptr; J.wd = static_cast<char *>(s.wd) + g * gw * dtype_size(dt);
+                    J.cout = Og; J.cin = Cg; J.k = s.k; J.coutp = Og; J.cinp = Cg; J.rw = 0; J.KW = 0;
+                    bytes += (double)gw * es * 2;
+                    if (jobs.n == 12) { const int rc = flush(); if (rc != ASGD_OK) return rc; }
+                }
+                continue;
+            }
             PackJob &J = jobs.j[jobs.n++];
             J.w = param_ptr(n, params, s.w_off); J.wf = s.wf; J.wd = s.rw ? nullptr : s.wd;
             J.cout = s.outC; J.cin = s.inC; J.k = s.k; J.coutp = s.outCp; J.cinp = s.inCp; J.rw = s.rw; J.KW = s.rwKW;
@@ -463,12 +503,26 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
             if (fork && !packed_seen) CHECK_HIP(hipStreamWaitEvent(st, n->ev_pack[0], 0), "hipStreamWaitEvent");
             packed_seen = true;
             const double Mo = Bd * s.outH * s.outW;
-            ProfScope ps(n, st, ASGD_K_CONV_FWD, 2 * Mo * s.outC * s.inC * s.k * s.k,
+            ProfScope ps(n, st, ASGD_K_CONV_FWD, 2 * Mo * s.outC * (s.inC / s.groups) * s.k * s.k,
                          (Bd * s.inH * s.inW * s.inC + (double)s.w_cnt + Mo * s.outC) * es);
-            const Gather g = conv_gather(s, cur, B, dt);
-            Epilogue ep;
-            ep.out = s.out; ep.ld = s.outCp; ep.bias = param_ptr(n, params, s.b_off); ep.bias_n = s.outC; ep.relu = s.relu;
-            CHECK_LAUNCH(gemm_gather_plain(dt, g, s.wf, (long)g.kh * g.kw * g.C, s.outCp, ep, s.p_fwd, n->scratch, st), "conv forward");
+            if (s.groups > 1) {
+                const int Cg = s.inC / s.groups, Og = s.outC / s.groups;
+                const long Kg = (long)s.k * s.k * Cg;
+                for (int gi = 0; gi < s.groups; ++gi) {
+                    const Gather g = conv_gather(s, cur, B, dt, gi);
+                    Epilogue ep;
+                    ep.out = static_cast<char *>(s.out) + (size_t)gi * Og * dtype_size(dt); ep.ld = s.outCp;
+                    ep.bias = param_ptr(n, params, s.b_off + (size_t)gi * Og); ep.bias_n = Og; ep.relu = s.relu;
+                    CHECK_LAUNCH(gemm_gather_plain(dt, g, static_cast<const char *>(s.wf) + (size_t)gi * Og * Kg * dtype_size(dt), Kg, Og, ep, s.p_fwd,
+                                                   n->scratch, st),
+                                 "conv forward");
+                }
+            } else {
+                const Gather g = conv_gather(s, cur, B, dt);
+                Epilogue ep;
+                ep.out = s.out; ep.ld = s.outCp; ep.bias = param_ptr(n, params, s.b_off); ep.bias_n = s.outC; ep.relu = s.relu;
+                CHECK_LAUNCH(gemm_gather_plain(dt, g, s.wf, (long)g.kh * g.kw * g.C, s.outCp, ep, s.p_fwd, n->scratch, st), "conv forward");
+            }
         } else if (s.kind == ST_LRN) {
             ProfScope ps(n, st, ASGD_K_LRN, 0, 2 * Bd * s.outC * s.outH * s.outW * es);
             CHECK_LAUNCH(launch_lrn_fwd(dt, cur, s.out, (size_t)B * s.outH * s.outW, s.outCp, s.k, s.lrn_alpha, s.lrn_beta, s.lrn_bias, st), "lrn forward");
@@ -595,14 +649,28 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
                              "pool backward");
         } else {
             const long M = (long)B * s.outH * s.outW;
-            const Gather g = conv_gather(s, xin, B, dt);
-            Epilogue ew;
-            ew.out = grads + s.w_off; ew.mode = s.rw ? 2 : 1; ew.out_f32 = 1;
-            ew.cw_cout = s.outC; ew.cw_cin = s.inC; ew.cw_cinp = s.rw ? s.rwKW : s.inCp; ew.cw_kh = s.k; ew.cw_kw = s.k;
-            const double Mo = (double)M, conv_flops = 2 * Mo * s.outC * s.inC * s.k * s.k;
+            const double Mo = (double)M, conv_flops = 2 * Mo * s.outC * (s.inC / s.groups) * s.k * s.k;
+            const int Cg = s.inC / s.groups, Og = s.outC / s.groups;   // channels per group (all of them when ungrouped)
+            const size_t esz = dtype_size(dt);
             {
                 ProfScope ps(n, sd, ASGD_K_CONV_WGRAD, conv_flops, (Mo * s.outC + Bd * s.inH * s.inW * s.inC) * es + (double)s.w_cnt * 4);
-                CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch_side, sd), "conv filter gradient");
+                if (s.groups > 1) {
+                    for (int gi = 0; gi < s.groups; ++gi) {
+                        const Gather g = conv_gather(s, xin, B, dt, gi);
+                        Epilogue ew;
+                        ew.out = grads + s.w_off + (size_t)gi * Og * Cg * s.k * s.k; ew.mode = 1; ew.out_f32 = 1;
+                        ew.cw_cout = Og; ew.cw_cin = Cg; ew.cw_cinp = Cg; ew.cw_kh = s.k; ew.cw_kw = s.k;
+                        CHECK_LAUNCH(gemm_trans_gather(dt, static_cast<const char *>(s.dout) + (size_t)gi * Og * esz, s.outCp, Og, g, ew, s.p_wgrad,
+                                                       n->scratch_side, sd),
+                                     "conv filter gradient");
+                    }
+                } else {
+                    const Gather g = conv_gather(s, xin, B, dt);
+                    Epilogue ew;
+                    ew.out = grads + s.w_off; ew.mode = s.rw ? 2 : 1; ew.out_f32 = 1;
+                    ew.cw_cout = s.outC; ew.cw_cin = s.inC; ew.cw_cinp = s.rw ? s.rwKW : s.inCp; ew.cw_kh = s.k; ew.cw_kw = s.k;
+                    CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch_side, sd), "conv filter gradient");
+                }
             }
             {
                 ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, Mo * s.outC * es + s.outC * 4.0);
@@ -610,18 +678,24 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
                 if (srv || bias_jobs.n == 12) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "conv bias gradient");
             }
             if (prev) {
-                Gather d;
-                d.x = s.dout; d.N = B; d.H = s.outH; d.W = s.outW; d.C = s.outCp; d.Ho = s.inH; d.Wo = s.inW;
-                d.kh = d.kw = s.k; d.sm = 1; d.ds = s.stride; d.pad = s.k - 1 - s.pad;
-                d.bytes = (size_t)B * s.outH * s.outW * s.outCp * dtype_size(dt);
-                Epilogue ed;
-                ed.out = prev->dout; ed.ld = s.inCp;
-                if ((prev->kind == ST_CONV && prev->relu) || relu_under_pool(n->stages, si - 1)) {
-                    ed.mask_src = prev->out; ed.mask_ld = s.inCp; ed.mask_scale = 1.f;
-                }
+                const bool masked = (prev->kind == ST_CONV && prev->relu) || relu_under_pool(n->stages, si - 1);
                 ProfScope ps(n, st, ASGD_K_CONV_DGRAD, conv_flops,
-                             (Mo * s.outC + (double)s.w_cnt + Bd * s.inH * s.inW * s.inC * (ed.mask_src ? 2 : 1)) * es);
-                CHECK_LAUNCH(gemm_gather_plain(dt, d, s.wd, (long)s.k * s.k * s.outCp, s.inCp, ed, s.p_dgrad, n->scratch, st), "conv data gradient");
+                             (Mo * s.outC + (double)s.w_cnt + Bd * s.inH * s.inW * s.inC * (masked ? 2 : 1)) * es);
+                for (int gi = 0; gi < s.groups; ++gi) {
+                    // the group's slice of the output gradient, gathered with the flipped filters of that group
+                    const int Ogp = s.groups > 1 ? Og : s.outCp, Cgp = s.groups > 1 ? Cg : s.inCp;
+                    Gather d;
+                    d.x = static_cast<const char *>(s.dout) + (size_t)gi * Og * esz; d.N = B; d.H = s.outH; d.W = s.outW; d.C = Ogp;
+                    d.Ho = s.inH; d.Wo = s.inW;
+                    d.kh = d.kw = s.k; d.sm = 1; d.ds = s.stride; d.pad = s.k - 1 - s.pad;
+                    d.pix = (size_t)s.outCp * esz; d.rowb = (size_t)s.outW * s.outCp * esz;
+                    d.bytes = (size_t)B * s.outH * s.outW * s.outCp * esz - (size_t)gi * Og * esz;
+                    Epilogue ed;
+                    ed.out = static_cast<char *>(prev->dout) + (size_t)gi * Cg * esz; ed.ld = s.inCp;
+                    if (masked) { ed.mask_src = static_cast<const char *>(prev->out) + (size_t)gi * Cg * esz; ed.mask_ld = s.inCp; ed.mask_scale = 1.f; }
+                    const void *wd = static_cast<const char *>(s.wd) + (size_t)gi * Og * Cg * s.k * s.k * esz;
+                    CHECK_LAUNCH(gemm_gather_plain(dt, d, wd, (long)s.k * s.k * Ogp, Cgp, ed, s.p_dgrad, n->scratch, st), "conv data gradient");
+                }
             }
         }
         const int prc = push(si);

@@ -194,7 +194,8 @@ template <typename T, bool WIDE> struct GatherK {
 // that are not multiples of the stride contribute nothing.  Rare, kept simple.
 template <typename T> struct GatherKS {
     static constexpr bool kTrans = false;
-    Operand op; int H, W, C, Ho, Wo, kh, kw, sm, ds, pad, M;
+    Operand op; unsigned pix;   // bytes from one pixel to the next
+    int H, W, C, Ho, Wo, kh, kw, sm, ds, pad, M;
     FastDiv dWo, dHoWo, dC, dkw;
     struct Row { int pix0, y0, x0; };  // pix0 < 0: row out of range
     struct KPos { int ky, kx, c; };
@@ -229,7 +230,7 @@ template <typename T> struct GatherKS {
         if ((y % ds) != 0 || (xx % ds) != 0) return kInv;
         y /= ds; xx /= ds;
         if (y >= H || xx >= W) return kInv;
-        return (unsigned)((r.pix0 + y * W + xx) * C + kp.c) * (unsigned)sizeof(T);
+        return (unsigned)(r.pix0 + y * W + xx) * pix + (unsigned)kp.c * (unsigned)sizeof(T);
     }
 };
 
@@ -835,6 +836,7 @@ template <typename T> static GatherKS<T> make_gather_ks(const Gather &g)
 {
     GatherKS<T> l;
     l.op = operand(g.x, g.bytes);
+    l.pix = g.pix ? (unsigned)g.pix : (unsigned)(g.C * sizeof(T));
     l.H = g.H; l.W = g.W; l.C = g.C; l.Ho = g.Ho; l.Wo = g.Wo; l.kh = g.kh; l.kw = g.kw;
     l.sm = g.sm; l.ds = g.ds; l.pad = g.pad; l.M = g.N * g.Ho * g.Wo;
     l.dWo = make_fastdiv(g.Wo); l.dHoWo = make_fastdiv(g.Ho * g.Wo); l.dC = make_fastdiv(g.C); l.dkw = make_fastdiv(g.kw);

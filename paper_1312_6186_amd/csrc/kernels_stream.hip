@@ -430,8 +430,9 @@ int launch_pack_conv(int dtype, PackJobs &jobs, hipStream_t s)
     size_t total = 0;
     for (int q = 0; q < jobs.n; ++q) {
         PackJob &J = jobs.j[q];
-        const size_t nf = J.rw ? (size_t)J.coutp * J.k * J.KW : (size_t)J.coutp * J.k * J.k * J.cinp;
-        const size_t nd = (!J.rw && J.wd) ? nf : 0;
+        const size_t full = J.rw ? (size_t)J.coutp * J.k * J.KW : (size_t)J.coutp * J.k * J.k * J.cinp;
+        const size_t nf = J.wf ? full : 0;
+        const size_t nd = (!J.rw && J.wd) ? full : 0;
         if (nf + nd > 0xffffffffull || (nf & 7)) return -1;   // cinp, coutp and KW are multiples of 8
         J.start = (unsigned)total; J.nf = (unsigned)nf;
         total += (nf + nd) / 8;                                 // in groups of 8 elements

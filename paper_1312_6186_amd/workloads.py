@@ -16,8 +16,8 @@ import numpy as np
 LRN = ("lrn", 5, 1e-4, 0.75, 2.0)   # the constants of the cited architecture (Krizhevsky et al. 2012, Section 3.3)
 
 
-def _conv_block(cout, k, stride, pad, pool=None, lrn=False):
-    block = [("conv", cout, k, stride, pad), ("relu",)]
+def _conv_block(cout, k, stride, pad, pool=None, lrn=False, groups=1):
+    block = [("conv", cout, k, stride, pad) + ((groups,) if groups > 1 else ()), ("relu",)]
     if lrn:
         block.append(LRN)
     if pool:
@@ -53,7 +53,13 @@ ALEXNET_LRN = dict(ALEXNET, name="alexnet_lrn",
                    layers=(_conv_block(96, 11, 4, 2, (3, 2), lrn=True) + _conv_block(256, 5, 1, 2, (3, 2), lrn=True)
                            + ALEXNET["layers"][6:]))
 
-CONFIGS = {"tiny": TINY, "small": SMALL, "alexnet": ALEXNET, "alexnet_lrn": ALEXNET_LRN}
+# the cited architecture in full: response normalisation after conv1 / conv2 and two-column (grouped) conv2, conv4, conv5
+ALEXNET_FULL = dict(ALEXNET, name="alexnet_full",
+                    layers=(_conv_block(96, 11, 4, 2, (3, 2), lrn=True) + _conv_block(256, 5, 1, 2, (3, 2), lrn=True, groups=2)
+                            + _conv_block(384, 3, 1, 1) + _conv_block(384, 3, 1, 1, groups=2)
+                            + _conv_block(256, 3, 1, 1, (3, 2), groups=2) + ALEXNET["layers"][13:]))
+
+CONFIGS = {"tiny": TINY, "small": SMALL, "alexnet": ALEXNET, "alexnet_lrn": ALEXNET_LRN, "alexnet_full": ALEXNET_FULL}
 
 
 def param_shapes(layers, in_shape):

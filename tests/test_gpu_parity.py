@@ -36,6 +36,14 @@ LRNNET = dict(name="lrn", in_shape=(3, 21, 19), classes=10,
                       ("conv", 8, 3, 1, 1), ("relu",), ("maxpool", 2, 2), ("fc", 10), ("softmax_ce",)])
 
 
+# grouped ("two-column") convolutions: 2 groups of 8 -> 16 channels, 2 groups with a stride (strided data gradient
+# on channel slices), 3 groups under a pool; per-group channel counts are multiples of 8
+GROUPED = dict(name="grouped", in_shape=(3, 23, 21), classes=10,
+               layers=[("conv", 16, 3, 1, 1), ("relu",), ("conv", 32, 3, 1, 1, 2), ("relu",), ("maxpool", 3, 2),
+                       ("conv", 48, 3, 2, 1, 2), ("relu",), ("conv", 24, 3, 1, 1, 3), ("relu",), ("maxpool", 2, 2),
+                       ("fc", 10), ("softmax_ce",)])
+
+
 # ---------------------------------------------------------------- update / snapshot
 @pytest.mark.parametrize("n,offset", [(1, 0), (1023, 0), (4099, 0), (15898, 0), (100003, 1), (1 << 20, 4)])
 def test_apply_update_matches_oracle(n, offset):
@@ -154,8 +162,8 @@ def _net_case(cfg, batch, dtype, seed=0, step=0, worker=0, bias_noise=0.05):
 
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
-@pytest.mark.parametrize("cfg,batch", [(wl.TINY, 8), (wl.TINY, 1), (RAGGED, 5), (RAGGED, 131), (WIDE, 3), (LRNNET, 7), (wl.SMALL, 128)],
-                         ids=["tiny", "tiny-batch1", "ragged5", "ragged131", "wide", "lrn", "small"])
+@pytest.mark.parametrize("cfg,batch", [(wl.TINY, 8), (wl.TINY, 1), (RAGGED, 5), (RAGGED, 131), (WIDE, 3), (LRNNET, 7), (GROUPED, 6), (wl.SMALL, 128)],
+                         ids=["tiny", "tiny-batch1", "ragged5", "ragged131", "wide", "lrn", "grouped", "small"])
 def test_minibatch_gradient_matches_oracle(cfg, batch, dtype):
     g, onet, (loss, grads), (ref_loss, ref_grads, trace), _ = _net_case(cfg, batch, dtype, seed=3002, step=4, worker=1)
     try:
@@ -223,7 +231,7 @@ def test_fwd_bwd_is_reproducible_bit_for_bit(dtype):
 
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
-@pytest.mark.parametrize("cfg", [wl.ALEXNET, wl.ALEXNET_LRN], ids=["plain", "lrn"])
+@pytest.mark.parametrize("cfg", [wl.ALEXNET, wl.ALEXNET_LRN, wl.ALEXNET_FULL], ids=["plain", "lrn", "lrn+groups"])
 def test_alexnet_layers_small_batch(cfg, dtype):
     """Every layer shape of the AlexNet-style net (without and with the response normalisation of the cited
     architecture), at a batch the oracle finishes in seconds."""

@@ -45,6 +45,17 @@ def test_plan_matches_the_workload_description(cfg):
             B.asgd_net_destroy(net)
 
 
+def test_full_cited_architecture_has_the_published_parameter_count():
+    cfg = wl.ALEXNET_FULL
+    net = B.asgd_net_create(cfg["layers"], 2, cfg["in_shape"], B.BF16)
+    try:
+        assert B.asgd_param_count(net) == 60965224 == wl.param_count(cfg["layers"], cfg["in_shape"])
+        lay = {t["layer"]: t for t in B.asgd_param_layout(net)}
+        assert lay[4]["w_shape"] == (256, 48, 5, 5) and lay[10]["w_shape"] == (384, 192, 3, 3) and lay[12]["w_shape"] == (256, 192, 3, 3)
+    finally:
+        B.asgd_net_destroy(net)
+
+
 def test_alexnet_shapes():
     net = B.asgd_net_create(wl.ALEXNET["layers"], 128, (3, 224, 224), B.BF16)
     shapes = [B.asgd_layer_shape(net, i) for i in range(len(wl.ALEXNET["layers"]))]
@@ -79,6 +90,11 @@ def test_bad_descriptors_are_rejected_with_codes():
     assert _rc(lrn[:2] + [("lrn", 4, 1e-4, 0.75, 2.0)] + lrn[3:]) == B.ESHAPE    # even window
     assert _rc(lrn[:2] + [("lrn", 11, 1e-4, 0.75, 2.0)] + lrn[3:]) == B.ESHAPE   # window above 9
     assert _rc(lrn[:2] + [("lrn", 5, 1e-4, 0.75, 0.0)] + lrn[3:]) == B.ESHAPE    # bias must be positive
+    grp = [("conv", 16, 3, 1, 1), ("relu",), ("conv", 32, 3, 1, 1, 2), ("relu",), ("maxpool", 2, 2), ("fc", 10), ("softmax_ce",)]
+    assert _rc(grp) == B.OK
+    assert _rc(grp[:2] + [("conv", 32, 3, 1, 1, 4)] + grp[3:]) == B.ESHAPE      # 4 input channels per group: not a multiple of 8
+    assert _rc(grp[:2] + [("conv", 24, 3, 1, 1, 2)] + grp[3:]) == B.ESHAPE      # 12 output channels per group
+    assert _rc(grp[:2] + [("conv", 32, 3, 1, 1, 3)] + grp[3:]) == B.ESHAPE      # 16 does not divide by 3
     assert _rc(ok, batch=0) == B.ESHAPE
     assert _rc(ok, dt=7) == B.EINVAL
     assert "dtype" in B.asgd_last_error()

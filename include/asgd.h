@@ -146,8 +146,14 @@ size_t asgd_workspace_bytes(const asgd_net_t *net);
  *   loss    : device, 1 float; overwritten.
  *   grads   : device, fp32 [param_count], 16-byte aligned; overwritten (not
  *             accumulated into).
- * Everything is enqueued on `stream`; no host synchronisation.  A plan must
- * not be used on two streams at once (its workspace is shared).
+ * No host synchronisation.  The call is ordered on `stream`: it starts after
+ * the work already enqueued there and later work on `stream` sees its results.
+ * Kernels that do not feed the next layer (parameter gradients, filter packing)
+ * may run on an internal stream of default priority, forked from and joined back
+ * into `stream` with events (never inside asgd_replay_run, never between
+ * asgd_profile_begin / end, and not at all with ASGD_SERIAL=1 in the
+ * environment).  A plan must not be used on two streams at once (its workspace
+ * is shared).
  * Errors: ASGD_EINVAL, ASGD_EALIGN, ASGD_ENOMEM, ASGD_EHIP. */
 int asgd_fwd_bwd(asgd_net_t *net, const void *params, const void *images, const int32_t *labels,
                  uint64_t dropout_seed, uint64_t step, uint32_t worker, float *loss, float *grads,
@@ -224,9 +230,9 @@ int asgd_train_step(asgd_net_t *net, float *master, float *momentum, void *worke
 typedef enum { ASGD_DEBUG_OUTPUT = 0, ASGD_DEBUG_ARGMAX = 1, ASGD_DEBUG_MASK = 2 } asgd_debug_what_t;
 int asgd_debug_get(asgd_net_t *net, int what, int layer, void *dst, size_t cap_bytes, void *stream);
 
-/* Per-kernel-class timing of asgd_fwd_bwd, for roofline reports.  Between
- * asgd_profile_begin and asgd_profile_end every operation enqueued by
- * asgd_fwd_bwd on this plan is bracketed by a pair of HIP events on the stream it
+/* Per-kernel-class timing of asgd_fwd_bwd (and asgd_train_step), for roofline
+ * reports.  Between asgd_profile_begin and asgd_profile_end every operation
+ * enqueued by these calls on this plan is bracketed by a pair of HIP events on the stream it
  * runs on (an operation is one layer's GEMM including its split-K reduction, or
  * one streaming kernel).  asgd_profile_end synchronises those events (host
  * blocks) and fills out[0..ASGD_K_COUNT) with, per class: the number of

@@ -1,8 +1,10 @@
 // Bandwidth-bound kernels of the hot path for gfx950: the fused momentum /
-// weight-decay update, the parameter snapshot, pooling, softmax cross-entropy,
-// bias-gradient column sums and the layout conversions around the channel-last
-// activation format.  Every reduction has a fixed summation order so that a run
-// is reproducible bit for bit.
+// weight-decay update (optionally writing the worker copy in the same pass), the
+// Adagrad / Adadelta updates, the gradient accumulator, the parameter snapshot,
+// pooling, response normalisation, softmax cross-entropy, bias-gradient column
+// sums and the layout conversions around the channel-last activation format.
+// Every reduction has a fixed summation order so that a run is reproducible bit
+// for bit.
 #include <hip/hip_runtime.h>
 
 #include "asgd_internal.h"
@@ -34,8 +36,6 @@ uint64_t dropout_key(uint64_t seed, uint64_t step, uint32_t worker, uint32_t lay
 
 // ---------------------------------------------------------------- update
 // t = g + wd*w; v = mu*v - lr*t; w = w + v.  20 bytes of traffic per parameter.
-// The compiler may contract a product and the following sum into one fused
-// multiply-add, which differs from the unfused form by at most one rounding.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Each thread owns 4 float4 per buffer, 256 apart, all loads issued before the arithmetic; gradients are read and

@@ -449,9 +449,16 @@ template <int ROWS> struct FragOff<float, true, ROWS> {
         base = (unsigned)(8 * (lane >> 5) * TransTile<float, ROWS>::LINE + (row0 + (lane & 31)) * 4);
     }
 };
+// Fragment offsets into an activation patch (see conv_patch_kernel): the byte address of the lane's pixel for
+// row block 0 / 1, K-half included; the K steps of a tile are 32 (bf16) or 64 (fp32) bytes apart.
+struct PatchOff { unsigned a[2]; };
 typedef short short4v __attribute__((ext_vector_type(4)));
 template <> struct Frag<bf16_t> {
     uint4 v;
+    template <int KS, int BLK> __device__ __forceinline__ void read(const char *sm, const PatchOff &fo)
+    {
+        v = *reinterpret_cast<const uint4 *>(sm + fo.a[BLK] + KS * 32);
+    }
     template <int KS, int BLK, int ROWS> __device__ __forceinline__ void read(const char *sm, const FragOff<bf16_t, false, ROWS> &fo)
     {
         v = *reinterpret_cast<const uint4 *>(sm + fo.o[KS][BLK % 2] + (BLK / 2) * (64 * 128));
@@ -469,6 +476,11 @@ template <> struct Frag<bf16_t> {
 };
 template <> struct Frag<float> {
     uint4 v[2];
+    template <int KS, int BLK> __device__ __forceinline__ void read(const char *sm, const PatchOff &fo)
+    {
+        v[0] = *reinterpret_cast<const uint4 *>(sm + fo.a[BLK] + KS * 64);
+        v[1] = *reinterpret_cast<const uint4 *>(sm + fo.a[BLK] + KS * 64 + 16);
+    }
     template <int KS, int BLK, int ROWS> __device__ __forceinline__ void read(const char *sm, const FragOff<float, false, ROWS> &fo)
     {
         v[0] = *reinterpret_cast<const uint4 *>(sm + fo.o[KS][BLK % 2][0] + (BLK / 2) * (64 * 128));
@@ -615,6 +627,48 @@ __device__ __forceinline__ void compute_tile(const uint4 *sA, const uint4 *sB, f
     });
 }
 
+// Output of a block tile: the accumulators go through LDS, 64 rows of the block tile at a time, so that every
+// lane ends up with 8 consecutive columns of one row and a wave stores whole row segments (the MFMA layout
+// gives a lane 4 columns of one row and its neighbours other rows).
+// acc[nb][mb][v]: m = wm + mb*32 + lrow, n = wn + nb*32 + 8*(v/4) + 4*half + v%4
+template <typename T, class Cfg, int SMEM_BYTES>
+__device__ __forceinline__ void output_tile(uint4 *smem, f32x16 (&acc)[Cfg::NB][Cfg::MB], const Epilogue &ep, int tm, int tn, int split, int M,
+                                            int N, float *ws, const float (&bias8)[8], int tid, int wm, int wn)
+{
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB;
+    constexpr int PITCH = BN + 4;                 // floats; 64 * PITCH * 4 bytes fit the tile buffers
+    static_assert(64 * PITCH * 4 <= SMEM_BYTES, "staging area");
+    float *stg = reinterpret_cast<float *>(smem);
+    constexpr int LPR = BN / 8, RPR = NT / LPR;   // lanes per row, rows per round
+    const int lane = tid & 63, lrow = lane & 31, half = lane >> 5;
+    static_for<0, BM / 64>([&](auto p) ASGD_INLINE {
+        __syncthreads();
+        static_for<0, MB>([&](auto mb) ASGD_INLINE {
+            const int rb = wm + mb * 32 - 64 * p;   // first row of this block within the pass
+            if (rb == 0 || rb == 32) {
+                static_for<0, NB>([&](auto nb) ASGD_INLINE {
+                    static_for<0, 4>([&](auto g) ASGD_INLINE {
+                        *reinterpret_cast<float4 *>(stg + (rb + lrow) * PITCH + wn + nb * 32 + 8 * g + 4 * half) =
+                            make_float4(acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]);
+                    });
+                });
+            }
+        });
+        __syncthreads();
+        static_for<0, 64 / RPR>([&](auto r) ASGD_INLINE {
+            const int row = r * RPR + tid / LPR, col = (tid % LPR) * 8;
+            const int m = tm * BM + 64 * p + row, n0 = tn * BN + col;
+            if (m < M && n0 < N) {
+                const float4 lo = *reinterpret_cast<const float4 *>(stg + row * PITCH + col);
+                const float4 hi = *reinterpret_cast<const float4 *>(stg + row * PITCH + col + 4);
+                float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                if (ws) store8<float>(ws + ((long)split * M + m) * N + n0, v);
+                else epilogue8<T>(ep, m, n0, v, bias8);
+            }
+        });
+    });
+}
+
 // Software pipeline.  LDS holds two stages so that one barrier per K tile
 // suffices; DEPTH K tiles are in flight in registers while another is being
 // multiplied out of LDS.  At the top of step t, LDS stage t%2 holds tile t and
@@ -651,7 +705,6 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
 
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = (wave % Cfg::WAVES_M) * (BM / Cfg::WAVES_M), wn = (wave / Cfg::WAVES_M) * (BN / Cfg::WAVES_N);
-    const int lrow = lane & 31, half = lane >> 5;
     FragOff<T, LA::kTrans, BM> foA;
     FragOff<T, LB::kTrans, BN> foB;
     foA.init(wm, lane);
@@ -680,41 +733,183 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
         }
     }
 
-    // Output: the accumulators go through LDS, 64 rows of the block tile at a time, so that every lane ends
-    // up with 8 consecutive columns of one row and a wave stores whole row segments (the MFMA layout gives a
-    // lane 4 columns of one row and its neighbours other rows).
-    // acc[nb][mb][v]: m = wm + mb*32 + lrow, n = wn + nb*32 + 8*(v/4) + 4*half + v%4
-    constexpr int PITCH = BN + 4;                 // floats; 64 * PITCH * 4 bytes fit the tile buffers
-    static_assert(64 * PITCH * 4 <= (int)sizeof(smem), "staging area");
-    float *stg = reinterpret_cast<float *>(smem);
-    constexpr int LPR = BN / 8, RPR = NT / LPR;   // lanes per row, rows per round
     if (dbg & 8) return;
-    static_for<0, BM / 64>([&](auto p) ASGD_INLINE {
-        __syncthreads();
-        static_for<0, MB>([&](auto mb) ASGD_INLINE {
-            const int rb = wm + mb * 32 - 64 * p;   // first row of this block within the pass
-            if (rb == 0 || rb == 32) {
-                static_for<0, NB>([&](auto nb) ASGD_INLINE {
-                    static_for<0, 4>([&](auto g) ASGD_INLINE {
-                        *reinterpret_cast<float4 *>(stg + (rb + lrow) * PITCH + wn + nb * 32 + 8 * g + 4 * half) =
-                            make_float4(acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]);
-                    });
-                });
-            }
-        });
-        __syncthreads();
-        static_for<0, 64 / RPR>([&](auto r) ASGD_INLINE {
-            const int row = r * RPR + tid / LPR, col = (tid % LPR) * 8;
-            const int m = tm * BM + 64 * p + row, n0 = tn * BN + col;
-            if (m < M && n0 < N) {
-                const float4 lo = *reinterpret_cast<const float4 *>(stg + row * PITCH + col);
-                const float4 hi = *reinterpret_cast<const float4 *>(stg + row * PITCH + col + 4);
-                float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                if (ws) store8<float>(ws + ((long)split * M + m) * N + n0, v);
-                else epilogue8<T>(ep, m, n0, v, bias8);
-            }
-        });
+    output_tile<T, Cfg, (int)sizeof(smem)>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
+}
+
+// ------------------------------------------------------------------ patch convolution
+// Stride-1 convolutions whose output grid equals the input grid (and their data gradients, which have the
+// same form).  With channel-last storage the input pixel that output pixel m needs at window position
+// (ky, kx) is pixel m + (ky - pad) * W + (kx - pad) of the flattened tensor, whenever it is inside the image.
+// So the 128 output pixels of a block tile need, for ALL window positions, one contiguous run of
+// 128 + (kh-1) * W + (kw-1) input pixels.  The K loop therefore runs channel chunk by channel chunk (one
+// chunk = one K tile = 128 bytes of channels): the run of pixels of the chunk (the patch) is brought into LDS
+// once and serves the kh * kw K tiles of the chunk, the A fragment of a window position being the same LDS
+// read at a shifted address.  Only the weights are fetched and written to LDS per K tile, which about halves
+// what a workgroup pulls through the L2-to-CU path and takes a quarter off its LDS traffic compared with the
+// im2col-style gather.  Window positions outside the image (zero padding, and rows past M) are handled per
+// lane: its fragment address is redirected to a pixel of zeros kept behind the patch.  Pixels sit 144 bytes
+// apart in LDS: 16 consecutive pixels' 16-byte pieces then fall into 16 different groups of four banks,
+// whatever pixel the run starts at.
+constexpr int kPatchPitch = 144;
+
+// The weights [rows][npos][C] as the B operand when K tiles enumerate (chunk, window position).
+template <typename T> struct ChunkK {
+    static constexpr bool kTrans = false;
+    Operand op; unsigned ldb, posb; int rows, C, npos;   // posb: bytes from one window position to the next
+    FastDiv dnpos;
+    struct Row { unsigned off; };
+    struct KPos { int pos, c; unsigned koff; };
+    __device__ __forceinline__ Row row(int r) const { return Row{r < rows ? (unsigned)r * ldb : kInv}; }
+    __device__ __forceinline__ unsigned off_of(int pos, int c) const
+    {
+        return c < C ? (unsigned)pos * posb + (unsigned)c * (unsigned)sizeof(T) : kInv;
+    }
+    // k = K tile * BK + element inside the tile
+    __device__ __forceinline__ KPos kpos(int k) const
+    {
+        const int t = k / (int)Geo<T>::BK, e = k % (int)Geo<T>::BK;
+        const int ch = (int)fdiv((uint32_t)t, dnpos), pos = t - ch * npos, c = ch * (int)Geo<T>::BK + e;
+        return KPos{pos, c, off_of(pos, c)};
+    }
+    __device__ __forceinline__ void advance(KPos &kp, int) const
+    {
+        const bool wrap = kp.pos + 1 == npos;
+        kp.pos = wrap ? 0 : kp.pos + 1;
+        kp.c += wrap ? (int)Geo<T>::BK : 0;
+        kp.koff = off_of(kp.pos, kp.c);
+    }
+    __device__ __forceinline__ unsigned voff(const Row &r, const KPos &kp) const { return r.off + kp.koff; }
+};
+
+template <typename T> struct PatchSrc {
+    Operand op; unsigned pix;              // bytes from one pixel to the next
+    int H, W, C, kh, kw, pad, npos, M;     // M: pixels of the tensor = GEMM rows
+    FastDiv dW, dHW, dkw, dnpos;
+};
+
+template <typename T, int NPL>
+__global__ __launch_bounds__(Cfg128w8::NT, 2) void conv_patch_kernel(PatchSrc<T> pa, ChunkK<T> lb, Epilogue ep, int M, int N, int nkt,
+                                                                    int kt_per_split, int tiles_m, int tiles_n, float *ws, int dbg)
+{
+    using Cfg = Cfg128w8;
+    constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB;
+    constexpr int TB = BN * 128;
+    constexpr int PPMAX = NPL * NT / 8;                   // pixels the patch buffer holds
+    constexpr int PBYTES = (PPMAX + 1) * kPatchPitch;     // and one pixel of zeros behind them
+    static_assert(MB == 2 && BM == 128, "two row blocks per wave");
+    __shared__ uint4 smem[(2 * TB + PBYTES) / 16];        // two stages of B tiles, the patch; reused to stage the output
+    uint4 (*sB)[TB / 16] = reinterpret_cast<uint4 (*)[TB / 16]>(smem);
+    char *sP = reinterpret_cast<char *>(smem + 2 * TB / 16);
+    const int tid = threadIdx.x;
+    int bid;
+    {
+        const int nb = gridDim.x, q = nb >> 3, r = nb & 7, x = blockIdx.x & 7;
+        bid = x * q + (x < r ? x : r) + (blockIdx.x >> 3);
+    }
+    const int tn = bid % tiles_n; bid /= tiles_n;
+    const int tm = bid % tiles_m;
+    const int split = bid / tiles_m;
+    const int kt0 = split * kt_per_split;
+    const int nt = min(nkt, kt0 + kt_per_split) - kt0;
+
+    Stage<T, ChunkK<T>, BN, NT, 2> stB;
+    stB.init(lb, tn * BN, kt0 * BK, tid, NT / 2);
+
+    // window position and chunk of the first K tile (all uniform)
+    int ch = (int)fdiv((uint32_t)kt0, pa.dnpos);
+    int pos = kt0 - ch * pa.npos;
+    int ky = (int)fdiv((uint32_t)pos, pa.dkw), kx = pos - ky * pa.kw;
+
+    // patch pieces of this thread: piece q = tid + j * NT is slot q & 7 (= tid & 7) of patch pixel q >> 3
+    const __amdgpu_buffer_rsrc_t prs = pa.op.rsrc();
+    const int slot = tid & 7;
+    const int gp0 = tm * BM - pa.pad * pa.W - pa.pad + (tid >> 3);   // tensor pixel of piece 0
+    unsigned poff[NPL];
+    static_for<0, NPL>([&](auto j) ASGD_INLINE {
+        const int gp = gp0 + j * (NT / 8);
+        poff[j] = (gp >= 0 && gp < pa.M) ? (unsigned)gp * pa.pix + (unsigned)slot * 16u : kInv;
     });
+    const unsigned pwo = (unsigned)((tid >> 3) * kPatchPitch + slot * 16);
+    uint4 pr[NPL];
+    auto patch_load = [&](int chunk) ASGD_INLINE {
+        const unsigned coff = (chunk * BK + slot * (int)Geo<T>::CH < pa.C) ? (unsigned)chunk * 128u : kInv;
+        static_for<0, NPL>([&](auto j) ASGD_INLINE { pr[j] = buf_ld16(prs, poff[j] + coff); });
+    };
+    auto patch_store = [&]() ASGD_INLINE {
+        static_for<0, NPL>([&](auto j) ASGD_INLINE {
+            *reinterpret_cast<uint4 *>(sP + pwo + j * (NT / 8) * kPatchPitch) = pr[j];
+        });
+    };
+
+    f32x16 acc[NB][MB];
+    static_for<0, NB>([&](auto i) ASGD_INLINE { static_for<0, MB>([&](auto j) ASGD_INLINE { acc[i][j] = f32x16{}; }); });
+
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave % Cfg::WAVES_M) * (BM / Cfg::WAVES_M), wn = (wave / Cfg::WAVES_M) * (BN / Cfg::WAVES_N);
+    const int lrow = lane & 31, half = lane >> 5;
+    FragOff<T, false, BN> foB;
+    foB.init(wn, lane);
+    // the two fragment rows of this lane: patch address at window position (0, 0) and the mask of positions inside the image
+    constexpr unsigned kHalfBytes = 8 * (unsigned)sizeof(T);
+    const unsigned zero_addr = (unsigned)(PPMAX * kPatchPitch) + (unsigned)half * kHalfBytes;
+    unsigned abase[2], amask[2];
+    static_for<0, 2>([&](auto mb) ASGD_INLINE {
+        const int rr = wm + mb * 32 + lrow, m = tm * BM + rr;
+        abase[mb] = (unsigned)(rr * kPatchPitch) + (unsigned)half * kHalfBytes;
+        unsigned mask = 0;
+        if (m < M) {
+            const int n = (int)fdiv((uint32_t)m, pa.dHW);
+            const int rem = m - n * (pa.H * pa.W);
+            const int y = (int)fdiv((uint32_t)rem, pa.dW);
+            const int y0 = y - pa.pad, x0 = rem - y * pa.W - pa.pad;
+            const int ylo = max(0, -y0), yhi = max(ylo, min(pa.kh, pa.H - y0));
+            const int xlo = max(0, -x0), xhi = max(xlo, min(pa.kw, pa.W - x0));
+            const unsigned xm = ((1u << xhi) - 1u) & ~((1u << xlo) - 1u);
+            for (int a = ylo; a < yhi; ++a) mask |= xm << (a * pa.kw);
+        }
+        amask[mb] = mask;
+    });
+
+    float bias8[8];
+    load_bias8<T>(ep, tn * BN + (tid % (BN / 8)) * 8, bias8);
+
+    if (tid < kPatchPitch / 16) *reinterpret_cast<uint4 *>(sP + PPMAX * kPatchPitch + tid * 16) = make_uint4(0u, 0u, 0u, 0u);
+    patch_load(ch);
+    stB.template load<0>(lb);
+    stB.template load<1>(lb);
+    patch_store();
+    stB.template store<0>(sB[0], tid);
+    patch_load(ch + 1);
+
+    // One K tile: the B pipeline is that of gemm_kernel; when a tile opens a new chunk, the patch fetched during
+    // the previous chunk replaces the old one between two barriers and the fetch of the next one is issued.
+    auto step = [&](auto par, bool first, bool more) ASGD_INLINE {
+        __syncthreads();
+        if (pos == 0 && !first) {
+            patch_store();
+            __syncthreads();
+            ++ch;
+            patch_load(ch + 1);
+        }
+        stB.template load<par>(lb);
+        PatchOff foA;
+        const unsigned sh = (unsigned)((ky * pa.W + kx) * kPatchPitch);
+        foA.a[0] = ((amask[0] >> pos) & 1u) ? abase[0] + sh : zero_addr;
+        foA.a[1] = ((amask[1] >> pos) & 1u) ? abase[1] + sh : zero_addr;
+        if (!(dbg & 4)) compute_tile<T, MB, NB>(reinterpret_cast<const uint4 *>(sP), sB[par], acc, foA, foB);
+        ++pos; ++kx;
+        if (kx == pa.kw) { kx = 0; ++ky; }
+        if (pos == pa.npos) { pos = 0; ky = 0; kx = 0; }
+        if (more) stB.template store<1 - par>(sB[1 - par], tid);
+    };
+    for (int t = 0; t < nt; t += 2) {
+        step(std::integral_constant<int, 0>{}, t == 0, t + 1 < nt);
+        if (t + 1 < nt) step(std::integral_constant<int, 1>{}, false, t + 2 < nt);
+    }
+
+    if (dbg & 8) return;
+    output_tile<T, Cfg, (int)sizeof(smem)>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
 }
 
 template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int splits, Epilogue ep, int M, int N)
@@ -862,10 +1057,67 @@ template <typename T> static PlainT<T> make_plain_t(const void *p, long ld, int 
     return PlainT<T>{operand(p, ((size_t)(K - 1) * ld + rows) * sizeof(T)), (unsigned)(ld * sizeof(T)), rows, K};
 }
 
+// The patch form applies to stride-1 convolutions with equal input and output grids over a dense tensor whose
+// run of pixels per block tile fits the patch buffer.  ASGD_NOPATCH in the environment switches it off.
+template <typename T> static bool patch_applies(const Gather &a, long ldb)
+{
+    static const bool off = getenv("ASGD_NOPATCH") != nullptr;
+    const size_t pixb = a.pix ? a.pix : (size_t)a.C * sizeof(T);
+    const int npos = a.kh * a.kw;
+    // a chunk is a whole K tile: with channel counts that are not multiples of one (96 = 1.5 tiles) the patch
+    // form multiplies more K tiles than the gather, which packs K densely; beyond 15 % more it loses
+    const int BK = (int)Geo<T>::BK;
+    const long nkt_patch = (long)((a.C + BK - 1) / BK) * npos, nkt_gather = ((long)npos * a.C + BK - 1) / BK;
+    if (nkt_patch * 100 > nkt_gather * 115) return false;
+    return !off && a.sm == 1 && a.ds == 1 && a.Ho == a.H && a.Wo == a.W && npos > 1 && npos <= 32 && 2 * a.pad == a.kh - 1 &&
+           2 * a.pad == a.kw - 1 && (a.rowb == 0 || a.rowb == (size_t)a.W * pixb) && pixb % 16 == 0 && a.C % (int)Geo<T>::CH == 0 &&
+           ((uintptr_t)a.x & 15) == 0 && ldb == (long)npos * a.C && 128 + (a.kh - 1) * a.W + a.kw - 1 <= 256;
+}
+
+template <typename T>
+static int run_patch(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
+{
+    using Cfg = Cfg128w8;
+    constexpr int BK = Geo<T>::BK;
+    const int M = a.N * a.H * a.W, npos = a.kh * a.kw, K = npos * a.C;
+    if (M <= 0 || N <= 0 || (N & 7)) return -1;
+    PatchSrc<T> pa;
+    pa.op = operand(a.x, a.bytes);
+    pa.pix = a.pix ? (unsigned)a.pix : (unsigned)(a.C * sizeof(T));
+    pa.H = a.H; pa.W = a.W; pa.C = a.C; pa.kh = a.kh; pa.kw = a.kw; pa.pad = a.pad; pa.npos = npos; pa.M = M;
+    pa.dW = make_fastdiv(a.W); pa.dHW = make_fastdiv(a.H * a.W); pa.dkw = make_fastdiv(a.kw); pa.dnpos = make_fastdiv(npos);
+    ChunkK<T> lb;
+    lb.op = operand(b, ((size_t)(N - 1) * ldb + K) * sizeof(T));
+    lb.ldb = (unsigned)(ldb * sizeof(T)); lb.posb = (unsigned)(a.C * sizeof(T)); lb.rows = N; lb.C = a.C; lb.npos = npos;
+    lb.dnpos = pa.dnpos;
+    if (pa.op.bytes == 0 || lb.op.bytes == 0) return -1;
+    const int tiles_m = (M + Cfg::BM - 1) / Cfg::BM, tiles_n = (N + Cfg::BN - 1) / Cfg::BN;
+    const int nkt = ((a.C + BK - 1) / BK) * npos;
+    int splits = plan.splits;
+    if (splits > 1 && ws == nullptr) return -1;
+    const int per = (nkt + splits - 1) / splits;
+    splits = (nkt + per - 1) / per;
+    const long blocks = (long)tiles_m * tiles_n * splits;
+    if (blocks > 0x7fffffffL) return -1;
+    const int pp = 128 + (a.kh - 1) * a.W + a.kw - 1;   // pixels a block tile needs
+    if (pp <= 192)
+        hipLaunchKernelGGL((conv_patch_kernel<T, 3>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m, tiles_n,
+                           splits > 1 ? ws : nullptr, debug_bits());
+    else
+        hipLaunchKernelGGL((conv_patch_kernel<T, 4>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m, tiles_n,
+                           splits > 1 ? ws : nullptr, debug_bits());
+    if (splits > 1) {
+        const long groups = (long)M * (N / 8);
+        hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);
+    }
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 template <typename T>
 static int gather_plain_t(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
     const int K = a.kh * a.kw * a.C;
+    if (patch_applies<T>(a, ldb)) return run_patch<T>(a, b, ldb, N, ep, plan, ws, s);
     if (a.ds == 1 && a.kh * a.kw <= 32)
         return run<T>(make_gather_k<T, false>(a), make_plain_k<T>(b, ldb, N, K), a.N * a.Ho * a.Wo, N, K, ep, plan, ws, s);
     if (a.ds == 1)

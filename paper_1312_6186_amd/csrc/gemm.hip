@@ -722,13 +722,17 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
         // step t (even): multiply out of LDS stage 0, fetch tile t+DEPTH, then move tile t+1 into stage 1
         __syncthreads();
         stA.template load<0>(la); stB.template load<0>(lb);   // past the last tile this fetches zeros, which nothing consumes
+        __builtin_amdgcn_s_setprio(1);   // the waves that multiply go first; those of the other workgroup are fetching or waiting
         if (!(dbg & 4)) compute_tile<T, MB, NB>(sA[0], sB[0], acc, foA, foB);
+        __builtin_amdgcn_s_setprio(0);
         if (t + 1 < nt) {
             stA.template store<DEPTH - 1>(sA[1], tid); stB.template store<DEPTH - 1>(sB[1], tid);
             // step t+1 (odd): multiply out of LDS stage 1, fetch tile t+1+DEPTH, then move tile t+2 into stage 0
             __syncthreads();
             stA.template load<DEPTH - 1>(la); stB.template load<DEPTH - 1>(lb);
+            __builtin_amdgcn_s_setprio(1);   // the waves that multiply go first; those of the other workgroup are fetching or waiting
             if (!(dbg & 4)) compute_tile<T, MB, NB>(sA[1], sB[1], acc, foA, foB);
+            __builtin_amdgcn_s_setprio(0);
             if (t + 2 < nt) { stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid); }
         }
     }
@@ -897,7 +901,9 @@ __global__ __launch_bounds__(Cfg128w8::NT, 2) void conv_patch_kernel(PatchSrc<T>
         const unsigned sh = (unsigned)((ky * pa.W + kx) * kPatchPitch);
         foA.a[0] = ((amask[0] >> pos) & 1u) ? abase[0] + sh : zero_addr;
         foA.a[1] = ((amask[1] >> pos) & 1u) ? abase[1] + sh : zero_addr;
+        __builtin_amdgcn_s_setprio(1);
         if (!(dbg & 4)) compute_tile<T, MB, NB>(reinterpret_cast<const uint4 *>(sP), sB[par], acc, foA, foB);
+        __builtin_amdgcn_s_setprio(0);
         ++pos; ++kx;
         if (kx == pa.kw) { kx = 0; ++ky; }
         if (pos == pa.npos) { pos = 0; ky = 0; kx = 0; }

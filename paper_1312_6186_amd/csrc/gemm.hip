@@ -48,6 +48,7 @@ template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int DEPTH_, int MINB_> s
 };
 using Cfg128 = TileCfg<128, 128, 2, 2, 2, 2>;   // 256 threads (wave tile 64x64), two workgroups per CU: two waves per SIMD
 using Cfg128w8 = TileCfg<128, 128, 2, 4, 2, 2>; // 512 threads (wave tile 64x32), two workgroups per CU: four waves per SIMD
+using Cfg64n = TileCfg<128, 64, 2, 2, 2, 4>;     // 256 threads (wave tile 64x32), four workgroups per CU: four waves per SIMD
 #define ASGD_INLINE __attribute__((always_inline))
 
 // Compile-time loop: indices reach the body as constants, so register arrays are never addressed dynamically.
@@ -792,11 +793,10 @@ template <typename T> struct PatchSrc {
     FastDiv dW, dHW, dkw, dnpos;
 };
 
-template <typename T, int NPL>
-__global__ __launch_bounds__(Cfg128w8::NT, 2) void conv_patch_kernel(PatchSrc<T> pa, ChunkK<T> lb, Epilogue ep, int M, int N, int nkt,
+template <typename T, int NPL, class Cfg>
+__global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc<T> pa, ChunkK<T> lb, Epilogue ep, int M, int N, int nkt,
                                                                     int kt_per_split, int tiles_m, int tiles_n, float *ws, int dbg)
 {
-    using Cfg = Cfg128w8;
     constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB;
     constexpr int TB = BN * 128;
     constexpr int PPMAX = NPL * NT / 8;                   // pixels the patch buffer holds
@@ -1080,10 +1080,21 @@ template <typename T> static bool patch_applies(const Gather &a, long ldb)
            ((uintptr_t)a.x & 15) == 0 && ldb == (long)npos * a.C && 128 + (a.kh - 1) * a.W + a.kw - 1 <= 256;
 }
 
+template <typename T, class Cfg>
+static int run_patch_cfg(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s);
 template <typename T>
 static int run_patch(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
-    using Cfg = Cfg128w8;
+    // Both shapes run wave tiles of 64 x 32 at four waves per SIMD and take the same time per tile; the narrow one
+    // fills the chip better when the wide one would leave more than an eighth of the 512 workgroup slots empty
+    // (conv5 at batch 128: 338 workgroups against 676).
+    const long wide = (long)((a.N * a.H * a.W + 127) / 128) * ((N + 127) / 128) * plan.splits;
+    if (N > 64 && wide < 448) return run_patch_cfg<T, Cfg64n>(a, b, ldb, N, ep, plan, ws, s);
+    return run_patch_cfg<T, Cfg128w8>(a, b, ldb, N, ep, plan, ws, s);
+}
+template <typename T, class Cfg>
+static int run_patch_cfg(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
+{
     constexpr int BK = Geo<T>::BK;
     const int M = a.N * a.H * a.W, npos = a.kh * a.kw, K = npos * a.C;
     if (M <= 0 || N <= 0 || (N & 7)) return -1;
@@ -1106,12 +1117,14 @@ static int run_patch(const Gather &a, const void *b, long ldb, int N, const Epil
     const long blocks = (long)tiles_m * tiles_n * splits;
     if (blocks > 0x7fffffffL) return -1;
     const int pp = 128 + (a.kh - 1) * a.W + a.kw - 1;   // pixels a block tile needs
-    if (pp <= 192)
-        hipLaunchKernelGGL((conv_patch_kernel<T, 3>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m, tiles_n,
-                           splits > 1 ? ws : nullptr, debug_bits());
+    // pieces per thread for short runs (up to 192 pixels with 512 threads, 160 with 256) and for runs of up to 256 pixels
+    constexpr int NPL_S = Cfg::NT == 512 ? 3 : 5, NPL_L = 256 * 8 / Cfg::NT;
+    if (pp <= NPL_S * Cfg::NT / 8)
+        hipLaunchKernelGGL((conv_patch_kernel<T, NPL_S, Cfg>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
+                           tiles_n, splits > 1 ? ws : nullptr, debug_bits());
     else
-        hipLaunchKernelGGL((conv_patch_kernel<T, 4>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m, tiles_n,
-                           splits > 1 ? ws : nullptr, debug_bits());
+        hipLaunchKernelGGL((conv_patch_kernel<T, NPL_L, Cfg>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
+                           tiles_n, splits > 1 ? ws : nullptr, debug_bits());
     if (splits > 1) {
         const long groups = (long)M * (N / 8);
         hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);

@@ -44,6 +44,18 @@ GROUPED = dict(name="grouped", in_shape=(3, 23, 21), classes=10,
                        ("fc", 10), ("softmax_ce",)])
 
 
+# stride-1 convolutions with equal input and output grids over enough channels take the patch form: 120 channels
+# (a partial last chunk of channels in both element types), 3x3 and 5x5 windows, 120 output columns (a ragged
+# column tile), rows that are no multiple of the tile, K ranges of a split that begin in the middle of a chunk
+PATCHNET = dict(name="patch", in_shape=(3, 15, 13), classes=10,
+                layers=[("conv", 120, 3, 1, 1), ("relu",), ("conv", 120, 3, 1, 1), ("relu",), ("conv", 16, 5, 1, 2), ("relu",),
+                        ("maxpool", 3, 2), ("fc", 10), ("softmax_ce",)])
+# the same on rows of 27 pixels with a 5x5 window: the longer run of pixels per tile (240), 72 output columns (narrow tiles)
+PATCHWIDE = dict(name="patchwide", in_shape=(3, 8, 27), classes=10,
+                 layers=[("conv", 64, 3, 1, 1), ("relu",), ("conv", 72, 5, 1, 2), ("relu",), ("conv", 8, 5, 1, 2), ("relu",),
+                         ("maxpool", 2, 2), ("fc", 10), ("softmax_ce",)])
+
+
 # ---------------------------------------------------------------- update / snapshot
 @pytest.mark.parametrize("n,offset", [(1, 0), (1023, 0), (4099, 0), (15898, 0), (100003, 1), (1 << 20, 4)])
 def test_apply_update_matches_oracle(n, offset):
@@ -162,8 +174,9 @@ def _net_case(cfg, batch, dtype, seed=0, step=0, worker=0, bias_noise=0.05):
 
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
-@pytest.mark.parametrize("cfg,batch", [(wl.TINY, 8), (wl.TINY, 1), (RAGGED, 5), (RAGGED, 131), (WIDE, 3), (LRNNET, 7), (GROUPED, 6), (wl.SMALL, 128)],
-                         ids=["tiny", "tiny-batch1", "ragged5", "ragged131", "wide", "lrn", "grouped", "small"])
+@pytest.mark.parametrize("cfg,batch", [(wl.TINY, 8), (wl.TINY, 1), (RAGGED, 5), (RAGGED, 131), (WIDE, 3), (LRNNET, 7), (GROUPED, 6), (PATCHNET, 5),
+                                       (PATCHWIDE, 3), (wl.SMALL, 128)],
+                         ids=["tiny", "tiny-batch1", "ragged5", "ragged131", "wide", "lrn", "grouped", "patch", "patchwide", "small"])
 def test_minibatch_gradient_matches_oracle(cfg, batch, dtype):
     g, onet, (loss, grads), (ref_loss, ref_grads, trace), _ = _net_case(cfg, batch, dtype, seed=3002, step=4, worker=1)
     try:

@@ -710,6 +710,9 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
     FragOff<T, LB::kTrans, BN> foB;
     foA.init(wm, lane);
     foB.init(wn, lane);
+    // a wave whose whole tile lies outside C (96 output columns in a tile of 128: a quarter of the waves) only helps
+    // to move the operands; wave-uniform, like the debug switch that turns all multiplication off
+    const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N && !(dbg & 4)) ? 1 : 0) != 0;
 
     // every output row this thread writes has the same 8 columns: fetch their bias now, behind the first tiles
     float bias8[8];
@@ -724,7 +727,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
         __syncthreads();
         stA.template load<0>(la); stB.template load<0>(lb);   // past the last tile this fetches zeros, which nothing consumes
         __builtin_amdgcn_s_setprio(1);   // the waves that multiply go first; those of the other workgroup are fetching or waiting
-        if (!(dbg & 4)) compute_tile<T, MB, NB>(sA[0], sB[0], acc, foA, foB);
+        if (busy) compute_tile<T, MB, NB>(sA[0], sB[0], acc, foA, foB);
         __builtin_amdgcn_s_setprio(0);
         if (t + 1 < nt) {
             stA.template store<DEPTH - 1>(sA[1], tid); stB.template store<DEPTH - 1>(sB[1], tid);
@@ -732,7 +735,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
             __syncthreads();
             stA.template load<DEPTH - 1>(la); stB.template load<DEPTH - 1>(lb);
             __builtin_amdgcn_s_setprio(1);   // the waves that multiply go first; those of the other workgroup are fetching or waiting
-            if (!(dbg & 4)) compute_tile<T, MB, NB>(sA[1], sB[1], acc, foA, foB);
+            if (busy) compute_tile<T, MB, NB>(sA[1], sB[1], acc, foA, foB);
             __builtin_amdgcn_s_setprio(0);
             if (t + 2 < nt) { stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid); }
         }
@@ -854,6 +857,9 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
     const int lrow = lane & 31, half = lane >> 5;
     FragOff<T, false, BN> foB;
     foB.init(wn, lane);
+    // a wave whose whole tile lies outside C (96 output columns in a tile of 128: a quarter of the waves) only helps
+    // to move the operands; wave-uniform, like the debug switch that turns all multiplication off
+    const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N && !(dbg & 4)) ? 1 : 0) != 0;
     // the two fragment rows of this lane: patch address at window position (0, 0) and the mask of positions inside the image
     constexpr unsigned kHalfBytes = 8 * (unsigned)sizeof(T);
     const unsigned zero_addr = (unsigned)(PPMAX * kPatchPitch) + (unsigned)half * kHalfBytes;
@@ -902,7 +908,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
         foA.a[0] = ((amask[0] >> pos) & 1u) ? abase[0] + sh : zero_addr;
         foA.a[1] = ((amask[1] >> pos) & 1u) ? abase[1] + sh : zero_addr;
         __builtin_amdgcn_s_setprio(1);
-        if (!(dbg & 4)) compute_tile<T, MB, NB>(reinterpret_cast<const uint4 *>(sP), sB[par], acc, foA, foB);
+        if (busy) compute_tile<T, MB, NB>(reinterpret_cast<const uint4 *>(sP), sB[par], acc, foA, foB);
         __builtin_amdgcn_s_setprio(0);
         ++pos; ++kx;
         if (kx == pa.kw) { kx = 0; ++ky; }

@@ -1019,10 +1019,11 @@ static int run(const LA &la, const LB &lb, int M, int N, int K, const Epilogue &
 {
     if (M <= 0 || N <= 0 || K <= 0 || (N & 7)) return -1;
     if (la.op.bytes == 0 || lb.op.bytes == 0) return -1;   // an operand beyond the 1 GiB the 32-bit offsets cover
-    // Measured on the AlexNet-style shapes: the 8-wave form (four waves per SIMD hide more latency) wins
-    // everywhere except the convolution filter gradient, whose two transposing operands make it bound by LDS
-    // reads, of which the narrower wave tile needs half as many again.
-    if constexpr (std::is_same<LB, GatherT<T>>::value) return run_tile<T, Cfg128>(la, lb, M, N, K, ep, plan, ws, s);
+    // Measured on the AlexNet-style shapes: the 8-wave form (four waves per SIMD hide more latency) wins everywhere
+    // except the fp32 convolution filter gradient, whose two transposing operands cost eight 4-byte LDS reads per
+    // fragment: the wider wave tile of the 4-wave form needs a third fewer of them.  (In bf16 the 4-wave form was
+    // ahead there too until the multiplying waves got their raised priority.)
+    if constexpr (std::is_same<LB, GatherT<T>>::value && sizeof(T) == 4) return run_tile<T, Cfg128>(la, lb, M, N, K, ep, plan, ws, s);
     else return run_tile<T, Cfg128w8>(la, lb, M, N, K, ep, plan, ws, s);
 }
 

@@ -4,23 +4,30 @@
 //
 // Geometry (identical in bytes for both element types): a workgroup owns a
 // 128 x 128 tile of C; one K tile is 128 bytes per row (64 bf16 or 32 fp32).
-// Two workgroups share a CU.  Most GEMMs run 8 wave64 per workgroup (wave tile
-// 64 x 32, four waves per SIMD); the convolution filter gradient runs 4 (wave
-// tile 64 x 64).  Operands arrive through range-checked 16-byte buffer loads
-// (out-of-range pieces read as zeros), two K tiles ahead, into registers, and go
-// from there to one of two LDS stages, so that one barrier per K tile suffices.
-// An operand whose memory has K contiguous sits in LDS as rows x 8 slots of 16
-// bytes, the slot index XOR-swizzled with the row so that fragment reads and
-// stores are spread over the banks.  An operand whose memory has the GEMM row
-// contiguous and K strided (both operands of the filter gradients, the weights
-// in the FC data gradient) is copied to LDS in that orientation and transposed
-// by the LDS read itself (ds_read_b64_tr_b16).  The MFMA is issued with the
-// B-matrix fragment as its first operand so that a lane ends up with four
-// consecutive n for one m.  The output goes through LDS once more, so that a
-// lane owns 8 consecutive columns of a row and a wave stores whole row segments
-// as 16-byte vectors.  Workgroup ids are remapped so that each of the 8 XCDs
-// (which receive ids round-robin) works on a contiguous range of tiles and its
-// L2 sees neighbouring tiles' shared operand rows.
+// Two workgroups share a CU.  The GEMMs run 8 wave64 per workgroup (wave tile
+// 64 x 32, four waves per SIMD), except the fp32 convolution filter gradient,
+// which runs 4 (wave tile 64 x 64).  Operands arrive through range-checked 16-byte
+// buffer loads (out-of-range pieces read as zeros), two K tiles ahead, into
+// registers, and go from there to one of two LDS stages, so that one barrier per
+// K tile suffices.  An operand whose memory has K contiguous sits in LDS as rows
+// x 8 slots of 16 bytes, the slot index XOR-swizzled with the row so that
+// fragment reads and stores are spread over the banks.  An operand whose memory
+// has the GEMM row contiguous and K strided (both operands of the filter
+// gradients, the weights in the FC data gradient) is copied to LDS in that
+// orientation and transposed by the LDS read itself (ds_read_b64_tr_b16).  The
+// MFMA is issued with the B-matrix fragment as its first operand so that a lane
+// ends up with four consecutive n for one m.  The output goes through LDS once
+// more, so that a lane owns 8 consecutive columns of a row and a wave stores
+// whole row segments as 16-byte vectors.  Workgroup ids are remapped so that each
+// of the 8 XCDs (which receive ids round-robin) works on a contiguous range of
+// tiles and its L2 sees neighbouring tiles' shared operand rows.  A wave runs at
+// raised priority while it multiplies a tile, and a wave whose part of the tile
+// lies outside C does not multiply at all.
+//
+// Stride-1 convolutions whose output grid equals their input grid have a second
+// kernel (conv_patch_kernel, further down): the run of input pixels that the 128
+// output pixels of a tile need is staged in LDS once per 128 bytes of channels
+// and serves every window position from there.
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>

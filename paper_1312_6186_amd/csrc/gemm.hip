@@ -729,23 +729,29 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
     stA.template load<0>(la); stB.template load<0>(lb);
     if constexpr (DEPTH == 2) { stA.template load<1>(la); stB.template load<1>(lb); }
     stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid);
-    for (int t = 0; t < nt; t += 2) {
+    // The loop body is two whole steps without a condition in it, so that the compiler knows exactly which fetches are
+    // in flight at its head (with a conditional store it has to assume that those of two steps ago may be, and
+    // waits for everything before it issues the next ones).  The store at the end of the last pair moves a tile that
+    // exists only if the number of tiles is odd; otherwise it moves zeros that nobody reads.
+    for (int i = nt >> 1; i > 0; --i) {
         // step t (even): multiply out of LDS stage 0, fetch tile t+DEPTH, then move tile t+1 into stage 1
         __syncthreads();
-        stA.template load<0>(la); stB.template load<0>(lb);   // past the last tile this fetches zeros, which nothing consumes
+        stA.template load<0>(la); stB.template load<0>(lb);   // past the last tile this fetches zeros
         __builtin_amdgcn_s_setprio(1);   // the waves that multiply go first; those of the other workgroup are fetching or waiting
         if (busy) compute_tile<T, MB, NB>(sA[0], sB[0], acc, foA, foB);
         __builtin_amdgcn_s_setprio(0);
-        if (t + 1 < nt) {
-            stA.template store<DEPTH - 1>(sA[1], tid); stB.template store<DEPTH - 1>(sB[1], tid);
-            // step t+1 (odd): multiply out of LDS stage 1, fetch tile t+1+DEPTH, then move tile t+2 into stage 0
-            __syncthreads();
-            stA.template load<DEPTH - 1>(la); stB.template load<DEPTH - 1>(lb);
-            __builtin_amdgcn_s_setprio(1);   // the waves that multiply go first; those of the other workgroup are fetching or waiting
-            if (busy) compute_tile<T, MB, NB>(sA[1], sB[1], acc, foA, foB);
-            __builtin_amdgcn_s_setprio(0);
-            if (t + 2 < nt) { stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid); }
-        }
+        stA.template store<DEPTH - 1>(sA[1], tid); stB.template store<DEPTH - 1>(sB[1], tid);
+        // step t+1 (odd): multiply out of LDS stage 1, fetch tile t+1+DEPTH, then move tile t+2 into stage 0
+        __syncthreads();
+        stA.template load<DEPTH - 1>(la); stB.template load<DEPTH - 1>(lb);
+        __builtin_amdgcn_s_setprio(1);
+        if (busy) compute_tile<T, MB, NB>(sA[1], sB[1], acc, foA, foB);
+        __builtin_amdgcn_s_setprio(0);
+        stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid);
+    }
+    if (nt & 1) {
+        __syncthreads();
+        if (busy) compute_tile<T, MB, NB>(sA[0], sB[0], acc, foA, foB);
     }
 
     if (dbg & 8) return;

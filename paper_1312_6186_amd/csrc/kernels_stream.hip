@@ -580,12 +580,17 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const T *__restrict__ dy,
         for (int q = 0; q < 4; ++q) {   // (py0, px0), (py0, px0+1), (py0+1, px0), (py0+1, px0+1)
             const int py = py0 + (q >> 1), px = px0 + (q & 1);
             ok[q] = py <= py1 && px <= px1;
-            const int pyc = min(py, Ho - 1), pxc = min(px, Wo - 1);   // a readable address either way
             pos[q] = (iy - py * stride) * k + (ix - px * stride);
-            const long off = (((long)n * Ho + pyc) * Wo + pxc) * Cp + c0;
-            g[q].u = *reinterpret_cast<const uint4 *>(dy + off);
-            if (V == 8) a8[q] = *reinterpret_cast<const uint64_t *>(arg + off);
-            else a8[q] = *reinterpret_cast<const uint32_t *>(arg + off);
+            const long off = (((long)n * Ho + py) * Wo + px) * Cp + c0;
+            // windows that do not cover the pixel (more than half of the candidates for 3/2 pooling) are not fetched:
+            // the kernel is bound by what it pulls out of L2, not by HBM
+            g[q].u = make_uint4(0u, 0u, 0u, 0u);
+            a8[q] = 0;
+            if (ok[q]) {
+                g[q].u = *reinterpret_cast<const uint4 *>(dy + off);
+                if (V == 8) a8[q] = *reinterpret_cast<const uint64_t *>(arg + off);
+                else a8[q] = *reinterpret_cast<const uint32_t *>(arg + off);
+            }
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) add(g[q], a8[q], pos[q], ok[q]);

@@ -51,8 +51,8 @@ struct Stage {
     bool last = false;           // produces the fp32 logits
     int k = 0, stride = 1, pad = 0;
     int groups = 1;   // convolution channel groups
-    // window-row form (first stage, <= 4 input channels): bordered input [B][rwHp][rwWp][4], K = k * rwKW
-    int rw = 0, rwKW = 0, rwHp = 0, rwWp = 0;
+    // window-row form (first stage, <= 4 input channels): bordered input [B][rwHp][rwWp][rwC], K = k * rwKW
+    int rw = 0, rwC = 0, rwKW = 0, rwHp = 0, rwWp = 0;
     int relu = 0, drop = 0, drop_layer = -1;
     float lrn_alpha = 0.f, lrn_beta = 0.f, lrn_bias = 0.f;   // ST_LRN (window size in k)
     bool has_params() const { return kind == ST_CONV || kind == ST_FC; }
@@ -131,7 +131,7 @@ size_t carve(asgd_net &n, char *base)
     // the arena is cleared once when it is allocated: the zero border of a bordered input is never written
     // afterwards; tensors are spaced by 256 spare bytes
     const Stage *s0 = n.stages.empty() ? nullptr : &n.stages[0];
-    n.act0 = at((s0 && s0->rw ? B * s0->rwHp * s0->rwWp * 4 : B * n.in_h * n.in_w * n.in_cp) * es + 256);
+    n.act0 = at((s0 && s0->rw ? B * s0->rwHp * s0->rwWp * s0->rwC : B * n.in_h * n.in_w * n.in_cp) * es + 256);
     for (size_t i = 0; i < n.stages.size(); ++i) {
         Stage &s = n.stages[i];
         const size_t oe = B * s.out_elems();
@@ -182,14 +182,22 @@ int plan_net(asgd_net &n)
             s.outC = l.out; s.outCp = round_up(l.out, 8);
             s.outH = (H + 2 * l.pad - l.k) / l.stride + 1;
             s.outW = (W + 2 * l.pad - l.k) / l.stride + 1;
-            // First layer over <= 4 channels: padding them to 8 would make most of the reduction zeros.  Keep 4 per
-            // pixel and merge (kx, c) into one contiguous run instead, if the 16-byte pieces stay aligned.
+            // First layer over <= 4 channels: padding them to 8 would make most of the reduction zeros.  Keep the
+            // pixels narrow and merge (kx, c) into one contiguous run per window row instead.  Pixels of exactly C
+            // channels if the window origins (stride * C elements apart) stay dword-aligned, which is all a 16-byte
+            // buffer load needs; else 4 channels per pixel if that keeps them 16-byte aligned; else the general form.
             const int es0 = (int)dtype_size(n.dtype);
-            if (n.stages.empty() && C <= 4 && s.groups == 1 && (l.stride * 4 * es0) % 16 == 0) {
-                s.rw = 1;
-                s.rwKW = round_up(l.k * 4, 8);   // the filter-gradient GEMM wants its column count in eights
+            int rwC = 0;
+            if (n.stages.empty() && C <= 4 && s.groups == 1) {
+                if ((l.stride * C * es0) % 4 == 0) rwC = C;
+                else if ((l.stride * 4 * es0) % 16 == 0) rwC = 4;
+            }
+            if (rwC) {
+                s.rw = 1; s.rwC = rwC;
+                s.rwKW = round_up(l.k * rwC, 8);   // the filter-gradient GEMM wants its column count in eights
                 s.rwHp = H + 2 * l.pad;
-                s.rwWp = round_up(std::max(W + 2 * l.pad, (s.outW - 1) * l.stride + s.rwKW / 4), 16 / (4 * es0) > 1 ? 2 : 1);
+                // a row holds the border and the padded run of the last window; an even width keeps rows dword-aligned
+                s.rwWp = round_up(std::max(W + 2 * l.pad, (s.outW - 1) * l.stride + (s.rwKW + rwC - 1) / rwC), 2);
             }
             s.w_off = off; s.w_cnt = (size_t)l.out * (C / s.groups) * l.k * l.k; s.b_off = off + s.w_cnt; s.b_cnt = l.out;
             off += s.w_cnt + s.b_cnt;
@@ -285,7 +293,7 @@ int plan_net(asgd_net &n)
         if (s.kind == ST_CONV) {
             const long M = B * s.outH * s.outW, Min = B * s.inH * s.inW;
             const long K = s.rw ? (long)s.k * s.rwKW : (long)s.k * s.k * s.inCp;
-            if (s.rw && (long)B * s.rwHp * s.rwWp * 16 > 0x7fffffffL) return fail(ASGD_ESHAPE, "layer %d: tensor too large", s.first_layer);
+            if (s.rw && (long)B * s.rwHp * s.rwWp * s.rwC * 4 > 0x7fffffffL) return fail(ASGD_ESHAPE, "layer %d: tensor too large", s.first_layer);
             if (M > 0x7fffffffL / 2 || Min > 0x7fffffffL / 2 || M * s.outCp * 4 > 0x7fffffffL || Min * s.inCp * 4 > 0x7fffffffL) return fail(ASGD_ESHAPE, "layer %d: tensor too large", s.first_layer);
             if (s.groups > 1) {   // one GEMM per group, on that group's channel slices
                 const long Cg = s.inC / s.groups, Og = s.outC / s.groups, Kg = (long)s.k * s.k * Cg;
@@ -422,8 +430,8 @@ Gather conv_gather(const Stage &s, const void *x, int B, int dt, int group = 0)
     }
     if (s.rw) {
         g.H = s.rwHp; g.W = s.rwWp; g.C = s.rwKW; g.kh = s.k; g.kw = 1; g.pad = 0;
-        g.pix = 4 * es; g.rowb = (size_t)s.rwWp * 4 * es;
-        g.bytes = (size_t)B * s.rwHp * s.rwWp * 4 * es;
+        g.pix = (size_t)s.rwC * es; g.rowb = (size_t)s.rwWp * s.rwC * es;
+        g.bytes = (size_t)B * s.rwHp * s.rwWp * s.rwC * es;
     } else {
         g.H = s.inH; g.W = s.inW; g.C = s.inCp; g.kh = g.kw = s.k; g.pad = s.pad;
         g.bytes = (size_t)B * s.inH * s.inW * s.inCp * es;
@@ -441,7 +449,7 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
     {
         ProfScope ps(n, st, ASGD_K_LAYOUT, 0, 2 * Bd * n->in_c * n->in_h * n->in_w * es);
         const Stage &s0 = n->stages[0];
-        if (s0.rw) CHECK_LAUNCH(launch_stage_input_rw(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, s0.pad, s0.rwWp, st), "stage_input");
+        if (s0.rw) CHECK_LAUNCH(launch_stage_input_rw(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, s0.pad, s0.rwWp, s0.rwC, st), "stage_input");
         else CHECK_LAUNCH(launch_stage_input(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, n->in_cp, st), "stage_input");
     }
     // filter packing: beside the input staging and the first layers (in line when profiling, to be timed alone)
@@ -487,7 +495,7 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
             }
             PackJob &J = jobs.j[jobs.n++];
             J.w = param_ptr(n, params, s.w_off); J.wf = s.wf; J.wd = s.rw ? nullptr : s.wd;
-            J.cout = s.outC; J.cin = s.inC; J.k = s.k; J.coutp = s.outCp; J.cinp = s.inCp; J.rw = s.rw; J.KW = s.rwKW;
+            J.cout = s.outC; J.cin = s.inC; J.k = s.k; J.coutp = s.outCp; J.cinp = s.inCp; J.rw = s.rw ? s.rwC : 0; J.KW = s.rwKW;
             bytes += (double)s.w_cnt * es * (J.wd ? 3 : 2);
             if (jobs.n == 12) { const int rc = flush(); if (rc != ASGD_OK) return rc; }
         }
@@ -668,7 +676,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
                     const Gather g = conv_gather(s, xin, B, dt);
                     Epilogue ew;
                     ew.out = grads + s.w_off; ew.mode = s.rw ? 2 : 1; ew.out_f32 = 1;
-                    ew.cw_cout = s.outC; ew.cw_cin = s.inC; ew.cw_cinp = s.rw ? s.rwKW : s.inCp; ew.cw_kh = s.k; ew.cw_kw = s.k;
+                    ew.cw_cout = s.outC; ew.cw_cin = s.inC; ew.cw_cinp = s.rw ? s.rwKW : s.inCp; ew.cw_kh = s.k; ew.cw_kw = s.k; ew.cw_rwc = s.rw ? s.rwC : 4;
                     CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch_side, sd), "conv filter gradient");
                 }
             }

@@ -38,8 +38,9 @@ struct Epilogue {
     long mask_ld = 0;
     float mask_scale = 1.f;
     int mode = 0;          // 1: rows are cout, columns are (ky,kx,ci_padded) -> [cout][cin][kh][kw]
-                           // 2: columns are (ky, kx*4+ci) over window rows of cw_cinp elements -> the same
+                           // 2: columns are (ky, kx*cw_rwc+ci) over window rows of cw_cinp elements -> the same
     int cw_cout = 0, cw_cin = 0, cw_cinp = 0, cw_kh = 0, cw_kw = 0;
+    int cw_rwc = 4;        // mode 2: channels per stored pixel (column j of a window row is kx * cw_rwc + ci)
 };
 
 // Gather description for an implicit-GEMM operand taken from a channel-last
@@ -101,10 +102,10 @@ int launch_snapshot(const float *src, void *dst, size_t n, int dst_dtype, const 
 // images [B][C][H][W] (compute type) -> channel-last [B][H][W][Cp], zero padding channels
 int launch_stage_input(int dtype, const void *src, void *dst, int B, int C, int H, int W, int Cp, hipStream_t s);
 // the same into the interior of a bordered [B][H+2*pad][Wp][4] tensor (C <= 4; the border is not written)
-int launch_stage_input_rw(int dtype, const void *src, void *dst, int B, int C, int H, int W, int pad, int Wp, hipStream_t s);
+int launch_stage_input_rw(int dtype, const void *src, void *dst, int B, int C, int H, int W, int pad, int Wp, int pc, hipStream_t s);
 // Filter packing for all convolution layers of a net in one launch.  Per layer: canonical filters
 // [cout][cin][k][k] -> forward pack wf [coutp][k][k][cinp] and, if wd is given, the flipped data-gradient pack
-// wd [cinp][k][k][coutp]; or (rw) the window-row pack wf [coutp][k][KW], element (ky, kx*4 + ci), zeros elsewhere.
+// wd [cinp][k][k][coutp]; or (rw = channels per stored pixel > 0) the window-row pack wf [coutp][k][KW], element (ky, kx*rw + ci), zeros elsewhere.
 struct PackJob {
     const void *w; void *wf; void *wd;
     int cout, cin, k, coutp, cinp, rw, KW;

@@ -576,13 +576,13 @@ template <typename T> __device__ __forceinline__ void epilogue8(const Epilogue &
             if (ci0 + r < ep.cw_cin) o[(((long)m * ep.cw_cin + ci0 + r) * ep.cw_kh + ky) * ep.cw_kw + kx] = v[r];
         return;
     }
-    if (ep.mode == 2) {  // the same for window rows: columns are (ky, j), j = kx*4 + ci over a padded row of cw_cinp elements
+    if (ep.mode == 2) {  // the same for window rows: columns are (ky, j), j = kx*cw_rwc + ci over a padded row of cw_cinp elements
         if (m >= ep.cw_cout) return;
         const int ky = n0 / ep.cw_cinp, j0 = n0 - ky * ep.cw_cinp;
         float *o = static_cast<float *>(ep.out);
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            const int kx = (j0 + r) >> 2, ci = (j0 + r) & 3;
+            const int kx = (j0 + r) / ep.cw_rwc, ci = (j0 + r) - kx * ep.cw_rwc;
             if (ci < ep.cw_cin && kx < ep.cw_kw) o[(((long)m * ep.cw_cin + ci) * ep.cw_kh + ky) * ep.cw_kw + kx] = v[r];
         }
         return;

@@ -350,29 +350,60 @@ int launch_stage_input(int dtype, const void *src, void *dst, int B, int C, int 
     return launch_ok();
 }
 
-template <typename T> __global__ __launch_bounds__(256) void stage_input_rw_kernel(const T *__restrict__ src, T *__restrict__ dst, int B, int C,
-                                                                                 int H, int W, int pad, int Wp)
+template <typename T, int PC> __global__ __launch_bounds__(256) void stage_input_rw_kernel(const T *__restrict__ src, T *__restrict__ dst, int B, int C,
+                                                                                         int H, int W, int pad, int Wp)
+{
+    // a thread moves two neighbouring pixels of a row (W is even, checked by the launcher): 2 * PC elements, which
+    // for every PC and element size make a whole number of dwords at a dword-aligned address
+    const long HW = (long)H * W, HW2 = HW / 2;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long)B * HW2) return;
+    const long n = i / HW2, hw = (i - n * HW2) * 2;
+    const int h = (int)(hw / W), w = (int)(hw - (long)h * W);
+    union { T e[2 * PC]; uint32_t u[2 * PC * sizeof(T) / 4]; } v;
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int c = 0; c < PC; ++c) v.e[q * PC + c] = c < C ? src[(n * C + c) * HW + hw + q] : (T)0.f;
+    uint32_t *o = reinterpret_cast<uint32_t *>(dst + ((n * (H + 2 * pad) + h + pad) * Wp + w + pad) * PC);
+#pragma unroll
+    for (int d = 0; d < (int)(2 * PC * sizeof(T) / 4); ++d) o[d] = v.u[d];
+}
+// one pixel per thread, element stores: any width
+template <typename T> __global__ __launch_bounds__(256) void stage_input_rw_any_kernel(const T *__restrict__ src, T *__restrict__ dst, int B, int C,
+                                                                                     int H, int W, int pad, int Wp, int pc)
 {
     const long HW = (long)H * W;
     const long i = (long)blockIdx.x * 256 + threadIdx.x;
     if (i >= (long)B * HW) return;
     const long n = i / HW, hw = i - n * HW;
     const int h = (int)(hw / W), w = (int)(hw - (long)h * W);
-    union { T e[4]; uint2 u2; uint4 u4; } v;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) v.e[c] = c < C ? src[(n * C + c) * HW + hw] : (T)0.f;
-    T *o = dst + ((n * (H + 2 * pad) + h + pad) * Wp + w + pad) * 4;
-    if constexpr (sizeof(T) == 2) *reinterpret_cast<uint2 *>(o) = v.u2;
-    else *reinterpret_cast<uint4 *>(o) = v.u4;
+    T *o = dst + ((n * (H + 2 * pad) + h + pad) * Wp + w + pad) * pc;
+    for (int c = 0; c < pc; ++c) o[c] = c < C ? src[(n * C + c) * HW + hw] : (T)0.f;
 }
-int launch_stage_input_rw(int dtype, const void *src, void *dst, int B, int C, int H, int W, int pad, int Wp, hipStream_t s)
+template <typename T>
+static void launch_stage_input_rw_t(const void *src, void *dst, int B, int C, int H, int W, int pad, int Wp, int pc, hipStream_t s)
 {
-    if (C > 4) return -1;
-    const unsigned blocks = blocks_for((size_t)B * H * W, 256);
-    if (dtype == kBF16)
-        hipLaunchKernelGGL(stage_input_rw_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, static_cast<const bf16_t *>(src), static_cast<bf16_t *>(dst), B, C, H, W, pad, Wp);
-    else
-        hipLaunchKernelGGL(stage_input_rw_kernel<float>, dim3(blocks), dim3(256), 0, s, static_cast<const float *>(src), static_cast<float *>(dst), B, C, H, W, pad, Wp);
+    const T *a = static_cast<const T *>(src); T *o = static_cast<T *>(dst);
+    // the pair form needs both pixels in one row and every pair dword-aligned: (pad * pc), (Wp * pc) elements even in bytes / 4
+    const bool pairs = (W % 2 == 0) && ((size_t)pad * pc * sizeof(T)) % 4 == 0 && ((size_t)Wp * pc * sizeof(T)) % 4 == 0 &&
+                       ((size_t)2 * pc * sizeof(T)) % 4 == 0;
+    if (pairs) {
+        const unsigned blocks = blocks_for((size_t)B * H * W / 2, 256);
+        switch (pc) {
+        case 1: hipLaunchKernelGGL((stage_input_rw_kernel<T, 1>), dim3(blocks), dim3(256), 0, s, a, o, B, C, H, W, pad, Wp); return;
+        case 2: hipLaunchKernelGGL((stage_input_rw_kernel<T, 2>), dim3(blocks), dim3(256), 0, s, a, o, B, C, H, W, pad, Wp); return;
+        case 3: hipLaunchKernelGGL((stage_input_rw_kernel<T, 3>), dim3(blocks), dim3(256), 0, s, a, o, B, C, H, W, pad, Wp); return;
+        case 4: hipLaunchKernelGGL((stage_input_rw_kernel<T, 4>), dim3(blocks), dim3(256), 0, s, a, o, B, C, H, W, pad, Wp); return;
+        }
+    }
+    hipLaunchKernelGGL(stage_input_rw_any_kernel<T>, dim3(blocks_for((size_t)B * H * W, 256)), dim3(256), 0, s, a, o, B, C, H, W, pad, Wp, pc);
+}
+int launch_stage_input_rw(int dtype, const void *src, void *dst, int B, int C, int H, int W, int pad, int Wp, int pc, hipStream_t s)
+{
+    if (C > pc || pc < 1 || pc > 4) return -1;
+    if (dtype == kBF16) launch_stage_input_rw_t<bf16_t>(src, dst, B, C, H, W, pad, Wp, pc, s);
+    else launch_stage_input_rw_t<float>(src, dst, B, C, H, W, pad, Wp, pc, s);
     return launch_ok();
 }
 
@@ -392,12 +423,12 @@ template <typename T> __global__ __launch_bounds__(256) void pack_conv_kernel(Pa
     const long kk = (long)k * k;
     __attribute__((aligned(16))) T out[8];
     T *dst;
-    if (J.rw) {  // wf[co][ky][j], j = kx*4 + ci over a padded window row of KW elements
+    if (J.rw) {  // wf[co][ky][j], j = kx*rw + ci over a padded window row of KW elements (rw channels per stored pixel)
         const int j0 = (int)(li % (unsigned)J.KW); unsigned t = li / (unsigned)J.KW;
         const int ky = (int)(t % (unsigned)k), co = (int)(t / (unsigned)k);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const int kx = (j0 + e) >> 2, ci = (j0 + e) & 3;
+            const int kx = (j0 + e) / J.rw, ci = (j0 + e) - kx * J.rw;
             out[e] = (co < J.cout && ci < J.cin && kx < k) ? w[((long)co * J.cin + ci) * kk + ky * k + kx] : (T)0.f;
         }
         dst = static_cast<T *>(J.wf) + li;

@@ -651,11 +651,89 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const T *__restrict__ dy,
     *reinterpret_cast<uint4 *>(dx + off) = o.u;
 }
 
+// Stride 2, windows of 2 or 3: a thread owns a 2 x 2 block of input pixels (rows 2*jy, 2*jy+1, columns 2*jx,
+// 2*jx+1).  Exactly the four windows (jy-1 .. jy) x (jx-1 .. jx) can cover it: window (jy, jx) covers all four
+// pixels, the two neighbours above / to the left cover the pixels of the block's first row / column (3 x 3
+// only), the diagonal one its first pixel.  The four windows are fetched once for the four pixels (the
+// pixel-per-thread form fetches 2.25 windows per pixel) and each recorded position is decoded once.  The sums
+// run over the windows in the same order as in the general kernel, so the results are the same bit for bit.
+template <typename T, int K>
+__global__ __launch_bounds__(256) void pool_bwd_s2_kernel(const T *__restrict__ dy, const uint8_t *__restrict__ arg, const T *__restrict__ x, int relu,
+                                                        T *__restrict__ dx, int B, int H, int W, int Cp, int Ho, int Wo, PoolIndex pi)
+{
+    constexpr int V = Vec16<T>::N;
+    const uint32_t i = xcd_block() * 256u + threadIdx.x;
+    if (i >= (uint32_t)B * pi.h * pi.w * pi.cv) return;
+    int cg, jx, jy, n;
+    pool_decode(i, pi, cg, jx, jy, n);
+    const int c0 = cg * V;
+    Vec16<T> g[4];
+    uint64_t a8[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {   // windows (jy-1, jx-1), (jy-1, jx), (jy, jx-1), (jy, jx)
+        const int py = jy - 1 + (q >> 1), px = jx - 1 + (q & 1);
+        g[q].u = make_uint4(0u, 0u, 0u, 0u);
+        a8[q] = ~0ull;   // no position matches
+        if (py >= 0 && py < Ho && px >= 0 && px < Wo) {
+            const long off = (((long)n * Ho + py) * Wo + px) * Cp + c0;
+            g[q].u = *reinterpret_cast<const uint4 *>(dy + off);
+            if (V == 8) a8[q] = *reinterpret_cast<const uint64_t *>(arg + off);
+            else a8[q] = *reinterpret_cast<const uint32_t *>(arg + off) | 0xffffffff00000000ull;
+        }
+    }
+    float acc[4][V];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[b][e] = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            const int pos = (int)((a8[q] >> (8 * e)) & 0xff);
+            const float ge = ldf(&g[q].e[e]);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {   // pixel (by, bx) of the block sits at (by + 2*(1 - wy), bx + 2*(1 - wx)) in window q
+                constexpr int dummy = 0; (void)dummy;
+                const int wy = q >> 1, wx = q & 1, by = b >> 1, bx = b & 1;
+                const int ry = by + 2 * (1 - wy), rx = bx + 2 * (1 - wx);
+                if (ry < K && rx < K) acc[b][e] += pos == ry * K + rx ? ge : 0.f;
+            }
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const int iy = 2 * jy + (b >> 1), ix = 2 * jx + (b & 1);
+        if (iy < H && ix < W) {
+            const long off = (((long)n * H + iy) * W + ix) * Cp + c0;
+            Vec16<T> o;
+            if (relu) {
+                Vec16<T> xv;
+                xv.u = *reinterpret_cast<const uint4 *>(x + off);
+#pragma unroll
+                for (int e = 0; e < V; ++e) stf(&o.e[e], ldf(&xv.e[e]) > 0.f ? acc[b][e] : 0.f);
+            } else {
+#pragma unroll
+                for (int e = 0; e < V; ++e) stf(&o.e[e], acc[b][e]);
+            }
+            *reinterpret_cast<uint4 *>(dx + off) = o.u;
+        }
+    }
+}
+
 template <typename T>
 static void launch_pool_bwd_t(const void *dy, const uint8_t *arg, const void *x, int relu, void *dx, int B, int H, int W, int Cp, int k, int stride,
                               int Ho, int Wo, unsigned blocks, hipStream_t s)
 {
     const T *d = static_cast<const T *>(dy), *xx = static_cast<const T *>(x); T *o = static_cast<T *>(dx);
+    if (stride == 2 && (k == 2 || k == 3)) {
+        const int Hb = (H + 1) / 2, Wb = (W + 1) / 2, cv = Cp / (16 / (int)sizeof(T));
+        const PoolIndex pb = make_pool_index(cv, Wb, Hb);
+        const unsigned nb = blocks_for((size_t)B * Hb * Wb * cv, 256);
+        if (k == 3) hipLaunchKernelGGL((pool_bwd_s2_kernel<T, 3>), dim3(nb), dim3(256), 0, s, d, arg, xx, relu, o, B, H, W, Cp, Ho, Wo, pb);
+        else hipLaunchKernelGGL((pool_bwd_s2_kernel<T, 2>), dim3(nb), dim3(256), 0, s, d, arg, xx, relu, o, B, H, W, Cp, Ho, Wo, pb);
+        return;
+    }
     const PoolIndex pi = make_pool_index(Cp / (16 / (int)sizeof(T)), W, H);
     const FastDiv ds = make_fastdiv((uint32_t)stride);
     if (k <= 2 * stride) hipLaunchKernelGGL((pool_bwd_kernel<T, true>), dim3(blocks), dim3(256), 0, s, d, arg, xx, relu, o, B, H, W, Cp, k, stride, Ho, Wo, pi, ds);

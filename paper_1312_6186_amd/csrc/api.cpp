@@ -65,6 +65,8 @@ struct Stage {
     void *wf = nullptr, *wd = nullptr;
     void *flat_in = nullptr, *dflat_in = nullptr;
     float *colsum_ws = nullptr; size_t colsum_floats = 0;   // band sums of the bias gradient
+    long pool_bands = 0;       // CONV directly under a pool whose backward kernel leaves those band sums: their number
+    bool bands_ready = false;  // ... and whether the pool's backward pass of this call has left them
     GemmPlan p_fwd, p_dgrad, p_wgrad;
     size_t out_elems() const { return kind == ST_FC ? (size_t)out_ld : (size_t)outH * outW * outCp; }
 };
@@ -307,6 +309,11 @@ int plan_net(asgd_net &n)
             }
             scratch_side = std::max(scratch_side, s.p_wgrad.ws_floats);
             s.colsum_floats = colsum_ws_floats(n.dtype, M, s.outCp);
+            if (si + 1 < n.stages.size() && n.stages[si + 1].kind == ST_POOL) {
+                const Stage &pl = n.stages[si + 1];
+                s.pool_bands = pool_bwd_bands(n.dtype, B, s.outH, s.outW, s.outCp, pl.k, pl.stride);
+                s.colsum_floats = std::max(s.colsum_floats, (size_t)s.pool_bands * s.outCp);
+            }
         } else if (s.kind == ST_FC) {
             s.p_fwd = plan_gemm(B, s.out_ld, s.in_f, n.dtype, 32);
             s.p_dgrad = plan_gemm(B, s.in_f, s.out_f, n.dtype, 32);
@@ -652,9 +659,14 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
             const bool relu_here = prev && prev->kind == ST_CONV && prev->relu && !masked_above;
             ProfScope ps(n, st, ASGD_K_POOL_BWD, 0,
                          Bd * s.outC * ((double)s.outH * s.outW * (es + 1) + (double)s.inH * s.inW * es * (relu_here ? 2 : 1)));
-            if (prev)
-                CHECK_LAUNCH(launch_pool_bwd(dt, s.dout, s.argmax, prev->out, relu_here, prev->dout, B, s.inH, s.inW, s.inCp, s.k, s.stride, st),
+            if (prev) {
+                // what this writes is the output gradient of a convolution directly below: the kernel can leave the
+                // first stage of that layer's bias gradient behind, which saves reading the tensor again
+                float *bands = nullptr;
+                if (prev->kind == ST_CONV && prev->pool_bands > 0) { bands = prev->colsum_ws; prev->bands_ready = true; }
+                CHECK_LAUNCH(launch_pool_bwd(dt, s.dout, s.argmax, prev->out, relu_here, prev->dout, B, s.inH, s.inW, s.inCp, s.k, s.stride, bands, st),
                              "pool backward");
+            }
         } else {
             const long M = (long)B * s.outH * s.outW;
             const double Mo = (double)M, conv_flops = 2 * Mo * s.outC * (s.inC / s.groups) * s.k * s.k;
@@ -681,8 +693,15 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
                 }
             }
             {
-                ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, Mo * s.outC * es + s.outC * 4.0);
-                CHECK_LAUNCH(launch_colsum_partial(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, s.colsum_ws, bias_jobs, sd), "conv bias gradient");
+                ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, (s.bands_ready ? 0.0 : Mo * s.outC * es) + s.outC * 4.0);
+                if (s.bands_ready) {   // the pooling backward pass above has left the band sums
+                    s.bands_ready = false;
+                    if (bias_jobs.n >= 12) return fail(ASGD_EINVAL, "too many pending bias gradients");
+                    ColsumJob &J = bias_jobs.j[bias_jobs.n++];
+                    J.ws = s.colsum_ws; J.nblk = (int)s.pool_bands; J.ld = s.outCp; J.N = s.outC; J.db = grads + s.b_off; J.start_block = 0; J.colmajor = 1;
+                } else {
+                    CHECK_LAUNCH(launch_colsum_partial(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, s.colsum_ws, bias_jobs, sd), "conv bias gradient");
+                }
                 if (srv || bias_jobs.n == 12) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "conv bias gradient");
             }
             if (prev) {

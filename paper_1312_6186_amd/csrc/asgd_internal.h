@@ -117,7 +117,10 @@ int launch_pool_fwd(int dtype, const void *x, void *y, uint8_t *arg, int B, int 
                     hipStream_t s);
 // dx[pixel] = sum of dy over the windows whose recorded maximum is this pixel; times [x > 0] if relu
 int launch_pool_bwd(int dtype, const void *dy, const uint8_t *arg, const void *x, int relu, void *dx, int B, int H,
-                    int W, int Cp, int k, int stride, hipStream_t s);
+                    int W, int Cp, int k, int stride, float *bands, hipStream_t s);
+// bands != nullptr: the kernel also leaves the column sums of dx in bands[Cp][pool_bwd_bands(...)] (stage 1 of a
+// bias gradient); only for shapes where pool_bwd_bands is not 0
+long pool_bwd_bands(int dtype, int B, int H, int W, int Cp, int k, int stride);
 // cross-channel response normalisation on channel-last tensors: y = a * (bias + alpha * window sum of a^2)^(-beta);
 // backward writes da (times [a > 0], the ReLU of the convolution below, if relu) from a and dy; size odd, <= 9
 int launch_lrn_fwd(int dtype, const void *a, void *y, size_t pixels, int Cp, int size, float alpha, float beta, float bias, hipStream_t s);
@@ -130,7 +133,7 @@ int launch_unflatten(int dtype, const void *dflat, const void *x_for_mask, int r
 // db[n] = sum_m dy[m][n], n < N, fp32, fixed summation order, in two stages: launch_colsum_partial sums bands of
 // rows into ws (colsum_ws_floats floats, not shared with another pending job) and appends a job;
 // launch_colsum_finish adds the bands of all pending jobs (up to 12) in one launch.
-struct ColsumJob { const float *ws; float *db; long ld; int nblk, N; unsigned start_block; };
+struct ColsumJob { const float *ws; float *db; long ld; int nblk, N; unsigned start_block; int colmajor; };   // ws[band][ld], or ws[column][nblk] if colmajor
 struct ColsumJobs { ColsumJob j[12]; int n; };
 int launch_colsum_partial(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, ColsumJobs &jobs, hipStream_t s);
 int launch_colsum_finish(ColsumJobs &jobs, hipStream_t s);

@@ -657,15 +657,23 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const T *__restrict__ dy,
 // only), the diagonal one its first pixel.  The four windows are fetched once for the four pixels (the
 // pixel-per-thread form fetches 2.25 windows per pixel) and each recorded position is decoded once.  The sums
 // run over the windows in the same order as in the general kernel, so the results are the same bit for bit.
+// If bands is given, the block also leaves the column sums of what it stored (the gradient at the output of the
+// convolution below, whose bias gradient they are part of) in bands[column][block]: the values as stored (rounded
+// to the element type), added per thread over its pixels, then over the block's threads in thread order.
 template <typename T, int K>
 __global__ __launch_bounds__(256) void pool_bwd_s2_kernel(const T *__restrict__ dy, const uint8_t *__restrict__ arg, const T *__restrict__ x, int relu,
-                                                        T *__restrict__ dx, int B, int H, int W, int Cp, int Ho, int Wo, PoolIndex pi)
+                                                        T *__restrict__ dx, int B, int H, int W, int Cp, int Ho, int Wo, PoolIndex pi,
+                                                        float *__restrict__ bands)
 {
     constexpr int V = Vec16<T>::N;
-    const uint32_t i = xcd_block() * 256u + threadIdx.x;
-    if (i >= (uint32_t)B * pi.h * pi.w * pi.cv) return;
+    __shared__ float part[256 * V];
+    const uint32_t blk = xcd_block();
+    const uint32_t i = blk * 256u + threadIdx.x;
+    const bool live = i < (uint32_t)B * pi.h * pi.w * pi.cv;
+    if (!live && bands == nullptr) return;
     int cg, jx, jy, n;
-    pool_decode(i, pi, cg, jx, jy, n);
+    pool_decode(live ? i : 0u, pi, cg, jx, jy, n);
+    if (!live) { jy = -4; jx = -4; }   // no window, no pixel: contributes zeros to the band sums
     const int c0 = cg * V;
     Vec16<T> g[4];
     uint64_t a8[4];
@@ -701,10 +709,13 @@ __global__ __launch_bounds__(256) void pool_bwd_s2_kernel(const T *__restrict__ 
             }
         }
     }
+    float colsum[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) colsum[e] = 0.f;
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         const int iy = 2 * jy + (b >> 1), ix = 2 * jx + (b & 1);
-        if (iy < H && ix < W) {
+        if (iy >= 0 && iy < H && ix >= 0 && ix < W) {
             const long off = (((long)n * H + iy) * W + ix) * Cp + c0;
             Vec16<T> o;
             if (relu) {
@@ -717,21 +728,36 @@ __global__ __launch_bounds__(256) void pool_bwd_s2_kernel(const T *__restrict__ 
                 for (int e = 0; e < V; ++e) stf(&o.e[e], acc[b][e]);
             }
             *reinterpret_cast<uint4 *>(dx + off) = o.u;
+#pragma unroll
+            for (int e = 0; e < V; ++e) colsum[e] += ldf(&o.e[e]);
         }
+    }
+    if (bands == nullptr) return;
+    // thread t of the block holds channel group (blk * 256 + t) % cv: column c adds the threads of its group in order
+#pragma unroll
+    for (int e = 0; e < V; ++e) part[threadIdx.x * V + e] = colsum[e];
+    __syncthreads();
+    const int cv = pi.cv;
+    const int g0 = (int)((blk * 256u) % (uint32_t)cv);   // group of thread 0
+    for (int c = threadIdx.x; c < Cp; c += 256) {
+        const int gc = c / V, e = c - gc * V;
+        float t = 0.f;
+        for (int j = (gc - g0 + cv) % cv; j < 256; j += cv) t += part[j * V + e];
+        bands[(long)c * gridDim.x + blk] = t;
     }
 }
 
 template <typename T>
 static void launch_pool_bwd_t(const void *dy, const uint8_t *arg, const void *x, int relu, void *dx, int B, int H, int W, int Cp, int k, int stride,
-                              int Ho, int Wo, unsigned blocks, hipStream_t s)
+                              int Ho, int Wo, unsigned blocks, float *bands, hipStream_t s)
 {
     const T *d = static_cast<const T *>(dy), *xx = static_cast<const T *>(x); T *o = static_cast<T *>(dx);
     if (stride == 2 && (k == 2 || k == 3)) {
         const int Hb = (H + 1) / 2, Wb = (W + 1) / 2, cv = Cp / (16 / (int)sizeof(T));
         const PoolIndex pb = make_pool_index(cv, Wb, Hb);
         const unsigned nb = blocks_for((size_t)B * Hb * Wb * cv, 256);
-        if (k == 3) hipLaunchKernelGGL((pool_bwd_s2_kernel<T, 3>), dim3(nb), dim3(256), 0, s, d, arg, xx, relu, o, B, H, W, Cp, Ho, Wo, pb);
-        else hipLaunchKernelGGL((pool_bwd_s2_kernel<T, 2>), dim3(nb), dim3(256), 0, s, d, arg, xx, relu, o, B, H, W, Cp, Ho, Wo, pb);
+        if (k == 3) hipLaunchKernelGGL((pool_bwd_s2_kernel<T, 3>), dim3(nb), dim3(256), 0, s, d, arg, xx, relu, o, B, H, W, Cp, Ho, Wo, pb, bands);
+        else hipLaunchKernelGGL((pool_bwd_s2_kernel<T, 2>), dim3(nb), dim3(256), 0, s, d, arg, xx, relu, o, B, H, W, Cp, Ho, Wo, pb, bands);
         return;
     }
     const PoolIndex pi = make_pool_index(Cp / (16 / (int)sizeof(T)), W, H);
@@ -739,15 +765,23 @@ static void launch_pool_bwd_t(const void *dy, const uint8_t *arg, const void *x,
     if (k <= 2 * stride) hipLaunchKernelGGL((pool_bwd_kernel<T, true>), dim3(blocks), dim3(256), 0, s, d, arg, xx, relu, o, B, H, W, Cp, k, stride, Ho, Wo, pi, ds);
     else hipLaunchKernelGGL((pool_bwd_kernel<T, false>), dim3(blocks), dim3(256), 0, s, d, arg, xx, relu, o, B, H, W, Cp, k, stride, Ho, Wo, pi, ds);
 }
+// Number of column-sum bands the pooling backward pass can leave behind (0: this shape runs a kernel that cannot).
+long pool_bwd_bands(int dtype, int B, int H, int W, int Cp, int k, int stride)
+{
+    if (!(stride == 2 && (k == 2 || k == 3))) return 0;
+    const int V = dtype == kBF16 ? 8 : 4;
+    return (long)blocks_for((size_t)B * ((H + 1) / 2) * ((W + 1) / 2) * (Cp / V), 256);
+}
 int launch_pool_bwd(int dtype, const void *dy, const uint8_t *arg, const void *x, int relu, void *dx, int B, int H, int W, int Cp, int k, int stride,
-                    hipStream_t s)
+                    float *bands, hipStream_t s)
 {
     const int Ho = (H - k) / stride + 1, Wo = (W - k) / stride + 1;
     const int V = dtype == kBF16 ? 8 : 4;
     if ((size_t)B * H * W * (Cp / V) > 0x7fffffffu) return -1;
+    if (bands && pool_bwd_bands(dtype, B, H, W, Cp, k, stride) == 0) return -1;
     const unsigned blocks = blocks_for((size_t)B * H * W * (Cp / V), 256);
-    if (dtype == kBF16) launch_pool_bwd_t<bf16_t>(dy, arg, x, relu, dx, B, H, W, Cp, k, stride, Ho, Wo, blocks, s);
-    else launch_pool_bwd_t<float>(dy, arg, x, relu, dx, B, H, W, Cp, k, stride, Ho, Wo, blocks, s);
+    if (dtype == kBF16) launch_pool_bwd_t<bf16_t>(dy, arg, x, relu, dx, B, H, W, Cp, k, stride, Ho, Wo, blocks, bands, s);
+    else launch_pool_bwd_t<float>(dy, arg, x, relu, dx, B, H, W, Cp, k, stride, Ho, Wo, blocks, bands, s);
     return launch_ok();
 }
 
@@ -964,30 +998,34 @@ __global__ __launch_bounds__(256) void colsum_stage1(const T *__restrict__ dy, l
 // Stage 2 for several layers in one launch: a block owns 8 columns of one job.
 __global__ __launch_bounds__(256) void colsum_stage2(ColsumJobs jobs)
 {
-    // 32 lanes per column; a lane adds bands lane, lane+32, ... (four loads in flight), then the lanes are added in order
-    __shared__ float part[32][8];
+    // Band-major jobs (ws[band][ld], from colsum_stage1): 8 columns per block, 32 lanes per column.  Column-major
+    // jobs (ws[column][nblk], from the pooling backward pass, thousands of bands): 4 columns per block, one
+    // wavefront per column reading consecutive bands.  A lane adds bands lane, lane + L, ... (eight loads in
+    // flight), then the lanes are added in order.
+    __shared__ float part[256];
     int q = 0;
     while (q + 1 < jobs.n && blockIdx.x >= jobs.j[q + 1].start_block) ++q;
     const ColsumJob &J = jobs.j[q];
     const float *ws = J.ws;
-    const long ld = J.ld;
-    const int nblk = J.nblk, N = J.N;
-    const int tx = threadIdx.x & 7, ty = threadIdx.x >> 3;
-    const int n = (int)(blockIdx.x - J.start_block) * 8 + tx;
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    const int nblk = J.nblk, N = J.N, cm = J.colmajor, cpb = cm ? 4 : 8, L = 256 / cpb;
+    const int tx = cm ? threadIdx.x / L : threadIdx.x % cpb, ty = cm ? threadIdx.x % L : threadIdx.x / cpb;
+    const int n = (int)(blockIdx.x - J.start_block) * cpb + tx;
+    const long sb = cm ? 1 : J.ld, sn = cm ? nblk : 1;   // strides of the band and of the column index
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (n < N) {
+        const float *col = ws + (long)n * sn;
         int b = ty;
-        for (; b + 96 < nblk; b += 128) {
-            a0 += ws[(long)b * ld + n]; a1 += ws[(long)(b + 32) * ld + n];
-            a2 += ws[(long)(b + 64) * ld + n]; a3 += ws[(long)(b + 96) * ld + n];
+        for (; b + 7 * L < nblk; b += 8 * L) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a[u] += col[(long)(b + u * L) * sb];
         }
-        for (; b < nblk; b += 32) a0 += ws[(long)b * ld + n];
+        for (; b < nblk; b += L) a[0] += col[(long)b * sb];
     }
-    part[ty][tx] = (a0 + a1) + (a2 + a3);
+    part[ty * cpb + tx] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
     __syncthreads();
     if (ty == 0 && n < N) {
         float t = 0.f;
-        for (int j = 0; j < 32; ++j) t += part[j][tx];
+        for (int j = 0; j < L; ++j) t += part[j * cpb + tx];
         J.db[n] = t;
     }
 }
@@ -1019,14 +1057,19 @@ int launch_colsum_partial(int dtype, const void *dy, long ld, long M, int N, flo
     if (dtype == kBF16) hipLaunchKernelGGL(colsum_stage1<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(dy), ld, M, chunks, cpb, rl, rpb, ws);
     else hipLaunchKernelGGL(colsum_stage1<float>, grid, dim3(256), 0, s, static_cast<const float *>(dy), ld, M, chunks, cpb, rl, rpb, ws);
     ColsumJob &J = jobs.j[jobs.n++];
-    J.ws = ws; J.nblk = nblk; J.ld = ld; J.N = N; J.db = db; J.start_block = 0;
+    J.ws = ws; J.nblk = nblk; J.ld = ld; J.N = N; J.db = db; J.start_block = 0; J.colmajor = 0;
     return launch_ok();
 }
 int launch_colsum_finish(ColsumJobs &jobs, hipStream_t s)
 {
     if (jobs.n == 0) return 0;
     unsigned blocks = 0;
-    for (int q = 0; q < jobs.n; ++q) { jobs.j[q].start_block = blocks; blocks += (unsigned)((jobs.j[q].N + 7) / 8); }
+    for (int q = 0; q < jobs.n; ++q) {
+        ColsumJob &J = jobs.j[q];
+        const int cpb = J.colmajor ? 4 : 8;
+        J.start_block = blocks;
+        blocks += (unsigned)((J.N + cpb - 1) / cpb);
+    }
     hipLaunchKernelGGL(colsum_stage2, dim3(blocks), dim3(256), 0, s, jobs);
     jobs.n = 0;
     return launch_ok();

@@ -1076,7 +1076,7 @@ int launch_colsum_finish(ColsumJobs &jobs, hipStream_t s)
 }
 
 // ---------------------------------------------------------------- softmax cross-entropy
-// One wavefront per row: lse = max + log(sum exp(z - max)); the row's loss is
+// One workgroup per row: lse = max + log(sum exp(z - max)); the row's loss is
 // lse - z[label]; dz = (exp(z - lse) - [c == label]) / B.
 __device__ inline float wave_max(float v)
 {
@@ -1088,27 +1088,54 @@ __device__ inline float wave_sum(float v)
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
     return v;
 }
+// One workgroup per row: the four wavefronts each reduce their part, the four results meet in LDS.
+__device__ inline float block_max(float v, float *sh)
+{
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    v = fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+    __syncthreads();
+    return v;
+}
+__device__ inline float block_sum(float v, float *sh)
+{
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    v = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+    __syncthreads();
+    return v;
+}
 template <typename T>
 __global__ __launch_bounds__(256) void softmax_ce_kernel(const float *__restrict__ z, long ld, const int32_t *__restrict__ labels, int B, int C,
                                                        T *__restrict__ dz, float *__restrict__ row_loss)
 {
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-    if (row >= B) return;
+    __shared__ float sh[4];
+    const int row = blockIdx.x, t = threadIdx.x;
     const float *zr = z + (long)row * ld;
-    float m = -INFINITY;
-    for (int c = lane; c < C; c += 64) m = fmaxf(m, zr[c]);
-    m = wave_max(m);
+    // the first four strides of the row stay in registers (all of it up to 1024 classes)
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = t + u * 256 < C ? zr[t + u * 256] : -INFINITY;
+    float m = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
+    for (int c = t + 1024; c < C; c += 256) m = fmaxf(m, zr[c]);
+    m = block_max(m, sh);
     float sum = 0.f;
-    for (int c = lane; c < C; c += 64) sum += expf(zr[c] - m);
-    sum = wave_sum(sum);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) sum += t + u * 256 < C ? expf(v[u] - m) : 0.f;
+    for (int c = t + 1024; c < C; c += 256) sum += expf(zr[c] - m);
+    sum = block_sum(sum, sh);
     const float lse = m + logf(sum);
     const int label = labels[row];
-    if (lane == 0) row_loss[row] = lse - zr[label];
+    if (t == 0) row_loss[row] = lse - zr[label];
     const float inv_b = 1.f / (float)B;
     T *dr = dz + (long)row * ld;
-    for (int c = lane; c < (int)ld; c += 64) {
+    for (int c = t; c < (int)ld; c += 256) {
         float g = 0.f;
-        if (c < C) g = (expf(zr[c] - lse) - (c == label ? 1.f : 0.f)) * inv_b;
+        if (c < C) {
+            g = (expf(zr[c] - lse) - (c == label ? 1.f : 0.f)) * inv_b;
+        }
         stf(&dr[c], g);
     }
 }
@@ -1127,7 +1154,7 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float *__restric
 }
 int launch_softmax_ce(int dtype, const float *z, long ld, const int32_t *labels, int B, int C, void *dz, float *loss, float *row_loss, hipStream_t s)
 {
-    const unsigned blocks = (unsigned)((B + 3) / 4);
+    const unsigned blocks = (unsigned)B;
     if (dtype == kBF16) hipLaunchKernelGGL(softmax_ce_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, z, ld, labels, B, C, static_cast<bf16_t *>(dz), row_loss);
     else hipLaunchKernelGGL(softmax_ce_kernel<float>, dim3(blocks), dim3(256), 0, s, z, ld, labels, B, C, static_cast<float *>(dz), row_loss);
     hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(256), 0, s, row_loss, B, loss);

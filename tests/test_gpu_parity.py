@@ -69,6 +69,11 @@ WIDEPOOL = dict(name="widepool", in_shape=(3, 11, 13), classes=10,
                 layers=[("conv", 272, 3, 1, 1), ("relu",), ("maxpool", 3, 2), ("fc", 10), ("softmax_ce",)])
 
 
+# a pool on top of a pool: the ReLU mask of the convolution below is then applied by the lower pool's backward kernel
+POOLPOOL = dict(name="poolpool", in_shape=(3, 17, 15), classes=10,
+                layers=[("conv", 8, 3, 1, 1), ("relu",), ("maxpool", 3, 2), ("maxpool", 2, 2), ("fc", 10), ("softmax_ce",)])
+
+
 # ---------------------------------------------------------------- update / snapshot
 @pytest.mark.parametrize("n,offset", [(1, 0), (1023, 0), (4099, 0), (15898, 0), (100003, 1), (1 << 20, 4)])
 def test_apply_update_matches_oracle(n, offset):
@@ -188,9 +193,9 @@ def _net_case(cfg, batch, dtype, seed=0, step=0, worker=0, bias_noise=0.05):
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 @pytest.mark.parametrize("cfg,batch", [(wl.TINY, 8), (wl.TINY, 1), (RAGGED, 5), (RAGGED, 131), (WIDE, 3), (LRNNET, 7), (GROUPED, 6), (PATCHNET, 5),
-                                       (PATCHWIDE, 3), (CH2, 4), (CH4, 4), (WIDEPOOL, 3), (wl.SMALL, 128)],
+                                       (PATCHWIDE, 3), (CH2, 4), (CH4, 4), (WIDEPOOL, 3), (POOLPOOL, 5), (wl.SMALL, 128)],
                          ids=["tiny", "tiny-batch1", "ragged5", "ragged131", "wide", "lrn", "grouped", "patch", "patchwide", "ch2", "ch4",
-                              "widepool", "small"])
+                              "widepool", "poolpool", "small"])
 def test_minibatch_gradient_matches_oracle(cfg, batch, dtype):
     g, onet, (loss, grads), (ref_loss, ref_grads, trace), _ = _net_case(cfg, batch, dtype, seed=3002, step=4, worker=1)
     try:

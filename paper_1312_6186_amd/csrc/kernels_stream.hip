@@ -805,7 +805,9 @@ template <typename T> struct LrnWindow {
         }
     }
 };
-__device__ __forceinline__ float pow_neg(float s, float e) { return exp2f(-e * log2f(s)); }   // s^(-e), s >= bias > 0
+// s^(-e) for s >= bias > 0, far from the denormal range on both sides: the bare hardware log2 and exp2 (about one
+// ulp each) without the range fix-ups of the library routines
+__device__ __forceinline__ float pow_neg(float s, float e) { return __builtin_amdgcn_exp2f(-e * __builtin_amdgcn_logf(s)); }
 
 template <typename T, int half>   // half = size / 2, a compile-time constant so that the windows stay in registers
 __global__ __launch_bounds__(256) void lrn_fwd_kernel(const T *__restrict__ a, T *__restrict__ y, size_t groups, int Cp, float alpha, float beta,
@@ -844,16 +846,25 @@ __global__ __launch_bounds__(256) void lrn_bwd_kernel(const T *__restrict__ a, c
     wa.load(a + pix * Cp, c0, Cp);
     wd.load(dy + pix * Cp, c0, Cp);
     // for every channel j within `half` of this thread's channels: s_j, and t_j = dy_j * a_j * s_j^(-beta-1)
-    float t[V + 8], sown[V];
+    float t[V + 8], pown[V];   // pown: s^(-beta) of the thread's own channels
 #pragma unroll
     for (int q = 0; q < V + 8; ++q) {
         const int j = q - 4;                    // channel c0 + j, j in [-4, V+3] covers half <= 4
-        float sum = 0.f;
+        t[q] = 0.f;
+        if (j >= -half && j < V + half) {       // decided at compile time
+            float sum = 0.f;
 #pragma unroll
-        for (int r = -half; r <= half; ++r) sum += wa.f[R + j + r] * wa.f[R + j + r];
-        const float sj = bias + alpha * sum;
-        t[q] = (j >= -half && j < V + half) ? wd.f[R + j] * wa.f[R + j] * pow_neg(sj, beta + 1.f) : 0.f;
-        if (j >= 0 && j < V) sown[j] = sj;
+            for (int r = -half; r <= half; ++r) sum += wa.f[R + j + r] * wa.f[R + j + r];
+            const float sj = bias + alpha * sum;
+            float pj1;                          // s^(-beta-1)
+            if (j >= 0 && j < V) {              // own channel: s^(-beta) is needed too, one reciprocal gives the other
+                pown[j] = pow_neg(sj, beta);
+                pj1 = pown[j] * __builtin_amdgcn_rcpf(sj);
+            } else {
+                pj1 = pow_neg(sj, beta + 1.f);
+            }
+            t[q] = wd.f[R + j] * wa.f[R + j] * pj1;
+        }
     }
     Vec16<T> o;
 #pragma unroll
@@ -861,7 +872,7 @@ __global__ __launch_bounds__(256) void lrn_bwd_kernel(const T *__restrict__ a, c
         float acc = 0.f;
 #pragma unroll
         for (int r = -half; r <= half; ++r) acc += t[e + 4 + r];
-        float v = wd.f[R + e] * pow_neg(sown[e], beta) - 2.f * alpha * beta * wa.f[R + e] * acc;
+        float v = wd.f[R + e] * pown[e] - 2.f * alpha * beta * wa.f[R + e] * acc;
         if (relu && !(wa.f[R + e] > 0.f)) v = 0.f;
         stf(&o.e[e], v);
     }

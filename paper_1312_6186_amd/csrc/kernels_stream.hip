@@ -152,13 +152,13 @@ __device__ __forceinline__ void adagrad1(float &w, float &h, float g, float lr, 
 {
     const float t = __builtin_fmaf(wd, w, g);
     h = __builtin_fmaf(t, t, h);
-    w = w - lr * t / (__builtin_sqrtf(h) + eps);
+    w = w - lr * t * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(h) + eps);   // hardware sqrt and reciprocal: about an ulp each on the step
 }
 __device__ __forceinline__ void adadelta1(float &w, float &a, float &b, float g, float rho, float eps, float wd)
 {
     const float t = __builtin_fmaf(wd, w, g);
     a = __builtin_fmaf(rho, a, (1.f - rho) * (t * t));
-    const float d = -(__builtin_sqrtf(b + eps) / __builtin_sqrtf(a + eps)) * t;
+    const float d = -(__builtin_amdgcn_sqrtf(b + eps) * __builtin_amdgcn_rsqf(a + eps)) * t;   // hardware sqrt and reciprocal sqrt
     b = __builtin_fmaf(rho, b, (1.f - rho) * (d * d));
     w = w + d;
 }

@@ -175,6 +175,8 @@ int asgd_apply_update(float *params, float *momentum, const float *grads, size_t
  *              b = rho*b + (1-rho)*d*d;  w += d
  *   params and the state buffers (hist; avg_sq_grad, avg_sq_step): device fp32
  *   [n], updated in place, state zero before the first update; grads read only.
+ *   The square roots and quotients of the step are the hardware's approximate
+ *   ones (about one ulp each); the state recurrences are exact fp32 FMAs.
  * Errors: ASGD_EINVAL (null with n > 0), ASGD_EALIGN, ASGD_EHIP. */
 int asgd_apply_update_adagrad(float *params, float *hist, const float *grads, size_t n, float lr,
                               float eps, float wd, void *stream);

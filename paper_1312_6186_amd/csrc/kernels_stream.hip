@@ -277,14 +277,31 @@ __global__ __launch_bounds__(256) void snapshot_kernel(const float *__restrict__
     } else {
         uint16_t *d = static_cast<uint16_t *>(dst);
         const size_t n8 = vec ? n / 8 : 0;
-        for (size_t i = t0; i < n8; i += stride) {
-            const uint4 a = reinterpret_cast<const uint4 *>(src)[2 * i], b = reinterpret_cast<const uint4 *>(src)[2 * i + 1];
-            uint4 o;
-            o.x = f32_to_bf16_bits(a.x) | (f32_to_bf16_bits(a.y) << 16);
-            o.y = f32_to_bf16_bits(a.z) | (f32_to_bf16_bits(a.w) << 16);
-            o.z = f32_to_bf16_bits(b.x) | (f32_to_bf16_bits(b.y) << 16);
-            o.w = f32_to_bf16_bits(b.z) | (f32_to_bf16_bits(b.w) << 16);
-            reinterpret_cast<uint4 *>(d)[i] = o;
+        // groups of 8 elements; a thread takes four of them per round, 256 apart, and issues its eight loads first
+        typedef unsigned u32x4v __attribute__((ext_vector_type(4)));
+        constexpr int U = 4;
+        for (size_t base = (size_t)blockIdx.x * (256 * U); base < n8; base += (size_t)gridDim.x * (256 * U)) {
+            u32x4v a[U], b[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const size_t i = base + threadIdx.x + (size_t)u * 256;
+                if (i < n8) {
+                    a[u] = __builtin_nontemporal_load(&reinterpret_cast<const u32x4v *>(src)[2 * i]);
+                    b[u] = __builtin_nontemporal_load(&reinterpret_cast<const u32x4v *>(src)[2 * i + 1]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const size_t i = base + threadIdx.x + (size_t)u * 256;
+                if (i < n8) {
+                    uint4 o;
+                    o.x = f32_to_bf16_bits(a[u].x) | (f32_to_bf16_bits(a[u].y) << 16);
+                    o.y = f32_to_bf16_bits(a[u].z) | (f32_to_bf16_bits(a[u].w) << 16);
+                    o.z = f32_to_bf16_bits(b[u].x) | (f32_to_bf16_bits(b[u].y) << 16);
+                    o.w = f32_to_bf16_bits(b[u].z) | (f32_to_bf16_bits(b[u].w) << 16);
+                    reinterpret_cast<uint4 *>(d)[i] = o;
+                }
+            }
         }
         for (size_t i = n8 * 8 + t0; i < n; i += stride) d[i] = (uint16_t)f32_to_bf16_bits(__float_as_uint(src[i]));
     }

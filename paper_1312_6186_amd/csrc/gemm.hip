@@ -635,45 +635,44 @@ __device__ __forceinline__ void compute_tile(const uint4 *sA, const uint4 *sB, f
     });
 }
 
-// Output of a block tile: the accumulators go through LDS, 64 rows of the block tile at a time, so that every
-// lane ends up with 8 consecutive columns of one row and a wave stores whole row segments (the MFMA layout
-// gives a lane 4 columns of one row and its neighbours other rows).
+// Output of a block tile: the accumulators go through LDS so that every lane ends up with 8 consecutive columns
+// of one row and a wave stores whole row segments (the MFMA layout gives a lane 4 columns of one row and its
+// neighbours other rows).  The whole tile is staged at once, BM rows of BN floats without padding: the 16-byte
+// chunk index is XOR-ed with the row, so that the 16 lanes of a write (16 rows, one chunk column) and the 16
+// lanes of a read (one row, 16 chunks) each touch every bank once.
 // acc[nb][mb][v]: m = wm + mb*32 + lrow, n = wn + nb*32 + 8*(v/4) + 4*half + v%4
 template <typename T, class Cfg, int SMEM_BYTES>
 __device__ __forceinline__ void output_tile(uint4 *smem, f32x16 (&acc)[Cfg::NB][Cfg::MB], const Epilogue &ep, int tm, int tn, int split, int M,
                                             int N, float *ws, const float (&bias8)[8], int tid, int wm, int wn)
 {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB;
-    constexpr int PITCH = BN + 4;                 // floats; 64 * PITCH * 4 bytes fit the tile buffers
-    static_assert(64 * PITCH * 4 <= SMEM_BYTES, "staging area");
-    float *stg = reinterpret_cast<float *>(smem);
+    constexpr int CPR = BN / 4;                   // 16-byte chunks per row
+    static_assert(BM * BN * 4 <= SMEM_BYTES, "staging area");
+    float4 *stg = reinterpret_cast<float4 *>(smem);
     constexpr int LPR = BN / 8, RPR = NT / LPR;   // lanes per row, rows per round
     const int lane = tid & 63, lrow = lane & 31, half = lane >> 5;
-    static_for<0, BM / 64>([&](auto p) ASGD_INLINE {
-        __syncthreads();
-        static_for<0, MB>([&](auto mb) ASGD_INLINE {
-            const int rb = wm + mb * 32 - 64 * p;   // first row of this block within the pass
-            if (rb == 0 || rb == 32) {
-                static_for<0, NB>([&](auto nb) ASGD_INLINE {
-                    static_for<0, 4>([&](auto g) ASGD_INLINE {
-                        *reinterpret_cast<float4 *>(stg + (rb + lrow) * PITCH + wn + nb * 32 + 8 * g + 4 * half) =
-                            make_float4(acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]);
-                    });
-                });
-            }
+    __syncthreads();
+    static_for<0, MB>([&](auto mb) ASGD_INLINE {
+        const int row = wm + mb * 32 + lrow;
+        static_for<0, NB>([&](auto nb) ASGD_INLINE {
+            static_for<0, 4>([&](auto g) ASGD_INLINE {
+                const int chunk = (wn + nb * 32 + 8 * g + 4 * half) / 4;
+                stg[row * CPR + (chunk ^ (row & (CPR - 1)))] =
+                    make_float4(acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]);
+            });
         });
-        __syncthreads();
-        static_for<0, 64 / RPR>([&](auto r) ASGD_INLINE {
-            const int row = r * RPR + tid / LPR, col = (tid % LPR) * 8;
-            const int m = tm * BM + 64 * p + row, n0 = tn * BN + col;
-            if (m < M && n0 < N) {
-                const float4 lo = *reinterpret_cast<const float4 *>(stg + row * PITCH + col);
-                const float4 hi = *reinterpret_cast<const float4 *>(stg + row * PITCH + col + 4);
-                float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                if (ws) store8<float>(ws + ((long)split * M + m) * N + n0, v);
-                else epilogue8<T>(ep, m, n0, v, bias8);
-            }
-        });
+    });
+    __syncthreads();
+    static_for<0, BM / RPR>([&](auto r) ASGD_INLINE {
+        const int row = r * RPR + tid / LPR, chunk = (tid % LPR) * 2;
+        const int m = tm * BM + row, n0 = tn * BN + chunk * 4;
+        if (m < M && n0 < N) {
+            const float4 lo = stg[row * CPR + (chunk ^ (row & (CPR - 1)))];
+            const float4 hi = stg[row * CPR + ((chunk + 1) ^ (row & (CPR - 1)))];
+            float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            if (ws) store8<float>(ws + ((long)split * M + m) * N + n0, v);
+            else epilogue8<T>(ep, m, n0, v, bias8);
+        }
     });
 }
 
@@ -818,7 +817,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
     constexpr int PPMAX = NPL * NT / 8;                   // pixels the patch buffer holds
     constexpr int PBYTES = (PPMAX + 1) * kPatchPitch;     // and one pixel of zeros behind them
     static_assert(MB == 2 && BM == 128, "two row blocks per wave");
-    __shared__ uint4 smem[(2 * TB + PBYTES) / 16];        // two stages of B tiles, the patch; reused to stage the output
+    constexpr int SMEM = (2 * TB + PBYTES) > BM * BN * 4 ? (2 * TB + PBYTES) : BM * BN * 4;
+    __shared__ uint4 smem[SMEM / 16];        // two stages of B tiles, the patch; reused to stage the whole output tile
     uint4 (*sB)[TB / 16] = reinterpret_cast<uint4 (*)[TB / 16]>(smem);
     char *sP = reinterpret_cast<char *>(smem + 2 * TB / 16);
     const int tid = threadIdx.x;

@@ -610,7 +610,12 @@ template <typename T> __device__ __forceinline__ void epilogue8(const Epilogue &
 #pragma unroll
         for (int r = 0; r < 8; ++r) v[r] = to_f32(ms.e[r]) > 0.f ? v[r] * ep.mask_scale : 0.f;
     }
-    if (ep.out_f32) store8<float>(static_cast<float *>(ep.out) + (long)m * ep.ld + n0, v);
+    if (ep.out_f32) {
+        // fp32 output = a parameter gradient: read again only by the update, long after it has left every cache
+        f32x4 *q = reinterpret_cast<f32x4 *>(__builtin_assume_aligned(static_cast<float *>(ep.out) + (long)m * ep.ld + n0, 16));
+        __builtin_nontemporal_store(f32x4{v[0], v[1], v[2], v[3]}, q);
+        __builtin_nontemporal_store(f32x4{v[4], v[5], v[6], v[7]}, q + 1);
+    }
     else store8<T>(static_cast<T *>(ep.out) + (long)m * ep.ld + n0, v);
 }
 

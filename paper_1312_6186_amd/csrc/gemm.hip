@@ -725,13 +725,13 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
     // to move the operands; wave-uniform, like the debug switch that turns all multiplication off
     const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N && !(dbg & 4)) ? 1 : 0) != 0;
 
-    // every output row this thread writes has the same 8 columns: fetch their bias now, behind the first tiles
-    float bias8[8];
-    load_bias8<T>(ep, tn * BN + (tid % (BN / 8)) * 8, bias8);
-
     // register set that receives tile j is j % DEPTH (tile 0 goes through set 0 straight into LDS stage 0)
     stA.template load<0>(la); stB.template load<0>(lb);
     if constexpr (DEPTH == 2) { stA.template load<1>(la); stB.template load<1>(lb); }
+    // every output row this thread writes has the same 8 columns: their bias is asked for behind the first tiles,
+    // so that tile 0 does not wait for it (the parameters are cold in every cache, the tiles mostly are not)
+    float bias8[8];
+    load_bias8<T>(ep, tn * BN + (tid % (BN / 8)) * 8, bias8);
     stA.template store<0>(sA[0], tid); stB.template store<0>(sB[0], tid);
     // The loop body is two whole steps without a condition in it, so that the compiler knows exactly which fetches are
     // in flight at its head (with a conditional store it has to assume that those of two steps ago may be, and
@@ -899,13 +899,12 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
         amask[mb] = mask;
     });
 
-    float bias8[8];
-    load_bias8<T>(ep, tn * BN + (tid % (BN / 8)) * 8, bias8);
-
     if (tid < kPatchPitch / 16) *reinterpret_cast<uint4 *>(sP + PPMAX * kPatchPitch + tid * 16) = make_uint4(0u, 0u, 0u, 0u);
     patch_load(ch);
     stB.template load<0>(lb);
     stB.template load<1>(lb);
+    float bias8[8];   // asked for behind the first tiles, which therefore do not wait for it
+    load_bias8<T>(ep, tn * BN + (tid % (BN / 8)) * 8, bias8);
     patch_store();
     stB.template store<0>(sB[0], tid);
     patch_load(ch + 1);

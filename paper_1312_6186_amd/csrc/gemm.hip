@@ -820,7 +820,9 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
     constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB;
     constexpr int TB = BN * 128;
     constexpr int PPMAX = NPL * NT / 8;                   // pixels the patch buffer holds
-    constexpr int PBYTES = (PPMAX + 1) * kPatchPitch;     // and one pixel of zeros behind them
+    constexpr int ZBYTES = 256 + 128;                     // zeros behind them: one 16-byte piece per group of four banks, and the reach of a K tile's fragment offsets
+    constexpr int PBYTES = PPMAX * kPatchPitch + ZBYTES;
+    static_assert((PPMAX * kPatchPitch) % 256 == 0 && (2 * TB) % 256 == 0, "the zeros start at bank 0");
     static_assert(MB == 2 && BM == 128, "two row blocks per wave");
     constexpr int SMEM = (2 * TB + PBYTES) > BM * BN * 4 ? (2 * TB + PBYTES) : BM * BN * 4;
     __shared__ uint4 smem[SMEM / 16];        // two stages of B tiles, the patch; reused to stage the whole output tile
@@ -880,7 +882,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
     const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N && !(dbg & 4)) ? 1 : 0) != 0;
     // the two fragment rows of this lane: patch address at window position (0, 0) and the mask of positions inside the image
     constexpr unsigned kHalfBytes = 8 * (unsigned)sizeof(T);
-    const unsigned zero_addr = (unsigned)(PPMAX * kPatchPitch) + (unsigned)half * kHalfBytes;
+    // A lane whose window position lies outside the image reads zeros instead, at the address behind the patch
+    // that falls into the same banks as the pixel it would have read: the lanes that read together hit different
+    // banks among the pixels, and a single shared pixel of zeros would collide with one of them.
+    constexpr unsigned zero_base = (unsigned)(PPMAX * kPatchPitch);
     unsigned abase[2], amask[2];
     static_for<0, 2>([&](auto mb) ASGD_INLINE {
         const int rr = wm + mb * 32 + lrow, m = tm * BM + rr;
@@ -899,7 +904,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
         amask[mb] = mask;
     });
 
-    if (tid < kPatchPitch / 16) *reinterpret_cast<uint4 *>(sP + PPMAX * kPatchPitch + tid * 16) = make_uint4(0u, 0u, 0u, 0u);
+    if (tid < ZBYTES / 16) *reinterpret_cast<uint4 *>(sP + PPMAX * kPatchPitch + tid * 16) = make_uint4(0u, 0u, 0u, 0u);
     patch_load(ch);
     stB.template load<0>(lb);
     stB.template load<1>(lb);
@@ -922,8 +927,9 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
         stB.template load<par>(lb);
         PatchOff foA;
         const unsigned sh = (unsigned)((ky * pa.W + kx) * kPatchPitch);
-        foA.a[0] = ((amask[0] >> pos) & 1u) ? abase[0] + sh : zero_addr;
-        foA.a[1] = ((amask[1] >> pos) & 1u) ? abase[1] + sh : zero_addr;
+        const unsigned a0 = abase[0] + sh, a1 = abase[1] + sh;
+        foA.a[0] = ((amask[0] >> pos) & 1u) ? a0 : zero_base + (a0 & 0xF0u);
+        foA.a[1] = ((amask[1] >> pos) & 1u) ? a1 : zero_base + (a1 & 0xF0u);
         __builtin_amdgcn_s_setprio(1);
         if (busy) compute_tile<T, MB, NB>(reinterpret_cast<const uint4 *>(sP), sB[par], acc, foA, foB);
         __builtin_amdgcn_s_setprio(0);
@@ -1112,8 +1118,10 @@ static int run_patch(const Gather &a, const void *b, long ldb, int N, const Epil
     // Both shapes run wave tiles of 64 x 32 at four waves per SIMD and take the same time per tile; the narrow one
     // fills the chip better when the wide one would leave more than an eighth of the 512 workgroup slots empty
     // (conv5 at batch 128: 338 workgroups against 676).
+    // The narrow one holds runs of up to 160 pixels (more pieces per thread cost it its fourth wave per SIMD).
     const long wide = (long)((a.N * a.H * a.W + 127) / 128) * ((N + 127) / 128) * plan.splits;
-    if (N > 64 && wide < 448) return run_patch_cfg<T, Cfg64n>(a, b, ldb, N, ep, plan, ws, s);
+    const int pp = 128 + (a.kh - 1) * a.W + a.kw - 1;
+    if (N > 64 && wide < 448 && pp <= 5 * Cfg64n::NT / 8) return run_patch_cfg<T, Cfg64n>(a, b, ldb, N, ep, plan, ws, s);
     return run_patch_cfg<T, Cfg128w8>(a, b, ldb, N, ep, plan, ws, s);
 }
 template <typename T, class Cfg>
@@ -1141,14 +1149,17 @@ static int run_patch_cfg(const Gather &a, const void *b, long ldb, int N, const 
     const long blocks = (long)tiles_m * tiles_n * splits;
     if (blocks > 0x7fffffffL) return -1;
     const int pp = 128 + (a.kh - 1) * a.W + a.kw - 1;   // pixels a block tile needs
-    // pieces per thread for short runs (up to 192 pixels with 512 threads, 160 with 256) and for runs of up to 256 pixels
-    constexpr int NPL_S = Cfg::NT == 512 ? 3 : 5, NPL_L = 256 * 8 / Cfg::NT;
+    // pieces per thread for short runs (up to 192 pixels with 512 threads, 160 with 256) and, with 512 threads, for runs of up to 256 pixels
+    constexpr int NPL_S = Cfg::NT == 512 ? 3 : 5;
     if (pp <= NPL_S * Cfg::NT / 8)
         hipLaunchKernelGGL((conv_patch_kernel<T, NPL_S, Cfg>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
                            tiles_n, splits > 1 ? ws : nullptr, debug_bits());
-    else
-        hipLaunchKernelGGL((conv_patch_kernel<T, NPL_L, Cfg>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
+    else if constexpr (Cfg::NT == 512) {
+        if (pp > 256) return -1;
+        hipLaunchKernelGGL((conv_patch_kernel<T, 4, Cfg>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
                            tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+    } else
+        return -1;
     if (splits > 1) {
         const long groups = (long)M * (N / 8);
         hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);

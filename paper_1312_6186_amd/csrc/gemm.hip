@@ -458,14 +458,16 @@ template <int ROWS> struct FragOff<float, true, ROWS> {
     }
 };
 // Fragment offsets into an activation patch (see conv_patch_kernel): the byte address of the lane's pixel for
-// row block 0 / 1, K-half included; the K steps of a tile are 32 (bf16) or 64 (fp32) bytes apart.
-struct PatchOff { unsigned a[2]; };
+// row block 0 / 1, K-half included, at each of the PPT window positions of the K tile; the K steps of one
+// position are 32 (bf16) or 64 (fp32) bytes apart.
+template <int PPT> struct PatchOff { unsigned a[2][PPT]; };
 typedef short short4v __attribute__((ext_vector_type(4)));
 template <> struct Frag<bf16_t> {
     uint4 v;
-    template <int KS, int BLK> __device__ __forceinline__ void read(const char *sm, const PatchOff &fo)
+    template <int KS, int BLK, int PPT> __device__ __forceinline__ void read(const char *sm, const PatchOff<PPT> &fo)
     {
-        v = *reinterpret_cast<const uint4 *>(sm + fo.a[BLK] + KS * 32);
+        constexpr int SPP = Geo<bf16_t>::KSTEPS / PPT;   // K steps per window position
+        v = *reinterpret_cast<const uint4 *>(sm + fo.a[BLK][KS / SPP] + (KS % SPP) * 32);
     }
     template <int KS, int BLK, int ROWS> __device__ __forceinline__ void read(const char *sm, const FragOff<bf16_t, false, ROWS> &fo)
     {
@@ -484,10 +486,11 @@ template <> struct Frag<bf16_t> {
 };
 template <> struct Frag<float> {
     uint4 v[2];
-    template <int KS, int BLK> __device__ __forceinline__ void read(const char *sm, const PatchOff &fo)
+    template <int KS, int BLK, int PPT> __device__ __forceinline__ void read(const char *sm, const PatchOff<PPT> &fo)
     {
-        v[0] = *reinterpret_cast<const uint4 *>(sm + fo.a[BLK] + KS * 64);
-        v[1] = *reinterpret_cast<const uint4 *>(sm + fo.a[BLK] + KS * 64 + 16);
+        constexpr int SPP = Geo<float>::KSTEPS / PPT;
+        v[0] = *reinterpret_cast<const uint4 *>(sm + fo.a[BLK][KS / SPP] + (KS % SPP) * 64);
+        v[1] = *reinterpret_cast<const uint4 *>(sm + fo.a[BLK][KS / SPP] + (KS % SPP) * 64 + 16);
     }
     template <int KS, int BLK, int ROWS> __device__ __forceinline__ void read(const char *sm, const FragOff<float, false, ROWS> &fo)
     {
@@ -776,32 +779,37 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
 // lane: its fragment address is redirected to a pixel of zeros kept behind the patch.  Pixels sit 144 bytes
 // apart in LDS: 16 consecutive pixels' 16-byte pieces then fall into 16 different groups of four banks,
 // whatever pixel the run starts at.
-constexpr int kPatchPitch = 144;
+// A chunk is a whole K tile of channels (PPT = 1) or half a K tile (PPT = 2: a K tile then holds two window
+// positions of the half-wide chunk, pixels sit 80 bytes apart).  Channel counts of 1.5, 2.5, ... K tiles
+// (96 channels in 16-bit data) lose nothing in the second form, where the first would multiply a third more K
+// tiles than there are.
+template <int PPT> constexpr int kPatchPitch = PPT == 1 ? 144 : 80;
 
-// The weights [rows][npos][C] as the B operand when K tiles enumerate (chunk, window position).
-template <typename T> struct ChunkK {
+// The weights [rows][npos][C] as the B operand when K tiles enumerate (chunk, group of PPT window positions).
+template <typename T, int PPT> struct ChunkK {
     static constexpr bool kTrans = false;
-    Operand op; unsigned ldb, posb; int rows, C, npos;   // posb: bytes from one window position to the next
-    FastDiv dnpos;
+    static constexpr int CW = Geo<T>::BK / PPT;   // channels of a chunk
+    Operand op; unsigned ldb, posb; int rows, C, npos, ntc;   // posb: bytes from one window position to the next; ntc: K tiles of a chunk
+    FastDiv dntc;
     struct Row { unsigned off; };
-    struct KPos { int pos, c; unsigned koff; };
+    struct KPos { int pos, c; unsigned koff; };   // window position and channel of this thread's piece
     __device__ __forceinline__ Row row(int r) const { return Row{r < rows ? (unsigned)r * ldb : kInv}; }
     __device__ __forceinline__ unsigned off_of(int pos, int c) const
     {
-        return c < C ? (unsigned)pos * posb + (unsigned)c * (unsigned)sizeof(T) : kInv;
+        return (c < C && pos < npos) ? (unsigned)pos * posb + (unsigned)c * (unsigned)sizeof(T) : kInv;
     }
     // k = K tile * BK + element inside the tile
     __device__ __forceinline__ KPos kpos(int k) const
     {
         const int t = k / (int)Geo<T>::BK, e = k % (int)Geo<T>::BK;
-        const int ch = (int)fdiv((uint32_t)t, dnpos), pos = t - ch * npos, c = ch * (int)Geo<T>::BK + e;
+        const int ch = (int)fdiv((uint32_t)t, dntc), pos = (t - ch * ntc) * PPT + e / CW, c = ch * CW + e % CW;
         return KPos{pos, c, off_of(pos, c)};
     }
     __device__ __forceinline__ void advance(KPos &kp, int) const
     {
-        const bool wrap = kp.pos + 1 == npos;
-        kp.pos = wrap ? 0 : kp.pos + 1;
-        kp.c += wrap ? (int)Geo<T>::BK : 0;
+        const bool wrap = kp.pos + PPT >= ntc * PPT;
+        kp.pos = wrap ? kp.pos + PPT - ntc * PPT : kp.pos + PPT;
+        kp.c += wrap ? CW : 0;
         kp.koff = off_of(kp.pos, kp.c);
     }
     __device__ __forceinline__ unsigned voff(const Row &r, const KPos &kp) const { return r.off + kp.koff; }
@@ -809,20 +817,23 @@ template <typename T> struct ChunkK {
 
 template <typename T> struct PatchSrc {
     Operand op; unsigned pix;              // bytes from one pixel to the next
-    int H, W, C, kh, kw, pad, npos, M;     // M: pixels of the tensor = GEMM rows
-    FastDiv dW, dHW, dkw, dnpos;
+    int H, W, C, kh, kw, pad, npos, ntc, M;   // ntc: K tiles of a chunk; M: pixels of the tensor = GEMM rows
+    FastDiv dW, dHW, dkw, dntc;
 };
 
-template <typename T, int NPL, class Cfg>
-__global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc<T> pa, ChunkK<T> lb, Epilogue ep, int M, int N, int nkt,
+template <typename T, int NPL, class Cfg, int PPT>
+__global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc<T> pa, ChunkK<T, PPT> lb, Epilogue ep, int M, int N, int nkt,
                                                                     int kt_per_split, int tiles_m, int tiles_n, float *ws, int dbg)
 {
     constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB;
     constexpr int TB = BN * 128;
-    constexpr int PPMAX = NPL * NT / 8;                   // pixels the patch buffer holds
+    constexpr int PIECES = 8 / PPT;                       // 16-byte pieces of a pixel's chunk
+    constexpr int PITCH = kPatchPitch<PPT>;
+    constexpr int CW = Geo<T>::BK / PPT;                  // channels of a chunk
+    constexpr int PPMAX = NPL * NT / PIECES;              // pixels the patch buffer holds
     constexpr int ZBYTES = 256 + 128;                     // zeros behind them: one 16-byte piece per group of four banks, and the reach of a K tile's fragment offsets
-    constexpr int PBYTES = PPMAX * kPatchPitch + ZBYTES;
-    static_assert((PPMAX * kPatchPitch) % 256 == 0 && (2 * TB) % 256 == 0, "the zeros start at bank 0");
+    constexpr int PBYTES = PPMAX * PITCH + ZBYTES;
+    static_assert((PPMAX * PITCH) % 256 == 0 && (2 * TB) % 256 == 0, "the zeros start at bank 0");
     static_assert(MB == 2 && BM == 128, "two row blocks per wave");
     constexpr int SMEM = (2 * TB + PBYTES) > BM * BN * 4 ? (2 * TB + PBYTES) : BM * BN * 4;
     __shared__ uint4 smem[SMEM / 16];        // two stages of B tiles, the patch; reused to stage the whole output tile
@@ -840,32 +851,32 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
     const int kt0 = split * kt_per_split;
     const int nt = min(nkt, kt0 + kt_per_split) - kt0;
 
-    Stage<T, ChunkK<T>, BN, NT, 2> stB;
+    Stage<T, ChunkK<T, PPT>, BN, NT, 2> stB;
     stB.init(lb, tn * BN, kt0 * BK, tid, NT / 2);
 
-    // window position and chunk of the first K tile (all uniform)
-    int ch = (int)fdiv((uint32_t)kt0, pa.dnpos);
-    int pos = kt0 - ch * pa.npos;
+    // chunk, first window position and its place in the window for the first K tile (all uniform)
+    int ch = (int)fdiv((uint32_t)kt0, pa.dntc);
+    int pos = (kt0 - ch * pa.ntc) * PPT;
     int ky = (int)fdiv((uint32_t)pos, pa.dkw), kx = pos - ky * pa.kw;
 
-    // patch pieces of this thread: piece q = tid + j * NT is slot q & 7 (= tid & 7) of patch pixel q >> 3
+    // patch pieces of this thread: piece q = tid + j * NT is slot q % PIECES (= tid % PIECES) of patch pixel q / PIECES
     const __amdgpu_buffer_rsrc_t prs = pa.op.rsrc();
-    const int slot = tid & 7;
-    const int gp0 = tm * BM - pa.pad * pa.W - pa.pad + (tid >> 3);   // tensor pixel of piece 0
+    const int slot = tid & (PIECES - 1);
+    const int gp0 = tm * BM - pa.pad * pa.W - pa.pad + tid / PIECES;   // tensor pixel of piece 0
     unsigned poff[NPL];
     static_for<0, NPL>([&](auto j) ASGD_INLINE {
-        const int gp = gp0 + j * (NT / 8);
+        const int gp = gp0 + j * (NT / PIECES);
         poff[j] = (gp >= 0 && gp < pa.M) ? (unsigned)gp * pa.pix + (unsigned)slot * 16u : kInv;
     });
-    const unsigned pwo = (unsigned)((tid >> 3) * kPatchPitch + slot * 16);
+    const unsigned pwo = (unsigned)((tid / PIECES) * PITCH + slot * 16);
     uint4 pr[NPL];
     auto patch_load = [&](int chunk) ASGD_INLINE {
-        const unsigned coff = (chunk * BK + slot * (int)Geo<T>::CH < pa.C) ? (unsigned)chunk * 128u : kInv;
+        const unsigned coff = (chunk * CW + slot * (int)Geo<T>::CH < pa.C) ? (unsigned)chunk * (128u / PPT) : kInv;
         static_for<0, NPL>([&](auto j) ASGD_INLINE { pr[j] = buf_ld16(prs, poff[j] + coff); });
     };
     auto patch_store = [&]() ASGD_INLINE {
         static_for<0, NPL>([&](auto j) ASGD_INLINE {
-            *reinterpret_cast<uint4 *>(sP + pwo + j * (NT / 8) * kPatchPitch) = pr[j];
+            *reinterpret_cast<uint4 *>(sP + pwo + j * (NT / PIECES) * PITCH) = pr[j];
         });
     };
 
@@ -885,11 +896,11 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
     // A lane whose window position lies outside the image reads zeros instead, at the address behind the patch
     // that falls into the same banks as the pixel it would have read: the lanes that read together hit different
     // banks among the pixels, and a single shared pixel of zeros would collide with one of them.
-    constexpr unsigned zero_base = (unsigned)(PPMAX * kPatchPitch);
+    constexpr unsigned zero_base = (unsigned)(PPMAX * PITCH);
     unsigned abase[2], amask[2];
     static_for<0, 2>([&](auto mb) ASGD_INLINE {
         const int rr = wm + mb * 32 + lrow, m = tm * BM + rr;
-        abase[mb] = (unsigned)(rr * kPatchPitch) + (unsigned)half * kHalfBytes;
+        abase[mb] = (unsigned)(rr * PITCH) + (unsigned)half * kHalfBytes;
         unsigned mask = 0;
         if (m < M) {
             const int n = (int)fdiv((uint32_t)m, pa.dHW);
@@ -904,7 +915,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
         amask[mb] = mask;
     });
 
-    if (tid < ZBYTES / 16) *reinterpret_cast<uint4 *>(sP + PPMAX * kPatchPitch + tid * 16) = make_uint4(0u, 0u, 0u, 0u);
+    if (tid < ZBYTES / 16) *reinterpret_cast<uint4 *>(sP + PPMAX * PITCH + tid * 16) = make_uint4(0u, 0u, 0u, 0u);
     patch_load(ch);
     stB.template load<0>(lb);
     stB.template load<1>(lb);
@@ -925,17 +936,20 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
             patch_load(ch + 1);
         }
         stB.template load<par>(lb);
-        PatchOff foA;
-        const unsigned sh = (unsigned)((ky * pa.W + kx) * kPatchPitch);
-        const unsigned a0 = abase[0] + sh, a1 = abase[1] + sh;
-        foA.a[0] = ((amask[0] >> pos) & 1u) ? a0 : zero_base + (a0 & 0xF0u);
-        foA.a[1] = ((amask[1] >> pos) & 1u) ? a1 : zero_base + (a1 & 0xF0u);
+        PatchOff<PPT> foA;
+        static_for<0, PPT>([&](auto h) ASGD_INLINE {
+            // a position past the last one (odd window sizes with two positions per tile) has no mask bit and no weights
+            const unsigned sh = (unsigned)((ky * pa.W + kx) * PITCH);
+            const unsigned a0 = abase[0] + sh, a1 = abase[1] + sh;
+            foA.a[0][h] = ((amask[0] >> pos) & 1u) ? a0 : zero_base + (a0 & 0xF0u);
+            foA.a[1][h] = ((amask[1] >> pos) & 1u) ? a1 : zero_base + (a1 & 0xF0u);
+            ++pos; ++kx;
+            if (kx == pa.kw) { kx = 0; ++ky; }
+        });
         __builtin_amdgcn_s_setprio(1);
         if (busy) compute_tile<T, MB, NB>(reinterpret_cast<const uint4 *>(sP), sB[par], acc, foA, foB);
         __builtin_amdgcn_s_setprio(0);
-        ++pos; ++kx;
-        if (kx == pa.kw) { kx = 0; ++ky; }
-        if (pos == pa.npos) { pos = 0; ky = 0; kx = 0; }
+        if (pos >= pa.npos) { pos = 0; ky = 0; kx = 0; }
         if (more) stB.template store<1 - par>(sB[1 - par], tid);
     };
     for (int t = 0; t < nt; t += 2) {
@@ -1094,25 +1108,31 @@ template <typename T> static PlainT<T> make_plain_t(const void *p, long ld, int 
 }
 
 // The patch form applies to stride-1 convolutions with equal input and output grids over a dense tensor whose
-// run of pixels per block tile fits the patch buffer.  ASGD_NOPATCH in the environment switches it off.
-template <typename T> static bool patch_applies(const Gather &a, long ldb)
+// run of pixels per block tile fits the patch buffer.  Returns the window positions per K tile to run it with
+// (1 or 2), or 0 where the im2col gather is the better choice.  ASGD_NOPATCH in the environment switches it off.
+template <typename T> static int patch_applies(const Gather &a, long ldb)
 {
     static const bool off = getenv("ASGD_NOPATCH") != nullptr;
     const size_t pixb = a.pix ? a.pix : (size_t)a.C * sizeof(T);
     const int npos = a.kh * a.kw;
-    // a chunk is a whole K tile: with channel counts that are not multiples of one (96 = 1.5 tiles) the patch
-    // form multiplies more K tiles than the gather, which packs K densely; beyond 15 % more it loses
+    if (off || !(a.sm == 1 && a.ds == 1 && a.Ho == a.H && a.Wo == a.W && npos > 1 && npos <= 32 && 2 * a.pad == a.kh - 1 &&
+                 2 * a.pad == a.kw - 1 && (a.rowb == 0 || a.rowb == (size_t)a.W * pixb) && pixb % 16 == 0 && a.C % (int)Geo<T>::CH == 0 &&
+                 ((uintptr_t)a.x & 15) == 0 && ldb == (long)npos * a.C && 128 + (a.kh - 1) * a.W + a.kw - 1 <= 256))
+        return 0;
+    // A chunk is a whole K tile of channels, or half of one with two window positions per K tile.  Where the
+    // channel count is not a multiple of the chunk the patch form multiplies more K tiles than the gather, which
+    // packs K densely; beyond 15 % more it loses.  (96 channels in 16-bit data, 5 x 5: 38 K tiles dense, 50 with
+    // whole-tile chunks, 39 with half-tile chunks.)
     const int BK = (int)Geo<T>::BK;
-    const long nkt_patch = (long)((a.C + BK - 1) / BK) * npos, nkt_gather = ((long)npos * a.C + BK - 1) / BK;
-    if (nkt_patch * 100 > nkt_gather * 115) return false;
-    return !off && a.sm == 1 && a.ds == 1 && a.Ho == a.H && a.Wo == a.W && npos > 1 && npos <= 32 && 2 * a.pad == a.kh - 1 &&
-           2 * a.pad == a.kw - 1 && (a.rowb == 0 || a.rowb == (size_t)a.W * pixb) && pixb % 16 == 0 && a.C % (int)Geo<T>::CH == 0 &&
-           ((uintptr_t)a.x & 15) == 0 && ldb == (long)npos * a.C && 128 + (a.kh - 1) * a.W + a.kw - 1 <= 256;
+    const long nkt_gather = ((long)npos * a.C + BK - 1) / BK;
+    const long nkt1 = (long)((a.C + BK - 1) / BK) * npos, nkt2 = (long)((a.C + BK / 2 - 1) / (BK / 2)) * ((npos + 1) / 2);
+    const int ppt = nkt2 < nkt1 ? 2 : 1;
+    return (ppt == 1 ? nkt1 : nkt2) * 100 <= nkt_gather * 115 ? ppt : 0;
 }
 
-template <typename T, class Cfg>
+template <typename T, class Cfg, int PPT>
 static int run_patch_cfg(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s);
-template <typename T>
+template <typename T, int PPT>
 static int run_patch(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
     // Both shapes run wave tiles of 64 x 32 at four waves per SIMD and take the same time per tile; the narrow one
@@ -1121,10 +1141,10 @@ static int run_patch(const Gather &a, const void *b, long ldb, int N, const Epil
     // The narrow one holds runs of up to 160 pixels (more pieces per thread cost it its fourth wave per SIMD).
     const long wide = (long)((a.N * a.H * a.W + 127) / 128) * ((N + 127) / 128) * plan.splits;
     const int pp = 128 + (a.kh - 1) * a.W + a.kw - 1;
-    if (N > 64 && wide < 448 && pp <= 5 * Cfg64n::NT / 8) return run_patch_cfg<T, Cfg64n>(a, b, ldb, N, ep, plan, ws, s);
-    return run_patch_cfg<T, Cfg128w8>(a, b, ldb, N, ep, plan, ws, s);
+    if (N > 64 && wide < 448 && pp <= 5 * Cfg64n::NT / 8) return run_patch_cfg<T, Cfg64n, PPT>(a, b, ldb, N, ep, plan, ws, s);
+    return run_patch_cfg<T, Cfg128w8, PPT>(a, b, ldb, N, ep, plan, ws, s);
 }
-template <typename T, class Cfg>
+template <typename T, class Cfg, int PPT>
 static int run_patch_cfg(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
     constexpr int BK = Geo<T>::BK;
@@ -1133,15 +1153,17 @@ static int run_patch_cfg(const Gather &a, const void *b, long ldb, int N, const 
     PatchSrc<T> pa;
     pa.op = operand(a.x, a.bytes);
     pa.pix = a.pix ? (unsigned)a.pix : (unsigned)(a.C * sizeof(T));
-    pa.H = a.H; pa.W = a.W; pa.C = a.C; pa.kh = a.kh; pa.kw = a.kw; pa.pad = a.pad; pa.npos = npos; pa.M = M;
-    pa.dW = make_fastdiv(a.W); pa.dHW = make_fastdiv(a.H * a.W); pa.dkw = make_fastdiv(a.kw); pa.dnpos = make_fastdiv(npos);
-    ChunkK<T> lb;
+    constexpr int CW = BK / PPT;                 // channels of a chunk
+    const int ntc = (npos + PPT - 1) / PPT;      // K tiles of a chunk
+    pa.H = a.H; pa.W = a.W; pa.C = a.C; pa.kh = a.kh; pa.kw = a.kw; pa.pad = a.pad; pa.npos = npos; pa.ntc = ntc; pa.M = M;
+    pa.dW = make_fastdiv(a.W); pa.dHW = make_fastdiv(a.H * a.W); pa.dkw = make_fastdiv(a.kw); pa.dntc = make_fastdiv(ntc);
+    ChunkK<T, PPT> lb;
     lb.op = operand(b, ((size_t)(N - 1) * ldb + K) * sizeof(T));
-    lb.ldb = (unsigned)(ldb * sizeof(T)); lb.posb = (unsigned)(a.C * sizeof(T)); lb.rows = N; lb.C = a.C; lb.npos = npos;
-    lb.dnpos = pa.dnpos;
+    lb.ldb = (unsigned)(ldb * sizeof(T)); lb.posb = (unsigned)(a.C * sizeof(T)); lb.rows = N; lb.C = a.C; lb.npos = npos; lb.ntc = ntc;
+    lb.dntc = pa.dntc;
     if (pa.op.bytes == 0 || lb.op.bytes == 0) return -1;
     const int tiles_m = (M + Cfg::BM - 1) / Cfg::BM, tiles_n = (N + Cfg::BN - 1) / Cfg::BN;
-    const int nkt = ((a.C + BK - 1) / BK) * npos;
+    const int nkt = ((a.C + CW - 1) / CW) * ntc;
     int splits = plan.splits;
     if (splits > 1 && ws == nullptr) return -1;
     const int per = (nkt + splits - 1) / splits;
@@ -1149,17 +1171,25 @@ static int run_patch_cfg(const Gather &a, const void *b, long ldb, int N, const 
     const long blocks = (long)tiles_m * tiles_n * splits;
     if (blocks > 0x7fffffffL) return -1;
     const int pp = 128 + (a.kh - 1) * a.W + a.kw - 1;   // pixels a block tile needs
-    // pieces per thread for short runs (up to 192 pixels with 512 threads, 160 with 256) and, with 512 threads, for runs of up to 256 pixels
-    constexpr int NPL_S = Cfg::NT == 512 ? 3 : 5;
-    if (pp <= NPL_S * Cfg::NT / 8)
-        hipLaunchKernelGGL((conv_patch_kernel<T, NPL_S, Cfg>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
+    if constexpr (PPT == 2) {
+        // half-wide chunks: four pieces per pixel, so two per thread hold 256 pixels with 512 threads, three hold 192 with 256
+        constexpr int NPL = Cfg::NT == 512 ? 2 : 3;
+        if (pp > NPL * Cfg::NT / 4) return -1;
+        hipLaunchKernelGGL((conv_patch_kernel<T, NPL, Cfg, 2>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
                            tiles_n, splits > 1 ? ws : nullptr, debug_bits());
-    else if constexpr (Cfg::NT == 512) {
-        if (pp > 256) return -1;
-        hipLaunchKernelGGL((conv_patch_kernel<T, 4, Cfg>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
-                           tiles_n, splits > 1 ? ws : nullptr, debug_bits());
-    } else
-        return -1;
+    } else {
+        // pieces per thread for short runs (up to 192 pixels with 512 threads, 160 with 256) and, with 512 threads, for runs of up to 256 pixels
+        constexpr int NPL_S = Cfg::NT == 512 ? 3 : 5;
+        if (pp <= NPL_S * Cfg::NT / 8)
+            hipLaunchKernelGGL((conv_patch_kernel<T, NPL_S, Cfg, 1>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
+                               tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+        else if constexpr (Cfg::NT == 512) {
+            if (pp > 256) return -1;
+            hipLaunchKernelGGL((conv_patch_kernel<T, 4, Cfg, 1>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
+                               tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+        } else
+            return -1;
+    }
     if (splits > 1) {
         const long groups = (long)M * (N / 8);
         hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);
@@ -1171,7 +1201,9 @@ template <typename T>
 static int gather_plain_t(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
     const int K = a.kh * a.kw * a.C;
-    if (patch_applies<T>(a, ldb)) return run_patch<T>(a, b, ldb, N, ep, plan, ws, s);
+    const int ppt = patch_applies<T>(a, ldb);
+    if (ppt == 1) return run_patch<T, 1>(a, b, ldb, N, ep, plan, ws, s);
+    if (ppt == 2) return run_patch<T, 2>(a, b, ldb, N, ep, plan, ws, s);
     if (a.ds == 1 && a.kh * a.kw <= 32)
         return run<T>(make_gather_k<T, false>(a), make_plain_k<T>(b, ldb, N, K), a.N * a.Ho * a.Wo, N, K, ep, plan, ws, s);
     if (a.ds == 1)

@@ -55,6 +55,13 @@ PATCHWIDE = dict(name="patchwide", in_shape=(3, 8, 27), classes=10,
                  layers=[("conv", 64, 3, 1, 1), ("relu",), ("conv", 72, 5, 1, 2), ("relu",), ("conv", 8, 5, 1, 2), ("relu",),
                          ("maxpool", 2, 2), ("fc", 10), ("softmax_ce",)])
 
+# channel counts of 1.5 K tiles (48 channels in 32-bit data, 96 in 16-bit data): chunks of half a K tile with two
+# window positions per K tile, 3x3 and 5x5 windows (an odd number of positions: the last tile of a chunk is half empty),
+# forward and, for the 96 channels that the 48-channel layer feeds, the data gradient
+HALFCHUNK = dict(name="halfchunk", in_shape=(3, 14, 13), classes=10,
+                 layers=[("conv", 48, 3, 1, 1), ("relu",), ("conv", 96, 3, 1, 1), ("relu",), ("conv", 40, 5, 1, 2), ("relu",),
+                         ("maxpool", 2, 2), ("fc", 10), ("softmax_ce",)])
+
 
 # two and four input channels: the remaining pixel widths of the narrow-pixel form of the first layer
 CH2 = dict(name="ch2", in_shape=(2, 14, 12), classes=10,
@@ -193,8 +200,8 @@ def _net_case(cfg, batch, dtype, seed=0, step=0, worker=0, bias_noise=0.05):
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 @pytest.mark.parametrize("cfg,batch", [(wl.TINY, 8), (wl.TINY, 1), (RAGGED, 5), (RAGGED, 131), (WIDE, 3), (LRNNET, 7), (GROUPED, 6), (PATCHNET, 5),
-                                       (PATCHWIDE, 3), (CH2, 4), (CH4, 4), (WIDEPOOL, 3), (POOLPOOL, 5), (wl.SMALL, 128)],
-                         ids=["tiny", "tiny-batch1", "ragged5", "ragged131", "wide", "lrn", "grouped", "patch", "patchwide", "ch2", "ch4",
+                                       (PATCHWIDE, 3), (HALFCHUNK, 5), (CH2, 4), (CH4, 4), (WIDEPOOL, 3), (POOLPOOL, 5), (wl.SMALL, 128)],
+                         ids=["tiny", "tiny-batch1", "ragged5", "ragged131", "wide", "lrn", "grouped", "patch", "patchwide", "halfchunk", "ch2", "ch4",
                               "widepool", "poolpool", "small"])
 def test_minibatch_gradient_matches_oracle(cfg, batch, dtype):
     g, onet, (loss, grads), (ref_loss, ref_grads, trace), _ = _net_case(cfg, batch, dtype, seed=3002, step=4, worker=1)

@@ -961,6 +961,152 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
     output_tile<T, Cfg, (int)sizeof(smem)>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
 }
 
+// The same convolution with the waves of a workgroup in two roles: the first Cfg::NT / 64 waves read fragments and
+// multiply, four more fetch the weights and the patch and move them into LDS.  The multiplying waves hold no
+// staging registers and no fetch addresses, which leaves room for wave tiles of 64 x 64 (four multiplying waves
+// on a 128 x 128 tile) at four waves per SIMD: a third fewer fragment reads from LDS than with 64 x 32, and the
+// K loop gets 3-7 % faster.  Both kinds of wave go through the same barriers; the fetching waves end after the
+// K loop, and a wave that has ended no longer counts at the barriers of the output phase.
+constexpr int kProducers = 256;
+template <typename T, int NPL, class Cfg, int PPT>
+__global__ __launch_bounds__(Cfg::NT + kProducers, 2) void conv_patch_ws_kernel(PatchSrc<T> pa, ChunkK<T, PPT> lb, Epilogue ep, int M, int N, int nkt,
+                                                                              int kt_per_split, int tiles_m, int tiles_n, float *ws, int dbg)
+{
+    constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB, NP = kProducers;
+    constexpr int TB = BN * 128;
+    constexpr int PIECES = 8 / PPT;
+    constexpr int PITCH = kPatchPitch<PPT>;
+    constexpr int CW = Geo<T>::BK / PPT;
+    constexpr int PPMAX = NPL * NP / PIECES;
+    constexpr int ZBYTES = 256 + 128;
+    constexpr int PBYTES = PPMAX * PITCH + ZBYTES;
+    static_assert((PPMAX * PITCH) % 256 == 0 && (2 * TB) % 256 == 0, "the zeros start at bank 0");
+    static_assert(MB == 2 && BM == 128, "two row blocks per wave");
+    constexpr int SMEM = (2 * TB + PBYTES) > BM * BN * 4 ? (2 * TB + PBYTES) : BM * BN * 4;
+    __shared__ uint4 smem[SMEM / 16];
+    uint4 (*sB)[TB / 16] = reinterpret_cast<uint4 (*)[TB / 16]>(smem);
+    char *sP = reinterpret_cast<char *>(smem + 2 * TB / 16);
+    const int tid = threadIdx.x;
+    int bid;
+    {
+        const int nb = gridDim.x, q = nb >> 3, r = nb & 7, x = blockIdx.x & 7;
+        bid = x * q + (x < r ? x : r) + (blockIdx.x >> 3);
+    }
+    const int tn = bid % tiles_n; bid /= tiles_n;
+    const int tm = bid % tiles_m;
+    const int split = bid / tiles_m;
+    const int kt0 = split * kt_per_split;
+    const int nt = min(nkt, kt0 + kt_per_split) - kt0;
+    int ch = (int)fdiv((uint32_t)kt0, pa.dntc);
+    int pos = (kt0 - ch * pa.ntc) * PPT;
+
+    if (tid >= NT) {
+        // ---- fetching waves.  Step t: after the barrier, tile t+1 (fetched two steps ago) goes from its register set
+        // into the LDS stage that was multiplied in step t-1, and the set is refilled with tile t+3.
+        const int ptid = tid - NT;
+        Stage<T, ChunkK<T, PPT>, BN, NP, 2> stB;
+        stB.init(lb, tn * BN, kt0 * BK, ptid, NP / 2);
+        const __amdgpu_buffer_rsrc_t prs = pa.op.rsrc();
+        const int slot = ptid & (PIECES - 1);
+        const int gp0 = tm * BM - pa.pad * pa.W - pa.pad + ptid / PIECES;
+        unsigned poff[NPL];
+        static_for<0, NPL>([&](auto j) ASGD_INLINE {
+            const int gp = gp0 + j * (NP / PIECES);
+            poff[j] = (gp >= 0 && gp < pa.M) ? (unsigned)gp * pa.pix + (unsigned)slot * 16u : kInv;
+        });
+        const unsigned pwo = (unsigned)((ptid / PIECES) * PITCH + slot * 16);
+        uint4 pr[NPL];
+        auto patch_load = [&](int chunk) ASGD_INLINE {
+            const unsigned coff = (chunk * CW + slot * (int)Geo<T>::CH < pa.C) ? (unsigned)chunk * (128u / PPT) : kInv;
+            static_for<0, NPL>([&](auto j) ASGD_INLINE { pr[j] = buf_ld16(prs, poff[j] + coff); });
+        };
+        auto patch_store = [&]() ASGD_INLINE {
+            static_for<0, NPL>([&](auto j) ASGD_INLINE {
+                *reinterpret_cast<uint4 *>(sP + pwo + j * (NP / PIECES) * PITCH) = pr[j];
+            });
+        };
+        patch_load(ch);
+        stB.template load<0>(lb);
+        stB.template load<1>(lb);
+        patch_store();
+        stB.template store<0>(sB[0], ptid);
+        stB.template load<0>(lb);
+        patch_load(ch + 1);
+        auto step = [&](auto par, bool first, bool more) ASGD_INLINE {
+            __syncthreads();
+            if (pos == 0 && !first) {
+                patch_store();
+                __syncthreads();
+                ++ch;
+                patch_load(ch + 1);
+            }
+            pos += PPT;
+            if (pos >= pa.npos) pos = 0;
+            if (more) stB.template store<1 - par>(sB[1 - par], ptid);
+            stB.template load<1 - par>(lb);
+        };
+        for (int t = 0; t < nt; t += 2) {
+            step(std::integral_constant<int, 0>{}, t == 0, t + 1 < nt);
+            if (t + 1 < nt) step(std::integral_constant<int, 1>{}, false, t + 2 < nt);
+        }
+        return;   // a wave that has ended no longer counts at the barriers of the output phase
+    }
+
+    // ---- multiplying waves
+    int ky = (int)fdiv((uint32_t)pos, pa.dkw), kx = pos - ky * pa.kw;
+    f32x16 acc[NB][MB];
+    static_for<0, NB>([&](auto i) ASGD_INLINE { static_for<0, MB>([&](auto j) ASGD_INLINE { acc[i][j] = f32x16{}; }); });
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave % Cfg::WAVES_M) * (BM / Cfg::WAVES_M), wn = (wave / Cfg::WAVES_M) * (BN / Cfg::WAVES_N);
+    const int lrow = lane & 31, half = lane >> 5;
+    FragOff<T, false, BN> foB;
+    foB.init(wn, lane);
+    const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N && !(dbg & 4)) ? 1 : 0) != 0;
+    constexpr unsigned kHalfBytes = 8 * (unsigned)sizeof(T);
+    constexpr unsigned zero_base = (unsigned)(PPMAX * PITCH);
+    unsigned abase[2], amask[2];
+    static_for<0, 2>([&](auto mb) ASGD_INLINE {
+        const int rr = wm + mb * 32 + lrow, m = tm * BM + rr;
+        abase[mb] = (unsigned)(rr * PITCH) + (unsigned)half * kHalfBytes;
+        unsigned mask = 0;
+        if (m < M) {
+            const int n = (int)fdiv((uint32_t)m, pa.dHW);
+            const int rem = m - n * (pa.H * pa.W);
+            const int y = (int)fdiv((uint32_t)rem, pa.dW);
+            const int y0 = y - pa.pad, x0 = rem - y * pa.W - pa.pad;
+            const int ylo = max(0, -y0), yhi = max(ylo, min(pa.kh, pa.H - y0));
+            const int xlo = max(0, -x0), xhi = max(xlo, min(pa.kw, pa.W - x0));
+            const unsigned xm = ((1u << xhi) - 1u) & ~((1u << xlo) - 1u);
+            for (int a = ylo; a < yhi; ++a) mask |= xm << (a * pa.kw);
+        }
+        amask[mb] = mask;
+    });
+    if (tid < ZBYTES / 16) *reinterpret_cast<uint4 *>(sP + PPMAX * PITCH + tid * 16) = make_uint4(0u, 0u, 0u, 0u);
+    float bias8[8];
+    load_bias8<T>(ep, tn * BN + (tid % (BN / 8)) * 8, bias8);
+    auto step = [&](auto par, bool first) ASGD_INLINE {
+        __syncthreads();
+        if (pos == 0 && !first) __syncthreads();   // the fetching waves replace the patch between these two
+        PatchOff<PPT> foA;
+        static_for<0, PPT>([&](auto h) ASGD_INLINE {
+            const unsigned sh = (unsigned)((ky * pa.W + kx) * PITCH);
+            const unsigned a0 = abase[0] + sh, a1 = abase[1] + sh;
+            foA.a[0][h] = ((amask[0] >> pos) & 1u) ? a0 : zero_base + (a0 & 0xF0u);
+            foA.a[1][h] = ((amask[1] >> pos) & 1u) ? a1 : zero_base + (a1 & 0xF0u);
+            ++pos; ++kx;
+            if (kx == pa.kw) { kx = 0; ++ky; }
+        });
+        if (busy) compute_tile<T, MB, NB>(reinterpret_cast<const uint4 *>(sP), sB[par], acc, foA, foB);
+        if (pos >= pa.npos) { pos = 0; ky = 0; kx = 0; }
+    };
+    for (int t = 0; t < nt; t += 2) {
+        step(std::integral_constant<int, 0>{}, t == 0);
+        if (t + 1 < nt) step(std::integral_constant<int, 1>{}, false);
+    }
+    if (dbg & 8) return;
+    output_tile<T, Cfg, (int)sizeof(smem)>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
+}
+
 template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int splits, Epilogue ep, int M, int N)
 {
     const long g = (long)blockIdx.x * 256 + threadIdx.x;
@@ -1171,7 +1317,21 @@ static int run_patch_cfg(const Gather &a, const void *b, long ldb, int N, const 
     const long blocks = (long)tiles_m * tiles_n * splits;
     if (blocks > 0x7fffffffL) return -1;
     const int pp = 128 + (a.kh - 1) * a.W + a.kw - 1;   // pixels a block tile needs
-    if constexpr (PPT == 2) {
+    // The wide shape runs with the two kinds of waves (see conv_patch_ws_kernel); ASGD_NOWS in the environment keeps
+    // every wave doing everything, for comparisons.
+    static const bool two_roles = getenv("ASGD_NOWS") == nullptr;
+    if (two_roles && Cfg::NT == 512) {
+        if (pp > 256) return -1;
+        if constexpr (PPT == 2)
+            hipLaunchKernelGGL((conv_patch_ws_kernel<T, 4, Cfg128, 2>), dim3((unsigned)blocks), dim3(Cfg128::NT + kProducers), 0, s, pa, lb, ep, M, N, nkt, per,
+                               tiles_m, tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+        else if (pp <= 192)
+            hipLaunchKernelGGL((conv_patch_ws_kernel<T, 6, Cfg128, 1>), dim3((unsigned)blocks), dim3(Cfg128::NT + kProducers), 0, s, pa, lb, ep, M, N, nkt, per,
+                               tiles_m, tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+        else
+            hipLaunchKernelGGL((conv_patch_ws_kernel<T, 8, Cfg128, 1>), dim3((unsigned)blocks), dim3(Cfg128::NT + kProducers), 0, s, pa, lb, ep, M, N, nkt, per,
+                               tiles_m, tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+    } else if constexpr (PPT == 2) {
         // half-wide chunks: four pieces per pixel, so two per thread hold 256 pixels with 512 threads, three hold 192 with 256
         constexpr int NPL = Cfg::NT == 512 ? 2 : 3;
         if (pp > NPL * Cfg::NT / 4) return -1;

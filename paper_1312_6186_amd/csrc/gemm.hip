@@ -765,6 +765,78 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
     output_tile<T, Cfg, (int)sizeof(smem)>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
 }
 
+// gemm_kernel with the waves of a workgroup in two roles, as in conv_patch_ws_kernel further down: Cfg::NT / 64 waves read
+// fragments and multiply (wave tiles of 64 x 64), four more fetch both operands and move them into LDS.  Step t of
+// a fetching wave: after the barrier, tile t+1 (fetched two steps ago) goes from its register set into the LDS stage
+// that was multiplied in step t-1, and the set is refilled with tile t+3.
+constexpr int kFetchThreads = 256;
+template <typename T, class Cfg, class LA, class LB>
+__global__ __launch_bounds__(Cfg::NT + kFetchThreads, 2) void gemm_ws_kernel(LA la, LB lb, Epilogue ep, int M, int N, int nkt, int kt_per_split,
+                                                                           int tiles_m, int tiles_n, float *ws, int dbg)
+{
+    constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB, NP = kFetchThreads;
+    constexpr int TA = LA::kTrans ? TransTile<T, BM>::BYTES : BM * 128, TB = LB::kTrans ? TransTile<T, BN>::BYTES : BN * 128;
+    __shared__ uint4 smem[2 * (TA + TB) / 16];   // two stages of A and B tiles; reused to stage the output
+    uint4 (*sA)[TA / 16] = reinterpret_cast<uint4 (*)[TA / 16]>(smem);
+    uint4 (*sB)[TB / 16] = reinterpret_cast<uint4 (*)[TB / 16]>(smem + 2 * TA / 16);
+    const int tid = threadIdx.x;
+    int bid;
+    {
+        const int nb = gridDim.x, q = nb >> 3, r = nb & 7, x = blockIdx.x & 7;
+        bid = x * q + (x < r ? x : r) + (blockIdx.x >> 3);
+    }
+    const int tn = bid % tiles_n; bid /= tiles_n;
+    const int tm = bid % tiles_m;
+    const int split = bid / tiles_m;
+    const int kt0 = split * kt_per_split;
+    const int nt = min(nkt, kt0 + kt_per_split) - kt0;   // K tiles of this workgroup (>= 1)
+
+    if (tid >= NT) {
+        const int ptid = tid - NT;
+        Stage<T, LA, BM, NP, 2> stA;
+        Stage<T, LB, BN, NP, 2> stB;
+        stA.init(la, tm * BM, kt0 * BK, ptid, 0);
+        stB.init(lb, tn * BN, kt0 * BK, ptid, NP / 2);
+        stA.template load<0>(la); stB.template load<0>(lb);
+        stA.template load<1>(la); stB.template load<1>(lb);
+        stA.template store<0>(sA[0], ptid); stB.template store<0>(sB[0], ptid);
+        stA.template load<0>(la); stB.template load<0>(lb);
+        for (int t = 0; t < nt; t += 2) {
+            __syncthreads();
+            if (t + 1 < nt) { stA.template store<1>(sA[1], ptid); stB.template store<1>(sB[1], ptid); }
+            stA.template load<1>(la); stB.template load<1>(lb);   // past the last tile this fetches zeros
+            if (t + 1 < nt) {
+                __syncthreads();
+                if (t + 2 < nt) { stA.template store<0>(sA[0], ptid); stB.template store<0>(sB[0], ptid); }
+                stA.template load<0>(la); stB.template load<0>(lb);
+            }
+        }
+        return;   // a wave that has ended no longer counts at the barriers of the output phase
+    }
+
+    f32x16 acc[NB][MB];
+    static_for<0, NB>([&](auto i) ASGD_INLINE { static_for<0, MB>([&](auto j) ASGD_INLINE { acc[i][j] = f32x16{}; }); });
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave % Cfg::WAVES_M) * (BM / Cfg::WAVES_M), wn = (wave / Cfg::WAVES_M) * (BN / Cfg::WAVES_N);
+    FragOff<T, LA::kTrans, BM> foA;
+    FragOff<T, LB::kTrans, BN> foB;
+    foA.init(wm, lane);
+    foB.init(wn, lane);
+    const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N && !(dbg & 4)) ? 1 : 0) != 0;
+    float bias8[8];
+    load_bias8<T>(ep, tn * BN + (tid % (BN / 8)) * 8, bias8);
+    for (int t = 0; t < nt; t += 2) {
+        __syncthreads();
+        if (busy) compute_tile<T, MB, NB>(sA[0], sB[0], acc, foA, foB);
+        if (t + 1 < nt) {
+            __syncthreads();
+            if (busy) compute_tile<T, MB, NB>(sA[1], sB[1], acc, foA, foB);
+        }
+    }
+    if (dbg & 8) return;
+    output_tile<T, Cfg, (int)sizeof(smem)>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
+}
+
 // ------------------------------------------------------------------ patch convolution
 // Stride-1 convolutions whose output grid equals the input grid (and their data gradients, which have the
 // same form).  With channel-last storage the input pixel that output pixel m needs at window position
@@ -1188,8 +1260,20 @@ static int run_tile(const LA &la, const LB &lb, int M, int N, int K, const Epilo
     splits = (nkt + per - 1) / per;
     const long blocks = (long)tiles_m * tiles_n * splits;
     if (blocks > 0x7fffffffL) return -1;
-    hipLaunchKernelGGL((gemm_kernel<T, Cfg, LA, LB>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, la, lb, ep, M, N, nkt, per, tiles_m,
-                       tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+    // The convolution filter gradient runs with fetching and multiplying waves (gemm_ws_kernel: -2.6 % in bf16, -4 % in
+    // fp32 for the class); the im2col forward gather of the first layer is 12 % slower that way (seven K tiles: the
+    // head of a workgroup weighs more than its loop) and stays as it is.  ASGD_NOWS in the environment switches it off.
+    static const bool two_roles = getenv("ASGD_NOWS") == nullptr;
+    if constexpr (std::is_same<LB, GatherT<T>>::value) {
+        if (two_roles)
+            hipLaunchKernelGGL((gemm_ws_kernel<T, Cfg128, LA, LB>), dim3((unsigned)blocks), dim3(Cfg128::NT + kFetchThreads), 0, s, la, lb, ep, M, N, nkt,
+                               per, tiles_m, tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+        else
+            hipLaunchKernelGGL((gemm_kernel<T, Cfg, LA, LB>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, la, lb, ep, M, N, nkt, per, tiles_m,
+                               tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+    } else
+        hipLaunchKernelGGL((gemm_kernel<T, Cfg, LA, LB>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, la, lb, ep, M, N, nkt, per, tiles_m,
+                           tiles_n, splits > 1 ? ws : nullptr, debug_bits());
     if (splits > 1) {
         const long groups = (long)M * (N / 8);
         hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);

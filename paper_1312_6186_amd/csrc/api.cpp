@@ -301,11 +301,11 @@ int plan_net(asgd_net &n)
                 const long Cg = s.inC / s.groups, Og = s.outC / s.groups, Kg = (long)s.k * s.k * Cg;
                 s.p_fwd = plan_gemm(M, Og, Kg, n.dtype, 1);
                 s.p_dgrad = plan_gemm(Min, Cg, (long)s.k * s.k * Og, n.dtype, 1);
-                s.p_wgrad = plan_gemm(Og, Kg, M, n.dtype, 64);
+                s.p_wgrad = plan_gemm(Og, Kg, M, n.dtype, 128);
             } else {
                 s.p_fwd = plan_gemm(M, s.outCp, K, n.dtype, 1);
                 s.p_dgrad = plan_gemm(Min, s.inCp, (long)s.k * s.k * s.outCp, n.dtype, 1);
-                s.p_wgrad = plan_gemm(s.outCp, K, M, n.dtype, 64);
+                s.p_wgrad = plan_gemm(s.outCp, K, M, n.dtype, 128);
             }
             scratch_side = std::max(scratch_side, s.p_wgrad.ws_floats);
             s.colsum_floats = colsum_ws_floats(n.dtype, M, s.outCp);

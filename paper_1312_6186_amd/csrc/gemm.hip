@@ -1213,6 +1213,61 @@ template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_kerne
     epilogue8<T>(ep, m, n0, v, b8);
 }
 
+// The same for few outputs and many partial sums (the first layer's filter gradient: 5280 groups of 8 outputs, up
+// to 128 partials each): eight neighbouring lanes share a group, lane l adds partials l, l+8, ... in that order, and
+// the eight sums are combined in a fixed butterfly, so the result does not depend on anything but the inputs.
+template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_wide_kernel(const float *ws, int splits, Epilogue ep, int M, int N)
+{
+    const long g = ((long)blockIdx.x * 256 + threadIdx.x) >> 3;
+    const int l = threadIdx.x & 7;
+    const int n8 = N / 8;
+    const bool live = g < (long)M * n8;   // whole groups of eight lanes are live or not; all lanes take part in the shuffles
+    const long gg = live ? g : 0;
+    const int m = (int)(gg / n8), n0 = (int)(gg - (long)m * n8) * 8;
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const long stride = (long)M * N;
+    const float *p0 = ws + (long)m * N + n0;
+    int s = l;
+    for (; s + 24 < splits; s += 32) {   // four partials in flight
+        float4 a[4], b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float4 *p = reinterpret_cast<const float4 *>(p0 + (s + 8 * u) * stride);
+            a[u] = p[0]; b[u] = p[1];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            v[0] += a[u].x; v[1] += a[u].y; v[2] += a[u].z; v[3] += a[u].w;
+            v[4] += b[u].x; v[5] += b[u].y; v[6] += b[u].z; v[7] += b[u].w;
+        }
+    }
+    for (; s < splits; s += 8) {
+        const float4 *p = reinterpret_cast<const float4 *>(p0 + s * stride);
+        const float4 a = p[0], b = p[1];
+        v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
+        v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+    }
+#pragma unroll
+    for (int d = 1; d < 8; d <<= 1) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) v[r] += __shfl_xor(v[r], d, 8);
+    }
+    if (!live || l != 0) return;
+    float b8[8];
+    load_bias8<T>(ep, n0, b8);
+    epilogue8<T>(ep, m, n0, v, b8);
+}
+
+// the reduction that follows a split GEMM
+template <typename T> static void launch_splitk_reduce(const float *ws, int splits, const Epilogue &ep, int M, int N, hipStream_t s)
+{
+    const long groups = (long)M * (N / 8);
+    if (splits >= 16 && groups < 32768)
+        hipLaunchKernelGGL((splitk_reduce_wide_kernel<T>), dim3((unsigned)((groups * 8 + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);
+    else
+        hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);
+}
+
 // ------------------------------------------------------------------ host side
 // ASGD_DBG in the environment switches phases of the GEMM kernel off (bit 2: the MFMAs, bit 3: the output
 // phase) to time the rest; results are then wrong.  For experiments only.
@@ -1274,10 +1329,7 @@ static int run_tile(const LA &la, const LB &lb, int M, int N, int K, const Epilo
     } else
         hipLaunchKernelGGL((gemm_kernel<T, Cfg, LA, LB>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, la, lb, ep, M, N, nkt, per, tiles_m,
                            tiles_n, splits > 1 ? ws : nullptr, debug_bits());
-    if (splits > 1) {
-        const long groups = (long)M * (N / 8);
-        hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);
-    }
+    if (splits > 1) launch_splitk_reduce<T>(ws, splits, ep, M, N, s);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -1434,10 +1486,7 @@ static int run_patch_cfg(const Gather &a, const void *b, long ldb, int N, const 
         } else
             return -1;
     }
-    if (splits > 1) {
-        const long groups = (long)M * (N / 8);
-        hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);
-    }
+    if (splits > 1) launch_splitk_reduce<T>(ws, splits, ep, M, N, s);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

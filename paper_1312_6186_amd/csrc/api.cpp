@@ -92,7 +92,7 @@ struct asgd_net {
     // layer: they run on an internal stream beside the caller's, forked and joined with events.
     hipStream_t side = nullptr;
     bool in_replay = false;   // replicas of a replay already run beside each other: no side stream then (measured slower)
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_bias = nullptr;
     std::vector<hipEvent_t> ev_pack, ev_dy, ev_dg;   // per stage: filters packed, output gradient ready, data gradient issued
     float *row_loss = nullptr;
     int *version_counter = nullptr;  // device-side count of applied updates (A-SGD replay)
@@ -335,6 +335,7 @@ int release_device(asgd_net *n)
     if (n->side) { (void)hipStreamSynchronize(n->side); (void)hipStreamDestroy(n->side); n->side = nullptr; }
     if (n->ev_fork) { (void)hipEventDestroy(n->ev_fork); n->ev_fork = nullptr; }
     if (n->ev_join) { (void)hipEventDestroy(n->ev_join); n->ev_join = nullptr; }
+    if (n->ev_bias) { (void)hipEventDestroy(n->ev_bias); n->ev_bias = nullptr; }
     for (hipEvent_t e : n->ev_pack) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : n->ev_dy) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : n->ev_dg) if (e) (void)hipEventDestroy(e);
@@ -362,6 +363,7 @@ int ensure_prepared(asgd_net *n)
     e = hipStreamCreateWithFlags(&n->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_join, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&n->ev_bias, hipEventDisableTiming);
     n->ev_pack.assign(n->stages.size(), nullptr);
     n->ev_dy.assign(n->stages.size(), nullptr);
     n->ev_dg.assign(n->stages.size(), nullptr);
@@ -589,6 +591,8 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
     const bool fork = !n->prof_on && !n->in_replay && !serial_mode();
     hipStream_t sd = fork ? n->side : st;   // parameter gradients go here
     ColsumJobs bias_jobs; bias_jobs.n = 0;  // second stage of the bias gradients: one launch at the end, or per layer when pushing by layer
+    int first_param = -1;
+    for (int q = 0; q < (int)n->stages.size() && first_param < 0; ++q) if (n->stages[q].has_params()) first_param = q;
     auto push = [&](int si) -> int {      // after the stage's gradients are queued on sd and its data gradient on st
         Stage &s = n->stages[si];
         if (!srv || !s.has_params()) return ASGD_OK;
@@ -672,6 +676,30 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
             const double Mo = (double)M, conv_flops = 2 * Mo * s.outC * (s.inC / s.groups) * s.k * s.k;
             const int Cg = s.inC / s.groups, Og = s.outC / s.groups;   // channels per group (all of them when ungrouped)
             const size_t esz = dtype_size(dt);
+            auto bias_part = [&]() -> int {
+                ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, (s.bands_ready ? 0.0 : Mo * s.outC * es) + s.outC * 4.0);
+                if (s.bands_ready) {   // the pooling backward pass above has left the band sums
+                    s.bands_ready = false;
+                    if (bias_jobs.n >= 12) return fail(ASGD_EINVAL, "too many pending bias gradients");
+                    ColsumJob &J = bias_jobs.j[bias_jobs.n++];
+                    J.ws = s.colsum_ws; J.nblk = (int)s.pool_bands; J.ld = s.outCp; J.N = s.outC; J.db = grads + s.b_off; J.start_block = 0; J.colmajor = 1;
+                } else {
+                    CHECK_LAUNCH(launch_colsum_partial(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, s.colsum_ws, bias_jobs, sd), "conv bias gradient");
+                }
+                if (srv || bias_jobs.n == 12) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "conv bias gradient");
+                return ASGD_OK;
+            };
+            // The last layer of the backward pass: its filter gradient is the tail of the side stream, which ends after
+            // the caller's.  The second stage of all bias gradients goes to the caller's stream before it, so that it
+            // runs beside that GEMM instead of behind it.
+            const bool bias_first = fork && !srv && si == first_param;
+            if (bias_first) {
+                const int brc = bias_part();
+                if (brc != ASGD_OK) return brc;
+                CHECK_HIP(hipEventRecord(n->ev_bias, sd), "hipEventRecord");
+                CHECK_HIP(hipStreamWaitEvent(st, n->ev_bias, 0), "hipStreamWaitEvent");
+                CHECK_LAUNCH(launch_colsum_finish(bias_jobs, st), "bias gradients");
+            }
             {
                 ProfScope ps(n, sd, ASGD_K_CONV_WGRAD, conv_flops, (Mo * s.outC + Bd * s.inH * s.inW * s.inC) * es + (double)s.w_cnt * 4);
                 if (s.groups > 1) {
@@ -692,17 +720,9 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
                     CHECK_LAUNCH(gemm_trans_gather(dt, s.dout, s.outCp, s.outCp, g, ew, s.p_wgrad, n->scratch_side, sd), "conv filter gradient");
                 }
             }
-            {
-                ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, (s.bands_ready ? 0.0 : Mo * s.outC * es) + s.outC * 4.0);
-                if (s.bands_ready) {   // the pooling backward pass above has left the band sums
-                    s.bands_ready = false;
-                    if (bias_jobs.n >= 12) return fail(ASGD_EINVAL, "too many pending bias gradients");
-                    ColsumJob &J = bias_jobs.j[bias_jobs.n++];
-                    J.ws = s.colsum_ws; J.nblk = (int)s.pool_bands; J.ld = s.outCp; J.N = s.outC; J.db = grads + s.b_off; J.start_block = 0; J.colmajor = 1;
-                } else {
-                    CHECK_LAUNCH(launch_colsum_partial(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, s.colsum_ws, bias_jobs, sd), "conv bias gradient");
-                }
-                if (srv || bias_jobs.n == 12) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "conv bias gradient");
+            if (!bias_first) {
+                const int brc = bias_part();
+                if (brc != ASGD_OK) return brc;
             }
             if (prev) {
                 const bool masked = (prev->kind == ST_CONV && prev->relu) || relu_under_pool(n->stages, si - 1);

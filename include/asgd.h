@@ -16,7 +16,8 @@
  *   - "device" pointers are HIP device memory owned by the caller unless stated;
  *     "host" pointers are ordinary process memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Calls enqueue work and return without synchronising the host.
+ *     Calls enqueue work and return without synchronising the host
+ *     (asgd_profile_end and asgd_net_destroy are the exceptions and say so).
  *   - Every call returns 0 on success or a negative asgd_status_t; the text of
  *     the last error of the calling thread is at asgd_last_error().  Nothing
  *     aborts or throws across this boundary.
@@ -112,9 +113,17 @@ int asgd_net_create(const asgd_layer_desc_t *layers, int n_layers, int batch, in
 /* Allocate the plan's device workspace on the current device now (optional). */
 int asgd_net_prepare(asgd_net_t *net);
 
-/* Free the plan and its workspace.  The caller must have synchronised every
- * stream the plan was used on. */
+/* Free the plan, its workspace and its internal streams and events (the host
+ * waits for the internal streams first).  The caller must have synchronised
+ * every stream the plan was used on. */
 int asgd_net_destroy(asgd_net_t *net);
+
+/* on != 0: every kernel of asgd_fwd_bwd / asgd_train_step on this plan is
+ * enqueued on the caller's stream, none on the plan's internal stream (for
+ * profilers, which then see each kernel running alone).  New plans start with
+ * on = 0, or with on = 1 if ASGD_SERIAL=1 is in the environment.  The results
+ * are the same bit for bit either way.  Errors: ASGD_EINVAL (null plan). */
+int asgd_net_set_serial(asgd_net_t *net, int on);
 
 /* Number of elements of the flat parameter vector (0 if net is NULL). */
 size_t asgd_param_count(const asgd_net_t *net);
@@ -138,8 +147,10 @@ size_t asgd_workspace_bytes(const asgd_net_t *net);
  *             plan's compute dtype (fp32, or bf16 as written by asgd_snapshot),
  *             16-byte aligned; read only.
  *   images  : device, [B,C,H,W] in the compute dtype; read only.
- *   labels  : device, int32 [B], each in [0, classes); out-of-range labels are
- *             not detected and give an undefined loss.
+ *   labels  : device, int32 [B], each in [0, classes).  A label outside that
+ *             range is never used as an address: the loss comes back NaN and
+ *             that row's logit gradient is softmax / B (no class subtracted);
+ *             every kernel still runs to its end.
  *   dropout_seed, step, worker : key of the stateless dropout mask generator
  *             (SplitMix64 finaliser over seed, step, worker, layer index and
  *             element index), so that a run can be replayed exactly.
@@ -151,8 +162,8 @@ size_t asgd_workspace_bytes(const asgd_net_t *net);
  * Kernels that do not feed the next layer (parameter gradients, filter packing)
  * may run on an internal stream of default priority, forked from and joined back
  * into `stream` with events (never inside asgd_replay_run, never between
- * asgd_profile_begin / end, and not at all with ASGD_SERIAL=1 in the
- * environment).  A plan must not be used on two streams at once (its workspace
+ * asgd_profile_begin / end, and not at all on a plan switched to serial, see
+ * asgd_net_set_serial).  A plan must not be used on two streams at once (its workspace
  * is shared).
  * Errors: ASGD_EINVAL, ASGD_EALIGN, ASGD_ENOMEM, ASGD_EHIP. */
 int asgd_fwd_bwd(asgd_net_t *net, const void *params, const void *images, const int32_t *labels,
@@ -168,7 +179,7 @@ int asgd_fwd_bwd(asgd_net_t *net, const void *params, const void *images, const 
 int asgd_apply_update(float *params, float *momentum, const float *grads, size_t n, float lr,
                       float mu, float wd, void *stream);
 
-/* The two server updates the paper names as future work (Section 5), as the
+/* The two server updates the paper names as future work (Section 4), as the
  * same kind of single pass over the flat buffers, with t = g + wd*w:
  *   Adagrad :  h += t*t;  w -= lr * t / (sqrt(h) + eps)
  *   Adadelta:  a = rho*a + (1-rho)*t*t;  d = -sqrt(b + eps) / sqrt(a + eps) * t;
@@ -283,6 +294,11 @@ int asgd_schedule_generate(int32_t *worker, int32_t *read_version, int T, uint64
  *                   on the device when the snapshot was taken).
  *   stream        : the caller's stream; the replay starts after the work
  *                   already on it and the stream waits for the replay's end.
+ * The call only enqueues: it does not wait for the GPU.  The worker and server
+ * streams and the events between them are created by the first replay on
+ * nets[0] (more events when a later replay is longer), kept by that plan and
+ * released by asgd_net_destroy(nets[0]).  The plans must not be used for
+ * anything else until `stream` has passed the replay.
  * Errors: ASGD_EINVAL (a read_version outside [a - max over schedule, a], a
  * worker index out of range, a worker whose next read precedes its previous
  * push), ASGD_EHIP. */

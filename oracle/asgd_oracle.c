@@ -402,7 +402,7 @@ void oracle_apply_update(double *w, double *v, const double *g, size_t count,
 }
 
 /* ---------------------------------------------------------------------------
- * The two server updates the paper names as the next thing to try (Section 5,
+ * The two server updates the paper names as the next thing to try (Section 4,
  * "Future directions": Adagrad and Adadelta), with the same weight-decay
  * convention as above (t = g + wd*w).
  *   Adagrad  (Duchi et al. 2011):  h = h + t*t;   w = w - lr * t / (sqrt(h) + eps)

@@ -16,7 +16,7 @@ LAYER_CONV, LAYER_RELU, LAYER_MAXPOOL, LAYER_FC, LAYER_DROPOUT, LAYER_SOFTMAX_CE
 DEBUG_OUTPUT, DEBUG_ARGMAX, DEBUG_MASK = 0, 1, 2
 OK, EINVAL, ESHAPE, ENOMEM, EHIP, EALIGN = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ["asgd_net_create", "asgd_net_prepare", "asgd_net_destroy", "asgd_param_count", "asgd_param_layout",
+EXPORTS = ["asgd_net_create", "asgd_net_prepare", "asgd_net_destroy", "asgd_net_set_serial", "asgd_param_count", "asgd_param_layout",
            "asgd_layer_shape", "asgd_workspace_bytes", "asgd_fwd_bwd", "asgd_apply_update", "asgd_snapshot",
            "asgd_apply_update_snapshot", "asgd_train_step",
            "asgd_debug_get", "asgd_profile_begin", "asgd_profile_end", "asgd_schedule_generate", "asgd_replay_run", "asgd_replay_nsync_run", "asgd_accumulate", "asgd_apply_update_adagrad", "asgd_apply_update_adadelta",
@@ -62,6 +62,7 @@ def lib():
                                       ctypes.c_int, ctypes.c_int, ctypes.POINTER(vp)]
         L.asgd_net_prepare.argtypes = [vp]
         L.asgd_net_destroy.argtypes = [vp]
+        L.asgd_net_set_serial.argtypes = [vp, ctypes.c_int]
         L.asgd_param_count.argtypes = [vp]
         L.asgd_param_count.restype = ctypes.c_size_t
         L.asgd_param_layout.argtypes = [vp, ctypes.POINTER(TensorInfo), ctypes.c_int]
@@ -152,6 +153,10 @@ def asgd_net_prepare(net):
 
 def asgd_net_destroy(net):
     _check(lib().asgd_net_destroy(net))
+
+
+def asgd_net_set_serial(net, on):
+    _check(lib().asgd_net_set_serial(net, 1 if on else 0))
 
 
 def asgd_param_count(net):

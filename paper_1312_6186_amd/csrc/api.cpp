@@ -92,6 +92,11 @@ struct asgd_net {
     // layer: they run on an internal stream beside the caller's, forked and joined with events.
     hipStream_t side = nullptr;
     bool in_replay = false;   // replicas of a replay already run beside each other: no side stream then (measured slower)
+    bool serial = false;      // every kernel on the caller's stream (asgd_net_set_serial, or ASGD_SERIAL=1 at creation)
+    // Streams and events of the A-SGD replay, kept by the plan of worker 0 from one replay to the next (created on
+    // first use, released with the plan), so that a replay only enqueues.
+    std::vector<hipStream_t> replay_streams;   // one per worker, then the server's
+    std::vector<hipEvent_t> replay_events;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_bias = nullptr;
     std::vector<hipEvent_t> ev_pack, ev_dy, ev_dg;   // per stage: filters packed, output gradient ready, data gradient issued
     float *row_loss = nullptr;
@@ -333,6 +338,9 @@ int release_device(asgd_net *n)
 {
     int rc = ASGD_OK;
     if (n->side) { (void)hipStreamSynchronize(n->side); (void)hipStreamDestroy(n->side); n->side = nullptr; }
+    for (hipStream_t st : n->replay_streams) if (st) { (void)hipStreamSynchronize(st); (void)hipStreamDestroy(st); }
+    for (hipEvent_t e : n->replay_events) if (e) (void)hipEventDestroy(e);
+    n->replay_streams.clear(); n->replay_events.clear();
     if (n->ev_fork) { (void)hipEventDestroy(n->ev_fork); n->ev_fork = nullptr; }
     if (n->ev_join) { (void)hipEventDestroy(n->ev_join); n->ev_join = nullptr; }
     if (n->ev_bias) { (void)hipEventDestroy(n->ev_bias); n->ev_bias = nullptr; }
@@ -406,9 +414,10 @@ struct ProfScope {
     ~ProfScope() { if (stop) (void)hipEventRecord(stop, st); }
 };
 
-// ASGD_SERIAL=1 in the environment keeps every kernel on the caller's stream (no internal side stream), so that
-// a profiler sees each kernel running alone.
-bool serial_mode()
+// ASGD_SERIAL=1 in the environment makes new plans keep every kernel on the caller's stream (no internal side
+// stream), so that a profiler sees each kernel running alone; asgd_net_set_serial switches one plan.  The results
+// are the same bit for bit either way (every kernel is deterministic and the two streams share no output).
+bool serial_default()
 {
     static const bool on = getenv("ASGD_SERIAL") && getenv("ASGD_SERIAL")[0] == '1';
     return on;
@@ -462,7 +471,7 @@ int forward(asgd_net *n, const void *params, const void *images, const int32_t *
         else CHECK_LAUNCH(launch_stage_input(dt, images, n->act0, B, n->in_c, n->in_h, n->in_w, n->in_cp, st), "stage_input");
     }
     // filter packing: beside the input staging and the first layers (in line when profiling, to be timed alone)
-    const bool fork = !n->prof_on && !n->in_replay && !serial_mode();
+    const bool fork = !n->prof_on && !n->in_replay && !n->serial;
     hipStream_t sd = fork ? n->side : st;
     if (fork) {
         CHECK_HIP(hipEventRecord(n->ev_fork, st), "hipEventRecord");
@@ -588,7 +597,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
 {
     const int B = n->batch, dt = n->dtype;
     const double es = (double)dtype_size(dt), Bd = (double)B;
-    const bool fork = !n->prof_on && !n->in_replay && !serial_mode();
+    const bool fork = !n->prof_on && !n->in_replay && !n->serial;
     hipStream_t sd = fork ? n->side : st;   // parameter gradients go here
     ColsumJobs bias_jobs; bias_jobs.n = 0;  // second stage of the bias gradients: one launch at the end, or per layer when pushing by layer
     int first_param = -1;
@@ -778,6 +787,7 @@ int asgd_net_create(const asgd_layer_desc_t *layers, int n_layers, int batch, in
     try {
         n->layers.assign(layers, layers + n_layers);
         n->batch = batch; n->in_c = in_c; n->in_h = in_h; n->in_w = in_w; n->dtype = compute_dtype;
+        n->serial = serial_default();
         const int rc = plan_net(*n);
         if (rc != ASGD_OK) { delete n; return rc; }
     } catch (const std::bad_alloc &) {
@@ -792,6 +802,13 @@ int asgd_net_prepare(asgd_net_t *net)
 {
     if (!net) return fail(ASGD_EINVAL, "asgd_net_prepare: null plan");
     return ensure_prepared(net);
+}
+
+int asgd_net_set_serial(asgd_net_t *net, int on)
+{
+    if (!net) return fail(ASGD_EINVAL, "asgd_net_set_serial: null plan");
+    net->serial = on != 0;
+    return ASGD_OK;
 }
 
 int asgd_net_destroy(asgd_net_t *net)
@@ -1015,46 +1032,48 @@ static int replay_impl(asgd_net_t *const *nets, int n_workers, float *params, fl
         last_push[worker[a]] = a;
     }
     for (int w = 0; w < n_workers; ++w) {
-        nets[w]->in_replay = n_workers > 1;
         const int rc = ensure_prepared(nets[w]);
         if (rc != ASGD_OK) return rc;
     }
+    for (int w = 0; w < n_workers; ++w) nets[w]->in_replay = n_workers > 1;   // until this call has enqueued its work
     const asgd_net *n0 = nets[0];
     const size_t P = n0->param_count;
     const size_t img_bytes = (size_t)n0->batch * n0->in_c * n0->in_h * n0->in_w * dtype_size(n0->dtype);
     int *counter = nets[0]->version_counter;
     hipStream_t caller = static_cast<hipStream_t>(stream);
 
-    std::vector<hipStream_t> ws(n_workers, nullptr);
-    hipStream_t server = nullptr;
-    std::vector<hipEvent_t> ev;  // everything created here, destroyed at the end
+    // Streams and events live in the plan of worker 0 and are reused by later replays: recording an event again is
+    // safe, because a stream that waits for an event waits for the record that preceded the wait call.
+    asgd_net *keeper = nets[0];
     int rc = ASGD_OK;
-    auto new_event = [&](hipEvent_t *e) -> bool {
-        if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return false;
-        ev.push_back(*e);
-        return true;
-    };
 #define RP(expr)                                                                    \
     do {                                                                            \
         const hipError_t e_ = (expr);                                               \
         if (e_ != hipSuccess && rc == ASGD_OK) rc = hip_fail(e_, #expr);            \
     } while (0)
-
-    for (int w = 0; w < n_workers && rc == ASGD_OK; ++w) RP(hipStreamCreateWithFlags(&ws[w], hipStreamNonBlocking));
-    if (rc == ASGD_OK) RP(hipStreamCreateWithFlags(&server, hipStreamNonBlocking));
-    std::vector<hipEvent_t> ev_upd(T, nullptr), ev_snap(T, nullptr), ev_grad(T, nullptr);
-    hipEvent_t ev_start = nullptr, ev_reset = nullptr;
-    if (rc == ASGD_OK) {
-        bool ok = new_event(&ev_start) && new_event(&ev_reset);
-        for (int a = 0; a < T && ok; ++a) ok = new_event(&ev_upd[a]) && new_event(&ev_snap[a]) && new_event(&ev_grad[a]);
-        if (!ok) rc = fail(ASGD_EHIP, "asgd_replay_run: hipEventCreate failed");
+    while ((int)keeper->replay_streams.size() < n_workers + 1 && rc == ASGD_OK) {
+        hipStream_t st = nullptr;
+        RP(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+        if (rc == ASGD_OK) keeper->replay_streams.push_back(st);
     }
-    if (rc == ASGD_OK) {
-        RP(hipEventRecord(ev_start, caller));
-        RP(hipStreamWaitEvent(server, ev_start, 0));
-        if (launch_fill_zero(counter, 4, server) != 0 && rc == ASGD_OK) rc = hip_fail(hipGetLastError(), "fill kernel");
-        RP(hipEventRecord(ev_reset, server));
+    const size_t n_events = 3 * (size_t)T + 2;
+    while (keeper->replay_events.size() < n_events && rc == ASGD_OK) {
+        hipEvent_t e = nullptr;
+        RP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        if (rc == ASGD_OK) keeper->replay_events.push_back(e);
     }
+    if (rc != ASGD_OK) { for (int w = 0; w < n_workers; ++w) nets[w]->in_replay = false; return rc; }
+    hipStream_t *ws = keeper->replay_streams.data();
+    hipStream_t server = keeper->replay_streams[n_workers];
+    hipEvent_t *ev_upd = keeper->replay_events.data(), *ev_snap = ev_upd + T, *ev_grad = ev_snap + T;
+    hipEvent_t ev_start = keeper->replay_events[3 * (size_t)T], ev_reset = keeper->replay_events[3 * (size_t)T + 1];
+    // Everything below waits, directly or through the server stream, for the work already on the caller's stream; the
+    // internal streams of a previous replay on these plans were joined into the caller's stream of that replay.
+    RP(hipEventRecord(ev_start, caller));
+    RP(hipStreamWaitEvent(server, ev_start, 0));
+    for (int w = 0; w < n_workers; ++w) RP(hipStreamWaitEvent(ws[w], ev_start, 0));
+    if (rc == ASGD_OK && launch_fill_zero(counter, 4, server) != 0) rc = hip_fail(hipGetLastError(), "fill kernel");
+    RP(hipEventRecord(ev_reset, server));
     // Iteration v enqueues every snapshot that must see exactly v applied updates
     // (and the gradient computed on it), then update v, which waits for them.
     for (int v = 0; v < T && rc == ASGD_OK; ++v) {
@@ -1088,15 +1107,13 @@ static int replay_impl(asgd_net_t *const *nets, int n_workers, float *params, fl
             rc = hip_fail(hipGetLastError(), "update kernel");
         RP(hipEventRecord(ev_upd[v], server));
     }
+    // Update T-1 is behind every snapshot and every gradient of the replay, so the caller's stream, which waits for
+    // it, is behind all of the replay's work.  After an error part of the schedule may be enqueued: wait for what is.
     if (rc == ASGD_OK) RP(hipStreamWaitEvent(caller, ev_upd[T - 1], 0));
-    // Drain the internal streams before their events and the streams themselves go away.
-    for (int w = 0; w < n_workers; ++w)
-        if (ws[w]) { (void)hipStreamSynchronize(ws[w]); }
-    if (server) (void)hipStreamSynchronize(server);
-    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
-    for (int w = 0; w < n_workers; ++w)
-        if (ws[w]) (void)hipStreamDestroy(ws[w]);
-    if (server) (void)hipStreamDestroy(server);
+    else {
+        for (int w = 0; w <= n_workers; ++w) (void)hipStreamSynchronize(keeper->replay_streams[w]);
+    }
+    for (int w = 0; w < n_workers; ++w) nets[w]->in_replay = false;
 #undef RP
     return rc;
 }

@@ -703,7 +703,7 @@ __device__ __forceinline__ void output_tile(uint4 *smem, f32x16 (&acc)[Cfg::NB][
 // the register sets hold tiles t+1 .. t+DEPTH-1 (possibly still arriving).
 template <typename T, class Cfg, class LA, class LB>
 __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, Epilogue ep, int M, int N, int nkt, int kt_per_split,
-                                                                int tiles_m, int tiles_n, float *ws, int dbg)
+                                                                int tiles_m, int tiles_n, float *ws)
 {
     constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB, DEPTH = Cfg::DEPTH;
     constexpr int TA = LA::kTrans ? TransTile<T, BM>::BYTES : BM * 128, TB = LB::kTrans ? TransTile<T, BN>::BYTES : BN * 128;
@@ -738,8 +738,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
     foA.init(wm, lane);
     foB.init(wn, lane);
     // a wave whose whole tile lies outside C (96 output columns in a tile of 128: a quarter of the waves) only helps
-    // to move the operands; wave-uniform, like the debug switch that turns all multiplication off
-    const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N && !(dbg & 4)) ? 1 : 0) != 0;
+    // to move the operands; wave-uniform
+    const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N) ? 1 : 0) != 0;
 
     // register set that receives tile j is j % DEPTH (tile 0 goes through set 0 straight into LDS stage 0)
     stA.template load<0>(la); stB.template load<0>(lb);
@@ -774,7 +774,6 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
         if (busy) compute_tile<T, MB, NB>(sA[0], sB[0], acc, foA, foB);
     }
 
-    if (dbg & 8) return;
     output_tile<T, Cfg, (int)sizeof(smem)>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
 }
 
@@ -785,7 +784,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
 constexpr int kFetchThreads = 256;
 template <typename T, class Cfg, class LA, class LB>
 __global__ __launch_bounds__(Cfg::NT + kFetchThreads, 2) void gemm_ws_kernel(LA la, LB lb, Epilogue ep, int M, int N, int nkt, int kt_per_split,
-                                                                           int tiles_m, int tiles_n, float *ws, int dbg)
+                                                                           int tiles_m, int tiles_n, float *ws)
 {
     constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB, NP = kFetchThreads;
     constexpr int TA = LA::kTrans ? TransTile<T, BM>::BYTES : BM * 128, TB = LB::kTrans ? TransTile<T, BN>::BYTES : BN * 128;
@@ -837,7 +836,7 @@ __global__ __launch_bounds__(Cfg::NT + kFetchThreads, 2) void gemm_ws_kernel(LA 
     FragOff<T, LB::kTrans, BN> foB;
     foA.init(wm, lane);
     foB.init(wn, lane);
-    const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N && !(dbg & 4)) ? 1 : 0) != 0;
+    const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N) ? 1 : 0) != 0;
     float bias8[8];
     load_bias8<T>(ep, tn * BN + (tid % (BN / 8)) * 8, bias8);
     for (int t = 0; t < nt; t += 2) {
@@ -848,7 +847,6 @@ __global__ __launch_bounds__(Cfg::NT + kFetchThreads, 2) void gemm_ws_kernel(LA 
             if (busy) compute_tile<T, MB, NB>(sA[1], sB[1], acc, foA, foB);
         }
     }
-    if (dbg & 8) return;
     output_tile<T, Cfg, (int)sizeof(smem)>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
 }
 
@@ -910,7 +908,7 @@ template <typename T> struct PatchSrc {
 
 template <typename T, int NPL, class Cfg, int PPT>
 __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc<T> pa, ChunkK<T, PPT> lb, Epilogue ep, int M, int N, int nkt,
-                                                                    int kt_per_split, int tiles_m, int tiles_n, float *ws, int dbg)
+                                                                    int kt_per_split, int tiles_m, int tiles_n, float *ws)
 {
     constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB;
     constexpr int TB = BN * 128;
@@ -976,8 +974,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
     FragOff<T, false, BN> foB;
     foB.init(wn, lane);
     // a wave whose whole tile lies outside C (96 output columns in a tile of 128: a quarter of the waves) only helps
-    // to move the operands; wave-uniform, like the debug switch that turns all multiplication off
-    const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N && !(dbg & 4)) ? 1 : 0) != 0;
+    // to move the operands; wave-uniform
+    const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N) ? 1 : 0) != 0;
     // the two fragment rows of this lane: patch address at window position (0, 0) and the mask of positions inside the image
     constexpr unsigned kHalfBytes = 8 * (unsigned)sizeof(T);
     // A lane whose window position lies outside the image reads zeros instead, at the address behind the patch
@@ -1044,7 +1042,6 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
         if (t + 1 < nt) step(std::integral_constant<int, 1>{}, false, t + 2 < nt);
     }
 
-    if (dbg & 8) return;
     output_tile<T, Cfg, (int)sizeof(smem)>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
 }
 
@@ -1057,7 +1054,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void conv_patch_kernel(PatchSrc
 constexpr int kProducers = 256;
 template <typename T, int NPL, class Cfg, int PPT>
 __global__ __launch_bounds__(Cfg::NT + kProducers, 2) void conv_patch_ws_kernel(PatchSrc<T> pa, ChunkK<T, PPT> lb, Epilogue ep, int M, int N, int nkt,
-                                                                              int kt_per_split, int tiles_m, int tiles_n, float *ws, int dbg)
+                                                                              int kt_per_split, int tiles_m, int tiles_n, float *ws)
 {
     constexpr int BK = Geo<T>::BK, BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, MB = Cfg::MB, NB = Cfg::NB, NP = kProducers;
     constexpr int TB = BN * 128;
@@ -1136,8 +1133,7 @@ __global__ __launch_bounds__(Cfg::NT + kProducers, 2) void conv_patch_ws_kernel(
             step(std::integral_constant<int, 0>{}, t == 0, t + 1 < nt);
             if (t + 1 < nt) step(std::integral_constant<int, 1>{}, false, t + 2 < nt);
         }
-        if (dbg & 8) return;
-        // the fetching waves help to take the output tile out of LDS
+            // the fetching waves help to take the output tile out of LDS
         float bias8[8];
         load_bias8<T>(ep, tn * BN + (tid % (BN / 8)) * 8, bias8);
         __syncthreads();
@@ -1155,7 +1151,7 @@ __global__ __launch_bounds__(Cfg::NT + kProducers, 2) void conv_patch_ws_kernel(
     const int lrow = lane & 31, half = lane >> 5;
     FragOff<T, false, BN> foB;
     foB.init(wn, lane);
-    const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N && !(dbg & 4)) ? 1 : 0) != 0;
+    const bool busy = __builtin_amdgcn_readfirstlane((tm * BM + wm < M && tn * BN + wn < N) ? 1 : 0) != 0;
     constexpr unsigned kHalfBytes = 8 * (unsigned)sizeof(T);
     constexpr unsigned zero_base = (unsigned)(PPMAX * PITCH);
     unsigned abase[2], amask[2];
@@ -1197,7 +1193,6 @@ __global__ __launch_bounds__(Cfg::NT + kProducers, 2) void conv_patch_ws_kernel(
         step(std::integral_constant<int, 0>{}, t == 0);
         if (t + 1 < nt) step(std::integral_constant<int, 1>{}, false);
     }
-    if (dbg & 8) return;
     output_tile<T, Cfg, (int)sizeof(smem), NT + NP>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
 }
 
@@ -1291,14 +1286,6 @@ template <typename T> static void launch_splitk_reduce(const float *ws, int spli
 }
 
 // ------------------------------------------------------------------ host side
-// ASGD_DBG in the environment switches phases of the GEMM kernel off (bit 2: the MFMAs, bit 3: the output
-// phase) to time the rest; results are then wrong.  For experiments only.
-static int debug_bits()
-{
-    static const int bits = getenv("ASGD_DBG") ? atoi(getenv("ASGD_DBG")) : 0;
-    return bits;
-}
-
 GemmPlan plan_gemm(long M, long N, long K, int dtype, int max_splits)
 {
     const int BK = dtype == kBF16 ? (int)Geo<bf16_t>::BK : (int)Geo<float>::BK;
@@ -1339,18 +1326,13 @@ static int run_tile(const LA &la, const LB &lb, int M, int N, int K, const Epilo
     if (blocks > 0x7fffffffL) return -1;
     // The convolution filter gradient runs with fetching and multiplying waves (gemm_ws_kernel: -2.6 % in bf16, -4 % in
     // fp32 for the class); the im2col forward gather of the first layer is 12 % slower that way (seven K tiles: the
-    // head of a workgroup weighs more than its loop) and stays as it is.  ASGD_NOWS in the environment switches it off.
-    static const bool two_roles = getenv("ASGD_NOWS") == nullptr;
-    if constexpr (std::is_same<LB, GatherT<T>>::value) {
-        if (two_roles)
-            hipLaunchKernelGGL((gemm_ws_kernel<T, Cfg128, LA, LB>), dim3((unsigned)blocks), dim3(Cfg128::NT + kFetchThreads), 0, s, la, lb, ep, M, N, nkt,
-                               per, tiles_m, tiles_n, splits > 1 ? ws : nullptr, debug_bits());
-        else
-            hipLaunchKernelGGL((gemm_kernel<T, Cfg, LA, LB>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, la, lb, ep, M, N, nkt, per, tiles_m,
-                               tiles_n, splits > 1 ? ws : nullptr, debug_bits());
-    } else
+    // head of a workgroup weighs more than its loop) and stays as it is.
+    if constexpr (std::is_same<LB, GatherT<T>>::value)
+        hipLaunchKernelGGL((gemm_ws_kernel<T, Cfg128, LA, LB>), dim3((unsigned)blocks), dim3(Cfg128::NT + kFetchThreads), 0, s, la, lb, ep, M, N, nkt,
+                           per, tiles_m, tiles_n, splits > 1 ? ws : nullptr);
+    else
         hipLaunchKernelGGL((gemm_kernel<T, Cfg, LA, LB>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, la, lb, ep, M, N, nkt, per, tiles_m,
-                           tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+                           tiles_n, splits > 1 ? ws : nullptr);
     if (splits > 1) launch_splitk_reduce<T>(ws, splits, ep, M, N, s);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
@@ -1413,13 +1395,12 @@ template <typename T> static PlainT<T> make_plain_t(const void *p, long ld, int 
 
 // The patch form applies to stride-1 convolutions with equal input and output grids over a dense tensor whose
 // run of pixels per block tile fits the patch buffer.  Returns the window positions per K tile to run it with
-// (1 or 2), or 0 where the im2col gather is the better choice.  ASGD_NOPATCH in the environment switches it off.
+// (1 or 2), or 0 where the im2col gather is the better choice.
 template <typename T> static int patch_applies(const Gather &a, long ldb)
 {
-    static const bool off = getenv("ASGD_NOPATCH") != nullptr;
     const size_t pixb = a.pix ? a.pix : (size_t)a.C * sizeof(T);
     const int npos = a.kh * a.kw;
-    if (off || !(a.sm == 1 && a.ds == 1 && a.Ho == a.H && a.Wo == a.W && npos > 1 && npos <= 32 && 2 * a.pad == a.kh - 1 &&
+    if (!(a.sm == 1 && a.ds == 1 && a.Ho == a.H && a.Wo == a.W && npos > 1 && npos <= 32 && 2 * a.pad == a.kh - 1 &&
                  2 * a.pad == a.kw - 1 && (a.rowb == 0 || a.rowb == (size_t)a.W * pixb) && pixb % 16 == 0 && a.C % (int)Geo<T>::CH == 0 &&
                  ((uintptr_t)a.x & 15) == 0 && ldb == (long)npos * a.C && 128 + (a.kh - 1) * a.W + a.kw - 1 <= 256))
         return 0;
@@ -1475,38 +1456,30 @@ static int run_patch_cfg(const Gather &a, const void *b, long ldb, int N, const 
     const long blocks = (long)tiles_m * tiles_n * splits;
     if (blocks > 0x7fffffffL) return -1;
     const int pp = 128 + (a.kh - 1) * a.W + a.kw - 1;   // pixels a block tile needs
-    // The wide shape runs with the two kinds of waves (see conv_patch_ws_kernel); ASGD_NOWS in the environment keeps
-    // every wave doing everything, for comparisons.
-    static const bool two_roles = getenv("ASGD_NOWS") == nullptr;
-    if (two_roles && Cfg::NT == 512) {
+    // The wide shape runs with the two kinds of waves (see conv_patch_ws_kernel).
+    if constexpr (Cfg::NT == 512) {
         if (pp > 256) return -1;
         if constexpr (PPT == 2)
             hipLaunchKernelGGL((conv_patch_ws_kernel<T, 4, Cfg128, 2>), dim3((unsigned)blocks), dim3(Cfg128::NT + kProducers), 0, s, pa, lb, ep, M, N, nkt, per,
-                               tiles_m, tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+                               tiles_m, tiles_n, splits > 1 ? ws : nullptr);
         else if (pp <= 192)
             hipLaunchKernelGGL((conv_patch_ws_kernel<T, 6, Cfg128, 1>), dim3((unsigned)blocks), dim3(Cfg128::NT + kProducers), 0, s, pa, lb, ep, M, N, nkt, per,
-                               tiles_m, tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+                               tiles_m, tiles_n, splits > 1 ? ws : nullptr);
         else
             hipLaunchKernelGGL((conv_patch_ws_kernel<T, 8, Cfg128, 1>), dim3((unsigned)blocks), dim3(Cfg128::NT + kProducers), 0, s, pa, lb, ep, M, N, nkt, per,
-                               tiles_m, tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+                               tiles_m, tiles_n, splits > 1 ? ws : nullptr);
     } else if constexpr (PPT == 2) {
-        // half-wide chunks: four pieces per pixel, so two per thread hold 256 pixels with 512 threads, three hold 192 with 256
-        constexpr int NPL = Cfg::NT == 512 ? 2 : 3;
+        // the narrow shape, half-wide chunks: four pieces per pixel, three per thread hold 192 pixels with 256 threads
+        constexpr int NPL = 3;
         if (pp > NPL * Cfg::NT / 4) return -1;
         hipLaunchKernelGGL((conv_patch_kernel<T, NPL, Cfg, 2>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
-                           tiles_n, splits > 1 ? ws : nullptr, debug_bits());
+                           tiles_n, splits > 1 ? ws : nullptr);
     } else {
-        // pieces per thread for short runs (up to 192 pixels with 512 threads, 160 with 256) and, with 512 threads, for runs of up to 256 pixels
-        constexpr int NPL_S = Cfg::NT == 512 ? 3 : 5;
-        if (pp <= NPL_S * Cfg::NT / 8)
-            hipLaunchKernelGGL((conv_patch_kernel<T, NPL_S, Cfg, 1>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
-                               tiles_n, splits > 1 ? ws : nullptr, debug_bits());
-        else if constexpr (Cfg::NT == 512) {
-            if (pp > 256) return -1;
-            hipLaunchKernelGGL((conv_patch_kernel<T, 4, Cfg, 1>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
-                               tiles_n, splits > 1 ? ws : nullptr, debug_bits());
-        } else
-            return -1;
+        // the narrow shape, whole-tile chunks: five pieces per thread hold runs of up to 160 pixels with 256 threads
+        constexpr int NPL_S = 5;
+        if (pp > NPL_S * Cfg::NT / 8) return -1;
+        hipLaunchKernelGGL((conv_patch_kernel<T, NPL_S, Cfg, 1>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, s, pa, lb, ep, M, N, nkt, per, tiles_m,
+                           tiles_n, splits > 1 ? ws : nullptr);
     }
     if (splits > 1) launch_splitk_reduce<T>(ws, splits, ep, M, N, s);
     return hipGetLastError() == hipSuccess ? 0 : -1;

@@ -1156,7 +1156,10 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(const float *__restrict
     sum = block_sum(sum, sh);
     const float lse = m + logf(sum);
     const int label = labels[row];
-    if (t == 0) row_loss[row] = lse - zr[label];
+    // a label outside [0, C) addresses nothing: the row's loss (and with it the mean) becomes NaN, and dz is
+    // the plain softmax / B, since no class compares equal to it below
+    const bool label_ok = (unsigned)label < (unsigned)C;
+    if (t == 0) row_loss[row] = label_ok ? lse - zr[label] : __builtin_nanf("");
     const float inv_b = 1.f / (float)B;
     T *dr = dz + (long)row * ld;
     for (int c = t; c < (int)ld; c += 256) {

@@ -183,9 +183,15 @@ def gpu_decisions(g, layers, trace, dtype, trace_plain=None):
             diff = g_arg != o_arg
             nflip = int(diff.sum())
             if nflip:
-                gap = trace[li]["out"] - oops.maxpool_gather(x_o, g_arg, k, s)      # >= 0
-                assert gap[diff].max() <= band, ("pooling position differs although the window has a clear maximum", li,
-                                                 float(gap[diff].max()), band)
+                p_o = trace[li]["out"]
+                gap = p_o - oops.maxpool_gather(x_o, g_arg, k, s)      # >= 0
+                allowed = np.full(p_o.shape, band)
+                if dtype == B.BF16:
+                    # stored activations are bf16 numbers: values that differ in their last fp32 bits can be stored one
+                    # bf16 step apart, so each of the two compared elements may be off by one step of its magnitude
+                    allowed += 2.0 * np.exp2(np.floor(np.log2(np.maximum(np.abs(p_o), 1e-30))) - 7)
+                assert (gap[diff] <= allowed[diff]).all(), ("pooling position differs although the window has a clear maximum", li,
+                                                            float(gap[diff].max()), band)
             bound = 4 + int((1e-5 if dtype == B.F32 else 2e-3) * o_arg.size)
             assert nflip <= bound, ("too many differing pooling positions", li, nflip, bound)
             report["layers"].append(dict(layer=li, kind="maxpool", flips=nflip, bound=bound, value_err=err, band_rel=band / rms if rms > 0 else 0.0,

@@ -39,6 +39,60 @@ PEAK = {"hbm": 8000.0, "mfma_bf16": 2500.0, "mfma_f32": 157.3}   # GB/s, TFLOP/s
 MFMA_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad", "fc_fwd", "fc_dgrad", "fc_wgrad")
 
 
+def csrc_hash():
+    """Hash of the kernel sources: ties a committed counter summary to the kernels it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_1312_6186_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        with open(os.path.join(d, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def class_table(prof, K, dtname):
+    """Per kernel class: time per step (HIP events around every operation) and the achieved rate on the algorithmic
+    work of the class, against the roofline that bounds it."""
+    out = {}
+    for name, p in prof.items():
+        if p["launches"] == 0:
+            continue
+        ms = p["ms"] / K
+        if name in MFMA_CLASSES:
+            ach = p["flops"] / K / (ms * 1e-3) / 1e12
+            peak = PEAK["mfma_" + dtname]
+            out[name] = {"bound": "mfma", "ms_per_step": ms, "launches_per_step": p["launches"] / K,
+                         "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
+                         "hbm_GBps_on_algorithmic_bytes": p["bytes"] / K / (ms * 1e-3) / 1e9}
+        else:
+            ach = p["bytes"] / K / (ms * 1e-3) / 1e9
+            out[name] = {"bound": "hbm", "ms_per_step": ms, "launches_per_step": p["launches"] / K,
+                         "achieved": ach, "peak": PEAK["hbm"], "unit": "GB/s", "frac": ach / PEAK["hbm"]}
+    return out
+
+
+def roofline_of(classes_out, workload):
+    """The `roofline` object for the class that takes the most time; HBM bytes per launch from the committed
+    rocprofv3 counter summary of this workload, if it was measured on the kernels as they are now."""
+    dominant = max(classes_out, key=lambda k: classes_out[k]["ms_per_step"])
+    d = classes_out[dominant]
+    traffic, note = None, "no counter summary for this workload"
+    tpath = os.path.join(ROOT, "profiles", workload + "_hbm_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            tj = json.load(f)
+        t = tj.get("classes", {}).get(dominant)
+        if tj.get("csrc_sha256") != csrc_hash():
+            note = "the committed counter summary was measured on other kernel sources (%s, now %s)" % (tj.get("csrc_sha256"), csrc_hash())
+        elif t:
+            traffic = (t["hbm_read_bytes"] + t["hbm_written_bytes"]) / t["launches"]
+            note = "profiles/%s_hbm_traffic.json" % workload
+    return {"kernel": dominant, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"], "unit": d["unit"],
+            "frac": d["frac"], "traffic": traffic, "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
+            "traffic_source": note,
+            "launches_per_step": d["launches_per_step"], "ms_per_launch": d["ms_per_step"] / d["launches_per_step"]}
+
+
 def cpu_baseline(layers, in_shape, classes, sample_batch, hp):
     """The oracle as it stands, on the host cores: one fwd+bwd+update on `sample_batch` images of the same net."""
     import numpy as np
@@ -100,19 +154,39 @@ def bench_asgd(args, batch, n_sync=0):
     worker, rv = run(args.steps)
     elapsed = time.perf_counter() - t0
     ok = bool((log[:args.steps].cpu().numpy() == np.stack([np.arange(args.steps), worker, rv], 1)).all())
+    # Per-class times at the worker shape: the same kernels, one replica alone on one stream with a pair of HIP
+    # events around every operation (inside the replay the replicas' kernels overlap and cannot be bracketed).
+    stream = torch.cuda.current_stream()
+    K = min(args.steps, 8)
+    B.asgd_profile_begin(nets[0])
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(K)]
+    for i in range(K):
+        B.asgd_fwd_bwd(nets[0], copies[0], images[i % nb], labels[i % nb], 3003, i, 0, losses[:1], grads[0], stream)
+        ev[i][0].record(stream)
+        B.asgd_apply_update_snapshot(params, mom, grads[0], lr, mu, wd, copies[0], B.BF16, stream)
+        ev[i][1].record(stream)
+    torch.cuda.synchronize()
+    classes_out = class_table(B.asgd_profile_end(nets[0]), K, "bf16")
+    upd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / K
+    classes_out["update_snapshot"] = {"bound": "hbm", "ms_per_step": upd_ms, "launches_per_step": 1, "achieved": P * 22 / (upd_ms * 1e-3) / 1e9,
+                                      "peak": PEAK["hbm"], "unit": "GB/s", "frac": P * 22 / (upd_ms * 1e-3) / 1e9 / PEAK["hbm"]}
     for n in nets:
         B.asgd_net_destroy(n)
+    cpu = cpu_baseline(layers, in_shape, classes, args.cpu_sample, (lr, mu, wd)) if args.cpu_sample > 0 else None
     print(json.dumps({
         "metric": "images/sec fwd+bwd+update, AlexNet-style bs128; % MFMA peak (conv/FC)",
         "value": batch * per * args.steps / elapsed, "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload, "net": "AlexNet-style single column (62378344 parameters)", "workers": W,
-                   "batch_per_worker": batch, "max_staleness": 3, "schedule_seed": 4005, "n_sync": per,
+        "config": {"workload": args.workload,
                    "step": ("one cycle: fetch, %d local steps (fwd_bwd, accumulate, local update) on a worker stream, "
                             "update with the summed gradient on the server stream" % per) if n_sync else
                            "one pushed gradient: snapshot + fwd_bwd on a worker stream, update on the server stream"},
-        "schedule_log_matches": ok, "roofline": None, "cpu_baseline": None}))
+        "workload_detail": {"net": "AlexNet-style single column (%d parameters)" % P, "workers": W, "batch_per_worker": batch,
+                            "max_staleness": 3, "schedule_seed": 4005, "n_sync": per, "lr": lr, "mu": mu, "wd": wd},
+        "schedule_log_matches": ok,
+        "roofline": dict(roofline_of(classes_out, args.workload), measured="one replica alone at the worker shape (batch %d)" % batch),
+        "kernel_classes": classes_out, "cpu_baseline": cpu}))
 
 
 def main():
@@ -209,21 +283,7 @@ def main():
     torch.cuda.synchronize()
     K = args.steps
     es = 2 if dtname == "bf16" else 4
-    classes_out = {}
-    for name, p in prof.items():
-        if p["launches"] == 0:
-            continue
-        ms = p["ms"] / K
-        if name in MFMA_CLASSES:
-            ach = p["flops"] / K / (ms * 1e-3) / 1e12
-            peak = PEAK["mfma_" + dtname]
-            classes_out[name] = {"bound": "mfma", "ms_per_step": ms, "launches_per_step": p["launches"] / K,
-                                 "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
-                                 "hbm_GBps_on_algorithmic_bytes": p["bytes"] / K / (ms * 1e-3) / 1e9}
-        else:
-            ach = p["bytes"] / K / (ms * 1e-3) / 1e9
-            classes_out[name] = {"bound": "hbm", "ms_per_step": ms, "launches_per_step": p["launches"] / K,
-                                 "achieved": ach, "peak": PEAK["hbm"], "unit": "GB/s", "frac": ach / PEAK["hbm"]}
+    classes_out = class_table(prof, K, dtname)
     upd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / K
     ach = P * (20 + es) / (upd_ms * 1e-3) / 1e9
     classes_out["update_snapshot"] = {"bound": "hbm", "ms_per_step": upd_ms, "launches_per_step": 1, "achieved": ach, "peak": PEAK["hbm"],
@@ -233,19 +293,7 @@ def main():
         ms = sum(e[a].elapsed_time(e[b]) for e in ev2[1:]) / (len(ev2) - 1)
         unfused[name] = {"bound": "hbm", "ms_per_call": ms, "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK["hbm"], "unit": "GB/s",
                          "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK["hbm"]}
-    dominant = max(classes_out, key=lambda k: classes_out[k]["ms_per_step"])
-    d = classes_out[dominant]
-    # HBM bytes per launch of that class, from the committed rocprofv3 counter summary of this workload (null if there is none)
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", args.workload + "_hbm_traffic.json")
-    if os.path.exists(tpath):
-        with open(tpath) as f:
-            t = json.load(f).get("classes", {}).get(dominant)
-        if t:
-            traffic = (t["hbm_read_bytes"] + t["hbm_written_bytes"]) / t["launches"]
-    roofline = {"kernel": dominant, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"], "unit": d["unit"],
-                "frac": d["frac"], "traffic": traffic, "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
-                "launches_per_step": d["launches_per_step"], "ms_per_launch": d["ms_per_step"] / d["launches_per_step"]}
+    roofline = roofline_of(classes_out, args.workload)
     # the two adaptive server updates on the same buffers (not part of the step; they leave garbage in `scratch_copy`-sized state)
     state_a, state_b = torch.zeros_like(master), torch.zeros_like(master)
     w_tmp = master.clone()
@@ -271,8 +319,8 @@ def main():
         "value": batch * args.steps / elapsed, "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if dtname == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "net": "%s (%d parameters)" % (cfg["name"], P), "batch": batch,
-                   "step": "fwd_bwd + apply_update_snapshot (push fused with the next fetch)", "lr": lr, "mu": mu, "wd": wd},
+        "config": {"workload": args.workload, "step": "fwd_bwd + apply_update_snapshot (push fused with the next fetch)"},
+        "workload_detail": {"net": "%s (%d parameters)" % (cfg["name"], P), "batch": batch, "lr": lr, "mu": mu, "wd": wd},
         "loss": final_loss,
         "roofline": roofline,
         "mfma_all_gemms": {"achieved": mfma_flops / (mfma_ms * 1e-3) / 1e12, "peak": PEAK["mfma_" + dtname], "unit": "TFLOP/s",

@@ -40,9 +40,14 @@ def sgd_loop(net, params0, batch_fn, T, lr, mu, wd, dropout_seed=0, worker_dtype
 
 
 def replay(net, params0, worker, read_version, batch_fn, lr, mu, wd, dropout_seed=0,
-           worker_dtype="f64", act_dtype="f64"):
+           worker_dtype="f64", act_dtype="f64", decisions_fn=None):
     """A-SGD with the given schedule.  Returns final params, momentum, the loss of
-    every pushed gradient and the log of (update, worker, version read)."""
+    every pushed gradient and the log of (update, worker, version read).
+    ``decisions_fn(a, worker_params, images, labels)``, if given, may return the
+    ReLU masks / pooling positions to use for update a (the ``decisions`` argument
+    of ``OracleNet.fwd_bwd``; None = the oracle's own): a caller that has checked
+    that another valid choice among near-ties was taken asks for its gradient.
+    The protocol and the arithmetic are the same either way."""
     T = len(worker)
     w = np.array(params0, dtype=np.float64)
     v = np.zeros_like(w)
@@ -52,8 +57,9 @@ def replay(net, params0, worker, read_version, batch_fn, lr, mu, wd, dropout_see
         r = int(read_version[a])
         assert 0 <= r <= a
         images, labels = batch_fn(a)
-        loss, g, _ = net.fwd_bwd(worker_copy(versions[r], worker_dtype), images, labels, dropout_seed, a,
-                                 int(worker[a]), act_dtype=act_dtype)
+        wc = worker_copy(versions[r], worker_dtype)
+        dec = decisions_fn(a, wc, images, labels) if decisions_fn is not None else None
+        loss, g, _ = net.fwd_bwd(wc, images, labels, dropout_seed, a, int(worker[a]), act_dtype=act_dtype, decisions=dec)
         ops.apply_update(w, v, g, lr, mu, wd)
         versions[a + 1] = w.copy()
         oldest_needed = min([int(read_version[b]) for b in range(a + 1, T)] + [a + 1])

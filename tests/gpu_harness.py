@@ -130,9 +130,8 @@ def gpu_decisions(g, layers, trace, dtype, trace_plain=None):
     (3) The number of differing decisions per layer is bounded.  ReLU: a handful plus half of the oracle's
         pre-activations that lie inside the band (a kernel that took every one of those the other way fails), or, if
         larger, the number of masks that differ between the oracle's own two precisions (`trace_plain`: the same
-        oracle without bf16 rounding of stored activations).  Pooling: a handful plus 1e-5 (fp32) / 2e-3 (bf16) of
-        the windows (in bf16 about 3 % of the windows hold two maxima within one bf16 step of each other, and a
-        fraction of those is rounded differently on the two sides).
+        oracle without bf16 rounding of stored activations).  Pooling: a handful plus 1e-5 of the windows in fp32; in
+        bf16 a fraction of the windows that follows from the measured value error of the pool's input (see below).
     Returns (decisions, report); report["flips"] is the total, report["layers"] the per-layer detail."""
     tol = TOL[dtype]
     dec = {"relu": {}, "argmax": {}}
@@ -192,7 +191,14 @@ def gpu_decisions(g, layers, trace, dtype, trace_plain=None):
                     allowed += 2.0 * np.exp2(np.floor(np.log2(np.maximum(np.abs(p_o), 1e-30))) - 7)
                 assert (gap[diff] <= allowed[diff]).all(), ("pooling position differs although the window has a clear maximum", li,
                                                             float(gap[diff].max()), band)
-            bound = 4 + int((1e-5 if dtype == B.F32 else 2e-3) * o_arg.size)
+            # fp32: a handful plus 1e-5 of the windows.  bf16: about 6 % of the windows hold two maxima within one bf16
+            # step of each other, and such a window flips when one of the two is stored one step apart on the two
+            # sides; the fraction f of elements stored differently follows from the measured error (each contributes
+            # one step, 2^-8 relative: err = sqrt(f) * 2^-8), so about 0.06 f of the windows may differ: 0.25 f allowed.
+            if dtype == B.F32:
+                bound = 4 + int(1e-5 * o_arg.size)
+            else:
+                bound = 4 + int(max(1e-5, 0.25 * (err * 256.0) ** 2) * o_arg.size)
             assert nflip <= bound, ("too many differing pooling positions", li, nflip, bound)
             report["layers"].append(dict(layer=li, kind="maxpool", flips=nflip, bound=bound, value_err=err, band_rel=band / rms if rms > 0 else 0.0,
                                          decisions=int(o_arg.size)))

@@ -418,7 +418,11 @@ def test_train_step_is_the_three_calls_bit_for_bit_and_matches_the_oracle(cfg, d
 def test_asgd_replay_matches_oracle_and_logs_the_schedule(dtype):
     cfg = wl.TINY
     layers, in_shape, batch = cfg["layers"], cfg["in_shape"], 8
-    W, T, lr, mu, wd = 4, 24, cfg["lr"], cfg["mu"], 5e-4    # the configuration's step size and momentum; weight decay on, to exercise it
+    # The configuration's step size (0.01) and momentum in fp32.  On this random-label problem that step size makes the
+    # stale trajectory overshoot (losses climb from 3.9 to 40 within a dozen updates); fp32 still agrees to 1e-4 there,
+    # but a diverging trajectory multiplies bf16's rounding differences from update to update, so the bf16 run is
+    # graded on the same schedule at a step size where the trajectory is stable.  Weight decay is on, to exercise it.
+    W, T, lr, mu, wd = 4, 24, (cfg["lr"] if dtype == B.F32 else 0.001), cfg["mu"], 5e-4
     worker, rv = B.asgd_schedule_generate(T, 4005, W, 3)
     w_o, rv_o = oops.schedule(T, 4005, W, 3)
     np.testing.assert_array_equal(worker, w_o); np.testing.assert_array_equal(rv, rv_o)
@@ -449,7 +453,10 @@ def test_asgd_replay_matches_oracle_and_logs_the_schedule(dtype):
         p, m, ls, lg = results[0]
         np.testing.assert_array_equal(lg, log_ref)               # (update, worker, version read) as prescribed
         tol = TOL[dtype]
-        assert rel_l2(ls, losses_ref) < tol and rel_l2(p, w_ref) < tol and rel_l2(m, v_ref) < tol
+        # the accumulated parameter change, not the parameters (which the initial weights dominate), and the momentum
+        errs = rel_l2(ls, losses_ref), rel_l2(p - params0, w_ref - params0), rel_l2(m, v_ref)
+        print("replay dtype %d: losses %.2e, parameter change %.2e, momentum %.2e" % ((dtype,) + errs))
+        assert max(errs) < tol, errs
         for a, b in zip(results[0], results[1]):                  # replay is reproducible bit for bit
             assert a.tobytes() == b.tobytes()
     finally:
@@ -475,7 +482,7 @@ def test_accumulate_matches_numpy(n, offset):
 def test_nsync_replay_matches_oracle_and_logs_the_schedule(n_sync, dtype):
     cfg = wl.TINY
     layers, in_shape, batch = cfg["layers"], cfg["in_shape"], 8
-    W, T, lr, mu, wd = 3, 9, cfg["lr"], cfg["mu"], 5e-4
+    W, T, lr, mu, wd = 3, 9, (cfg["lr"] if dtype == B.F32 else 0.001), cfg["mu"], 5e-4    # step sizes as in the replay test above
     worker, rv = B.asgd_schedule_generate(T, 4005, W, 2)
     params0 = wl.make_params(layers, in_shape, 2001)
     batches = [wl.make_batch(in_shape, batch, 10, 1105 + b) for b in range(T * n_sync)]
@@ -508,9 +515,11 @@ def test_nsync_replay_matches_oracle_and_logs_the_schedule(n_sync, dtype):
         p, m, ls, lg = results[0][:4]
         np.testing.assert_array_equal(lg, log_ref)
         tol = TOL[dtype]
-        assert rel_l2(ls, np.array(losses_ref).ravel()) < tol and rel_l2(p, w_ref) < tol and rel_l2(m, v_ref) < tol
-        for k in range(W):                                       # the replicas' own parameters and momentum
-            assert rel_l2(results[0][4 + k], local_ref[k][0]) < tol and rel_l2(results[0][4 + W + k], local_ref[k][1]) < tol
+        errs = rel_l2(ls, np.array(losses_ref).ravel()), rel_l2(p - params0, w_ref - params0), rel_l2(m, v_ref)
+        print("n_sync %d dtype %d: losses %.2e, parameter change %.2e, momentum %.2e" % ((n_sync, dtype) + errs))
+        assert max(errs) < tol, errs
+        for k in range(W):                                       # the replicas' own parameters (their change) and momentum
+            assert rel_l2(results[0][4 + k] - params0, local_ref[k][0] - params0) < tol and rel_l2(results[0][4 + W + k], local_ref[k][1]) < tol
         for a, b in zip(results[0], results[1]):                  # reproducible bit for bit
             assert a.tobytes() == b.tobytes()
         if n_sync == 1:                                           # the plain replay, bit for bit
@@ -587,56 +596,86 @@ def test_alexnet_full_batch_gradient_is_the_mean_of_its_chunks(dtype):
         big.close(); small.close()
 
 
+class _PlanView:
+    """What gpu_decisions needs of a plan that a replay ran on: the exports of its last forward pass."""
+    def __init__(self, net, batch):
+        self.net, self.batch = net, batch
+
+    def debug(self, what, layer):
+        shape = B.asgd_layer_shape(self.net, layer)
+        dst = torch.empty((self.batch,) + shape, dtype=torch.float32 if what == B.DEBUG_OUTPUT else torch.uint8, device=DEV)
+        B.asgd_debug_get(self.net, what, layer, dst)
+        torch.cuda.synchronize()
+        return dst.cpu().numpy()
+
+
 def test_asgd_replay_at_worker_shape_matches_oracle(capsys):
     """Four workers on the AlexNet-style net at batch 32 in bf16 (the worker shape of the on-one-GPU A-SGD
-    configuration), a seeded schedule with reads up to 3 updates stale: the device-side log must equal the
-    prescribed schedule, two replays must agree bit for bit, and the losses, the accumulated parameter change
-    and the momentum must match the oracle's replay of the same schedule."""
+    configuration, with its step size, momentum and weight decay), a seeded schedule with stale reads.
+    (i) Twelve updates: the device-side log equals the prescribed schedule and two replays agree bit for bit.
+    (ii) Four updates, one per worker, so that every worker's plan still holds the ReLU masks and pooling positions
+    of its update afterwards: the oracle replays the same schedule, taking for each update the HIP path's decisions
+    after gpu_decisions has validated them against its own forward pass on the version that update reads; losses,
+    accumulated parameter change and momentum must then agree per tensor at the bf16 tolerance."""
     cfg = wl.ALEXNET
-    layers, in_shape, batch, W, T = cfg["layers"], cfg["in_shape"], 32, 4, 6
+    layers, in_shape, batch, W = cfg["layers"], cfg["in_shape"], 32, 4
     lr, mu, wd = cfg["lr"], cfg["mu"], cfg["wd"]
-    worker, rv = B.asgd_schedule_generate(T, 4005, W, 3)
-    assert (np.arange(T) - rv).max() >= 2      # the schedule does contain stale reads
     params0 = wl.make_params(layers, in_shape, cfg["seeds"]["init"])
     rng = np.random.default_rng(1005)
-    images_np = wl.round_to_bf16(rng.standard_normal((T, batch) + tuple(in_shape), dtype=np.float32))
-    labels_np = rng.integers(0, cfg["classes"], size=(T, batch), dtype=np.int32)
+    T_long, T = 12, 4
+    images_np = wl.round_to_bf16(rng.standard_normal((T_long, batch) + tuple(in_shape), dtype=np.float32))
+    labels_np = rng.integers(0, cfg["classes"], size=(T_long, batch), dtype=np.int32)
     nets = [B.asgd_net_create(layers, batch, in_shape, B.BF16) for _ in range(W)]
     P = B.asgd_param_count(nets[0])
     try:
         images = torch.from_numpy(images_np).to(DEV).to(torch.bfloat16).contiguous()
         labels = torch.from_numpy(labels_np).to(DEV)
-        results = []
-        for rep in range(2):
+
+        def run(n_updates, seed):
+            worker, rv = B.asgd_schedule_generate(n_updates, seed, W, 3)
             params = torch.from_numpy(params0).to(DEV); mom = torch.zeros_like(params)
             copies = [torch.empty(P, dtype=torch.bfloat16, device=DEV) for _ in range(W)]
             grads = [torch.empty(P, dtype=torch.float32, device=DEV) for _ in range(W)]
-            losses = torch.zeros(T, dtype=torch.float32, device=DEV)
-            log = torch.full((T, 3), -7, dtype=torch.int32, device=DEV)
+            losses = torch.zeros(n_updates, dtype=torch.float32, device=DEV)
+            log = torch.full((n_updates, 3), -7, dtype=torch.int32, device=DEV)
             B.asgd_replay_run(nets, params, mom, copies, grads, images, labels, worker, rv, lr, mu, wd, 3003, losses, log)
             torch.cuda.synchronize()
-            results.append((params.cpu().numpy(), mom.cpu().numpy(), losses.cpu().numpy(), log.cpu().numpy()))
-        np.testing.assert_array_equal(results[0][3], np.stack([np.arange(T), worker, rv], 1))
-        for a, b in zip(results[0], results[1]):
+            return worker, rv, (params.cpu().numpy(), mom.cpu().numpy(), losses.cpu().numpy(), log.cpu().numpy())
+
+        # (i)
+        worker, rv, first = run(T_long, 4005)
+        _, _, second = run(T_long, 4005)
+        assert (np.arange(T_long) - rv).max() == 3
+        np.testing.assert_array_equal(first[3], np.stack([np.arange(T_long), worker, rv], 1))
+        assert np.isfinite(first[2]).all() and (first[2] > 0).all()
+        for a, b in zip(first, second):
             assert a.tobytes() == b.tobytes()
-        progress(capsys, "replay at worker shape: HIP side done, oracle replay of %d updates starts" % T)
+        # (ii) a schedule seed whose first four rows read versions 0, 0, 1 or 2, and a version at least 2 behind
+        seed = next(sd for sd in range(4005, 4100) if (np.arange(T) - oops.schedule(T, sd, W, 3)[1]).max() >= 2)
+        worker, rv, (p, m, ls, lg) = run(T, seed)
+        progress(capsys, "replay at worker shape: HIP side done (schedule seed %d, versions read %s); oracle replay starts" % (seed, list(rv)))
         onet = oracle.OracleNet(layers, in_shape)
+        flips = []
 
-        def batch_fn(a):
-            progress(capsys, "oracle replay: update %d" % a)
-            return images_np[a], labels_np[a]
+        def decisions_fn(a, wc, imgs, labs):
+            _, _, trace = onet.fwd_bwd(wc, imgs, labs, 3003, a, int(worker[a]), want_grads=False, act_dtype="bf16")
+            dec, report = gpu_decisions(_PlanView(nets[int(worker[a])], batch), layers, trace, B.BF16)
+            flips.append(report["flips"])
+            progress(capsys, "oracle replay: update %d, %d decisions of the HIP path followed" % (a, report["flips"]))
+            return dec
 
-        w_ref, v_ref, losses_ref, log_ref = oasgd.replay(onet, params0, worker, rv, batch_fn, np.float32(lr), np.float32(mu),
-                                                         np.float32(wd), dropout_seed=3003, worker_dtype="bf16", act_dtype="bf16")
-        p, m, ls, lg = results[0]
+        w_ref, v_ref, losses_ref, log_ref = oasgd.replay(onet, params0, worker, rv, lambda a: (images_np[a], labels_np[a]), np.float32(lr),
+                                                         np.float32(mu), np.float32(wd), dropout_seed=3003, worker_dtype="bf16",
+                                                         act_dtype="bf16", decisions_fn=decisions_fn)
         np.testing.assert_array_equal(lg, log_ref)
         tol = TOL[B.BF16]
-        e_loss, e_dw, e_v = rel_l2(ls, losses_ref), rel_l2(p - params0, w_ref - params0), rel_l2(m, v_ref)
-        per_tensor = [(name, err) for name, err in grad_errors(onet, m, v_ref, "momentum")]
-        progress(capsys, "replay at worker shape: losses %.2e, parameter change %.2e, momentum %.2e; per tensor %s"
-                 % (e_loss, e_dw, e_v, ", ".join("%s %.1e" % (n.split()[-1], e) for n, e in per_tensor)))
-        # the oracle replays with its own ReLU / pooling decisions (a free trajectory on both sides): whole-buffer tolerance
-        assert e_loss < tol and e_dw < tol and e_v < tol
+        e_loss = rel_l2(ls, losses_ref)
+        table = error_table("worker-shape replay, %d updates, relative L2 per tensor" % T,
+                            [("parameter change", grad_errors(onet, p - params0, w_ref - params0)), ("momentum", grad_errors(onet, m, v_ref))])
+        progress(capsys, ("losses %.2e; " % e_loss) + table.replace("\n", "\n     "))
+        assert e_loss < tol
+        compare_grads(onet, p - params0, w_ref - params0, tol, "parameter change")
+        compare_grads(onet, m, v_ref, tol, "momentum")
     finally:
         for n in nets:
             B.asgd_net_destroy(n)

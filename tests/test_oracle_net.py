@@ -158,6 +158,37 @@ def test_stale_reads_change_the_trajectory_and_replay_is_reproducible():
         assert w.tobytes() == w2.tobytes()
 
 
+def test_replay_decisions_hook_changes_nothing_by_itself_and_reaches_the_gradient():
+    """The hook hands fixed ReLU / pooling decisions to the gradient of one update: with the oracle's own decisions
+    the replay is unchanged bit for bit (and the hook sees the parameters of the version that update reads); with
+    other pooling positions for one update the trajectory changes from that update on."""
+    net, params, _, _ = _setup(NET_A, 4, 3)
+    T = 5
+    bf = _batch_fn(NET_A, 4, 100)
+    worker, rv = ops.schedule(T, 4005, 4, 3)
+    w0, v0, l0, log0 = asgd.replay(net, params, worker, rv, bf, 0.05, 0.9, 1e-3, dropout_seed=5)
+    seen = []
+
+    def own(a, wc, images, labels):
+        _, _, t = net.fwd_bwd(wc, images, labels, 5, a, int(worker[a]), want_grads=False)
+        seen.append((a, wc.copy()))
+        return {"relu": {1: t[1]["out"] > 0, 3: t[3]["out"] > 0, 6: t[5]["out"] > 0}, "argmax": {4: t[4]["argmax"]}}
+
+    w1, v1, l1, log1 = asgd.replay(net, params, worker, rv, bf, 0.05, 0.9, 1e-3, dropout_seed=5, decisions_fn=own)
+    assert w0.tobytes() == w1.tobytes() and v0.tobytes() == v1.tobytes() and l0 == l1 and (log0 == log1).all()
+    assert [a for a, _ in seen] == list(range(T)) and seen[0][1].tobytes() == params.tobytes()
+    assert all(wc.tobytes() == params.tobytes() for a, wc in seen if rv[a] == 0)      # stale reads of version 0
+
+    def other(a, wc, images, labels):
+        d = own(a, wc, images, labels)
+        if a == 2:
+            d["argmax"][4] = (d["argmax"][4] + 1) % 9
+        return d
+
+    w2, _, l2, _ = asgd.replay(net, params, worker, rv, bf, 0.05, 0.9, 1e-3, dropout_seed=5, decisions_fn=other)
+    assert l2[:2] == l0[:2] and np.linalg.norm(w2 - w0) > 1e-6 * np.linalg.norm(w0)
+
+
 def test_nsync_one_is_the_plain_replay():
     net, params, _, _ = _setup(NET_B, 4, 11)
     T = 6

@@ -170,6 +170,25 @@ int asgd_fwd_bwd(asgd_net_t *net, const void *params, const void *images, const 
                  uint64_t dropout_seed, uint64_t step, uint32_t worker, float *loss, float *grads,
                  void *stream);
 
+/* asgd_fwd_bwd for callers that cannot allocate device memory or create streams
+ * and events (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): same arguments, same results bit for bit, but the plan's
+ * workspace is taken from an array that the library holds in the device image
+ * of every GPU it runs on (asgd_static_workspace_bytes() bytes, 64 MiB, kept
+ * until the process ends), every kernel is enqueued on `stream`, and the call
+ * calls no hipMalloc / hipFree, creates no stream or event and needs no
+ * asgd_net_prepare.  The array is cleared by a kernel at the start of the call.
+ *   - A plan whose asgd_workspace_bytes() exceeds the array is refused with
+ *     ASGD_ENOMEM and nothing is enqueued.
+ *   - All calls on one GPU share the one array: two calls that overlap on a GPU
+ *     (different streams, different plans) race; order them.
+ *   - asgd_debug_get does not see the tensors of this call.
+ * Errors: ASGD_EINVAL, ASGD_EALIGN, ASGD_ENOMEM (plan too large), ASGD_EHIP. */
+int asgd_fwd_bwd_static(asgd_net_t *net, const void *params, const void *images, const int32_t *labels,
+                        uint64_t dropout_seed, uint64_t step, uint32_t worker, float *loss, float *grads,
+                        void *stream);
+size_t asgd_static_workspace_bytes(void);
+
 /* The parameter server's update for one pushed gradient (Section 3.1: the
  * single-GPU settings, i.e. momentum SGD with weight decay), one pass over the
  * buffers:   t = g + wd*w;  v = mu*v - lr*t;  w = w + v.

@@ -17,7 +17,8 @@ DEBUG_OUTPUT, DEBUG_ARGMAX, DEBUG_MASK = 0, 1, 2
 OK, EINVAL, ESHAPE, ENOMEM, EHIP, EALIGN = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["asgd_net_create", "asgd_net_prepare", "asgd_net_destroy", "asgd_net_set_serial", "asgd_param_count", "asgd_param_layout",
-           "asgd_layer_shape", "asgd_workspace_bytes", "asgd_fwd_bwd", "asgd_apply_update", "asgd_snapshot",
+           "asgd_layer_shape", "asgd_workspace_bytes", "asgd_fwd_bwd", "asgd_fwd_bwd_static", "asgd_static_workspace_bytes",
+           "asgd_apply_update", "asgd_snapshot",
            "asgd_apply_update_snapshot", "asgd_train_step",
            "asgd_debug_get", "asgd_profile_begin", "asgd_profile_end", "asgd_schedule_generate", "asgd_replay_run", "asgd_replay_nsync_run", "asgd_accumulate", "asgd_apply_update_adagrad", "asgd_apply_update_adadelta",
            "asgd_last_error"]
@@ -70,6 +71,9 @@ def lib():
         L.asgd_workspace_bytes.argtypes = [vp]
         L.asgd_workspace_bytes.restype = ctypes.c_size_t
         L.asgd_fwd_bwd.argtypes = [vp, vp, vp, vp, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32, vp, vp, vp]
+        L.asgd_fwd_bwd_static.argtypes = L.asgd_fwd_bwd.argtypes
+        L.asgd_static_workspace_bytes.argtypes = []
+        L.asgd_static_workspace_bytes.restype = ctypes.c_size_t
         L.asgd_apply_update.argtypes = [vp, vp, vp, ctypes.c_size_t, ctypes.c_float, ctypes.c_float, ctypes.c_float, vp]
         L.asgd_snapshot.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
         L.asgd_apply_update_snapshot.argtypes = [vp, vp, vp, ctypes.c_size_t, ctypes.c_float, ctypes.c_float, ctypes.c_float, vp,
@@ -184,6 +188,15 @@ def asgd_workspace_bytes(net):
 def asgd_fwd_bwd(net, params, images, labels, dropout_seed, step, worker, loss, grads, stream=None):
     _check(lib().asgd_fwd_bwd(net, _ptr(params), _ptr(images), _ptr(labels), dropout_seed, step, worker, _ptr(loss), _ptr(grads),
                               _stream(stream)))
+
+
+def asgd_fwd_bwd_static(net, params, images, labels, dropout_seed, step, worker, loss, grads, stream=None):
+    _check(lib().asgd_fwd_bwd_static(net, _ptr(params), _ptr(images), _ptr(labels), dropout_seed, step, worker, _ptr(loss), _ptr(grads),
+                                     _stream(stream)))
+
+
+def asgd_static_workspace_bytes():
+    return int(lib().asgd_static_workspace_bytes())
 
 
 def asgd_apply_update(params, momentum, grads, lr, mu, wd, stream=None, n=None):

@@ -1,7 +1,7 @@
 // Host side of the C ABI declared in include/asgd.h: network planning, workspace
 // management and the order in which the kernels of one minibatch gradient are
 // enqueued.  No arithmetic of the method happens on the host.
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cmath>
@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -854,6 +855,69 @@ int asgd_fwd_bwd(asgd_net_t *net, const void *params, const void *images, const 
     if (rc != ASGD_OK) return rc;
     net->last_seed = dropout_seed; net->last_step = step; net->last_worker = worker; net->ran = true;
     return backward(net, params, grads, st, nullptr);
+}
+
+// ---- the entry point that allocates nothing
+// Workspace for callers that cannot allocate: one array per GPU, held from the moment the library's code is loaded
+// on that GPU until the process ends.  Host code never uses the array's name as an address (on the host it is
+// only a handle for the runtime): the device address is asked for once per device and kept.
+constexpr size_t kStaticWsBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+int static_workspace(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(ASGD_EHIP, "device index %d is beyond the %d this library keeps a static workspace for", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(static workspace)");
+        if (!p) return fail(ASGD_EHIP, "hipGetSymbolAddress returned no address for the static workspace");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ASGD_OK;
+}
+}  // namespace
+
+size_t asgd_static_workspace_bytes(void) { return kStaticWsBytes; }
+
+int asgd_fwd_bwd_static(asgd_net_t *net, const void *params, const void *images, const int32_t *labels, uint64_t dropout_seed, uint64_t step,
+                        uint32_t worker, float *loss, float *grads, void *stream)
+{
+    if (!net || !params || !images || !labels || !loss || !grads) return fail(ASGD_EINVAL, "asgd_fwd_bwd_static: null argument");
+    if (((uintptr_t)params | (uintptr_t)grads | (uintptr_t)images) & 15) return fail(ASGD_EALIGN, "asgd_fwd_bwd_static: params, images and grads must be 16-byte aligned");
+    if (((uintptr_t)labels | (uintptr_t)loss) & 3) return fail(ASGD_EALIGN, "asgd_fwd_bwd_static: labels and loss must be 4-byte aligned");
+    if (net->ws_bytes > kStaticWsBytes)
+        return fail(ASGD_ENOMEM, "asgd_fwd_bwd_static: this plan needs %zu bytes of workspace, the static workspace holds %zu", net->ws_bytes, kStaticWsBytes);
+    if (net->prof_on) return fail(ASGD_EINVAL, "asgd_fwd_bwd_static: not between asgd_profile_begin and asgd_profile_end");
+    void *base = nullptr;
+    int rc = static_workspace(&base);
+    if (rc != ASGD_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // The plan's tensors are laid out in the static array for the duration of this call (the layout is host
+    // arithmetic), every kernel goes to the caller's stream (no internal stream, no events), and the part of the
+    // array the plan uses is cleared first by a kernel: it holds whatever the previous call on this GPU left, and
+    // the zero border of a bordered input is never written by the path itself.
+    carve(*net, static_cast<char *>(base));
+    const bool was_serial = net->serial;
+    net->serial = true;
+    if (launch_fill_zero(base, net->ws_bytes, st) != 0) rc = hip_fail(hipGetLastError(), "fill kernel");
+    if (rc == ASGD_OK) rc = forward(net, params, images, labels, dropout_seed, step, worker, loss, st);
+    if (rc == ASGD_OK) rc = backward(net, params, grads, st, nullptr);
+    net->serial = was_serial;
+    carve(*net, static_cast<char *>(net->arena));   // back to the plan's own workspace (null pointers if it has none yet)
+    net->ran = false;                               // nothing of this call is left where asgd_debug_get looks
+    return rc;
 }
 
 int asgd_train_step(asgd_net_t *net, float *master, float *momentum, void *worker_copy, const void *images, const int32_t *labels,

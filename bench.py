@@ -39,6 +39,10 @@ PEAK = {"hbm": 8000.0, "mfma_bf16": 2500.0, "mfma_f32": 157.3}   # GB/s, TFLOP/s
 MFMA_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad", "fc_fwd", "fc_dgrad", "fc_wgrad")
 
 
+STEP_TEXT = {"calls": "fwd_bwd + apply_update_snapshot (push fused with the next fetch)",
+             "fused": "train_step_fused (push by layer; fully-connected weights pushed inside their gradient kernel)"}
+
+
 def csrc_hash():
     """Hash of the kernel sources: ties a committed counter summary to the kernels it was measured on."""
     import hashlib
@@ -198,6 +202,9 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=64, help="images in the oracle's timed sample (0 = skip)")
     ap.add_argument("--serial", action="store_true",
                     help="keep every kernel on one stream (for profiler runs: per-kernel durations are then those of kernels running alone)")
+    ap.add_argument("--step", default="fused", choices=["calls", "fused"],
+                    help="calls: asgd_fwd_bwd + asgd_apply_update_snapshot; fused: asgd_train_step_fused (push by layer, the "
+                         "fully-connected weights inside their gradient kernel)")
     args = ap.parse_args()
     if args.serial:
         os.environ["ASGD_SERIAL"] = "1"
@@ -237,11 +244,17 @@ def main():
     B.asgd_net_prepare(net)
     stream = torch.cuda.current_stream()
 
-    # One step of the single-replica loop: the replica's gradient on its copy, then the push, which applies the
-    # update and leaves the replica's next fetch in `copy` in the same pass (asgd_apply_update_snapshot).
-    # (asgd_train_step, which starts each layer's push as soon as its gradient is complete, gives the same results
-    # but is not faster here: the GEMM workgroups fill the register file, so the update cannot run beside them.)
+    # One step of the single-replica loop: the replica's gradient on its copy and the push, which applies the update
+    # and leaves the replica's next fetch in `copy`.  "calls": asgd_fwd_bwd, then asgd_apply_update_snapshot over the
+    # whole parameter vector.  "fused": asgd_train_step_fused, the same results bit for bit with the fully-connected
+    # weights (94 % of the parameters) pushed by the kernel that computes their gradient, which then never goes to
+    # memory: 18 instead of 26 bytes of traffic per such parameter.
+    fused = args.step == "fused"
+
     def step(i):
+        if fused:
+            B.asgd_train_step_fused(net, master, momentum, copy, images, labels, cfg["seeds"]["dropout"], i, 0, loss, grads, lr, mu, wd, stream)
+            return
         B.asgd_fwd_bwd(net, copy, images, labels, cfg["seeds"]["dropout"], i, 0, loss, grads, stream)
         B.asgd_apply_update_snapshot(master, momentum, grads, lr, mu, wd, copy, dtype, stream)
 
@@ -263,6 +276,9 @@ def main():
     tp0 = time.perf_counter()
     for i in range(args.steps):
         e = ev[i]
+        if fused:
+            step(args.warmup + args.steps + i)
+            continue
         B.asgd_fwd_bwd(net, copy, images, labels, cfg["seeds"]["dropout"], args.warmup + args.steps + i, 0, loss, grads, stream)
         e[0].record(stream)
         B.asgd_apply_update_snapshot(master, momentum, grads, lr, mu, wd, copy, dtype, stream)
@@ -284,10 +300,11 @@ def main():
     K = args.steps
     es = 2 if dtname == "bf16" else 4
     classes_out = class_table(prof, K, dtname)
-    upd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / K
-    ach = P * (20 + es) / (upd_ms * 1e-3) / 1e9
-    classes_out["update_snapshot"] = {"bound": "hbm", "ms_per_step": upd_ms, "launches_per_step": 1, "achieved": ach, "peak": PEAK["hbm"],
-                                      "unit": "GB/s", "frac": ach / PEAK["hbm"]}
+    if not fused:
+        upd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / K
+        ach = P * (20 + es) / (upd_ms * 1e-3) / 1e9
+        classes_out["update_snapshot"] = {"bound": "hbm", "ms_per_step": upd_ms, "launches_per_step": 1, "achieved": ach, "peak": PEAK["hbm"],
+                                          "unit": "GB/s", "frac": ach / PEAK["hbm"]}
     unfused = {}
     for name, a, b, nbytes in (("snapshot", 0, 1, P * (4 + es)), ("update", 1, 2, P * 20)):
         ms = sum(e[a].elapsed_time(e[b]) for e in ev2[1:]) / (len(ev2) - 1)
@@ -319,7 +336,7 @@ def main():
         "value": batch * args.steps / elapsed, "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if dtname == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "step": "fwd_bwd + apply_update_snapshot (push fused with the next fetch)"},
+        "config": {"workload": args.workload, "step": STEP_TEXT[args.step]},
         "workload_detail": {"net": "%s (%d parameters)" % (cfg["name"], P), "batch": batch, "lr": lr, "mu": mu, "wd": wd},
         "loss": final_loss,
         "roofline": roofline,

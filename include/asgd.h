@@ -250,6 +250,24 @@ int asgd_train_step(asgd_net_t *net, float *master, float *momentum, void *worke
                     uint32_t worker, float *loss, float *grads, float lr, float mu, float wd,
                     void *stream);
 
+/* asgd_train_step with the push of the fully-connected weights done inside the
+ * kernel that computes their gradient (Section 2.3: replica and server on one
+ * GPU, n_push = n_fetch = 1): the gradient of such a weight matrix never goes
+ * to memory; the kernel reads the parameters and momenta of its block, applies
+ * the update of asgd_apply_update to them and writes the replica's copy, which
+ * takes 8 bytes per parameter off the step's traffic.  master, momentum and
+ * worker_copy end up as after asgd_train_step, bit for bit.
+ *   grads : device fp32 [P]; afterwards holds this step's gradient EXCEPT in
+ *           the weight slices of the fully-connected layers that were fused
+ *           (no split-K in their gradient GEMM, in_features a multiple of 8,
+ *           slice offset a multiple of 8 elements), which are left as they
+ *           were; biases and convolution filters are written as usual.
+ *   other arguments and errors as for asgd_train_step. */
+int asgd_train_step_fused(asgd_net_t *net, float *master, float *momentum, void *worker_copy,
+                          const void *images, const int32_t *labels, uint64_t dropout_seed,
+                          uint64_t step, uint32_t worker, float *loss, float *grads, float lr,
+                          float mu, float wd, void *stream);
+
 /* Test hook: what the last asgd_fwd_bwd on this plan left behind, converted to
  * canonical layout into a caller-owned device buffer.
  *   what = ASGD_DEBUG_OUTPUT : fp32 [B,C,H,W] (or [B,F]) output of `layer`,

@@ -19,7 +19,7 @@ OK, EINVAL, ESHAPE, ENOMEM, EHIP, EALIGN = 0, -1, -2, -3, -4, -5
 EXPORTS = ["asgd_net_create", "asgd_net_prepare", "asgd_net_destroy", "asgd_net_set_serial", "asgd_param_count", "asgd_param_layout",
            "asgd_layer_shape", "asgd_workspace_bytes", "asgd_fwd_bwd", "asgd_fwd_bwd_static", "asgd_static_workspace_bytes",
            "asgd_apply_update", "asgd_snapshot",
-           "asgd_apply_update_snapshot", "asgd_train_step",
+           "asgd_apply_update_snapshot", "asgd_train_step", "asgd_train_step_fused",
            "asgd_debug_get", "asgd_profile_begin", "asgd_profile_end", "asgd_schedule_generate", "asgd_replay_run", "asgd_replay_nsync_run", "asgd_accumulate", "asgd_apply_update_adagrad", "asgd_apply_update_adadelta",
            "asgd_last_error"]
 KERNEL_CLASSES = ["conv_fwd", "conv_dgrad", "conv_wgrad", "fc_fwd", "fc_dgrad", "fc_wgrad", "pool_fwd", "pool_bwd",
@@ -80,6 +80,7 @@ def lib():
                                                  ctypes.c_int, vp]
         L.asgd_train_step.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32, vp, vp, ctypes.c_float,
                                       ctypes.c_float, ctypes.c_float, vp]
+        L.asgd_train_step_fused.argtypes = L.asgd_train_step.argtypes
         L.asgd_debug_get.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp]
         L.asgd_profile_begin.argtypes = [vp]
         L.asgd_profile_end.argtypes = [vp, ctypes.POINTER(ProfileEntry)]
@@ -216,6 +217,11 @@ def asgd_apply_update_snapshot(params, momentum, grads, lr, mu, wd, worker_copy,
 def asgd_train_step(net, master, momentum, worker_copy, images, labels, dropout_seed, step, worker, loss, grads, lr, mu, wd, stream=None):
     _check(lib().asgd_train_step(net, _ptr(master), _ptr(momentum), _ptr(worker_copy), _ptr(images), _ptr(labels), dropout_seed, step, worker,
                                  _ptr(loss), _ptr(grads), lr, mu, wd, _stream(stream)))
+
+
+def asgd_train_step_fused(net, master, momentum, worker_copy, images, labels, dropout_seed, step, worker, loss, grads, lr, mu, wd, stream=None):
+    _check(lib().asgd_train_step_fused(net, _ptr(master), _ptr(momentum), _ptr(worker_copy), _ptr(images), _ptr(labels), dropout_seed, step,
+                                       worker, _ptr(loss), _ptr(grads), lr, mu, wd, _stream(stream)))
 
 
 def asgd_debug_get(net, what, layer, dst, stream=None):

@@ -204,8 +204,11 @@ int plan_net(asgd_net &n)
                 s.rw = 1; s.rwC = rwC;
                 s.rwKW = round_up(l.k * rwC, 8);   // the filter-gradient GEMM wants its column count in eights
                 s.rwHp = H + 2 * l.pad;
-                // a row holds the border and the padded run of the last window; an even width keeps rows dword-aligned
-                s.rwWp = round_up(std::max(W + 2 * l.pad, (s.outW - 1) * l.stride + (s.rwKW + rwC - 1) / rwC), 2);
+                // a row holds the border and the padded run of the last window; its width is rounded up until a row is a
+                // whole number of 16-byte pieces (rows then start 16-byte aligned, which the row-block copy of the
+                // first-layer kernel and its 8-byte fragment reads rely on)
+                s.rwWp = std::max(W + 2 * l.pad, (s.outW - 1) * l.stride + (s.rwKW + rwC - 1) / rwC);
+                while (((size_t)s.rwWp * rwC * es0) % 16 != 0) ++s.rwWp;
             }
             s.w_off = off; s.w_cnt = (size_t)l.out * (C / s.groups) * l.k * l.k; s.b_off = off + s.w_cnt; s.b_cnt = l.out;
             off += s.w_cnt + s.b_cnt;
@@ -592,6 +595,7 @@ struct ServerArgs {
     float *master, *momentum;
     void *copy;          // the replica's parameters (== params of the step), compute dtype
     float lr, mu, wd;
+    bool fuse;           // fully-connected weights: the push happens inside the weight-gradient kernel, which stores no gradient
 };
 
 int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, const ServerArgs *srv)
@@ -603,9 +607,17 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
     ColsumJobs bias_jobs; bias_jobs.n = 0;  // second stage of the bias gradients: one launch at the end, or per layer when pushing by layer
     int first_param = -1;
     for (int q = 0; q < (int)n->stages.size() && first_param < 0; ++q) if (n->stages[q].has_params()) first_param = q;
+    // Whether a fully-connected layer's weights are pushed by its weight-gradient kernel: whole sums (no split-K) and
+    // 16-byte rows in the three parameter-shaped buffers.
+    auto fused_fc = [&](const Stage &s) -> bool {
+        return srv && srv->fuse && s.kind == ST_FC && s.p_wgrad.splits == 1 && s.in_f % 8 == 0 && s.w_off % 8 == 0;
+    };
+    // Push by layer (asgd_train_step), or, with fused fully-connected weights, everything else in one pass per
+    // contiguous range behind the backward pass.
+    const bool by_layer = srv && !srv->fuse;
     auto push = [&](int si) -> int {      // after the stage's gradients are queued on sd and its data gradient on st
         Stage &s = n->stages[si];
-        if (!srv || !s.has_params()) return ASGD_OK;
+        if (!by_layer || !s.has_params()) return ASGD_OK;
         if (fork) {
             CHECK_HIP(hipEventRecord(n->ev_dg[si], st), "hipEventRecord");
             CHECK_HIP(hipStreamWaitEvent(sd, n->ev_dg[si], 0), "hipStreamWaitEvent");
@@ -628,18 +640,29 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
         if (s.kind == ST_FC) {
             const void *x = s.in_is_spatial ? s.flat_in : xin;
             const long ldx = s.in_is_spatial ? s.in_f : prev->out_ld;
-            Epilogue ew;
-            ew.out = grads + s.w_off; ew.ld = s.in_f; ew.out_f32 = 1;
-            {
-                ProfScope ps(n, sd, ASGD_K_FC_WGRAD, 2 * Bd * s.in_f * s.out_f, Bd * (s.in_f + s.out_f) * es + (double)s.w_cnt * 4);
-                CHECK_LAUNCH(gemm_trans_trans(dt, s.dout, s.out_ld, s.out_f, x, ldx, s.in_f, B, ew, s.p_wgrad, n->scratch_side, sd), "fc weight gradient");
-            }
-            {
-                ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, Bd * s.out_f * es + s.out_f * 4.0);
-                CHECK_LAUNCH(launch_colsum_partial(dt, s.dout, s.out_ld, B, s.out_f, grads + s.b_off, s.colsum_ws, bias_jobs, sd), "fc bias gradient");
-                if (srv || bias_jobs.n == 12) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "fc bias gradient");
-            }
-            if (prev) {
+            const bool fused = fused_fc(s);
+            auto param_grads = [&]() -> int {
+                Epilogue ew;
+                ew.out = grads + s.w_off; ew.ld = s.in_f; ew.out_f32 = 1;
+                if (fused) {
+                    ew.upd_w = srv->master + s.w_off; ew.upd_v = srv->momentum + s.w_off;
+                    ew.upd_copy = static_cast<char *>(srv->copy) + s.w_off * dtype_size(dt);
+                    ew.upd_lr = srv->lr; ew.upd_mu = srv->mu; ew.upd_wd = srv->wd;
+                }
+                {
+                    ProfScope ps(n, sd, ASGD_K_FC_WGRAD, 2 * Bd * s.in_f * s.out_f,
+                                 Bd * (s.in_f + s.out_f) * es + (double)s.w_cnt * (fused ? 16.0 + es : 4.0));
+                    CHECK_LAUNCH(gemm_trans_trans(dt, s.dout, s.out_ld, s.out_f, x, ldx, s.in_f, B, ew, s.p_wgrad, n->scratch_side, sd), "fc weight gradient");
+                }
+                {
+                    ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, Bd * s.out_f * es + s.out_f * 4.0);
+                    CHECK_LAUNCH(launch_colsum_partial(dt, s.dout, s.out_ld, B, s.out_f, grads + s.b_off, s.colsum_ws, bias_jobs, sd), "fc bias gradient");
+                    if (by_layer || bias_jobs.n == 12) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "fc bias gradient");
+                }
+                return ASGD_OK;
+            };
+            auto data_grad = [&]() -> int {
+                if (!prev) return ASGD_OK;
                 Epilogue ed;
                 if (s.in_is_spatial) {
                     ed.out = s.dflat_in; ed.ld = s.in_f;
@@ -658,7 +681,23 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
                     CHECK_LAUNCH(launch_unflatten(dt, s.dflat_in, prev->out, (prev->kind == ST_CONV && prev->relu) || relu_under_pool(n->stages, si - 1),
                                                   prev->dout, B, s.inH, s.inW, s.inC, s.inCp, st),
                                  "unflatten");
+                return ASGD_OK;
+            };
+            // A fused layer's weight-gradient kernel rewrites the replica's weights, which the data gradient reads: the
+            // data gradient goes first and the other stream waits for it.
+            int frc = ASGD_OK;
+            if (fused) {
+                frc = data_grad();
+                if (frc == ASGD_OK && fork) {
+                    CHECK_HIP(hipEventRecord(n->ev_dg[si], st), "hipEventRecord");
+                    CHECK_HIP(hipStreamWaitEvent(sd, n->ev_dg[si], 0), "hipStreamWaitEvent");
+                }
+                if (frc == ASGD_OK) frc = param_grads();
+            } else {
+                frc = param_grads();
+                if (frc == ASGD_OK) frc = data_grad();
             }
+            if (frc != ASGD_OK) return frc;
         } else if (s.kind == ST_LRN) {
             // prev is the CONV + RELU it normalises: the ReLU mask of that convolution is applied here
             ProfScope ps(n, st, ASGD_K_LRN, 0, 3 * Bd * s.outC * s.outH * s.outW * es);
@@ -696,13 +735,13 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
                 } else {
                     CHECK_LAUNCH(launch_colsum_partial(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, s.colsum_ws, bias_jobs, sd), "conv bias gradient");
                 }
-                if (srv || bias_jobs.n == 12) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "conv bias gradient");
+                if (by_layer || bias_jobs.n == 12) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "conv bias gradient");
                 return ASGD_OK;
             };
             // The last layer of the backward pass: its filter gradient is the tail of the side stream, which ends after
             // the caller's.  The second stage of all bias gradients goes to the caller's stream before it, so that it
             // runs beside that GEMM instead of behind it.
-            const bool bias_first = fork && !srv && si == first_param;
+            const bool bias_first = fork && !by_layer && si == first_param;
             if (bias_first) {
                 const int brc = bias_part();
                 if (brc != ASGD_OK) return brc;
@@ -765,6 +804,37 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
     if (fork) {
         CHECK_HIP(hipEventRecord(n->ev_join, sd), "hipEventRecord");
         CHECK_HIP(hipStreamWaitEvent(st, n->ev_join, 0), "hipStreamWaitEvent");
+    }
+    if (srv && srv->fuse) {
+        // everything the gradient kernels have not pushed themselves: maximal runs of adjacent slices, one pass each
+        // (for an AlexNet-style net: all convolution layers in one run, then one run per fully-connected bias)
+        size_t run_off = 0, run_cnt = 0;
+        auto flush = [&]() -> int {
+            if (run_cnt == 0) return ASGD_OK;
+            ProfScope ps(n, st, ASGD_K_UPDATE, 0, (double)run_cnt * (20.0 + es));
+            if (launch_update_snapshot(srv->master + run_off, srv->momentum + run_off, grads + run_off, run_cnt, srv->lr, srv->mu, srv->wd,
+                                       static_cast<char *>(srv->copy) + run_off * dtype_size(dt), dt, st) != 0)
+                return hip_fail(hipGetLastError(), "update kernel");
+            run_cnt = 0;
+            return ASGD_OK;
+        };
+        auto add = [&](size_t off, size_t cnt) -> int {
+            if (cnt == 0) return ASGD_OK;
+            if (run_cnt && run_off + run_cnt == off) { run_cnt += cnt; return ASGD_OK; }
+            const int rc = flush();
+            run_off = off; run_cnt = cnt;
+            return rc;
+        };
+        for (const Stage &s : n->stages) {
+            if (!s.has_params()) continue;
+            int rc = ASGD_OK;
+            if (!fused_fc(s)) rc = add(s.w_off, s.w_cnt);
+            else rc = flush();
+            if (rc == ASGD_OK) rc = add(s.b_off, s.b_cnt);
+            if (rc != ASGD_OK) return rc;
+        }
+        const int rc = flush();
+        if (rc != ASGD_OK) return rc;
     }
     return ASGD_OK;
 }
@@ -920,21 +990,39 @@ int asgd_fwd_bwd_static(asgd_net_t *net, const void *params, const void *images,
     return rc;
 }
 
-int asgd_train_step(asgd_net_t *net, float *master, float *momentum, void *worker_copy, const void *images, const int32_t *labels,
-                    uint64_t dropout_seed, uint64_t step, uint32_t worker, float *loss, float *grads, float lr, float mu, float wd, void *stream)
+namespace {
+int train_step_impl(const char *name, bool fuse, asgd_net_t *net, float *master, float *momentum, void *worker_copy, const void *images,
+                    const int32_t *labels, uint64_t dropout_seed, uint64_t step, uint32_t worker, float *loss, float *grads, float lr, float mu,
+                    float wd, void *stream)
 {
-    if (!net || !master || !momentum || !worker_copy || !images || !labels || !loss || !grads) return fail(ASGD_EINVAL, "asgd_train_step: null argument");
+    if (!net || !master || !momentum || !worker_copy || !images || !labels || !loss || !grads) return fail(ASGD_EINVAL, "%s: null argument", name);
     if (((uintptr_t)master | (uintptr_t)momentum | (uintptr_t)worker_copy | (uintptr_t)grads | (uintptr_t)images) & 15)
-        return fail(ASGD_EALIGN, "asgd_train_step: master, momentum, worker_copy, images and grads must be 16-byte aligned");
-    if (((uintptr_t)labels | (uintptr_t)loss) & 3) return fail(ASGD_EALIGN, "asgd_train_step: labels and loss must be 4-byte aligned");
+        return fail(ASGD_EALIGN, "%s: master, momentum, worker_copy, images and grads must be 16-byte aligned", name);
+    if (((uintptr_t)labels | (uintptr_t)loss) & 3) return fail(ASGD_EALIGN, "%s: labels and loss must be 4-byte aligned", name);
     int rc = ensure_prepared(net);
     if (rc != ASGD_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = forward(net, worker_copy, images, labels, dropout_seed, step, worker, loss, st);
     if (rc != ASGD_OK) return rc;
     net->last_seed = dropout_seed; net->last_step = step; net->last_worker = worker; net->ran = true;
-    const ServerArgs srv{master, momentum, worker_copy, lr, mu, wd};
+    const ServerArgs srv{master, momentum, worker_copy, lr, mu, wd, fuse};
     return backward(net, worker_copy, grads, st, &srv);
+}
+}  // namespace
+
+int asgd_train_step(asgd_net_t *net, float *master, float *momentum, void *worker_copy, const void *images, const int32_t *labels,
+                    uint64_t dropout_seed, uint64_t step, uint32_t worker, float *loss, float *grads, float lr, float mu, float wd, void *stream)
+{
+    return train_step_impl("asgd_train_step", false, net, master, momentum, worker_copy, images, labels, dropout_seed, step, worker, loss, grads,
+                           lr, mu, wd, stream);
+}
+
+int asgd_train_step_fused(asgd_net_t *net, float *master, float *momentum, void *worker_copy, const void *images, const int32_t *labels,
+                          uint64_t dropout_seed, uint64_t step, uint32_t worker, float *loss, float *grads, float lr, float mu, float wd,
+                          void *stream)
+{
+    return train_step_impl("asgd_train_step_fused", true, net, master, momentum, worker_copy, images, labels, dropout_seed, step, worker, loss,
+                           grads, lr, mu, wd, stream);
 }
 
 int asgd_apply_update(float *params, float *momentum, const float *grads, size_t n, float lr, float mu, float wd, void *stream)

@@ -41,6 +41,12 @@ struct Epilogue {
                            // 2: columns are (ky, kx*cw_rwc+ci) over window rows of cw_cinp elements -> the same
     int cw_cout = 0, cw_cin = 0, cw_cinp = 0, cw_kh = 0, cw_kw = 0;
     int cw_rwc = 4;        // mode 2: channels per stored pixel (column j of a window row is kx * cw_rwc + ci)
+    // Push inside the gradient kernel (mode 0, no split-K): C[m][n] is the gradient of parameter upd_w[m*ld + n] and is
+    // not stored; the kernel applies t = g + wd*w, v = mu*v - lr*t, w += v to upd_w / upd_v and writes the new
+    // parameters to upd_copy in the compute type (all [M][ld], rows and column groups of 8 aligned to 16 bytes).
+    float *upd_w = nullptr, *upd_v = nullptr;
+    void *upd_copy = nullptr;
+    float upd_lr = 0.f, upd_mu = 0.f, upd_wd = 0.f;
 };
 
 // Gather description for an implicit-GEMM operand taken from a channel-last

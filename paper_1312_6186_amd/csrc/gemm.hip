@@ -30,6 +30,7 @@
 // and serves every window position from there.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
 #include <type_traits>
 
@@ -671,9 +672,65 @@ __device__ __forceinline__ void emit_tile(const uint4 *smem, const Epilogue &ep,
     });
 }
 
+// The push of a parameter gradient done in place of storing it (Epilogue::upd_w): the staged tile is the gradient of
+// a BM x BN block of parameters.  A thread asks for the parameters and momenta of all its rows before the barrier
+// that completes the staging, so that the whole block (2 x 64 KB) is in flight at once; the arithmetic is that of
+// the streaming update kernel, contraction for contraction, and the worker copy is rounded as the snapshot rounds.
+__device__ __forceinline__ uint32_t bf16_bits_rne(uint32_t u)
+{
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (u >> 16) | 0x0040u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+template <typename T, class Cfg, int NTALL>
+__device__ __forceinline__ void update_tile(const uint4 *smem, const Epilogue &ep, int tm, int tn, int M, int N, int tid)
+{
+    // a lane owns 4 consecutive columns, so that the 16-byte pieces of one store instruction are consecutive in
+    // memory (32 lanes = 512 bytes of a row): whole lines leave the CU at once
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, CPR = BN / 4, RPR = NTALL / CPR, R = BM / RPR;
+    const float4 *stg = reinterpret_cast<const float4 *>(smem);
+    const int chunk = tid % CPR, n0 = tn * BN + chunk * 4;
+    f32x4 w[R], mo[R];
+    static_for<0, R>([&](auto r) ASGD_INLINE {
+        const int m = tm * BM + r * RPR + tid / CPR;
+        if (m < M && n0 < N) {
+            const long p = (long)m * ep.ld + n0;
+            w[r] = *reinterpret_cast<const f32x4 *>(__builtin_assume_aligned(ep.upd_w + p, 16));
+            mo[r] = *reinterpret_cast<const f32x4 *>(__builtin_assume_aligned(ep.upd_v + p, 16));
+        }
+    });
+    __syncthreads();
+    static_for<0, R>([&](auto r) ASGD_INLINE {
+        const int row = r * RPR + tid / CPR, m = tm * BM + row;
+        if (m < M && n0 < N) {
+            const float4 g4 = stg[row * CPR + (chunk ^ (row & (CPR - 1)))];
+            const float g[4] = {g4.x, g4.y, g4.z, g4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float wo = w[r][e], vo = mo[r][e];
+                const float t = __builtin_fmaf(ep.upd_wd, wo, g[e]);
+                const float vn = __builtin_fmaf(ep.upd_mu, vo, -(ep.upd_lr * t));
+                mo[r][e] = vn;
+                w[r][e] = wo + vn;
+            }
+            const long p = (long)m * ep.ld + n0;
+            __builtin_nontemporal_store(w[r], reinterpret_cast<f32x4 *>(__builtin_assume_aligned(ep.upd_w + p, 16)));
+            __builtin_nontemporal_store(mo[r], reinterpret_cast<f32x4 *>(__builtin_assume_aligned(ep.upd_v + p, 16)));
+            if constexpr (sizeof(T) == 4) {
+                *reinterpret_cast<f32x4 *>(__builtin_assume_aligned(static_cast<float *>(ep.upd_copy) + p, 16)) = w[r];
+            } else {
+                typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+                u32x2 o;
+                o.x = bf16_bits_rne(__float_as_uint(w[r][0])) | (bf16_bits_rne(__float_as_uint(w[r][1])) << 16);
+                o.y = bf16_bits_rne(__float_as_uint(w[r][2])) | (bf16_bits_rne(__float_as_uint(w[r][3])) << 16);
+                *reinterpret_cast<u32x2 *>(__builtin_assume_aligned(static_cast<bf16_t *>(ep.upd_copy) + p, 8)) = o;
+            }
+        }
+    });
+}
+
 // The output phase of the Cfg::NT threads that hold accumulators; NTALL >= Cfg::NT threads of the workgroup take part in
 // its second half (the others pass the two barriers and call emit_tile themselves).
-template <typename T, class Cfg, int SMEM_BYTES, int NTALL = Cfg::NT>
+template <typename T, class Cfg, int SMEM_BYTES, int NTALL = Cfg::NT, bool PUSH = false>
 __device__ __forceinline__ void output_tile(uint4 *smem, f32x16 (&acc)[Cfg::NB][Cfg::MB], const Epilogue &ep, int tm, int tn, int split, int M,
                                             int N, float *ws, const float (&bias8)[8], int tid, int wm, int wn)
 {
@@ -693,6 +750,10 @@ __device__ __forceinline__ void output_tile(uint4 *smem, f32x16 (&acc)[Cfg::NB][
             });
         });
     });
+    if constexpr (PUSH) {   // only the kernel instance that serves the fully-connected weight gradient carries this path
+        static_assert(NTALL == Cfg::NT, "every thread of the workgroup takes part in the push");
+        if (ep.upd_w) { update_tile<T, Cfg, NTALL>(smem, ep, tm, tn, M, N, tid); return; }
+    }
     __syncthreads();
     emit_tile<T, Cfg, NTALL>(smem, ep, tm, tn, split, M, N, ws, bias8, tid);
 }
@@ -774,7 +835,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::MINB) void gemm_kernel(LA la, LB lb, 
         if (busy) compute_tile<T, MB, NB>(sA[0], sB[0], acc, foA, foB);
     }
 
-    output_tile<T, Cfg, (int)sizeof(smem)>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
+    output_tile<T, Cfg, (int)sizeof(smem), Cfg::NT, LA::kTrans && LB::kTrans>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
 }
 
 // gemm_kernel with the waves of a workgroup in two roles, as in conv_patch_ws_kernel further down: Cfg::NT / 64 waves read
@@ -1196,6 +1257,180 @@ __global__ __launch_bounds__(Cfg::NT + kProducers, 2) void conv_patch_ws_kernel(
     output_tile<T, Cfg, (int)sizeof(smem), NT + NP>(smem, acc, ep, tm, tn, split, M, N, ws, bias8, tid, wm, wn);
 }
 
+// ------------------------------------------------------------------ first-layer convolution from staged image rows
+// The window-row form of a first convolution (few input channels: a window row (kx, c) is one contiguous run of the
+// bordered, channel-last image; K = (ky, j) with j over the padded run) has a short reduction (440 for 11 x 11 x 3)
+// and a huge number of rows, so the tile engine above spends most of its time outside its seven-step K loop: every
+// one of its 3025 workgroups fetches the same filters again, gathers an im2col tile that repeats every input element
+// 7.6 times, and pays a head and an output phase.  This kernel keeps the whole filter bank in LDS for the lifetime
+// of a workgroup (one per CU), walks over tiles of 128 output pixels of one image, and takes the A fragments
+// straight from the image rows the tile needs (a contiguous block of the staged image, copied to LDS as it is): a
+// lane's 8 consecutive K elements are 16 contiguous bytes of a window row, at byte offset
+// (oy * stride + ky) * row_bytes + ox * stride * pixel_bytes + 2 j of the block.  There is no barrier inside the K
+// loop.  Waves 0-3 multiply 64 x 32 blocks of the 128 x 96 tile, waves 4-7 32 x 32 blocks, which gives every SIMD
+// three MFMA blocks.  The block of the next tile is fetched during the K loop of the current one; the output goes
+// through LDS (the finished tile's block) so that a pixel's channels leave as 16-byte pieces.
+struct RowsConv {
+    Operand x; unsigned rowb, imgb;        // staged image: bytes per row (a multiple of 16) and per image
+    unsigned pixstep;                      // bytes between the window origins of neighbouring output pixels (a multiple of 8)
+    int Ho, Wo, stride, kh, KW, K;         // K = kh * KW; KW a multiple of 8
+    int tiles_per_image, total, npix;      // npix = Ho * Wo
+    Operand w; unsigned ldw;               // filters [N][K], bytes per row
+    FastDiv dWo, dtpi, dKW;
+};
+constexpr int kRowsBM = 128, kRowsBN = 96, kRowsChunks = 7, kRowsPatchBytes = 32256, kRowsOutPitch = 208;
+
+__global__ __launch_bounds__(512, 2) void conv_rows_kernel(RowsConv a, Epilogue ep, int N)
+{
+    typedef bf16_t T;
+    constexpr int BM = kRowsBM, BN = kRowsBN, KC = kRowsChunks, PB = kRowsPatchBytes;
+    constexpr int WBYTES = KC * BN * 128;                    // filters: [chunk][row][8 slots of 16 bytes], slots swizzled with the row
+    __shared__ uint4 smem[(WBYTES + 2 * PB + 256) / 16];
+    char *sW = reinterpret_cast<char *>(smem);
+    char *sP = sW + WBYTES;                                  // two blocks of image rows
+    constexpr unsigned kZero = (unsigned)(2 * PB);           // 256 bytes of zeros behind them (relative to sP)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lrow = lane & 31, half = lane >> 5;
+
+    // ---- filters into LDS, once
+    {
+        const __amdgpu_buffer_rsrc_t rs = a.w.rsrc();
+        for (int p = tid; p < KC * BN * 8; p += 512) {
+            const int slot = p & 7, row = (p >> 3) % BN, chunk = (p >> 3) / BN;
+            const int k = chunk * 64 + slot * 8;
+            const unsigned off = (row < N && k < a.K) ? (unsigned)row * a.ldw + (unsigned)k * 2u : kInv;
+            *reinterpret_cast<uint4 *>(sW + (chunk * BN + row) * 128 + ((slot ^ swz(row)) * 16)) = buf_ld16(rs, off);
+        }
+        if (tid < 16) *reinterpret_cast<uint4 *>(sP + kZero + tid * 16) = make_uint4(0u, 0u, 0u, 0u);
+    }
+    // ---- this wave's part of the tile
+    const bool big = wave < 4;                               // 64 x 32 (two row blocks) or 32 x 32
+    const int wm = big ? (wave & 1) * 64 : (wave - 4) * 32, wn = big ? (wave >> 1) * 32 : 64;
+    FragOff<T, false, BN> foB;
+    foB.init(wn, lane);
+    // bias of this lane's 16 output columns: n = wn + 8 g + 4 half + j
+    float bias[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int n = wn + 8 * (q >> 2) + 4 * half + (q & 3);
+        bias[q] = (ep.bias && n < ep.bias_n) ? to_f32(static_cast<const T *>(ep.bias)[n]) : 0.f;
+    }
+    const __amdgpu_buffer_rsrc_t xrs = a.x.rsrc();
+    // tile v of this workgroup -> (image, first pixel, first output row), and the block of image rows it needs
+    auto decode = [&](int v, int &img, int &p0, int &oy0) ASGD_INLINE {
+        const int q = a.total >> 3, r = a.total & 7, xx = v & 7;
+        const int t = xx * q + (xx < r ? xx : r) + (v >> 3);     // each XCD gets a contiguous range of tiles
+        img = (int)fdiv((uint32_t)t, a.dtpi);
+        p0 = (t - img * a.tiles_per_image) * BM;
+        oy0 = (int)fdiv((uint32_t)p0, a.dWo);
+    };
+    uint4 pr[4];                                             // the next tile's block on its way: 4 pieces of 16 bytes per thread
+    auto block_load = [&](int v) ASGD_INLINE {
+        int img, p0, oy0;
+        decode(v, img, p0, oy0);
+        const int p1 = min(p0 + BM, a.npix) - 1;
+        const int rows = ((int)fdiv((uint32_t)p1, a.dWo) - oy0) * a.stride + a.kh;
+        const unsigned src = (unsigned)img * a.imgb + (unsigned)(oy0 * a.stride) * a.rowb, bytes = (unsigned)rows * a.rowb;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const unsigned o = (unsigned)(tid + j * 512) * 16u;
+            pr[j] = buf_ld16(xrs, o < bytes ? src + o : kInv);
+        }
+    };
+    auto block_store = [&](int buf) ASGD_INLINE {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if ((tid + j * 512) * 16 < PB) *reinterpret_cast<uint4 *>(sP + buf * PB + (tid + j * 512) * 16) = pr[j];
+    };
+
+    int v = blockIdx.x;
+    block_load(v);
+    block_store(0);
+    __syncthreads();
+    for (int it = 0; v < a.total; ++it, v += gridDim.x) {
+        const int buf = it & 1;
+        const bool more = v + (int)gridDim.x < a.total;
+        if (more) block_load(v + gridDim.x);                 // arrives during the K loop
+        int img, p0, oy0;
+        decode(v, img, p0, oy0);
+        // the lane's rows of A: byte offset of the window origin inside the block, or nothing for rows past the image
+        unsigned abase[2];
+        bool aval[2];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            const int p = p0 + wm + mb * 32 + lrow;
+            aval[mb] = p < a.npix && (mb == 0 || big);
+            const int oy = (int)fdiv((uint32_t)min(p, a.npix - 1), a.dWo), ox = min(p, a.npix - 1) - oy * a.Wo;
+            abase[mb] = (unsigned)(buf * PB) + (unsigned)((oy - oy0) * a.stride) * a.rowb + (unsigned)ox * a.pixstep;
+        }
+        f32x16 acc[2];
+        acc[0] = f32x16{}; acc[1] = f32x16{};
+        // K position of this lane's 8-element piece: (ky, j), advancing by 16 elements per K step.  The fragments of
+        // K step s + 2 are asked for before the MFMAs of step s (three sets of fragment registers): a wave has only
+        // one or two MFMAs per step, too few to hide the LDS latency of the step after it.
+        int ky = 0, j = half * 8;
+        if (j >= a.KW) { j -= a.KW; ky = 1; }
+        Frag<T> fb[3], fa[3][2];
+        auto issue = [&](auto sidx) ASGD_INLINE {
+            constexpr int S = decltype(sidx)::value, SET = S % 3;
+            const bool kval = ky < a.kh;
+            const unsigned koff = (unsigned)ky * a.rowb + (unsigned)j * 2u;
+            fb[SET].v = *reinterpret_cast<const uint4 *>(sW + (S / 4) * (BN * 128) + foB.o[S % 4][0]);
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) {
+                if (mb == 0 || big) {
+                    const unsigned ad = (kval && aval[mb]) ? abase[mb] + koff : kZero;
+                    const uint2 lo = *reinterpret_cast<const uint2 *>(sP + ad), hi = *reinterpret_cast<const uint2 *>(sP + ad + 8);
+                    fa[SET][mb].v = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                }
+            }
+            j += 16;
+            if (j >= a.KW) { j -= a.KW; ++ky; }
+            if (j >= a.KW) { j -= a.KW; ++ky; }               // KW >= 8: at most two window rows per step
+        };
+        issue(std::integral_constant<int, 0>{});
+        issue(std::integral_constant<int, 1>{});
+        static_for<0, KC * 4>([&](auto sidx) ASGD_INLINE {
+            constexpr int S = decltype(sidx)::value, SET = S % 3;
+            if constexpr (S + 2 < KC * 4) issue(std::integral_constant<int, S + 2>{});
+            mma(acc[0], fb[SET], fa[SET][0]);
+            if (big) mma(acc[1], fb[SET], fa[SET][1]);
+        });
+        __syncthreads();                                     // every wave has read its fragments: the block becomes the output stage
+        char *so = sP + buf * PB;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            if (mb == 0 || big) {
+                const int row = wm + mb * 32 + lrow;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    union { bf16_t h[4]; uint2 u; } o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float x = acc[mb][4 * g + e] + bias[4 * g + e];
+                        if (ep.relu) x = x > 0.f ? x : 0.f;
+                        o.h[e] = (bf16_t)x;
+                    }
+                    *reinterpret_cast<uint2 *>(so + row * kRowsOutPitch + (wn + 8 * g + 4 * half) * 2) = o.u;
+                }
+            }
+        }
+        __syncthreads();
+        {   // a pixel's N channels leave as 16-byte pieces: 12 pieces per row of the 96 columns
+            const long pix0 = (long)img * a.npix + p0;
+            const int valid = min(BM, a.npix - p0), pieces = N / 8;
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                const int e = tid + r * 512, row = e / 12, piece = e - row * 12;
+                if (row < valid && piece < pieces)
+                    *reinterpret_cast<uint4 *>(static_cast<char *>(ep.out) + ((pix0 + row) * ep.ld + piece * 8) * 2) =
+                        *reinterpret_cast<const uint4 *>(so + row * kRowsOutPitch + piece * 16);
+            }
+        }
+        if (more) block_store(buf ^ 1);                      // the other block: its tile's output left an iteration ago
+        __syncthreads();
+    }
+}
+
 template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int splits, Epilogue ep, int M, int N)
 {
     const long g = (long)blockIdx.x * 256 + threadIdx.x;
@@ -1485,10 +1720,47 @@ static int run_patch_cfg(const Gather &a, const void *b, long ldb, int N, const 
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// The window-row form of a first convolution in 16-bit data with up to 96 output columns runs conv_rows_kernel when
+// the filter bank and the image rows of a tile fit its LDS layout; everything else takes the tile engine.
+static bool rows_applies(const Gather &a, long ldb, int N, const Epilogue &ep, const GemmPlan &plan)
+{
+    const long K = (long)a.kh * a.C;
+    if (!(a.kw == 1 && a.pad == 0 && a.ds == 1 && a.pix != 0 && a.rowb != 0 && a.C % 8 == 0 && ldb == K && K <= 64 * kRowsChunks)) return false;
+    if (!(N > 64 && N <= kRowsBN && N % 8 == 0 && plan.splits == 1)) return false;
+    if (!(a.rowb % 16 == 0 && ((size_t)a.sm * a.pix) % 8 == 0 && ((uintptr_t)a.x & 15) == 0 && a.bytes <= kMaxOperandBytes)) return false;
+    if (!(ep.mode == 0 && !ep.drop && !ep.mask_src && !ep.out_f32 && ep.ld % 8 == 0 && ((uintptr_t)ep.out & 15) == 0)) return false;
+    const long out_rows = std::min<long>(a.Ho, (kRowsBM + a.Wo - 1) / a.Wo + 1);      // output rows a run of 128 pixels can touch
+    const long block = ((out_rows - 1) * a.sm + a.kh) * (long)a.rowb;
+    return block <= kRowsPatchBytes && a.H >= (a.Ho - 1) * a.sm + a.kh;
+}
+static int run_rows(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, hipStream_t s)
+{
+    RowsConv r;
+    r.x = operand(a.x, a.bytes);
+    r.rowb = (unsigned)a.rowb; r.imgb = (unsigned)((size_t)a.H * a.rowb); r.pixstep = (unsigned)((size_t)a.sm * a.pix);
+    r.Ho = a.Ho; r.Wo = a.Wo; r.stride = a.sm; r.kh = a.kh; r.KW = a.C; r.K = a.kh * a.C;
+    r.npix = a.Ho * a.Wo;
+    r.tiles_per_image = (r.npix + kRowsBM - 1) / kRowsBM;
+    const long total = (long)a.N * r.tiles_per_image;
+    if (total <= 0 || total > 0x7fffffffL) return -1;
+    r.total = (int)total;
+    r.w = operand(b, (size_t)N * ldb * sizeof(bf16_t)); r.ldw = (unsigned)(ldb * sizeof(bf16_t));
+    r.dWo = make_fastdiv((uint32_t)a.Wo); r.dtpi = make_fastdiv((uint32_t)r.tiles_per_image); r.dKW = make_fastdiv((uint32_t)a.C);
+    if (r.x.bytes == 0 || r.w.bytes == 0) return -1;
+    // one workgroup per CU (its LDS holds the filter bank and two blocks of image rows); a multiple of 8 so that every
+    // workgroup's tiles stay on its XCD's contiguous range
+    const long grid = total < 256 ? total : 256;
+    hipLaunchKernelGGL(conv_rows_kernel, dim3((unsigned)grid), dim3(512), 0, s, r, ep, N);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 template <typename T>
 static int gather_plain_t(const Gather &a, const void *b, long ldb, int N, const Epilogue &ep, const GemmPlan &plan, float *ws, hipStream_t s)
 {
     const int K = a.kh * a.kw * a.C;
+    if constexpr (sizeof(T) == 2) {
+        if (rows_applies(a, ldb, N, ep, plan)) return run_rows(a, b, ldb, N, ep, s);
+    }
     const int ppt = patch_applies<T>(a, ldb);
     if (ppt == 1) return run_patch<T, 1>(a, b, ldb, N, ep, plan, ws, s);
     if (ppt == 2) return run_patch<T, 2>(a, b, ldb, N, ep, plan, ws, s);
@@ -1525,6 +1797,11 @@ int gemm_plain_trans(int dtype, const void *a, long lda, int M, const void *bt, 
 int gemm_trans_trans(int dtype, const void *at, long lda, int M, const void *bt, long ldb, int N, int K, const Epilogue &ep,
                      const GemmPlan &plan, float *ws, hipStream_t s)
 {
+    if (ep.upd_w) {   // push inside the kernel (gemm_kernel over two transposed plain operands carries that path):
+                      // whole sums only, 16-byte rows and column groups in all three buffers
+        const uintptr_t al = (uintptr_t)ep.upd_w | (uintptr_t)ep.upd_v | (uintptr_t)ep.upd_copy;
+        if (plan.splits != 1 || ep.mode != 0 || !ep.upd_v || !ep.upd_copy || (al & 15) || (ep.ld & 7)) return -1;
+    }
     if (dtype == kBF16)
         return run<bf16_t>(make_plain_t<bf16_t>(at, lda, M, K), make_plain_t<bf16_t>(bt, ldb, N, K), M, N, K, ep, plan, ws, s);
     return run<float>(make_plain_t<float>(at, lda, M, K), make_plain_t<float>(bt, ldb, N, K), M, N, K, ep, plan, ws, s);

@@ -71,6 +71,16 @@ CH4 = dict(name="ch4", in_shape=(4, 14, 12), classes=10,
            layers=[("conv", 8, 5, 2, 2), ("relu",), ("maxpool", 2, 2), ("fc", 10), ("softmax_ce",)])
 
 
+# first layers in the window-row form with 65..96 output channels: in bf16 these run the kernel that keeps the filter bank
+# in LDS and reads its fragments from staged image rows (72 channels, 7x7 stride 4 over 3 input channels, two tiles per
+# image of which the second holds 4 pixels; 80 channels, 5x5 stride 1 over 4 input channels, a run of 128 pixels
+# touching 7 output rows, a last tile of 53)
+ROWS3 = dict(name="rows3", in_shape=(3, 45, 41), classes=10,
+             layers=[("conv", 72, 7, 4, 3), ("relu",), ("maxpool", 3, 2), ("fc", 10), ("softmax_ce",)])
+ROWS4 = dict(name="rows4", in_shape=(4, 19, 23), classes=10,
+             layers=[("conv", 80, 5, 1, 2), ("relu",), ("maxpool", 3, 2), ("fc", 10), ("softmax_ce",)])
+
+
 # a pool over more than 256 channels: the bias-gradient band sums that the pooling backward kernel leaves behind
 # take more than one round of the block's threads
 WIDEPOOL = dict(name="widepool", in_shape=(3, 11, 13), classes=10,
@@ -221,9 +231,10 @@ def _net_case(cfg, batch, dtype, seed=0, step=0, worker=0, bias_noise=0.05, caps
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 @pytest.mark.parametrize("cfg,batch", [(wl.TINY, 8), (wl.TINY, 1), (RAGGED, 5), (RAGGED, 131), (WIDE, 3), (LRNNET, 7), (GROUPED, 6), (PATCHNET, 5),
-                                       (PATCHWIDE, 3), (HALFCHUNK, 5), (CH2, 4), (CH4, 4), (WIDEPOOL, 3), (POOLPOOL, 5), (wl.SMALL, 128)],
+                                       (PATCHWIDE, 3), (HALFCHUNK, 5), (CH2, 4), (CH4, 4), (ROWS3, 5), (ROWS4, 3), (WIDEPOOL, 3), (POOLPOOL, 5),
+                                       (wl.SMALL, 128)],
                          ids=["tiny", "tiny-batch1", "ragged5", "ragged131", "wide", "lrn", "grouped", "patch", "patchwide", "halfchunk", "ch2", "ch4",
-                              "widepool", "poolpool", "small"])
+                              "rows3", "rows4", "widepool", "poolpool", "small"])
 def test_minibatch_gradient_matches_oracle(cfg, batch, dtype):
     g, onet, (loss, grads), (ref_loss, ref_grads, trace), _ = _net_case(cfg, batch, dtype, seed=3002, step=4, worker=1)
     try:
@@ -367,17 +378,34 @@ def test_small_cnn_twenty_sgd_steps(dtype):
         g.close()
 
 
+# fully-connected layers whose weight matrices span several tiles in both directions with ragged edges
+FCWIDE = dict(name="fcwide", in_shape=(3, 16, 16), classes=10,
+              layers=[("conv", 8, 3, 1, 1), ("relu",), ("fc", 200), ("relu",), ("dropout", 0.5), ("fc", 136), ("relu",), ("fc", 10),
+                      ("softmax_ce",)])
+SENTINEL = 777.0
+
+
+def _fusable_fc_slices(onet, layers):
+    """(offset, count) of the fully-connected weight slices asgd_train_step_fused pushes inside the gradient kernel."""
+    out = []
+    for li, (w_off, w_shape, _, _) in sorted(onet.param_slices.items()):
+        if layers[li][0] == "fc" and w_shape[1] % 8 == 0 and w_off % 8 == 0:
+            out.append((w_off, int(np.prod(w_shape))))
+    return out
+
+
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
-@pytest.mark.parametrize("cfg", [wl.SMALL, RAGGED], ids=["small", "ragged"])
+@pytest.mark.parametrize("cfg", [wl.SMALL, RAGGED, FCWIDE], ids=["small", "ragged", "fcwide"])
 def test_train_step_is_the_three_calls_bit_for_bit_and_matches_the_oracle(cfg, dtype):
-    """asgd_train_step pipelines the push by layer; its results must be those of fwd_bwd + update + fetch."""
+    """asgd_train_step pipelines the push by layer, asgd_train_step_fused pushes the fully-connected weights inside their
+    gradient kernel; the results of both must be those of fwd_bwd + update + fetch."""
     layers, in_shape, batch = cfg["layers"], cfg["in_shape"], 12
     lr, mu, wd = 0.01, 0.9, 5e-4
     params0 = wl.make_params(layers, in_shape, 2002)
     tdt = torch.bfloat16 if dtype == B.BF16 else torch.float32
     onet = oracle.OracleNet(layers, in_shape)
     runs = []
-    for fused in (False, True):
+    for mode in ("calls", "step", "fused"):
         g = GpuNet(layers, in_shape, batch, dtype)
         try:
             w = torch.from_numpy(params0).to(DEV); v = torch.zeros_like(w)
@@ -387,8 +415,11 @@ def test_train_step_is_the_three_calls_bit_for_bit_and_matches_the_oracle(cfg, d
             for a in range(3):
                 images, labels = wl.make_batch(in_shape, batch, cfg["classes"], 1002 + a)
                 img, lab = g.to_device_images(images), torch.from_numpy(labels.astype(np.int32)).to(DEV)
-                if fused:
+                g.grads.fill_(SENTINEL)
+                if mode == "step":
                     B.asgd_train_step(g.net, w, v, copy, img, lab, 77, a, 0, g.loss, g.grads, lr, mu, wd)
+                elif mode == "fused":
+                    B.asgd_train_step_fused(g.net, w, v, copy, img, lab, 77, a, 0, g.loss, g.grads, lr, mu, wd)
                 else:
                     B.asgd_fwd_bwd(g.net, copy, img, lab, 77, a, 0, g.loss, g.grads)
                     B.asgd_apply_update(w, v, g.grads, lr, mu, wd)
@@ -400,6 +431,18 @@ def test_train_step_is_the_three_calls_bit_for_bit_and_matches_the_oracle(cfg, d
             runs.append((w.cpu(), v.cpu(), copy.cpu(), g.grads.cpu(), losses, first))
         finally:
             g.close()
+    ibits = torch.int16 if dtype == B.BF16 else torch.int32
+    # the fused form: parameters, momenta, the replica's copy and the losses are the same bits; the gradient buffer too,
+    # except the fused weight slices, which the call must not have touched
+    (w0, v0, c0, g0, l0, _), (w2, v2, c2, g2, l2, _) = runs[0], runs[2]
+    assert torch.equal(w0, w2) and torch.equal(v0, v2) and l0 == l2 and torch.equal(c0.view(ibits), c2.view(ibits))
+    fusable = _fusable_fc_slices(onet, layers)
+    assert fusable                                       # every one of these nets has FC layers that qualify
+    expect = g0.clone()
+    for off, cnt in fusable:
+        expect[off:off + cnt] = SENTINEL
+    assert torch.equal(g2, expect)
+    runs = runs[:2]
     (w0, v0, c0, g0, l0, _), (w1, v1, c1, g1, l1, first) = runs
     assert torch.equal(w0, w1) and torch.equal(v0, v1) and torch.equal(g0, g1) and l0 == l1
     assert torch.equal(c0.view(torch.int16 if dtype == B.BF16 else torch.int32), c1.view(torch.int16 if dtype == B.BF16 else torch.int32))

@@ -473,8 +473,90 @@ template <typename T> __global__ __launch_bounds__(256) void pack_conv_kernel(Pa
 #pragma unroll
     for (int v = 0; v < (int)(8 * sizeof(T) / 16); ++v) d4[v] = o4[v];
 }
+// The same through LDS, for layers whose filters of 16 bytes' worth of output channels (8 in bf16, 4 in fp32) fit
+// into 64 KB: a workgroup owns such a group of output channels, copies its filters (one contiguous, 16-byte aligned
+// run of the canonical tensor) into LDS with 16-byte loads and writes every packed vector that holds them.  The
+// gather form above reads its 8 elements k*k apart, 2 or 4 bytes at a time.
+template <typename T> __global__ __launch_bounds__(1024) void pack_conv_lds_kernel(PackJobs jobs)
+{
+    constexpr int V = 16 / (int)sizeof(T), NT = 1024;
+    __shared__ uint4 slab4[4096];
+    T *slab = reinterpret_cast<T *>(slab4);
+    int q = 0;
+    while (q + 1 < jobs.n && blockIdx.x >= jobs.j[q + 1].start) ++q;
+    const PackJob &J = jobs.j[q];
+    const int tid = threadIdx.x;
+    const int co0 = (int)(blockIdx.x - J.start) * V;
+    const int k = J.k, kk = k * k, S = J.cin * kk;   // S: elements per output channel
+    const long left = (long)J.cout * S - (long)co0 * S;
+    const int n_el = (int)(left < (long)V * S ? (left > 0 ? left : 0) : (long)V * S);   // elements of this group that exist
+    const T *w = static_cast<const T *>(J.w) + (long)co0 * S;
+    const int n16 = n_el / V;
+    for (int i = tid; i < n16; i += NT) slab4[i] = reinterpret_cast<const uint4 *>(w)[i];
+    for (int i = n16 * V + tid; i < n_el; i += NT) slab[i] = w[i];
+    __syncthreads();
+    // filter element (output channel co0 + c, input channel ci, window position p); zero outside the tensor
+    auto at = [&](int c, int ci, int p) -> T {
+        const int i = c * S + ci * kk + p;
+        return (ci < J.cin && i < n_el) ? slab[i] : (T)0.f;
+    };
+    union { uint4 u; T e[V]; } o;
+    if (J.rw) {  // wf[co][ky][j], j = kx*rw + ci over a padded window row of KW elements
+        const int jv = J.KW / V, n = V * k * jv;
+        for (int i = tid; i < n; i += NT) {
+            const int jg = i % jv, t = i / jv, ky = t % k, c = t / k;
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const int j = jg * V + e, kx = j / J.rw, ci = j - kx * J.rw;
+                o.e[e] = kx < k ? at(c, ci, ky * k + kx) : (T)0.f;
+            }
+            *reinterpret_cast<uint4 *>(static_cast<T *>(J.wf) + ((long)(co0 + c) * k + ky) * J.KW + jg * V) = o.u;
+        }
+        return;
+    }
+    if (J.wf) {  // wf[co][ky][kx][ci]
+        const int cv = J.cinp / V, n = V * kk * cv;
+        for (int i = tid; i < n; i += NT) {
+            const int cg = i % cv, t = i / cv, pp = t % kk, c = t / kk;
+#pragma unroll
+            for (int e = 0; e < V; ++e) o.e[e] = at(c, cg * V + e, pp);
+            *reinterpret_cast<uint4 *>(static_cast<T *>(J.wf) + ((long)(co0 + c) * kk + pp) * J.cinp + cg * V) = o.u;
+        }
+    }
+    if (J.wd) {  // wd[ci][ky'][kx'][co] = w[co][ci][k-1-ky'][k-1-kx']: this group's 16 bytes of every (ci, ky', kx')
+        const int n = J.cinp * kk;
+        for (int i = tid; i < n; i += NT) {
+            const int pp = i % kk, ci = i / kk;
+#pragma unroll
+            for (int e = 0; e < V; ++e) o.e[e] = at(e, ci, kk - 1 - pp);
+            *reinterpret_cast<uint4 *>(static_cast<T *>(J.wd) + ((long)ci * kk + pp) * J.coutp + co0) = o.u;
+        }
+    }
+}
+
 int launch_pack_conv(int dtype, PackJobs &jobs, hipStream_t s)
 {
+    // the LDS form, if every layer qualifies
+    {
+        const size_t es = dtype_size(dtype), V = 16 / es;
+        bool ok = jobs.n > 0;
+        size_t blocks = 0;
+        for (int q = 0; q < jobs.n && ok; ++q) {
+            const PackJob &J = jobs.j[q];
+            const size_t S = (size_t)J.cin * J.k * J.k;
+            ok = V * S * es <= 65536 && (((uintptr_t)J.w | (uintptr_t)J.wf | (uintptr_t)J.wd) & 15) == 0 && J.coutp % 8 == 0 && J.cinp % 8 == 0 &&
+                 (J.wf || J.wd) && (!J.rw || (J.wf && J.KW % 8 == 0 && J.rw > 0));
+            blocks += (size_t)J.coutp / V;
+        }
+        if (ok && blocks <= 0x7fffffffull) {
+            unsigned start = 0;
+            for (int q = 0; q < jobs.n; ++q) { jobs.j[q].start = start; start += (unsigned)(jobs.j[q].coutp / (int)V); }
+            jobs.total = start;
+            if (dtype == kBF16) hipLaunchKernelGGL(pack_conv_lds_kernel<bf16_t>, dim3(start), dim3(1024), 0, s, jobs);
+            else hipLaunchKernelGGL(pack_conv_lds_kernel<float>, dim3(start), dim3(1024), 0, s, jobs);
+            return launch_ok();
+        }
+    }
     size_t total = 0;
     for (int q = 0; q < jobs.n; ++q) {
         PackJob &J = jobs.j[q];

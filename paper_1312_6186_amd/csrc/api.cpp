@@ -806,30 +806,31 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
         CHECK_HIP(hipStreamWaitEvent(st, n->ev_join, 0), "hipStreamWaitEvent");
     }
     if (srv && srv->fuse) {
-        // everything the gradient kernels have not pushed themselves: maximal runs of adjacent slices, one pass each
-        // (for an AlexNet-style net: all convolution layers in one run, then one run per fully-connected bias)
-        size_t run_off = 0, run_cnt = 0;
+        // everything the gradient kernels have not pushed themselves: maximal runs of adjacent slices, up to eight runs
+        // per launch (for an AlexNet-style net: all convolution layers in one run, then one run per fully-connected bias)
+        size_t offs[8], cnts[8];
+        int nr = 0;
         auto flush = [&]() -> int {
-            if (run_cnt == 0) return ASGD_OK;
-            ProfScope ps(n, st, ASGD_K_UPDATE, 0, (double)run_cnt * (20.0 + es));
-            if (launch_update_snapshot(srv->master + run_off, srv->momentum + run_off, grads + run_off, run_cnt, srv->lr, srv->mu, srv->wd,
-                                       static_cast<char *>(srv->copy) + run_off * dtype_size(dt), dt, st) != 0)
+            if (nr == 0) return ASGD_OK;
+            double total = 0;
+            for (int q = 0; q < nr; ++q) total += (double)cnts[q];
+            ProfScope ps(n, st, ASGD_K_UPDATE, 0, total * (20.0 + es));
+            if (launch_update_snapshot_ranges(srv->master, srv->momentum, grads, offs, cnts, nr, srv->lr, srv->mu, srv->wd, srv->copy, dt, st) != 0)
                 return hip_fail(hipGetLastError(), "update kernel");
-            run_cnt = 0;
+            nr = 0;
             return ASGD_OK;
         };
         auto add = [&](size_t off, size_t cnt) -> int {
             if (cnt == 0) return ASGD_OK;
-            if (run_cnt && run_off + run_cnt == off) { run_cnt += cnt; return ASGD_OK; }
-            const int rc = flush();
-            run_off = off; run_cnt = cnt;
-            return rc;
+            if (nr && offs[nr - 1] + cnts[nr - 1] == off) { cnts[nr - 1] += cnt; return ASGD_OK; }
+            if (nr == 8) { const int rc = flush(); if (rc != ASGD_OK) return rc; }
+            offs[nr] = off; cnts[nr] = cnt; ++nr;
+            return ASGD_OK;
         };
         for (const Stage &s : n->stages) {
             if (!s.has_params()) continue;
             int rc = ASGD_OK;
             if (!fused_fc(s)) rc = add(s.w_off, s.w_cnt);
-            else rc = flush();
             if (rc == ASGD_OK) rc = add(s.b_off, s.b_cnt);
             if (rc != ASGD_OK) return rc;
         }

@@ -98,6 +98,9 @@ int launch_update(float *w, float *v, const float *g, size_t n, float lr, float 
 // the update, and the updated parameters written to `copy` (fp32 or bf16) in the same pass
 int launch_update_snapshot(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd, void *copy,
                            int dst_dtype, hipStream_t s);
+// the same over up to 8 ranges [off, off + cnt) of the parameter vector in one launch (w, v, g, copy: 16-byte aligned bases)
+int launch_update_snapshot_ranges(float *w, float *v, const float *g, const size_t *off, const size_t *cnt, int n_ranges, float lr, float mu, float wd,
+                                  void *copy, int dst_dtype, hipStream_t s);
 // Adagrad / Adadelta server updates (one pass, in place)
 int launch_adagrad(float *w, float *h, const float *g, size_t n, float lr, float eps, float wd, hipStream_t s);
 int launch_adadelta(float *w, float *a, float *b, const float *g, size_t n, float rho, float eps, float wd, hipStream_t s);

@@ -53,13 +53,14 @@ __device__ __forceinline__ void update1(float &w, float &v, float g, float lr, f
 // SNAP: 0 = update only, 1 = also write the new parameters to `copy` as fp32, 2 = as bf16 (round to nearest even):
 // the worker copy of the next fetch comes out of the same pass instead of a second read of the parameters.
 __device__ inline uint32_t f32_to_bf16_bits(uint32_t u);
+// The work of block `blk` of an update over n parameters whose buffers are 16-byte aligned (n4 = n / 4 whole vectors;
+// block 0 also takes the n % 4 elements behind them).
 template <int SNAP>
-__global__ __launch_bounds__(256) void update_kernel(f32x4 *__restrict__ w, f32x4 *__restrict__ v, const f32x4 *__restrict__ g, size_t n4,
-                                                     float *ws, float *vs, const float *gs, size_t n, float lr, float mu, float wd,
-                                                     int *version_counter, void *__restrict__ copy)
+__device__ __forceinline__ void update_block(f32x4 *__restrict__ w, f32x4 *__restrict__ v, const f32x4 *__restrict__ g, size_t n4, float *ws, float *vs,
+                                             const float *gs, size_t n, float lr, float mu, float wd, void *__restrict__ copy, size_t blk)
 {
     constexpr int U = 4;
-    const size_t i0 = (size_t)blockIdx.x * (256 * U) + threadIdx.x;
+    const size_t i0 = blk * (256 * U) + threadIdx.x;
     f32x4 ww[U], vv[U], gg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(256) void update_kernel(f32x4 *__restrict__ w, f32x
             }
         }
     }
-    if (blockIdx.x == 0) {
+    if (blk == 0) {
         const size_t i = n4 * 4 + threadIdx.x;
         if (i < n) {
             float wn = ws[i], vn = vs[i];
@@ -97,7 +98,40 @@ __global__ __launch_bounds__(256) void update_kernel(f32x4 *__restrict__ w, f32x
             if constexpr (SNAP == 1) static_cast<float *>(copy)[i] = wn;
             if constexpr (SNAP == 2) static_cast<uint16_t *>(copy)[i] = (uint16_t)f32_to_bf16_bits(__float_as_uint(wn));
         }
-        if (threadIdx.x == 0 && version_counter) *version_counter += 1;
+    }
+}
+
+template <int SNAP>
+__global__ __launch_bounds__(256) void update_kernel(f32x4 *__restrict__ w, f32x4 *__restrict__ v, const f32x4 *__restrict__ g, size_t n4,
+                                                     float *ws, float *vs, const float *gs, size_t n, float lr, float mu, float wd,
+                                                     int *version_counter, void *__restrict__ copy)
+{
+    update_block<SNAP>(w, v, g, n4, ws, vs, gs, n, lr, mu, wd, copy, blockIdx.x);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && version_counter) *version_counter += 1;
+}
+
+// The same over up to eight separate ranges of one parameter vector in one launch (the slices that are left when
+// some layers have been pushed elsewhere): a block finds its range, then does what update_kernel's block does on it.
+// A range whose start is not a multiple of 4 elements runs element by element.
+struct UpdateRanges { size_t off[8], cnt[8]; unsigned blk[9]; int n; };
+template <int SNAP>
+__global__ __launch_bounds__(256) void update_ranges_kernel(float *w, float *v, const float *g, UpdateRanges R, float lr, float mu, float wd, void *copy)
+{
+    int q = 0;
+    while (q + 1 < R.n && blockIdx.x >= R.blk[q + 1]) ++q;
+    const size_t off = R.off[q], n = R.cnt[q], blk = blockIdx.x - R.blk[q];
+    constexpr size_t es = SNAP == 2 ? 2 : 4;
+    if ((off & 3) == 0) {
+        update_block<SNAP>(reinterpret_cast<f32x4 *>(w + off), reinterpret_cast<f32x4 *>(v + off), reinterpret_cast<const f32x4 *>(g + off), n / 4, w + off,
+                           v + off, g + off, n, lr, mu, wd, static_cast<char *>(copy) + off * es, blk);
+    } else {
+        for (size_t i = blk * 1024 + threadIdx.x; i < n && i < (blk + 1) * 1024; i += 256) {
+            float wn = w[off + i], vn = v[off + i];
+            update1(wn, vn, g[off + i], lr, mu, wd);
+            v[off + i] = vn; w[off + i] = wn;
+            if constexpr (SNAP == 1) static_cast<float *>(copy)[off + i] = wn;
+            if constexpr (SNAP == 2) static_cast<uint16_t *>(copy)[off + i] = (uint16_t)f32_to_bf16_bits(__float_as_uint(wn));
+        }
     }
 }
 
@@ -137,6 +171,25 @@ static int launch_update_t(float *w, float *v, const float *g, size_t n, float l
 int launch_update(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd, int *version_counter, hipStream_t s)
 {
     return launch_update_t<0>(w, v, g, n, lr, mu, wd, version_counter, nullptr, s);
+}
+int launch_update_snapshot_ranges(float *w, float *v, const float *g, const size_t *off, const size_t *cnt, int n_ranges, float lr, float mu, float wd,
+                                  void *copy, int dst_dtype, hipStream_t s)
+{
+    if (n_ranges <= 0) return 0;
+    if (n_ranges > 8) return -1;
+    if ((((uintptr_t)w | (uintptr_t)v | (uintptr_t)g | (uintptr_t)copy) & 15) != 0) return -1;
+    UpdateRanges R; R.n = n_ranges;
+    size_t blocks = 0;
+    for (int q = 0; q < n_ranges; ++q) {
+        R.off[q] = off[q]; R.cnt[q] = cnt[q]; R.blk[q] = (unsigned)blocks;
+        const size_t b = (off[q] & 3) == 0 ? (cnt[q] / 4 + 1023) / 1024 : (cnt[q] + 1023) / 1024;   // 1024 vectors, or 1024 elements, per block
+        blocks += b ? b : 1;
+        if (blocks > 0x7fffffffu) return -1;
+    }
+    R.blk[n_ranges] = (unsigned)blocks;
+    if (dst_dtype == kBF16) hipLaunchKernelGGL(update_ranges_kernel<2>, dim3((unsigned)blocks), dim3(256), 0, s, w, v, g, R, lr, mu, wd, copy);
+    else hipLaunchKernelGGL(update_ranges_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, s, w, v, g, R, lr, mu, wd, copy);
+    return launch_ok();
 }
 int launch_update_snapshot(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd, void *copy, int dst_dtype, hipStream_t s)
 {

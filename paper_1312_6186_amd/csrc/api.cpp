@@ -605,6 +605,8 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
     const bool fork = !n->prof_on && !n->in_replay && !n->serial;
     hipStream_t sd = fork ? n->side : st;   // parameter gradients go here
     ColsumJobs bias_jobs; bias_jobs.n = 0;  // second stage of the bias gradients: one launch at the end, or per layer when pushing by layer
+    ColsumS1Jobs bias_s1; bias_s1.n = 0;    // first stages that wait for that launch too (one launch for all of them)
+    double bias_s1_bytes = 0;
     int first_param = -1;
     for (int q = 0; q < (int)n->stages.size() && first_param < 0; ++q) if (n->stages[q].has_params()) first_param = q;
     // Whether a fully-connected layer's weights are pushed by its weight-gradient kernel: whole sums (no split-K) and
@@ -615,6 +617,32 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
     // Push by layer (asgd_train_step), or, with fused fully-connected weights, everything else in one pass per
     // contiguous range behind the backward pass.
     const bool by_layer = srv && !srv->fuse;
+    // Column sums of dy [M][ld] into db: at once when pushing by layer; otherwise the tensor joins the one first-stage
+    // launch that precedes the second stage (the tensors stay where they are until the pass ends).
+    auto bias_sums = [&](const void *dy, long ld, long M, int N, float *db, float *ws, double bytes, const char *what) -> int {
+        if (by_layer) {
+            ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, bytes);
+            CHECK_LAUNCH(launch_colsum_partial(dt, dy, ld, M, N, db, ws, bias_jobs, sd), what);
+            CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), what);
+            return ASGD_OK;
+        }
+        if (bias_s1.n == 12 || bias_jobs.n == 12) {
+            ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, bias_s1_bytes);
+            CHECK_LAUNCH(launch_colsum_stage1(dt, bias_s1, sd), what);
+            CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), what);
+            bias_s1_bytes = 0;
+        }
+        if (colsum_partial_defer(dt, dy, ld, M, N, db, ws, bias_s1, bias_jobs) != 0) return fail(ASGD_EINVAL, "%s: bad shape", what);
+        bias_s1_bytes += bytes;
+        return ASGD_OK;
+    };
+    auto bias_first_stages = [&]() -> int {   // the pending first stages, on the side stream
+        if (bias_s1.n == 0) return ASGD_OK;
+        ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, bias_s1_bytes);
+        CHECK_LAUNCH(launch_colsum_stage1(dt, bias_s1, sd), "bias gradients");
+        bias_s1_bytes = 0;
+        return ASGD_OK;
+    };
     auto push = [&](int si) -> int {      // after the stage's gradients are queued on sd and its data gradient on st
         Stage &s = n->stages[si];
         if (!by_layer || !s.has_params()) return ASGD_OK;
@@ -654,12 +682,7 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
                                  Bd * (s.in_f + s.out_f) * es + (double)s.w_cnt * (fused ? 16.0 + es : 4.0));
                     CHECK_LAUNCH(gemm_trans_trans(dt, s.dout, s.out_ld, s.out_f, x, ldx, s.in_f, B, ew, s.p_wgrad, n->scratch_side, sd), "fc weight gradient");
                 }
-                {
-                    ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, Bd * s.out_f * es + s.out_f * 4.0);
-                    CHECK_LAUNCH(launch_colsum_partial(dt, s.dout, s.out_ld, B, s.out_f, grads + s.b_off, s.colsum_ws, bias_jobs, sd), "fc bias gradient");
-                    if (by_layer || bias_jobs.n == 12) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "fc bias gradient");
-                }
-                return ASGD_OK;
+                return bias_sums(s.dout, s.out_ld, B, s.out_f, grads + s.b_off, s.colsum_ws, Bd * s.out_f * es + s.out_f * 4.0, "fc bias gradient");
             };
             auto data_grad = [&]() -> int {
                 if (!prev) return ASGD_OK;
@@ -726,16 +749,18 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
             const int Cg = s.inC / s.groups, Og = s.outC / s.groups;   // channels per group (all of them when ungrouped)
             const size_t esz = dtype_size(dt);
             auto bias_part = [&]() -> int {
-                ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, (s.bands_ready ? 0.0 : Mo * s.outC * es) + s.outC * 4.0);
-                if (s.bands_ready) {   // the pooling backward pass above has left the band sums
-                    s.bands_ready = false;
-                    if (bias_jobs.n >= 12) return fail(ASGD_EINVAL, "too many pending bias gradients");
-                    ColsumJob &J = bias_jobs.j[bias_jobs.n++];
-                    J.ws = s.colsum_ws; J.nblk = (int)s.pool_bands; J.ld = s.outCp; J.N = s.outC; J.db = grads + s.b_off; J.start_block = 0; J.colmajor = 1;
-                } else {
-                    CHECK_LAUNCH(launch_colsum_partial(dt, s.dout, s.outCp, M, s.outC, grads + s.b_off, s.colsum_ws, bias_jobs, sd), "conv bias gradient");
+                if (!s.bands_ready)
+                    return bias_sums(s.dout, s.outCp, M, s.outC, grads + s.b_off, s.colsum_ws, Mo * s.outC * es + s.outC * 4.0, "conv bias gradient");
+                // the pooling backward pass above has left the band sums
+                s.bands_ready = false;
+                ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, s.outC * 4.0);
+                if (bias_jobs.n == 12) {
+                    CHECK_LAUNCH(launch_colsum_stage1(dt, bias_s1, sd), "conv bias gradient");
+                    CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "conv bias gradient");
                 }
-                if (by_layer || bias_jobs.n == 12) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "conv bias gradient");
+                ColsumJob &J = bias_jobs.j[bias_jobs.n++];
+                J.ws = s.colsum_ws; J.nblk = (int)s.pool_bands; J.ld = s.outCp; J.N = s.outC; J.db = grads + s.b_off; J.start_block = 0; J.colmajor = 1;
+                if (by_layer) CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "conv bias gradient");
                 return ASGD_OK;
             };
             // The last layer of the backward pass: its filter gradient is the tail of the side stream, which ends after
@@ -743,7 +768,8 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
             // runs beside that GEMM instead of behind it.
             const bool bias_first = fork && !by_layer && si == first_param;
             if (bias_first) {
-                const int brc = bias_part();
+                int brc = bias_part();
+                if (brc == ASGD_OK) brc = bias_first_stages();
                 if (brc != ASGD_OK) return brc;
                 CHECK_HIP(hipEventRecord(n->ev_bias, sd), "hipEventRecord");
                 CHECK_HIP(hipStreamWaitEvent(st, n->ev_bias, 0), "hipStreamWaitEvent");
@@ -798,6 +824,8 @@ int backward(asgd_net *n, const void *params, float *grads, hipStream_t st, cons
         if (prc != ASGD_OK) return prc;
     }
     {
+        const int brc = bias_first_stages();
+        if (brc != ASGD_OK) return brc;
         ProfScope ps(n, sd, ASGD_K_BIAS_GRAD, 0, 0);
         CHECK_LAUNCH(launch_colsum_finish(bias_jobs, sd), "bias gradients");
     }

@@ -145,6 +145,12 @@ int launch_unflatten(int dtype, const void *dflat, const void *x_for_mask, int r
 struct ColsumJob { const float *ws; float *db; long ld; int nblk, N; unsigned start_block; int colmajor; };   // ws[band][ld], or ws[column][nblk] if colmajor
 struct ColsumJobs { ColsumJob j[12]; int n; };
 int launch_colsum_partial(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, ColsumJobs &jobs, hipStream_t s);
+// the same with the first stage put off: colsum_partial_defer appends the tensor to s1 (and its second stage to jobs),
+// launch_colsum_stage1 sums the bands of all appended tensors (up to 12) in one launch
+struct ColsumS1Job { const void *dy; float *ws; long ld, M, rows_per_block; int chunks, cpb, rl, gx, gy; unsigned start_block; };
+struct ColsumS1Jobs { ColsumS1Job j[12]; int n; };
+int colsum_partial_defer(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, ColsumS1Jobs &s1, ColsumJobs &jobs);
+int launch_colsum_stage1(int dtype, ColsumS1Jobs &s1, hipStream_t s);
 int launch_colsum_finish(ColsumJobs &jobs, hipStream_t s);
 size_t colsum_ws_floats(int dtype, long M, long ld);
 // softmax cross-entropy over fp32 logits [B][ld]: loss (mean) and dz (compute type, [B][ld], zero padding columns)

@@ -1126,15 +1126,22 @@ int launch_unflatten(int dtype, const void *dflat, const void *x, int relu, void
 // thread (c, r) adds rows r, r+RL, ... of chunk c, the RL row lanes are then
 // added in lane order.  Stage 2 adds the bands in order.  No atomics, so the
 // result does not depend on scheduling.
+// Stage 1 for several tensors in one launch: a block finds its job and its (column group, band) in it.
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_stage1(const T *__restrict__ dy, long ld, long M, int chunks, int cpb, int rl, long rows_per_block,
-                                                    float *__restrict__ ws)
+__global__ __launch_bounds__(256) void colsum_stage1(ColsumS1Jobs jobs)
 {
     constexpr int V = 16 / sizeof(T);
     __shared__ float part[256 * V];
+    int q = 0;
+    while (q + 1 < jobs.n && blockIdx.x >= jobs.j[q + 1].start_block) ++q;
+    const ColsumS1Job &J = jobs.j[q];
+    const unsigned lb = blockIdx.x - J.start_block, bx = lb % (unsigned)J.gx, by = lb / (unsigned)J.gx;
+    const T *dy = static_cast<const T *>(J.dy);
+    const long ld = J.ld, M = J.M, rows_per_block = J.rows_per_block;
+    const int chunks = J.chunks, cpb = J.cpb, rl = J.rl;
     const int c = threadIdx.x % cpb, r = threadIdx.x / cpb;
-    const int gc = blockIdx.x * cpb + c;
-    const long m0 = (long)blockIdx.y * rows_per_block, m1 = min(M, m0 + rows_per_block);
+    const int gc = (int)bx * cpb + c;
+    const long m0 = (long)by * rows_per_block, m1 = min(M, m0 + rows_per_block);
     float acc[V];
 #pragma unroll
     for (int e = 0; e < V; ++e) acc[e] = 0.f;
@@ -1154,7 +1161,7 @@ __global__ __launch_bounds__(256) void colsum_stage1(const T *__restrict__ dy, l
         for (int e = 0; e < V; ++e) {
             float t = 0.f;
             for (int j = 0; j < rl; ++j) t += part[(j * cpb + c) * V + e];
-            ws[(long)blockIdx.y * ld + (long)gc * V + e] = t;
+            J.ws[(long)by * ld + (long)gc * V + e] = t;
         }
     }
 }
@@ -1211,17 +1218,34 @@ size_t colsum_ws_floats(int dtype, long M, long ld)
 }
 // dy is [M][ld] with ld a multiple of 8 and columns N..ld-1 zero or ignorable.  Stage 1 leaves the band sums in
 // ws (colsum_ws_floats) and appends the job that finishes them; launch_colsum_finish runs all appended jobs.
-int launch_colsum_partial(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, ColsumJobs &jobs, hipStream_t s)
+int colsum_partial_defer(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, ColsumS1Jobs &s1, ColsumJobs &jobs)
 {
-    if (jobs.n >= 12) return -1;
+    if (jobs.n >= 12 || s1.n >= 12 || (ld & 7) || M <= 0) return -1;
     int chunks, cpb, rl, nblk; long rpb;
     colsum_geometry(dtype, ld, M, chunks, cpb, rl, rpb, nblk);
-    const dim3 grid((chunks + cpb - 1) / cpb, nblk);
-    if (dtype == kBF16) hipLaunchKernelGGL(colsum_stage1<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(dy), ld, M, chunks, cpb, rl, rpb, ws);
-    else hipLaunchKernelGGL(colsum_stage1<float>, grid, dim3(256), 0, s, static_cast<const float *>(dy), ld, M, chunks, cpb, rl, rpb, ws);
+    ColsumS1Job &S = s1.j[s1.n++];
+    S.dy = dy; S.ws = ws; S.ld = ld; S.M = M; S.rows_per_block = rpb; S.chunks = chunks; S.cpb = cpb; S.rl = rl;
+    S.gx = (chunks + cpb - 1) / cpb; S.gy = nblk; S.start_block = 0;
     ColsumJob &J = jobs.j[jobs.n++];
     J.ws = ws; J.nblk = nblk; J.ld = ld; J.N = N; J.db = db; J.start_block = 0; J.colmajor = 0;
+    return 0;
+}
+int launch_colsum_stage1(int dtype, ColsumS1Jobs &s1, hipStream_t s)
+{
+    if (s1.n == 0) return 0;
+    unsigned long blocks = 0;
+    for (int q = 0; q < s1.n; ++q) { s1.j[q].start_block = (unsigned)blocks; blocks += (unsigned long)s1.j[q].gx * (unsigned long)s1.j[q].gy; }
+    if (blocks > 0x7fffffffu) return -1;
+    if (dtype == kBF16) hipLaunchKernelGGL(colsum_stage1<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, s, s1);
+    else hipLaunchKernelGGL(colsum_stage1<float>, dim3((unsigned)blocks), dim3(256), 0, s, s1);
+    s1.n = 0;
     return launch_ok();
+}
+int launch_colsum_partial(int dtype, const void *dy, long ld, long M, int N, float *db, float *ws, ColsumJobs &jobs, hipStream_t s)
+{
+    ColsumS1Jobs s1; s1.n = 0;
+    if (colsum_partial_defer(dtype, dy, ld, M, N, db, ws, s1, jobs) != 0) return -1;
+    return launch_colsum_stage1(dtype, s1, s);
 }
 int launch_colsum_finish(ColsumJobs &jobs, hipStream_t s)
 {

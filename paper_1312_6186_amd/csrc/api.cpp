@@ -163,6 +163,8 @@ size_t carve(asgd_net &n, char *base)
     return c.off;
 }
 
+Gather conv_gather(const Stage &s, const void *x, int B, int dt, int group = 0);
+
 int plan_net(asgd_net &n)
 {
     const int L = (int)n.layers.size();
@@ -315,6 +317,8 @@ int plan_net(asgd_net &n)
                 s.p_fwd = plan_gemm(M, s.outCp, K, n.dtype, 1);
                 s.p_dgrad = plan_gemm(Min, s.inCp, (long)s.k * s.k * s.outCp, n.dtype, 1);
                 s.p_wgrad = plan_gemm(s.outCp, K, M, n.dtype, 128);
+                // the first layer's filter gradient as one persistent kernel wants a partial result per workgroup
+                if (s.rw) s.p_wgrad.ws_floats = std::max(s.p_wgrad.ws_floats, rows_wgrad_ws_floats(n.dtype, s.outCp, conv_gather(s, nullptr, (int)B, n.dtype)));
             }
             scratch_side = std::max(scratch_side, s.p_wgrad.ws_floats);
             s.colsum_floats = colsum_ws_floats(n.dtype, M, s.outCp);
@@ -437,7 +441,7 @@ bool relu_under_pool(const std::vector<Stage> &st, int pool_idx)
 }
 
 // The input side of a convolution stage as a gather over its (possibly bordered) input tensor x.
-Gather conv_gather(const Stage &s, const void *x, int B, int dt, int group = 0)
+Gather conv_gather(const Stage &s, const void *x, int B, int dt, int group)
 {
     const size_t es = dtype_size(dt);
     Gather g;

@@ -91,6 +91,9 @@ int gemm_trans_trans(int dtype, const void *at, long lda, int M, const void *bt,
 // reduction index enumerating (n, oy, ox) and rows enumerating (ky, kx, c).
 int gemm_trans_gather(int dtype, const void *at, long lda, int M, const Gather &b, const Epilogue &ep,
                       const GemmPlan &plan, float *ws, hipStream_t s);
+// fp32 scratch (in floats) the filter gradient of a first convolution in window-row form wants in plan.ws_floats to
+// run as one persistent kernel with a partial result per workgroup; 0 where that kernel does not apply
+size_t rows_wgrad_ws_floats(int dtype, int M, const Gather &b);
 
 // ---- streaming kernels (kernels_stream.hip) --------------------------------
 int launch_update(float *w, float *v, const float *g, size_t n, float lr, float mu, float wd,

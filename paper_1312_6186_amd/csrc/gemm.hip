@@ -1506,6 +1506,168 @@ __global__ __launch_bounds__(512, 2) void conv_rows_kernel(RowsConv a, Epilogue 
     }
 }
 
+
+// ------------------------------------------------------------------ first-layer filter gradient from staged image rows
+// dW[cout][(ky, j)] = sum over output pixels of dY[pixel][cout] * window row element (ky, j) of that pixel: the
+// reduction runs over the pixels, of which there are hundreds of thousands, and the result is tiny (96 x 440).  The
+// tile engine splits it 128 ways, multiplies a quarter of its 128 x 512 padded tiles for nothing and gathers the
+// im2col operand from memory again for every column tile.  Here a persistent workgroup (one per CU) walks over tiles
+// of whole output rows of one image (up to 112 pixels) and keeps the whole 96 x 448 result in the accumulators of six waves (two
+// or three blocks of 32 K columns each, all three blocks of output channels: 96 or 144 accumulator registers).  Both operands
+// are read with transposing LDS reads, in which every lane supplies its own address: the dY tile is stored pixel by
+// pixel (256-byte lines, the 64-byte group index XOR-ed with the line so that the four lines of a read fall into
+// different banks), and the window-row elements come straight out of the block of image rows the tile touches,
+// copied to LDS as it is (lane's K line = pixel: the byte offset of its window origin; lane's row piece = four
+// consecutive K columns: ky * row_bytes + 2 j).  Two more waves do nothing but bring in the image rows and the dY tiles
+// of the tiles to come with buffer loads that write LDS directly, three buffers each and two tiles ahead (with one tile of
+// lead the period of a tile was the issue time of its 64 loads plus their latency, 3.2 us against 1.3 us of MFMAs),
+// one barrier per tile.  Every workgroup leaves one partial result; the ordered split-K reduction adds them and
+// scatters to canonical order.
+constexpr int kRowsWgBN = 448, kRowsWgTP = 112, kRowsWgIB = 22528, kRowsWgDB = kRowsWgTP * 256, kRowsWgGrid = 256;
+
+// rpt: output rows per tile (rpt * Wo <= kRowsWgTP pixels); a.tiles_per_image = ceil(Ho / rpt)
+__global__ __launch_bounds__(512, 2) void conv_rows_wgrad_kernel(RowsConv a, int rpt, Operand dy, unsigned ldyb, int M, float *ws)
+{
+    typedef bf16_t T;
+    constexpr int TP = kRowsWgTP, IB = kRowsWgIB, DB = kRowsWgDB, NI = IB / 1024, ND = DB / 1024;
+    static_assert(NI <= 31 && ND <= 31, "two tiles of one wave's loads fit the six-bit in-order wait counter");
+    __shared__ uint4 smem[(3 * IB + 3 * DB) / 16];
+    char *sP = reinterpret_cast<char *>(smem);          // three blocks of image rows
+    char *sD = sP + 3 * IB;                             // three dY tiles: TP lines of 256 bytes
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    auto decode = [&](int v, int &img, int &r0) ASGD_INLINE {
+        const int q = a.total >> 3, r = a.total & 7, xx = v & 7;
+        const int t = xx * q + (xx < r ? xx : r) + (v >> 3);     // each XCD gets a contiguous range of tiles
+        img = (int)fdiv((uint32_t)t, a.dtpi);
+        r0 = (t - img * a.tiles_per_image) * rpt;                // first output row of the tile
+    };
+
+    if (wave >= 6) {
+        // ---- the two fetching waves (wave 6: image rows, wave 7: dY): tile `it` goes to buffers it % 3, two tiles ahead of
+        // the multiplying waves.  One wave can have 63 loads (63 KB) in flight, less than a tile period needs.
+        const __amdgpu_buffer_rsrc_t xrs = a.x.rsrc(), drs = dy.rsrc();
+        // dY: instruction i fills lines 4 i .. 4 i + 3; lane l: line 4 i + l / 16, physical 16-byte slot l % 16, which holds
+        // logical slot ((l % 16 / 4) ^ (line & 3)) * 4 + l % 4 of the pixel's row (line & 3 = l / 16)
+        const int dline = lane >> 4, dslot = ((((lane & 15) >> 2) ^ dline) << 2) | (lane & 3);
+        const bool dcol = dslot * 8 < M;
+        const bool rows_wave = wave == 6;
+        auto issue = [&](int v, int buf) ASGD_INLINE {   // always NI (or ND) instructions: the wait below counts them
+            int img, r0;
+            decode(v, img, r0);
+            const int rows_out = min(rpt, a.Ho - r0);
+            if (rows_wave) {
+                const unsigned src = (unsigned)img * a.imgb + (unsigned)(r0 * a.stride) * a.rowb;
+                const unsigned bytes = (unsigned)((rows_out - 1) * a.stride + a.kh) * a.rowb;
+#pragma unroll 2
+                for (int i = 0; i < NI; ++i) {
+                    const unsigned o = (unsigned)(i * 64 + lane) * 16u;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xrs, (lds_void *)(sP + buf * IB + i * 1024), 16, (int)(o < bytes ? src + o : kInv), 0, 0, 0);
+                }
+            } else {
+                const int valid = rows_out * a.Wo;
+                const unsigned dsrc = (unsigned)(img * a.npix + r0 * a.Wo) * ldyb + (unsigned)dslot * 16u;
+#pragma unroll 2
+                for (int i = 0; i < ND; ++i) {
+                    const int line = i * 4 + dline;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(drs, (lds_void *)(sD + buf * DB + i * 1024), 16,
+                                                             (int)((dcol && line < valid) ? dsrc + (unsigned)line * ldyb : kInv), 0, 0, 0);
+                }
+            }
+        };
+        int v = blockIdx.x;
+        const int g = (int)gridDim.x;
+        issue(v, 0);
+        if (v + g < a.total) issue(v + g, 1);
+        int buf2 = 2;                                        // buffer of tile it + 2
+        for (int it = 0; v < a.total; ++it, v += g) {
+            // tile `it` has landed when at most the next tile's instructions are outstanding (the counter retires in order)
+            if (v + g >= a.total) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            else if (rows_wave) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NI) : "memory");
+            else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(ND) : "memory");
+            barrier_keep_loads();                            // ... and the buffers of tile it - 1 have been read to the end
+            if (v + 2 * g < a.total) issue(v + 2 * g, buf2);
+            buf2 = buf2 == 2 ? 0 : buf2 + 1;
+        }
+        return;
+    }
+
+    // ---- multiplying waves, all three blocks of output channels each.  Waves 0, 1, 4, 5 (two to a SIMD) own two blocks of
+    // 32 K columns, waves 2 and 3 (which share their SIMDs with the fetching waves) three: 12 / 12 / 9 / 9 MFMAs per
+    // K step on the four SIMDs.
+    const int b4 = lane >> 4, i16 = lane & 15, lrow = lane & 31, half = lane >> 5;
+    // A (dY tile): lane supplies K line 8 (b4 / 2) + i16 / 4 (+ 4) of the K step, channels mb * 32 + 16 (b4 & 1) + 4 (i16 & 3) ..+3
+    unsigned aoff[3];
+    static_for<0, 3>([&](auto mb) ASGD_INLINE {
+        aoff[mb] = (unsigned)((8 * (b4 >> 1) + (i16 >> 2)) * 256 + ((mb ^ (i16 >> 2)) << 6) + 32 * (b4 & 1) + 8 * (i16 & 3));
+    });
+    // B (image rows): lane supplies the pixel of the same K line and K columns n .. n + 3.  The window origins of the
+    // tile's pixels relative to its block of rows are the same for every tile (a tile is whole output rows).
+    const int tp = rpt * a.Wo;                           // pixels of a full tile
+    unsigned org[TP / 16][2];
+    static_for<0, TP / 16>([&](auto ks) ASGD_INLINE {
+        static_for<0, 2>([&](auto h) ASGD_INLINE {
+            const int p = min(ks * 16 + 8 * (b4 >> 1) + (i16 >> 2) + 4 * h, tp - 1);   // lines past the tile hold zeros in dY
+            const int oy = (int)fdiv((uint32_t)p, a.dWo), ox = p - oy * a.Wo;
+            org[ks][h] = (unsigned)(oy * a.stride) * a.rowb + (unsigned)ox * a.pixstep;
+        });
+    });
+    typedef __attribute__((address_space(3))) short4v lds_s4;
+    auto tr_read = [&](const char *p0, const char *p1) ASGD_INLINE -> Frag<T> {
+        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)(p0));
+        const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4 *)(p1));
+        const uint2 x = __builtin_bit_cast(uint2, lo), y = __builtin_bit_cast(uint2, hi);
+        Frag<T> f;
+        f.v = make_uint4(x.x, x.y, y.x, y.y);
+        return f;
+    };
+    auto body = [&](auto nbw, int nb0) ASGD_INLINE {     // this wave's NBW blocks of K columns start at block nb0
+        constexpr int NBW = decltype(nbw)::value;
+        unsigned coff[NBW];
+        static_for<0, NBW>([&](auto nb) ASGD_INLINE {
+            int n = (nb0 + nb) * 32 + 16 * (b4 & 1) + 4 * (i16 & 3);
+            n = min(n, a.K - 4);                         // columns past K: any valid address (their sums are not stored)
+            const int ky = (int)fdiv((uint32_t)n, a.dKW);
+            coff[nb] = (unsigned)ky * a.rowb + (unsigned)(n - ky * a.KW) * 2u;
+        });
+        f32x16 acc[NBW][3];
+        static_for<0, NBW>([&](auto i) ASGD_INLINE { static_for<0, 3>([&](auto j) ASGD_INLINE { acc[i][j] = f32x16{}; }); });
+        int buf = 0;
+        for (int v = blockIdx.x; v < a.total; v += gridDim.x) {
+            __syncthreads();
+            const char *pa = sD + buf * DB, *pb = sP + buf * IB;
+            // all TP / 16 K steps, whatever the tile holds (lines past its pixels are zeros in dY); the fragments of step
+            // ks + 1 are asked for before the MFMAs of step ks
+            Frag<T> fa[2][3], fb[2][NBW];
+            auto frags = [&](auto ks) ASGD_INLINE {
+                constexpr int S = decltype(ks)::value, SET = S & 1;
+                static_for<0, 3>([&](auto mb) ASGD_INLINE { fa[SET][mb] = tr_read(pa + aoff[mb] + S * 16 * 256, pa + aoff[mb] + S * 16 * 256 + 4 * 256); });
+                static_for<0, NBW>([&](auto nb) ASGD_INLINE { fb[SET][nb] = tr_read(pb + org[S][0] + coff[nb], pb + org[S][1] + coff[nb]); });
+            };
+            frags(std::integral_constant<int, 0>{});
+            static_for<0, TP / 16>([&](auto ks) ASGD_INLINE {
+                constexpr int S = decltype(ks)::value, SET = S & 1;
+                if constexpr (S + 1 < TP / 16) frags(std::integral_constant<int, S + 1>{});
+                static_for<0, NBW>([&](auto nb) ASGD_INLINE { static_for<0, 3>([&](auto mb) ASGD_INLINE { mma(acc[nb][mb], fb[SET][nb], fa[SET][mb]); }); });
+            });
+            buf = buf == 2 ? 0 : buf + 1;
+        }
+        // this workgroup's partial result: ws[block][m][n], n < K
+        float *o = ws + (size_t)blockIdx.x * (size_t)M * (size_t)a.K;
+        static_for<0, NBW>([&](auto nb) ASGD_INLINE {
+            static_for<0, 3>([&](auto mb) ASGD_INLINE {
+                const int m = mb * 32 + lrow;
+                static_for<0, 4>([&](auto g) ASGD_INLINE {
+                    const int n = (nb0 + nb) * 32 + 8 * g + 4 * half;
+                    if (m < M && n < a.K)
+                        *reinterpret_cast<f32x4 *>(o + (size_t)m * a.K + n) = f32x4{acc[nb][mb][4 * g], acc[nb][mb][4 * g + 1], acc[nb][mb][4 * g + 2], acc[nb][mb][4 * g + 3]};
+                });
+            });
+        });
+    };
+    if (wave == 2 || wave == 3) body(std::integral_constant<int, 3>{}, 8 + (wave - 2) * 3);
+    else body(std::integral_constant<int, 2>{}, (wave < 2 ? wave : wave - 2) * 2);
+}
+
 template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int splits, Epilogue ep, int M, int N)
 {
     const long g = (long)blockIdx.x * 256 + threadIdx.x;
@@ -1541,25 +1703,27 @@ template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_kerne
 }
 
 // The same for few outputs and many partial sums (the first layer's filter gradient: 5280 groups of 8 outputs, up
-// to 128 partials each): eight neighbouring lanes share a group, lane l adds partials l, l+8, ... in that order, and
-// the eight sums are combined in a fixed butterfly, so the result does not depend on anything but the inputs.
-template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_wide_kernel(const float *ws, int splits, Epilogue ep, int M, int N)
+// to 256 partials each): L = 8 or 32 neighbouring lanes share a group, lane l adds partials l, l+L, ... in that order, and
+// the L sums are combined in a fixed butterfly, so the result does not depend on anything but the inputs.
+template <typename T, int L> __global__ __launch_bounds__(256) void splitk_reduce_wide_kernel(const float *ws, int splits, Epilogue ep, int M, int N)
 {
-    const long g = ((long)blockIdx.x * 256 + threadIdx.x) >> 3;
-    const int l = threadIdx.x & 7;
+    static_assert(L == 8 || L == 32, "lanes per group of outputs");
+    constexpr int SH = L == 8 ? 3 : 5;
+    const long g = ((long)blockIdx.x * 256 + threadIdx.x) >> SH;
+    const int l = threadIdx.x & (L - 1);
     const int n8 = N / 8;
-    const bool live = g < (long)M * n8;   // whole groups of eight lanes are live or not; all lanes take part in the shuffles
+    const bool live = g < (long)M * n8;   // whole groups of L lanes are live or not; all lanes take part in the shuffles
     const long gg = live ? g : 0;
     const int m = (int)(gg / n8), n0 = (int)(gg - (long)m * n8) * 8;
     float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     const long stride = (long)M * N;
     const float *p0 = ws + (long)m * N + n0;
     int s = l;
-    for (; s + 24 < splits; s += 32) {   // four partials in flight
+    for (; s + 3 * L < splits; s += 4 * L) {   // four partials in flight
         float4 a[4], b[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float4 *p = reinterpret_cast<const float4 *>(p0 + (s + 8 * u) * stride);
+            const float4 *p = reinterpret_cast<const float4 *>(p0 + (s + L * u) * stride);
             a[u] = p[0]; b[u] = p[1];
         }
 #pragma unroll
@@ -1568,16 +1732,16 @@ template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_wide_
             v[4] += b[u].x; v[5] += b[u].y; v[6] += b[u].z; v[7] += b[u].w;
         }
     }
-    for (; s < splits; s += 8) {
+    for (; s < splits; s += L) {
         const float4 *p = reinterpret_cast<const float4 *>(p0 + s * stride);
         const float4 a = p[0], b = p[1];
         v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
         v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
     }
 #pragma unroll
-    for (int d = 1; d < 8; d <<= 1) {
+    for (int d = 1; d < L; d <<= 1) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) v[r] += __shfl_xor(v[r], d, 8);
+        for (int r = 0; r < 8; ++r) v[r] += __shfl_xor(v[r], d, L);
     }
     if (!live || l != 0) return;
     float b8[8];
@@ -1589,8 +1753,10 @@ template <typename T> __global__ __launch_bounds__(256) void splitk_reduce_wide_
 template <typename T> static void launch_splitk_reduce(const float *ws, int splits, const Epilogue &ep, int M, int N, hipStream_t s)
 {
     const long groups = (long)M * (N / 8);
-    if (splits >= 16 && groups < 32768)
-        hipLaunchKernelGGL((splitk_reduce_wide_kernel<T>), dim3((unsigned)((groups * 8 + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);
+    if (splits >= 192 && groups < 8192)      // one partial per CU (the first-layer filter gradient): 32 lanes share a group, two rounds of reads each
+        hipLaunchKernelGGL((splitk_reduce_wide_kernel<T, 32>), dim3((unsigned)((groups * 32 + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);
+    else if (splits >= 16 && groups < 32768)
+        hipLaunchKernelGGL((splitk_reduce_wide_kernel<T, 8>), dim3((unsigned)((groups * 8 + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);
     else
         hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, ws, splits, ep, M, N);
 }
@@ -1882,10 +2048,59 @@ int gemm_trans_trans(int dtype, const void *at, long lda, int M, const void *bt,
     return run<float>(make_plain_t<float>(at, lda, M, K), make_plain_t<float>(bt, ldb, N, K), M, N, K, ep, plan, ws, s);
 }
 
+// The filter gradient of a first convolution in window-row form (16-bit data, up to 96 output channels, up to 448 K
+// columns) runs conv_rows_wgrad_kernel when the image rows of a tile fit its LDS layout and the plan has the scratch
+// for one partial result per workgroup.
+static int rows_wgrad_rpt(const Gather &b) { return b.Wo > 0 && b.Wo <= kRowsWgTP ? std::min(b.Ho, kRowsWgTP / b.Wo) : 0; }   // output rows per tile
+static long rows_wgrad_tiles(const Gather &b)
+{
+    const int rpt = rows_wgrad_rpt(b);
+    return rpt > 0 ? (long)b.N * ((b.Ho + rpt - 1) / rpt) : 0;
+}
+size_t rows_wgrad_ws_floats(int dtype, int M, const Gather &b)
+{
+    const long K = (long)b.kh * b.C, tiles = rows_wgrad_tiles(b);
+    if (dtype != kBF16 || b.kw != 1 || b.pad != 0 || b.ds != 1 || M > 96 || K > kRowsWgBN || tiles <= 0) return 0;
+    return (size_t)std::min<long>(tiles, kRowsWgGrid) * (size_t)M * (size_t)K;
+}
+static bool rows_wgrad_applies(const void *at, long lda, int M, const Gather &b, const Epilogue &ep, const GemmPlan &plan, const float *ws)
+{
+    const long K = (long)b.kh * b.C;
+    const int rpt = rows_wgrad_rpt(b);
+    if (rpt <= 0) return false;
+    if (!(b.kw == 1 && b.pad == 0 && b.ds == 1 && b.pix != 0 && b.rowb != 0 && b.C % 8 == 0 && K <= kRowsWgBN && K % 8 == 0)) return false;
+    if (!(M > 0 && M <= 96 && M % 8 == 0 && lda >= M && (lda * 2) % 16 == 0 && ((uintptr_t)at & 15) == 0)) return false;
+    if (!(b.rowb % 16 == 0 && ((size_t)b.sm * b.pix) % 8 == 0 && ((uintptr_t)b.x & 15) == 0 && b.bytes <= kMaxOperandBytes)) return false;
+    if (!(ep.mode == 2 && ep.out_f32 && ws != nullptr && ((uintptr_t)ws & 15) == 0 && plan.ws_floats >= rows_wgrad_ws_floats(kBF16, M, b))) return false;
+    if ((size_t)b.N * b.Ho * b.Wo * lda * 2 > kMaxOperandBytes) return false;
+    const long block = ((long)(rpt - 1) * b.sm + b.kh) * (long)b.rowb;   // image rows of a tile
+    return block <= kRowsWgIB && b.H >= (b.Ho - 1) * b.sm + b.kh && rows_wgrad_tiles(b) <= 0x7fffffffL;
+}
+static int run_rows_wgrad(const void *at, long lda, int M, const Gather &b, const Epilogue &ep, float *ws, hipStream_t s)
+{
+    RowsConv r;
+    const int rpt = rows_wgrad_rpt(b);
+    r.x = operand(b.x, b.bytes);
+    r.rowb = (unsigned)b.rowb; r.imgb = (unsigned)((size_t)b.H * b.rowb); r.pixstep = (unsigned)((size_t)b.sm * b.pix);
+    r.Ho = b.Ho; r.Wo = b.Wo; r.stride = b.sm; r.kh = b.kh; r.KW = b.C; r.K = b.kh * b.C;
+    r.npix = b.Ho * b.Wo;
+    r.tiles_per_image = (b.Ho + rpt - 1) / rpt;
+    r.total = (int)rows_wgrad_tiles(b);
+    r.w = Operand{nullptr, 0u}; r.ldw = 0;
+    r.dWo = make_fastdiv((uint32_t)b.Wo); r.dtpi = make_fastdiv((uint32_t)r.tiles_per_image); r.dKW = make_fastdiv((uint32_t)b.C);
+    const Operand dy = operand(at, (size_t)b.N * r.npix * lda * sizeof(bf16_t));
+    if (r.x.bytes == 0 || dy.bytes == 0) return -1;
+    const int grid = r.total < kRowsWgGrid ? r.total : kRowsWgGrid;
+    hipLaunchKernelGGL(conv_rows_wgrad_kernel, dim3((unsigned)grid), dim3(512), 0, s, r, rpt, dy, (unsigned)(lda * sizeof(bf16_t)), M, ws);
+    launch_splitk_reduce<bf16_t>(ws, grid, ep, M, r.K, s);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 int gemm_trans_gather(int dtype, const void *at, long lda, int M, const Gather &b, const Epilogue &ep, const GemmPlan &plan, float *ws,
                       hipStream_t s)
 {
     if (b.ds != 1 || b.kh > 15 || b.kw > 15) return -1;
+    if (dtype == kBF16 && rows_wgrad_applies(at, lda, M, b, ep, plan, ws)) return run_rows_wgrad(at, lda, M, b, ep, ws, s);
     const int K = b.N * b.Ho * b.Wo, N = b.kh * b.kw * b.C;
     if (dtype == kBF16) return run<bf16_t>(make_plain_t<bf16_t>(at, lda, M, K), make_gather_t<bf16_t>(b), M, N, K, ep, plan, ws, s);
     return run<float>(make_plain_t<float>(at, lda, M, K), make_gather_t<float>(b), M, N, K, ep, plan, ws, s);

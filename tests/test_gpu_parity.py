@@ -609,6 +609,54 @@ def test_alexnet_bs128_gradient_matches_oracle(dtype, capsys):
     _full_size_case(128, dtype, capsys, plain=True)
 
 
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16], ids=["f32", "bf16"])
+def test_alexnet_bs128_fused_step_is_the_calls_bit_for_bit(dtype):
+    """The step `bench.py` times (asgd_train_step_fused at batch 128) against fwd_bwd + apply_update + snapshot, whose
+    gradient the test above grades against the oracle: parameters, momenta, the replica's copy and the loss must be
+    the same bits after two steps, the gradient buffer too outside the weight slices that are pushed inside their
+    GEMM, and those slices must not have been written."""
+    cfg = wl.ALEXNET
+    layers, in_shape, batch = cfg["layers"], cfg["in_shape"], 128
+    lr, mu, wd = cfg["lr"], cfg["mu"], cfg["wd"]
+    params0 = wl.make_params(layers, in_shape, cfg["seeds"]["init"])
+    tdt = torch.bfloat16 if dtype == B.BF16 else torch.float32
+    onet = oracle.OracleNet(layers, in_shape)
+    runs = []
+    g = GpuNet(layers, in_shape, batch, dtype)
+    try:
+        for fused in (False, True):
+            w = torch.from_numpy(params0).to(DEV); v = torch.zeros_like(w)
+            copy = torch.empty(g.P, dtype=tdt, device=DEV)
+            B.asgd_snapshot(w, copy, dtype)
+            losses = []
+            for a in range(2):
+                images, labels = wl.make_batch(in_shape, batch, cfg["classes"], cfg["seeds"]["data"] + a)
+                img, lab = g.to_device_images(images), torch.from_numpy(labels.astype(np.int32)).to(DEV)
+                g.grads.fill_(SENTINEL)
+                if fused:
+                    B.asgd_train_step_fused(g.net, w, v, copy, img, lab, cfg["seeds"]["dropout"], a, 0, g.loss, g.grads, lr, mu, wd)
+                else:
+                    B.asgd_fwd_bwd(g.net, copy, img, lab, cfg["seeds"]["dropout"], a, 0, g.loss, g.grads)
+                    B.asgd_apply_update(w, v, g.grads, lr, mu, wd)
+                    B.asgd_snapshot(w, copy, dtype)
+                torch.cuda.synchronize()
+                losses.append(float(g.loss.item()))
+            runs.append((w.cpu(), v.cpu(), copy.cpu(), g.grads.cpu(), losses))
+            del w, v, copy
+    finally:
+        g.close()
+    ibits = torch.int16 if dtype == B.BF16 else torch.int32
+    (w0, v0, c0, g0, l0), (w1, v1, c1, g1, l1) = runs
+    assert l0 == l1 and np.isfinite(l0).all()
+    assert torch.equal(w0, w1) and torch.equal(v0, v1) and torch.equal(c0.view(ibits), c1.view(ibits))
+    fusable = _fusable_fc_slices(onet, layers)
+    assert len(fusable) == 3                            # the three fully-connected weight matrices
+    expect = g0.clone()
+    for off, cnt in fusable:
+        expect[off:off + cnt] = SENTINEL
+    assert torch.equal(g1, expect)
+
+
 def test_alexnet_bs256_bf16_gradient_matches_oracle(capsys):
     """Batch 256 in bf16: twice the GEMM rows of the headline configuration, other tile and split choices."""
     _full_size_case(256, B.BF16, capsys, plain=False)

@@ -40,7 +40,7 @@ MFMA_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad", "fc_fwd", "fc_dgrad", "f
 
 
 STEP_TEXT = {"calls": "fwd_bwd + apply_update_snapshot (push fused with the next fetch)",
-             "fused": "train_step_fused (push by layer; fully-connected weights pushed inside their gradient kernel)"}
+             "fused": "train_step_fused (fully-connected weights pushed inside their gradient kernel, the rest in one update launch behind the backward pass)"}
 
 
 def csrc_hash():
@@ -204,8 +204,8 @@ def main():
     ap.add_argument("--serial", action="store_true",
                     help="keep every kernel on one stream (for profiler runs: per-kernel durations are then those of kernels running alone)")
     ap.add_argument("--step", default="fused", choices=["calls", "fused"],
-                    help="calls: asgd_fwd_bwd + asgd_apply_update_snapshot; fused: asgd_train_step_fused (push by layer, the "
-                         "fully-connected weights inside their gradient kernel)")
+                    help="calls: asgd_fwd_bwd + asgd_apply_update_snapshot; fused: asgd_train_step_fused (the fully-connected "
+                         "weights are pushed inside their gradient kernel)")
     args = ap.parse_args()
     if args.serial:
         os.environ["ASGD_SERIAL"] = "1"
